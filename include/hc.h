@@ -1,0 +1,187 @@
+/* hc.h -- C ABI of the HeteroCache decode hot path for AMD MI355X (gfx950).
+ *
+ * What is computed is the per-step online inference of HeteroCache (arXiv 2601.13684,
+ * Sec. 4.3 "Hierarchical Storage & Retrieval" and Algorithm 1, stage 3), for one layer:
+ *
+ *   hc_decode_attn      attention of the decode token over the heterogeneous cache C_GPU:
+ *                       full (volatile / pivot) heads over the whole context, compressed
+ *                       (anchor / satellite) heads over their l_i resident slots;
+ *   hc_rep_topk_drift   the pivot heads' drift monitor: GQA-aggregated score (App. C.1),
+ *                       TopIndices_k, overlap with the baseline set (Eq. 9), windowed-median
+ *                       retrieval signal (Eq. 10), baseline update;
+ *   hc_gather_retrieve  AsyncUpdate: C_GPU^(s) <- C_CPU^(s)[I_s] for the satellites of every
+ *                       pivot whose signal fired, reading a pinned host-memory tier.
+ *
+ * Conventions
+ *   - C99, no C++ types.  Every function returns an hc_status; nothing aborts, throws or prints.
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers ordinary host memory,
+ *     "pinned" pointers host memory allocated with hipHostMalloc (device-visible).
+ *   - The caller owns every buffer it passes in.  The library owns only what hc_create and
+ *     hc_layer_create allocate (split-K partials, selection workspaces, launch plans) and
+ *     frees it in the matching destroy call.  No caller pointer is kept after a call returns.
+ *   - The three hot-path calls only enqueue work on the given HIP stream: they never
+ *     synchronise, allocate or copy from the host, so they may be captured in a HIP graph.
+ *     Results are valid once the stream (or done_event) has completed.  Trigger decisions
+ *     stay in device memory (flag); the host may read them later.
+ *   - One hc_ctx per host thread; calls on one ctx are not re-entrant, and two hot-path calls
+ *     that use the same workspace (two hc_decode_attn, or two hc_rep_topk_drift) must be
+ *     ordered by the caller's streams.  A decode_attn and a rep_topk_drift may overlap.
+ *   - Arguments are validated on the host before anything is launched.
+ *
+ * Index-list tables (topk_idx, base_idx) have one row of max_k int32 per (b, KV head):
+ * row (b*Hkv + h).  Per-head scalars (inter, flag) are indexed the same way; ring has
+ * (window + 1) int32 per row: [0] = number of stored values, [1..] = values, oldest first.
+ */
+#ifndef HC_H
+#define HC_H
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hc_ctx hc_ctx;       /* device-wide workspaces                                  */
+typedef struct hc_layer hc_layer;   /* one layer's head table, split-K plan and selection plan */
+
+typedef enum {
+    HC_OK = 0,
+    HC_EINVAL = 1,   /* null pointer, bad enum, inconsistent role / rep table                   */
+    HC_ESHAPE = 2,   /* a size is outside what the kernels support                              */
+    HC_ENOMEM = 3,   /* host or device allocation failed                                        */
+    HC_EHIP = 4,     /* a HIP call failed; hc_last_error has its text                           */
+    HC_ESTATE = 5    /* object used after destroy / with the wrong ctx                          */
+} hc_status;
+
+enum { HC_ROLE_FULL = 0, HC_ROLE_SATELLITE = 1, HC_ROLE_ANCHOR = 2 };
+enum { HC_METRIC_OVERLAP = 0, HC_METRIC_JACCARD = 1 };
+enum { HC_AGG_PROB = 0, HC_AGG_LOGIT = 1 };
+enum { HC_MAX_WINDOW = 64, HC_MAX_K_PER_REP = 8 };
+
+typedef struct {
+    int32_t B;         /* sequences in the batch (>= 1)                                         */
+    int32_t Hq;        /* query heads; Hq = G * Hkv with G in {1, 2, 4, 8}                      */
+    int32_t Hkv;       /* KV heads                                                              */
+    int32_t D;         /* head dimension; must be 128                                           */
+    int32_t max_ctx;   /* upper bound of every context length; multiple of 64; row stride of
+                          rep_logits and scores                                                 */
+    int32_t max_k;     /* row stride of the index-list tables; >= every k used                  */
+    int32_t window;    /* W of Eq. 10, 1..HC_MAX_WINDOW                                         */
+    int32_t metric;    /* HC_METRIC_OVERLAP: inter/k (Eq. 9); HC_METRIC_JACCARD: inter/(2k-inter) */
+    int32_t tau_num;   /* drift threshold tau_drift = tau_num / tau_den, compared exactly in    */
+    int32_t tau_den;   /*   integers: statistic < tau  (strict, Eq. 10); tau_den >= 1           */
+    int32_t agg;       /* HC_AGG_PROB: mean over the GQA group of softmax weights (App. C.1);
+                          HC_AGG_LOGIT: mean of scaled logits (exactly reproducible test mode)  */
+} hc_config;
+
+/* One KV head of one sequence; table of B*Hkv entries, row (b*Hkv + h), HOST memory. */
+typedef struct {
+    int64_t k_off;     /* element (bf16) offset of this head's K rows [len][D] in the arena;
+                          multiple of 8                                                          */
+    int64_t v_off;     /* same for V rows [len][D]                                               */
+    int64_t tier_off;  /* satellites: element offset of this head's [ctx][2][D] block (K row then
+                          V row per position) in the host tier; multiple of 8; others: ignored   */
+    int32_t ctx;       /* N_b: context length of the sequence, 1..max_ctx                        */
+    int32_t len;       /* resident rows: ctx for a full head, the budget l_i for a compressed one */
+    int32_t role;      /* HC_ROLE_*                                                              */
+    int32_t rep;       /* satellite: KV-head index (same sequence) of its pivot, which must be
+                          HC_ROLE_FULL; otherwise -1                                             */
+    int32_t sink;      /* compressed: slots [0,sink) hold positions [0,sink)                     */
+    int32_t recent;    /* compressed: slots [sink,sink+recent) hold positions [ctx-recent,ctx);
+                          slots [sink+recent, len) are the r retrieved ones                      */
+    int32_t k_mon;     /* pivot: size of the monitored set (L_base of Eq. 9); 0 = largest r of
+                          its satellites                                                         */
+    int32_t reserved;  /* must be 0                                                              */
+} hc_head_desc;
+
+/* ---- life cycle (these may allocate and synchronise; not for capture) -------------------- */
+hc_status hc_create(const hc_config* cfg, hc_ctx** out);
+hc_status hc_destroy(hc_ctx* ctx);
+const char* hc_strerror(hc_status st);
+const char* hc_last_error(const hc_ctx* ctx);       /* text of the last failure on this ctx   */
+
+/* Validates the head table (all satellites of one pivot must share sink and recent; every k
+ * must fit the candidate range [sink, ctx-recent) and max_k; at most HC_MAX_K_PER_REP distinct
+ * set sizes per pivot), builds the split-K work partition and uploads the plans. */
+hc_status hc_layer_create(hc_ctx* ctx, const hc_head_desc* heads_host, hc_layer** out);
+hc_status hc_layer_destroy(hc_layer* layer);
+/* Number of pivots (full heads with at least one satellite), and the slot 0..n-1 of pivot (b,h)
+ * in rep_logits / scores (-1 if (b,h) is not a pivot). */
+int32_t hc_layer_num_reps(const hc_layer* layer);
+int32_t hc_layer_rep_slot(const hc_layer* layer, int32_t b, int32_t h);
+/* Split-K plan facts for reporting: workgroups launched and partial results combined. */
+int32_t hc_layer_num_workgroups(const hc_layer* layer);
+int32_t hc_layer_num_partials(const hc_layer* layer);
+/* Tuning knob (before hc_layer_create): target workgroups per compute unit of the split pass
+ * (default 2) and host override of the compute-unit count (0 = ask the device). */
+hc_status hc_set_split(hc_ctx* ctx, int32_t workgroups_per_cu, int32_t compute_units);
+
+/* Host-only dry run of hc_layer_create: validates the head table exactly as hc_layer_create does
+ * and reports the plan it would build for a device with the given number of compute units.  Touches
+ * no GPU.  err (may be NULL) receives the text of a validation failure. */
+typedef struct {
+    int32_t n_workgroups;             /* workgroups of the split pass                               */
+    int32_t n_partials;               /* partial results the combine pass merges                    */
+    int32_t n_reps;                   /* pivots                                                     */
+    int32_t n_lists;                  /* index lists emitted per monitor call                       */
+    int32_t n_satellites;             /* satellites with at least one retrieved slot                */
+    int32_t max_rows_per_workgroup;
+    int32_t min_rows_per_workgroup;
+    int32_t reserved;
+    int64_t total_rows;               /* sum of len over all heads                                  */
+    int64_t rows_covered;             /* rows of heads whose segments add up to exactly len         */
+} hc_plan_info;
+hc_status hc_plan_describe(const hc_config* cfg, const hc_head_desc* heads_host, int32_t compute_units,
+                           int32_t workgroups_per_cu, hc_plan_info* info, char* err, int32_t err_len);
+
+/* ---- hot path ---------------------------------------------------------------------------- */
+
+/* Attention of the decode token over the heterogeneous cache (Algorithm 1, ModelForward over
+ * C_GPU; Sec. 4.3): for query head a of sequence b, with h = a / G,
+ *     out[b,a,:] = softmax_j( q[b,a,:] . K_{b,h}[j,:] / sqrt(D) ) V_{b,h}[j,:]   over the len
+ * resident rows of KV head (b,h); lse[b,a] is the log-sum-exp of those scaled logits.
+ *   kv_arena    dev, bf16; rows of 128 elements addressed by the head table's offsets
+ *   q           dev, bf16 [B][Hq][D]
+ *   out         dev, f32  [B][Hq][D]
+ *   lse         dev, f32  [B][Hq]
+ *   rep_logits  dev, f32  [num_reps][G][max_ctx], or NULL.  If given, the scaled logits of
+ *               every pivot's query group over all ctx positions are stored for the monitor.
+ *   stream      hipStream_t (NULL = default stream)
+ * bf16 inputs, fp32 accumulation; split over the token axis with a second combine pass. */
+hc_status hc_decode_attn(hc_ctx* ctx, const hc_layer* layer, const void* kv_arena, const void* q,
+                         float* out, float* lse, float* rep_logits, void* stream);
+
+/* Pivot drift monitor (Sec. 4.3, Eq. 9-10; Algorithm 1, the block under "t mod W = 0" with the
+ * window read as sliding and tested every step once it holds W values).  For every pivot p:
+ *   1. score s[j] = (1/G) sum_g exp(rep_logits[p][g][j] - lse[b, pG+g])        (agg = PROB)
+ *      for the candidates j in [sink, ctx-recent); stored to scores (f32 [num_reps][max_ctx]).
+ *      With scores_given != 0 this step is skipped and scores is an INPUT.
+ *   2. for k = k_mon and every satellite's r: T_k = the k candidates that come first under
+ *      (score descending, index ascending); written as ascending lists to topk_idx row of the
+ *      pivot (T_{k_mon}) and of each satellite (T_r).  NaN scores rank last; -0 equals +0.
+ *   3. inter[p] = |T_{k_mon} ∩ base_idx row p| (entries < 0 in the baseline never match);
+ *      pushed into ring[p]; once W values are stored, r_t = [lower-median statistic < tau];
+ *      flag[p] = r_t.  On r_t = 1 the baseline row becomes T_{k_mon} and the ring is emptied.
+ * All of topk_idx, base_idx, ring, inter, flag are dev int32 tables as described above;
+ * rows of heads that are not pivots (or their satellites, for topk_idx) are left untouched. */
+hc_status hc_rep_topk_drift(hc_ctx* ctx, const hc_layer* layer, const float* rep_logits, const float* lse,
+                            float* scores, int32_t scores_given,
+                            int32_t* topk_idx, int32_t* base_idx, int32_t* ring,
+                            int32_t* inter, int32_t* flag, void* stream);
+
+/* AsyncUpdate (Algorithm 1; Sec. 4.3): for every satellite s whose pivot has flag != 0, slot
+ * sink+recent+i of its K and V rows in the arena <- host-tier rows at position topk_idx[s][i],
+ * i = 0..r-1.  Satellites of pivots with flag == 0 and anchors are not touched (the predicate is
+ * evaluated on the device; the call always enqueues).
+ *   host_tier   pinned, bf16; the kernel reads it over the host link
+ *   stream      stream to run the gather on (typically a side stream)
+ *   wait_event  hipEvent_t or NULL: the stream waits for it first (record it after the monitor)
+ *   done_event  hipEvent_t or NULL: recorded after the gather; the attention that next reads this
+ *               layer's arena must wait for it (a refill decided at step t is used from t+1). */
+hc_status hc_gather_retrieve(hc_ctx* ctx, const hc_layer* layer, const void* host_tier,
+                             const int32_t* topk_idx, const int32_t* flag, void* kv_arena,
+                             void* stream, void* wait_event, void* done_event);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,198 @@
+"""ctypes binding of the C ABI in include/hc.h: same names, argument marshalling only.
+
+Every function takes torch tensors (or raw integer addresses) where the C call takes pointers
+and raises ``HcError`` on a non-zero status.  Nothing is computed here and there is no fallback:
+if the HIP library has not been built, loading fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence, Union
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhc.so")
+
+HC_OK, HC_EINVAL, HC_ESHAPE, HC_ENOMEM, HC_EHIP, HC_ESTATE = range(6)
+HC_MAX_WINDOW, HC_MAX_K_PER_REP = 64, 8
+
+EXPORTS = ["hc_create", "hc_destroy", "hc_strerror", "hc_last_error", "hc_layer_create", "hc_layer_destroy",
+           "hc_layer_num_reps", "hc_layer_rep_slot", "hc_layer_num_workgroups", "hc_layer_num_partials",
+           "hc_set_split", "hc_plan_describe", "hc_decode_attn", "hc_rep_topk_drift", "hc_gather_retrieve"]
+
+
+class hc_config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("B", "Hq", "Hkv", "D", "max_ctx", "max_k", "window", "metric",
+                                         "tau_num", "tau_den", "agg")]
+
+
+class hc_head_desc(C.Structure):
+    _fields_ = [("k_off", C.c_int64), ("v_off", C.c_int64), ("tier_off", C.c_int64),
+                ("ctx", C.c_int32), ("len", C.c_int32), ("role", C.c_int32), ("rep", C.c_int32),
+                ("sink", C.c_int32), ("recent", C.c_int32), ("k_mon", C.c_int32), ("reserved", C.c_int32)]
+
+
+class hc_plan_info(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_workgroups", "n_partials", "n_reps", "n_lists", "n_satellites",
+                                         "max_rows_per_workgroup", "min_rows_per_workgroup", "reserved")] + \
+               [("total_rows", C.c_int64), ("rows_covered", C.c_int64)]
+
+
+class HcError(RuntimeError):
+    def __init__(self, status: int, where: str, detail: str = ""):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({_strerror(status)}){': ' + detail if detail else ''}")
+
+
+_lib = None
+
+
+def lib():
+    """The loaded HIP library.  Raises if it has not been built (no CPU fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2601_13684_amd.build` "
+                               "(hipcc, gfx950); this package has no other execution path")
+        L = C.CDLL(LIB_PATH)
+        vp, i32 = C.c_void_p, C.c_int32
+        L.hc_create.argtypes = [C.POINTER(hc_config), C.POINTER(vp)]
+        L.hc_destroy.argtypes = [vp]
+        L.hc_strerror.argtypes = [C.c_int]
+        L.hc_strerror.restype = C.c_char_p
+        L.hc_last_error.argtypes = [vp]
+        L.hc_last_error.restype = C.c_char_p
+        L.hc_layer_create.argtypes = [vp, C.POINTER(hc_head_desc), C.POINTER(vp)]
+        L.hc_layer_destroy.argtypes = [vp]
+        for n in ("hc_layer_num_reps", "hc_layer_num_workgroups", "hc_layer_num_partials"):
+            getattr(L, n).argtypes = [vp]
+            getattr(L, n).restype = i32
+        L.hc_layer_rep_slot.argtypes = [vp, i32, i32]
+        L.hc_layer_rep_slot.restype = i32
+        L.hc_set_split.argtypes = [vp, i32, i32]
+        L.hc_plan_describe.argtypes = [C.POINTER(hc_config), C.POINTER(hc_head_desc), i32, i32,
+                                       C.POINTER(hc_plan_info), C.c_char_p, i32]
+        L.hc_decode_attn.argtypes = [vp] * 8
+        L.hc_rep_topk_drift.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
+        L.hc_gather_retrieve.argtypes = [vp] * 9
+        for n in EXPORTS:
+            if n not in ("hc_strerror", "hc_last_error", "hc_layer_num_reps", "hc_layer_rep_slot",
+                         "hc_layer_num_workgroups", "hc_layer_num_partials"):
+                getattr(L, n).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _strerror(st: int) -> str:
+    try:
+        return lib().hc_strerror(st).decode()
+    except Exception:
+        return "?"
+
+
+Ptr = Union[torch.Tensor, int, None]
+
+
+def _p(x: Ptr) -> Optional[int]:
+    if x is None:
+        return None
+    if isinstance(x, torch.Tensor):
+        assert x.is_contiguous(), "tensors handed to the C ABI must be contiguous"
+        return x.data_ptr()
+    return int(x)
+
+
+def _stream(s) -> Optional[int]:
+    if s is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(s, torch.cuda.Stream):
+        return s.cuda_stream
+    return int(s)
+
+
+def _event(e) -> Optional[int]:
+    if e is None:
+        return None
+    if isinstance(e, torch.cuda.Event):
+        return e.cuda_event
+    return int(e)
+
+
+def _check(st: int, where: str, ctx=None):
+    if st != HC_OK:
+        detail = lib().hc_last_error(ctx).decode() if ctx else ""
+        raise HcError(st, where, detail)
+
+
+def hc_create(cfg: hc_config) -> int:
+    h = C.c_void_p()
+    _check(lib().hc_create(C.byref(cfg), C.byref(h)), "hc_create")
+    return h.value
+
+
+def hc_destroy(ctx: int) -> None:
+    _check(lib().hc_destroy(ctx), "hc_destroy")
+
+
+def hc_set_split(ctx: int, workgroups_per_cu: int, compute_units: int = 0) -> None:
+    _check(lib().hc_set_split(ctx, workgroups_per_cu, compute_units), "hc_set_split", ctx)
+
+
+def hc_plan_describe(cfg: hc_config, heads: Sequence[hc_head_desc], compute_units: int = 256,
+                     workgroups_per_cu: int = 2) -> hc_plan_info:
+    arr = (hc_head_desc * len(heads))(*heads)
+    info = hc_plan_info()
+    err = C.create_string_buffer(512)
+    st = lib().hc_plan_describe(C.byref(cfg), arr, compute_units, workgroups_per_cu, C.byref(info), err, 512)
+    if st != HC_OK:
+        raise HcError(st, "hc_plan_describe", err.value.decode())
+    return info
+
+
+def hc_layer_create(ctx: int, heads: Sequence[hc_head_desc]) -> int:
+    arr = (hc_head_desc * len(heads))(*heads)
+    h = C.c_void_p()
+    _check(lib().hc_layer_create(ctx, arr, C.byref(h)), "hc_layer_create", ctx)
+    return h.value
+
+
+def hc_layer_destroy(layer: int) -> None:
+    _check(lib().hc_layer_destroy(layer), "hc_layer_destroy")
+
+
+def hc_layer_num_reps(layer: int) -> int:
+    return lib().hc_layer_num_reps(layer)
+
+
+def hc_layer_rep_slot(layer: int, b: int, h: int) -> int:
+    return lib().hc_layer_rep_slot(layer, b, h)
+
+
+def hc_layer_num_workgroups(layer: int) -> int:
+    return lib().hc_layer_num_workgroups(layer)
+
+
+def hc_layer_num_partials(layer: int) -> int:
+    return lib().hc_layer_num_partials(layer)
+
+
+def hc_decode_attn(ctx: int, layer: int, kv_arena: Ptr, q: Ptr, out: Ptr, lse: Ptr, rep_logits: Ptr = None,
+                   stream=None) -> None:
+    _check(lib().hc_decode_attn(ctx, layer, _p(kv_arena), _p(q), _p(out), _p(lse), _p(rep_logits), _stream(stream)),
+           "hc_decode_attn", ctx)
+
+
+def hc_rep_topk_drift(ctx: int, layer: int, rep_logits: Ptr, lse: Ptr, scores: Ptr, scores_given: bool,
+                      topk_idx: Ptr, base_idx: Ptr, ring: Ptr, inter: Ptr, flag: Ptr, stream=None) -> None:
+    _check(lib().hc_rep_topk_drift(ctx, layer, _p(rep_logits), _p(lse), _p(scores), int(bool(scores_given)),
+                                   _p(topk_idx), _p(base_idx), _p(ring), _p(inter), _p(flag), _stream(stream)),
+           "hc_rep_topk_drift", ctx)
+
+
+def hc_gather_retrieve(ctx: int, layer: int, host_tier: Ptr, topk_idx: Ptr, flag: Ptr, kv_arena: Ptr,
+                       stream=None, wait_event=None, done_event=None) -> None:
+    _check(lib().hc_gather_retrieve(ctx, layer, _p(host_tier), _p(topk_idx), _p(flag), _p(kv_arena),
+                                    _stream(stream), _event(wait_event), _event(done_event)),
+           "hc_gather_retrieve", ctx)

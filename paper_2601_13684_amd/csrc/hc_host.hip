@@ -1,0 +1,503 @@
+// hc_host.hip -- life cycle, validation and work planning of the HeteroCache decode library.
+//
+// Everything here runs on the host at set-up time.  The per-step entry points at the bottom only
+// validate their arguments and enqueue kernels (hc_attn.hip, hc_monitor.hip, hc_gather.hip).
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <limits.h>
+
+#include <algorithm>
+#include <new>
+#include <utility>
+
+#include "hc_internal.h"
+
+hc_status hc_fail(hc_ctx* ctx, hc_status st, const char* fmt, ...)
+{
+    if (ctx) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(ctx->err, sizeof ctx->err, fmt, ap);
+        va_end(ap);
+    }
+    return st;
+}
+
+hc_status hc_hip_fail(hc_ctx* ctx, hipError_t e, const char* what)
+{
+    return hc_fail(ctx, e == hipErrorOutOfMemory ? HC_ENOMEM : HC_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+extern "C" const char* hc_strerror(hc_status st)
+{
+    switch (st) {
+    case HC_OK: return "ok";
+    case HC_EINVAL: return "invalid argument";
+    case HC_ESHAPE: return "unsupported shape";
+    case HC_ENOMEM: return "out of memory";
+    case HC_EHIP: return "HIP call failed";
+    case HC_ESTATE: return "object in wrong state";
+    }
+    return "unknown status";
+}
+
+extern "C" const char* hc_last_error(const hc_ctx* ctx)
+{
+    return (ctx && ctx->magic == HC_CTX_MAGIC) ? ctx->err : "invalid context";
+}
+
+static bool ctx_ok(const hc_ctx* c) { return c && c->magic == HC_CTX_MAGIC; }
+static bool layer_ok(const hc_layer* l) { return l && l->magic == HC_LAYER_MAGIC && ctx_ok(l->ctx); }
+
+// Words of selection workspace per pivot that a monitor call clears before use:
+// digit histograms (one shared first pass, then one per set size for passes two and three),
+// the selection state and the intersection accumulator / ticket.
+static size_t rep_hist_words() { return (size_t)(1 + 2 * HC_MAX_K_PER_REP) * HC_RADIX_BINS; }
+
+static hc_status check_config(const hc_config* cfg)
+{
+    if (!cfg) return HC_EINVAL;
+    if (cfg->D != HC_D) return HC_ESHAPE;
+    if (cfg->B < 1 || cfg->Hkv < 1 || cfg->Hq < 1 || cfg->Hq % cfg->Hkv != 0) return HC_EINVAL;
+    const int G = cfg->Hq / cfg->Hkv;
+    if (G != 1 && G != 2 && G != 4 && G != 8) return HC_ESHAPE;
+    if (cfg->max_ctx < 64 || cfg->max_ctx % 64 != 0 || cfg->max_ctx > (1 << 24)) return HC_ESHAPE;
+    if (cfg->max_k < 1 || cfg->max_k > cfg->max_ctx) return HC_EINVAL;
+    if (cfg->window < 1 || cfg->window > HC_MAX_WINDOW) return HC_EINVAL;
+    if (cfg->metric != HC_METRIC_OVERLAP && cfg->metric != HC_METRIC_JACCARD) return HC_EINVAL;
+    if (cfg->agg != HC_AGG_PROB && cfg->agg != HC_AGG_LOGIT) return HC_EINVAL;
+    if (cfg->tau_den < 1 || cfg->tau_num < 0) return HC_EINVAL;
+    if ((int64_t)cfg->B * cfg->Hkv > (1 << 20)) return HC_ESHAPE;
+    return HC_OK;
+}
+
+extern "C" hc_status hc_create(const hc_config* cfg, hc_ctx** out)
+{
+    if (!cfg || !out) return HC_EINVAL;
+    *out = nullptr;
+    const hc_status cs = check_config(cfg);
+    if (cs != HC_OK) return cs;
+    const int G = cfg->Hq / cfg->Hkv;
+
+    hc_ctx* c = new (std::nothrow) hc_ctx();
+    if (!c) return HC_ENOMEM;
+    c->magic = HC_CTX_MAGIC;
+    c->cfg = *cfg;
+    c->G = G;
+    c->wg_per_cu = 2;
+    c->err[0] = 0;
+    hipDeviceProp_t prop;
+    hipError_t e = hipGetDevice(&c->device);
+    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, c->device);
+    if (e != hipSuccess) {
+        delete c;
+        return HC_EHIP;
+    }
+    c->n_cu = prop.multiProcessorCount;
+
+    c->max_reps = std::max(1, cfg->B * cfg->Hkv / 2);
+    c->max_chunks = (cfg->max_ctx + HC_SEL_CHUNK - 1) / HC_SEL_CHUNK;
+    const size_t hist_w = (size_t)c->max_reps * rep_hist_words();
+    const size_t sel_w = (size_t)c->max_reps * HC_MAX_K_PER_REP * 4;
+    const size_t misc_w = (size_t)c->max_reps * 4;
+    const size_t cnt_w = (size_t)c->max_reps * HC_MAX_K_PER_REP * c->max_chunks * 2;
+    const size_t bm_w = (size_t)c->max_reps * (cfg->max_ctx / 32);
+    uint32_t* base = nullptr;
+    e = hipMalloc((void**)&base, (hist_w + sel_w + misc_w + cnt_w + bm_w) * sizeof(uint32_t));
+    if (e != hipSuccess) {
+        delete c;
+        return e == hipErrorOutOfMemory ? HC_ENOMEM : HC_EHIP;
+    }
+    c->hist = base;
+    c->sel = c->hist + hist_w;
+    c->misc = c->sel + sel_w;
+    c->cnt = c->misc + misc_w;
+    c->bitmap = c->cnt + cnt_w;
+    *out = c;
+    return HC_OK;
+}
+
+extern "C" hc_status hc_destroy(hc_ctx* ctx)
+{
+    if (!ctx_ok(ctx)) return HC_ESTATE;
+    (void)hipFree(ctx->hist);
+    (void)hipFree(ctx->part_acc);
+    (void)hipFree(ctx->part_ml);
+    ctx->magic = 0;
+    delete ctx;
+    return HC_OK;
+}
+
+extern "C" hc_status hc_set_split(hc_ctx* ctx, int32_t workgroups_per_cu, int32_t compute_units)
+{
+    if (!ctx_ok(ctx)) return HC_ESTATE;
+    if (workgroups_per_cu < 1 || workgroups_per_cu > 16 || compute_units < 0 || compute_units > 4096)
+        return hc_fail(ctx, HC_EINVAL, "hc_set_split: workgroups_per_cu 1..16, compute_units 0..4096");
+    ctx->wg_per_cu = workgroups_per_cu;
+    if (compute_units > 0) ctx->n_cu = compute_units;
+    return HC_OK;
+}
+
+static hc_status ensure_partials(hc_ctx* ctx, size_t slots)
+{
+    if (slots <= ctx->part_slots) return HC_OK;
+    HC_HIP(ctx, hipDeviceSynchronize());      // set-up time: nothing may still read the old buffers
+    (void)hipFree(ctx->part_acc);
+    (void)hipFree(ctx->part_ml);
+    ctx->part_acc = ctx->part_ml = nullptr;
+    ctx->part_slots = 0;
+    HC_HIP(ctx, hipMalloc((void**)&ctx->part_acc, slots * ctx->G * HC_D * sizeof(float)));
+    HC_HIP(ctx, hipMalloc((void**)&ctx->part_ml, slots * ctx->G * 2 * sizeof(float)));
+    ctx->part_slots = slots;
+    return HC_OK;
+}
+
+template <class T>
+static hc_status upload(hc_ctx* ctx, const std::vector<T>& v, T** dev)
+{
+    *dev = nullptr;
+    const size_t n = std::max<size_t>(1, v.size());
+    HC_HIP(ctx, hipMalloc((void**)dev, n * sizeof(T)));
+    if (!v.empty()) HC_HIP(ctx, hipMemcpy(*dev, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice));
+    return HC_OK;
+}
+
+static void layer_free(hc_layer* L)
+{
+    (void)hipFree(L->heads);
+    (void)hipFree(L->segs);
+    (void)hipFree(L->blk_seg);
+    (void)hipFree(L->reps);
+    (void)hipFree(L->outs);
+    (void)hipFree(L->sats);
+    L->magic = 0;
+    delete L;
+}
+
+// Everything hc_layer_create derives from the head table, on the host only.
+struct Plan {
+    std::vector<HeadDev> heads;
+    std::vector<SegDev> segs;
+    std::vector<int32_t> blk_seg;
+    std::vector<RepDev> reps;
+    std::vector<OutDev> outs;
+    std::vector<SatDev> sats;
+    std::vector<int32_t> rep_slot_of;
+    int n_blocks = 0, max_r = 0, max_nchunk = 1;
+    int64_t total_rows = 0;
+};
+
+struct ErrBuf {
+    char* buf;
+    size_t len;
+    hc_status fail(hc_status st, const char* fmt, ...) const
+    {
+        if (buf && len) {
+            va_list ap;
+            va_start(ap, fmt);
+            vsnprintf(buf, len, fmt, ap);
+            va_end(ap);
+        }
+        return st;
+    }
+};
+
+static hc_status make_plan(const hc_config& cfg, const hc_head_desc* hd, int n_cu, int wg_per_cu, Plan& P,
+                           const ErrBuf& E)
+{
+    const int nh = cfg.B * cfg.Hkv;
+    const int max_reps = std::max(1, nh / 2);
+
+    // ---- validate the head table ----
+    for (int i = 0; i < nh; ++i) {
+        const hc_head_desc& h = hd[i];
+        if (h.role != HC_ROLE_FULL && h.role != HC_ROLE_SATELLITE && h.role != HC_ROLE_ANCHOR)
+            return E.fail(HC_EINVAL, "head %d: bad role %d", i, h.role);
+        if (h.reserved != 0) return E.fail(HC_EINVAL, "head %d: reserved field must be 0", i);
+        if (h.ctx < 1 || h.ctx > cfg.max_ctx) return E.fail(HC_ESHAPE, "head %d: ctx %d outside 1..%d", i, h.ctx, cfg.max_ctx);
+        if (h.ctx != hd[i - i % cfg.Hkv].ctx) return E.fail(HC_EINVAL, "head %d: ctx differs within its sequence", i);
+        if (h.len < 1 || h.len > h.ctx) return E.fail(HC_ESHAPE, "head %d: len %d outside 1..ctx", i, h.len);
+        if (h.k_off < 0 || h.v_off < 0 || (h.k_off & 7) || (h.v_off & 7))
+            return E.fail(HC_EINVAL, "head %d: k_off/v_off must be non-negative multiples of 8 elements", i);
+        if (h.role == HC_ROLE_FULL) {
+            if (h.len != h.ctx) return E.fail(HC_EINVAL, "head %d: a full head must have len == ctx", i);
+            if (h.k_mon < 0) return E.fail(HC_EINVAL, "head %d: negative k_mon", i);
+        } else {
+            if (h.sink < 0 || h.recent < 0 || (int64_t)h.sink + h.recent > h.len)
+                return E.fail(HC_EINVAL, "head %d: sink + recent exceeds its budget", i);
+        }
+        if (h.role == HC_ROLE_SATELLITE) {
+            if (h.rep < 0 || h.rep >= cfg.Hkv || hd[i - i % cfg.Hkv + h.rep].role != HC_ROLE_FULL)
+                return E.fail(HC_EINVAL, "head %d: rep %d is not a full head of the same sequence", i, h.rep);
+            if (h.tier_off < 0 || (h.tier_off & 7)) return E.fail(HC_EINVAL, "head %d: bad tier_off", i);
+        }
+    }
+    // K and V blocks of all heads must not overlap each other
+    {
+        std::vector<std::pair<int64_t, int64_t>> iv;
+        for (int i = 0; i < nh; ++i) {
+            iv.push_back({hd[i].k_off, hd[i].k_off + (int64_t)hd[i].len * HC_D});
+            iv.push_back({hd[i].v_off, hd[i].v_off + (int64_t)hd[i].len * HC_D});
+        }
+        std::sort(iv.begin(), iv.end());
+        for (size_t i = 1; i < iv.size(); ++i)
+            if (iv[i].first < iv[i - 1].second) return E.fail(HC_EINVAL, "K/V blocks of two heads overlap in the arena");
+    }
+
+    // ---- pivots, their set sizes, the lists to emit, the satellites to refill ----
+    P.rep_slot_of.assign(nh, -1);
+    for (int b = 0; b < cfg.B; ++b) {
+        for (int p = 0; p < cfg.Hkv; ++p) {
+            const int pi = b * cfg.Hkv + p;
+            std::vector<int> mine;
+            for (int s = 0; s < cfg.Hkv; ++s) {
+                const hc_head_desc& h = hd[b * cfg.Hkv + s];
+                if (h.role == HC_ROLE_SATELLITE && h.rep == p) mine.push_back(b * cfg.Hkv + s);
+            }
+            if (mine.empty()) continue;
+            RepDev r;
+            memset(&r, 0, sizeof r);
+            r.bh = pi;
+            const hc_head_desc& s0 = hd[mine[0]];
+            r.lo = s0.sink;
+            r.hi = s0.ctx - s0.recent;
+            int maxr = 0;
+            for (int si : mine) {
+                const hc_head_desc& h = hd[si];
+                if (h.sink != s0.sink || h.recent != s0.recent)
+                    return E.fail(HC_EINVAL, "pivot %d: its satellites must share sink and recent", pi);
+                maxr = std::max(maxr, h.len - h.sink - h.recent);
+            }
+            const int kmon = hd[pi].k_mon > 0 ? hd[pi].k_mon : maxr;
+            if (kmon < 1 || kmon > r.hi - r.lo || kmon > cfg.max_k)
+                return E.fail(HC_EINVAL, "pivot %d: k_mon %d outside 1..min(candidates %d, max_k %d)", pi, kmon,
+                              r.hi - r.lo, cfg.max_k);
+            r.k[0] = kmon;
+            r.nk = 1;
+            const int slot = (int)P.reps.size();
+            if (slot >= max_reps) return E.fail(HC_ESHAPE, "more pivots than the context was sized for");
+            P.outs.push_back(OutDev{slot, 0, pi, 1});
+            for (int si : mine) {
+                const hc_head_desc& h = hd[si];
+                const int rr = h.len - h.sink - h.recent;
+                if (rr == 0) continue;
+                if (rr > cfg.max_k) return E.fail(HC_EINVAL, "head %d: r %d exceeds max_k %d", si, rr, cfg.max_k);
+                if (rr > r.hi - r.lo) return E.fail(HC_EINVAL, "head %d: more retrieved slots than candidate positions", si);
+                int ks = -1;
+                for (int t = 0; t < r.nk; ++t)
+                    if (r.k[t] == rr) ks = t;
+                if (ks < 0) {
+                    if (r.nk == HC_MAX_K_PER_REP)
+                        return E.fail(HC_ESHAPE, "pivot %d: more than %d distinct set sizes", pi, HC_MAX_K_PER_REP);
+                    ks = r.nk++;
+                    r.k[ks] = rr;
+                }
+                P.outs.push_back(OutDev{slot, ks, si, 0});
+                P.sats.push_back(SatDev{si, pi, rr, h.sink + h.recent});
+                P.max_r = std::max(P.max_r, rr);
+            }
+            r.nchunk = (r.hi - r.lo + HC_SEL_CHUNK - 1) / HC_SEL_CHUNK;
+            P.max_nchunk = std::max(P.max_nchunk, r.nchunk);
+            P.rep_slot_of[pi] = slot;
+            P.reps.push_back(r);
+        }
+    }
+
+    // ---- split-K plan: the rows of all heads, in granules of HC_UNIT_ROWS, are cut into equal
+    // contiguous shares, one per workgroup; a share that crosses a head boundary becomes several
+    // segments, each producing its own partial result.
+    P.heads.resize(nh);
+    int64_t total_units = 0;
+    for (int i = 0; i < nh; ++i) {
+        total_units += (hd[i].len + HC_UNIT_ROWS - 1) / HC_UNIT_ROWS;
+        P.total_rows += hd[i].len;
+        HeadDev& H = P.heads[i];
+        H.k_off = hd[i].k_off;
+        H.v_off = hd[i].v_off;
+        H.tier_off = hd[i].tier_off;
+        H.len = hd[i].len;
+        H.ctx = hd[i].ctx;
+        H.rep_slot = P.rep_slot_of[i];
+        H.part_begin = 0;
+        H.part_count = 0;
+        H.pad = 0;
+    }
+    const int64_t max_blocks = (int64_t)wg_per_cu * n_cu;
+    const int64_t min_units = 4;
+    const int nb = (int)std::max<int64_t>(1, std::min<int64_t>(max_blocks, total_units / min_units));
+    P.n_blocks = nb;
+    P.blk_seg.assign(nb + 1, 0);
+    int head = 0;
+    int64_t head_first_unit = 0;      // global index of the current head's first granule
+    int slot = 0;
+    for (int blk = 0; blk < nb; ++blk) {
+        int64_t u0 = total_units * blk / nb;
+        const int64_t u1 = total_units * (blk + 1) / nb;
+        P.blk_seg[blk] = (int32_t)P.segs.size();
+        while (u0 < u1) {
+            int64_t head_units = (hd[head].len + HC_UNIT_ROWS - 1) / HC_UNIT_ROWS;
+            while (u0 >= head_first_unit + head_units) {
+                head_first_unit += head_units;
+                ++head;
+                head_units = (hd[head].len + HC_UNIT_ROWS - 1) / HC_UNIT_ROWS;
+            }
+            const int64_t take_end = std::min(u1, head_first_unit + head_units);
+            SegDev sg;
+            sg.bh = head;
+            sg.row_begin = (int32_t)((u0 - head_first_unit) * HC_UNIT_ROWS);
+            sg.row_end = (int32_t)std::min<int64_t>((take_end - head_first_unit) * HC_UNIT_ROWS, hd[head].len);
+            sg.slot = slot++;
+            if (P.heads[head].part_count == 0) P.heads[head].part_begin = sg.slot;
+            P.heads[head].part_count++;
+            P.segs.push_back(sg);
+            u0 = take_end;
+        }
+    }
+    P.blk_seg[nb] = (int32_t)P.segs.size();
+    return HC_OK;
+}
+
+extern "C" hc_status hc_plan_describe(const hc_config* cfg, const hc_head_desc* heads_host, int32_t compute_units,
+                                      int32_t workgroups_per_cu, hc_plan_info* info, char* err, int32_t err_len)
+{
+    if (err && err_len > 0) err[0] = 0;
+    if (!cfg || !heads_host || !info) return HC_EINVAL;
+    const hc_status cs = check_config(cfg);
+    if (cs != HC_OK) return cs;
+    if (compute_units < 1 || compute_units > 4096 || workgroups_per_cu < 1 || workgroups_per_cu > 16) return HC_EINVAL;
+    Plan P;
+    const hc_status st = make_plan(*cfg, heads_host, compute_units, workgroups_per_cu, P,
+                                   ErrBuf{err, err_len > 0 ? (size_t)err_len : 0});
+    if (st != HC_OK) return st;
+    memset(info, 0, sizeof *info);
+    info->n_workgroups = P.n_blocks;
+    info->n_partials = (int32_t)P.segs.size();
+    info->n_reps = (int32_t)P.reps.size();
+    info->n_lists = (int32_t)P.outs.size();
+    info->n_satellites = (int32_t)P.sats.size();
+    info->total_rows = P.total_rows;
+    info->min_rows_per_workgroup = INT32_MAX;
+    std::vector<int64_t> covered(cfg->B * cfg->Hkv, 0);
+    for (int b = 0; b < P.n_blocks; ++b) {
+        int rows = 0;
+        for (int s = P.blk_seg[b]; s < P.blk_seg[b + 1]; ++s) {
+            rows += P.segs[s].row_end - P.segs[s].row_begin;
+            covered[P.segs[s].bh] += P.segs[s].row_end - P.segs[s].row_begin;
+        }
+        info->max_rows_per_workgroup = std::max(info->max_rows_per_workgroup, rows);
+        info->min_rows_per_workgroup = std::min(info->min_rows_per_workgroup, rows);
+    }
+    info->rows_covered = 0;
+    for (int i = 0; i < cfg->B * cfg->Hkv; ++i)
+        if (covered[i] == heads_host[i].len) info->rows_covered += covered[i];
+    return HC_OK;
+}
+
+extern "C" hc_status hc_layer_create(hc_ctx* ctx, const hc_head_desc* hd, hc_layer** out)
+{
+    if (!ctx_ok(ctx)) return HC_ESTATE;
+    if (!hd || !out) return hc_fail(ctx, HC_EINVAL, "hc_layer_create: null argument");
+    *out = nullptr;
+    Plan P;
+    hc_status st = make_plan(ctx->cfg, hd, ctx->n_cu, ctx->wg_per_cu, P, ErrBuf{ctx->err, sizeof ctx->err});
+    if (st != HC_OK) return st;
+
+    hc_layer* L = new (std::nothrow) hc_layer();
+    if (!L) return hc_fail(ctx, HC_ENOMEM, "host allocation failed");
+    L->magic = HC_LAYER_MAGIC;
+    L->ctx = ctx;
+    L->n_heads = ctx->cfg.B * ctx->cfg.Hkv;
+    L->rep_slot_of = P.rep_slot_of;
+    L->max_r = P.max_r;
+    L->max_nchunk = P.max_nchunk;
+    L->n_reps = (int)P.reps.size();
+    L->n_outs = (int)P.outs.size();
+    L->n_sats = (int)P.sats.size();
+    L->n_blocks = P.n_blocks;
+    L->n_segs = L->n_partials = (int)P.segs.size();
+
+    st = ensure_partials(ctx, P.segs.size());
+    if (st == HC_OK) st = upload(ctx, P.heads, &L->heads);
+    if (st == HC_OK) st = upload(ctx, P.segs, &L->segs);
+    if (st == HC_OK) st = upload(ctx, P.blk_seg, &L->blk_seg);
+    if (st == HC_OK) st = upload(ctx, P.reps, &L->reps);
+    if (st == HC_OK) st = upload(ctx, P.outs, &L->outs);
+    if (st == HC_OK) st = upload(ctx, P.sats, &L->sats);
+    if (st != HC_OK) {
+        layer_free(L);
+        return st;
+    }
+    *out = L;
+    return HC_OK;
+}
+
+extern "C" hc_status hc_layer_destroy(hc_layer* layer)
+{
+    if (!layer_ok(layer)) return HC_ESTATE;
+    layer_free(layer);
+    return HC_OK;
+}
+
+extern "C" int32_t hc_layer_num_reps(const hc_layer* layer) { return layer_ok(layer) ? layer->n_reps : -1; }
+extern "C" int32_t hc_layer_num_workgroups(const hc_layer* layer) { return layer_ok(layer) ? layer->n_blocks : -1; }
+extern "C" int32_t hc_layer_num_partials(const hc_layer* layer) { return layer_ok(layer) ? layer->n_partials : -1; }
+
+extern "C" int32_t hc_layer_rep_slot(const hc_layer* layer, int32_t b, int32_t h)
+{
+    if (!layer_ok(layer)) return -1;
+    const hc_config& c = layer->ctx->cfg;
+    if (b < 0 || b >= c.B || h < 0 || h >= c.Hkv) return -1;
+    return layer->rep_slot_of[b * c.Hkv + h];
+}
+
+// ---- hot path: validate, then enqueue ------------------------------------------------------
+
+extern "C" hc_status hc_decode_attn(hc_ctx* ctx, const hc_layer* layer, const void* kv_arena, const void* q,
+                                    float* out, float* lse, float* rep_logits, void* stream)
+{
+    if (!ctx_ok(ctx)) return HC_ESTATE;
+    if (!layer_ok(layer) || layer->ctx != ctx) return hc_fail(ctx, HC_ESTATE, "hc_decode_attn: layer does not belong to this context");
+    if (!kv_arena || !q || !out || !lse) return hc_fail(ctx, HC_EINVAL, "hc_decode_attn: null pointer");
+    if (((uintptr_t)kv_arena | (uintptr_t)q) & 15) return hc_fail(ctx, HC_EINVAL, "hc_decode_attn: kv_arena and q must be 16-byte aligned");
+    if (((uintptr_t)out | (uintptr_t)lse | (uintptr_t)rep_logits) & 3) return hc_fail(ctx, HC_EINVAL, "hc_decode_attn: misaligned float pointer");
+    return hc_launch_attn(ctx, layer, kv_arena, q, out, lse, rep_logits, (hipStream_t)stream);
+}
+
+extern "C" hc_status hc_rep_topk_drift(hc_ctx* ctx, const hc_layer* layer, const float* rep_logits, const float* lse,
+                                       float* scores, int32_t scores_given, int32_t* topk_idx, int32_t* base_idx,
+                                       int32_t* ring, int32_t* inter, int32_t* flag, void* stream)
+{
+    if (!ctx_ok(ctx)) return HC_ESTATE;
+    if (!layer_ok(layer) || layer->ctx != ctx) return hc_fail(ctx, HC_ESTATE, "hc_rep_topk_drift: layer does not belong to this context");
+    if (!scores || !topk_idx || !base_idx || !ring || !inter || !flag)
+        return hc_fail(ctx, HC_EINVAL, "hc_rep_topk_drift: null pointer");
+    if (!scores_given && (!rep_logits || (ctx->cfg.agg == HC_AGG_PROB && !lse)))
+        return hc_fail(ctx, HC_EINVAL, "hc_rep_topk_drift: rep_logits and lse are needed unless scores are given");
+    if (((uintptr_t)scores | (uintptr_t)rep_logits) & 15)
+        return hc_fail(ctx, HC_EINVAL, "hc_rep_topk_drift: scores and rep_logits must be 16-byte aligned");
+    if (layer->n_reps == 0) return HC_OK;
+    return hc_launch_monitor(ctx, layer, rep_logits, lse, scores, scores_given != 0, topk_idx, base_idx, ring,
+                             inter, flag, (hipStream_t)stream);
+}
+
+extern "C" hc_status hc_gather_retrieve(hc_ctx* ctx, const hc_layer* layer, const void* host_tier,
+                                        const int32_t* topk_idx, const int32_t* flag, void* kv_arena,
+                                        void* stream, void* wait_event, void* done_event)
+{
+    if (!ctx_ok(ctx)) return HC_ESTATE;
+    if (!layer_ok(layer) || layer->ctx != ctx) return hc_fail(ctx, HC_ESTATE, "hc_gather_retrieve: layer does not belong to this context");
+    if (!topk_idx || !flag || !kv_arena || (!host_tier && layer->n_sats > 0))
+        return hc_fail(ctx, HC_EINVAL, "hc_gather_retrieve: null pointer");
+    if (((uintptr_t)kv_arena | (uintptr_t)host_tier) & 15)
+        return hc_fail(ctx, HC_EINVAL, "hc_gather_retrieve: kv_arena and host_tier must be 16-byte aligned");
+    hipStream_t st = (hipStream_t)stream;
+    if (wait_event) HC_HIP(ctx, hipStreamWaitEvent(st, (hipEvent_t)wait_event, 0));
+    if (layer->n_sats > 0) {
+        hc_status s = hc_launch_gather(ctx, layer, host_tier, topk_idx, flag, kv_arena, st);
+        if (s != HC_OK) return s;
+    }
+    if (done_event) HC_HIP(ctx, hipEventRecord((hipEvent_t)done_event, st));
+    return HC_OK;
+}

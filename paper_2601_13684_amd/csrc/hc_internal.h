@@ -1,0 +1,109 @@
+// hc_internal.h -- shared declarations of the HIP library (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "../../include/hc.h"
+
+constexpr int HC_D = 128;            // head dimension the kernels are written for
+constexpr int HC_UNIT_ROWS = 32;     // split-K granule: 4 waves x 8 rows
+constexpr int HC_SEL_CHUNK = 4096;   // candidates per workgroup in the selection passes
+constexpr int HC_RADIX_BINS = 2048;  // 11-bit digits (11 + 11 + 10 bits of the 32-bit key)
+
+// One KV head as the kernels see it.
+struct HeadDev {
+    int64_t k_off, v_off, tier_off;
+    int32_t len, ctx;
+    int32_t rep_slot;      // >= 0: this full head is a pivot and owns that slot of rep_logits
+    int32_t part_begin;    // first split-K partial of this head
+    int32_t part_count;
+    int32_t pad;
+};
+
+// A contiguous run of rows of one head handled by one workgroup of the split pass.
+struct SegDev {
+    int32_t bh, row_begin, row_end, slot;
+};
+
+// One pivot of the layer.
+struct RepDev {
+    int32_t bh;                       // table row b*Hkv+h
+    int32_t lo, hi;                   // candidate positions [lo, hi)
+    int32_t nk;                       // distinct set sizes
+    int32_t k[HC_MAX_K_PER_REP];      // k[0] = k_mon
+    int32_t nchunk;                   // ceil((hi-lo)/HC_SEL_CHUNK)
+    int32_t pad;
+};
+
+// One index list to emit: row `row` of topk_idx gets T_k with k = rep.k[kslot].
+struct OutDev {
+    int32_t rep, kslot, row, is_mon;
+};
+
+// One satellite to refill.
+struct SatDev {
+    int32_t bh, rep_bh, r, first_slot;   // first_slot = sink + recent
+};
+
+struct hc_ctx {
+    uint32_t magic;
+    hc_config cfg;
+    int G;
+    int n_cu;
+    int wg_per_cu;
+    int device;
+    char err[512];
+    // split-K partial workspace
+    float* part_acc = nullptr;   // [slots][G][D]
+    float* part_ml = nullptr;    // [slots][G][2]  (running max in log2 units, sum)
+    size_t part_slots = 0;
+    // selection workspace, sized for max_reps pivots
+    int max_reps = 0;
+    uint32_t* hist = nullptr;      // [max_reps][HC_MAX_K_PER_REP][3][HC_RADIX_BINS]
+    uint32_t* sel = nullptr;       // [max_reps][HC_MAX_K_PER_REP][4]: prefix, remaining k, (tau, need)
+    uint32_t* cnt = nullptr;       // [max_reps][HC_MAX_K_PER_REP][max_chunks][2]: greater, equal
+    uint32_t* bitmap = nullptr;    // [max_reps][max_ctx/32]
+    uint32_t* misc = nullptr;      // [max_reps][4]: intersection accumulator, ticket
+    int max_chunks = 0;
+    size_t zero_words = 0;         // words of the contiguous region cleared at the start of a monitor call
+};
+
+struct hc_layer {
+    uint32_t magic;
+    hc_ctx* ctx;
+    int n_heads;
+    int n_blocks, n_partials, n_segs;
+    int n_reps, n_outs, n_sats;
+    int max_r;                     // largest r among satellites
+    int max_nchunk;
+    std::vector<int32_t> rep_slot_of;   // [B*Hkv]
+    HeadDev* heads = nullptr;
+    SegDev* segs = nullptr;
+    int32_t* blk_seg = nullptr;    // [n_blocks+1]
+    RepDev* reps = nullptr;
+    OutDev* outs = nullptr;
+    SatDev* sats = nullptr;
+};
+
+constexpr uint32_t HC_CTX_MAGIC = 0x48435458u;    // "HCTX"
+constexpr uint32_t HC_LAYER_MAGIC = 0x48434c59u;  // "HCLY"
+
+hc_status hc_fail(hc_ctx* ctx, hc_status st, const char* fmt, ...);
+hc_status hc_hip_fail(hc_ctx* ctx, hipError_t e, const char* what);
+
+#define HC_HIP(ctx, call)                                             \
+    do {                                                              \
+        hipError_t e_ = (call);                                       \
+        if (e_ != hipSuccess) return hc_hip_fail((ctx), e_, #call);   \
+    } while (0)
+
+// kernel launchers (one translation unit each)
+hc_status hc_launch_attn(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* q, float* out,
+                         float* lse, float* rep_logits, hipStream_t st);
+hc_status hc_launch_monitor(hc_ctx* ctx, const hc_layer* L, const float* rep_logits, const float* lse,
+                            float* scores, int scores_given, int32_t* topk_idx, int32_t* base_idx,
+                            int32_t* ring, int32_t* inter, int32_t* flag, hipStream_t st);
+hc_status hc_launch_gather(hc_ctx* ctx, const hc_layer* L, const void* tier, const int32_t* topk_idx,
+                           const int32_t* flag, void* arena, hipStream_t st);

@@ -1,0 +1,176 @@
+"""Device-side plumbing around the C ABI: lay a layer out in HBM and pinned host memory, and issue
+the three hot-path calls of one decode step in order.  No arithmetic of the method lives here; every
+value is produced by the HIP kernels behind ``binding``.
+
+HBM layout of one layer (the "arena", bf16): for every (sequence, KV head) a K block [len][128]
+followed by a V block [len][128], each starting on a 256-byte boundary.  A full head's blocks hold
+all ctx positions; a compressed head's hold its slots: [0,sink) the first positions, then the
+``recent`` last positions, then the r retrieved positions in ascending order.  The host tier (pinned)
+holds, for every satellite, [ctx][2][128]: the K row then the V row of each position, 512 contiguous
+bytes per position, so that one retrieved position is one contiguous host read.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional, Tuple
+
+import torch
+
+from . import binding as hc
+from .inputs import ROLE_FULL, ROLE_SATELLITE, LayerData, LayerSpec
+
+D = 128
+
+
+def make_config(spec: LayerSpec, max_ctx: Optional[int] = None, max_k: Optional[int] = None) -> hc.hc_config:
+    mc = max_ctx or max(spec.ctx)
+    mc = (mc + 63) // 64 * 64
+    ks = [1]
+    for b in range(spec.B):
+        for p in spec.reps(b):
+            ks.append(spec.k_mon(b, p))
+            ks += [spec.r(b, s) for s in spec.satellites(b, p)]
+    return hc.hc_config(B=spec.B, Hq=spec.Hq, Hkv=spec.Hkv, D=spec.D, max_ctx=mc, max_k=max_k or max(ks),
+                        window=spec.window, metric=spec.metric, tau_num=spec.tau_num, tau_den=spec.tau_den,
+                        agg=spec.agg)
+
+
+def make_descs(spec: LayerSpec) -> Tuple[List[hc.hc_head_desc], int, int]:
+    """Head table of a layer plus the arena and host-tier sizes in bf16 elements."""
+    descs: List[hc.hc_head_desc] = []
+    off = 0
+    tier_off = 0
+    for b in range(spec.B):
+        for h in range(spec.Hkv):
+            hs = spec.heads[b][h]
+            ln = spec.resident(b, h)
+            d = hc.hc_head_desc(k_off=off, v_off=off + ln * D, tier_off=0, ctx=spec.ctx[b], len=ln, role=hs.role,
+                                rep=hs.rep if hs.role == ROLE_SATELLITE else -1, sink=hs.sink, recent=hs.recent,
+                                k_mon=hs.k_mon if hs.role == ROLE_FULL else 0, reserved=0)
+            off += 2 * ln * D
+            if hs.role == ROLE_SATELLITE:
+                d.tier_off = tier_off
+                tier_off += spec.ctx[b] * 2 * D
+            descs.append(d)
+    return descs, off, tier_off
+
+
+class Context:
+    """Owns an hc_ctx and the scratch that consecutive layers can share."""
+
+    def __init__(self, cfg: hc.hc_config, device: str = "cuda:0", workgroups_per_cu: Optional[int] = None):
+        self.cfg = cfg
+        self.device = torch.device(device)
+        with torch.cuda.device(self.device):
+            self.handle = hc.hc_create(cfg)
+        if workgroups_per_cu:
+            hc.hc_set_split(self.handle, workgroups_per_cu)
+        self.G = cfg.Hq // cfg.Hkv
+        self._scratch: Dict[int, Tuple[torch.Tensor, torch.Tensor]] = {}
+
+    def scratch(self, n_reps: int) -> Tuple[torch.Tensor, torch.Tensor]:
+        """(rep_logits [n_reps,G,max_ctx] f32, scores [n_reps,max_ctx] f32), shared by layers."""
+        n = max(1, n_reps)
+        if n not in self._scratch:
+            self._scratch[n] = (torch.zeros((n, self.G, self.cfg.max_ctx), dtype=torch.float32, device=self.device),
+                                torch.zeros((n, self.cfg.max_ctx), dtype=torch.float32, device=self.device))
+        return self._scratch[n]
+
+    def close(self):
+        if self.handle:
+            hc.hc_destroy(self.handle)
+            self.handle = None
+
+
+class LayerRuntime:
+    def __init__(self, ctx: Context, spec: LayerSpec, data: LayerData,
+                 retrieved: Dict[Tuple[int, int], torch.Tensor], base: Dict[Tuple[int, int], torch.Tensor],
+                 host_tier: bool = True):
+        self.ctx, self.spec = ctx, spec
+        cfg, dev = ctx.cfg, ctx.device
+        B, Hkv = spec.B, spec.Hkv
+        descs, off, tier_off = make_descs(spec)
+        self.descs = descs
+        # ---- arena ----
+        self.arena = torch.zeros((off,), dtype=torch.bfloat16, device=dev)
+        for b in range(B):
+            for h in range(Hkv):
+                d = descs[b * Hkv + h]
+                hs = spec.heads[b][h]
+                K, V = data.K[(b, h)], data.V[(b, h)]
+                if hs.role == ROLE_FULL:
+                    Kr, Vr = K, V
+                else:
+                    N = spec.ctx[b]
+                    idx = torch.cat([torch.arange(0, hs.sink), torch.arange(N - hs.recent, N),
+                                     retrieved[(b, h)].long().cpu()]).to(K.device)
+                    Kr, Vr = K[idx], V[idx]
+                self.arena[d.k_off:d.k_off + d.len * D].copy_(Kr.reshape(-1))
+                self.arena[d.v_off:d.v_off + d.len * D].copy_(Vr.reshape(-1))
+        # ---- host tier (pinned): [ctx][2][D] per satellite ----
+        self.tier = None
+        if host_tier and tier_off > 0:
+            self.tier = torch.empty((tier_off,), dtype=torch.bfloat16, pin_memory=True)
+            for b in range(B):
+                for h in range(Hkv):
+                    if spec.heads[b][h].role == ROLE_SATELLITE:
+                        d = descs[b * Hkv + h]
+                        blk = torch.stack([data.K[(b, h)], data.V[(b, h)]], dim=1)      # [N,2,D]
+                        self.tier[d.tier_off:d.tier_off + blk.numel()].copy_(blk.reshape(-1))
+        # ---- monitor state tables ----
+        nh = B * Hkv
+        self.topk_idx = torch.full((nh, cfg.max_k), -1, dtype=torch.int32, device=dev)
+        self.base_idx = torch.full((nh, cfg.max_k), -1, dtype=torch.int32, device=dev)
+        for (b, p), lst in base.items():
+            self.base_idx[b * Hkv + p, :lst.numel()] = lst.to(dev, torch.int32)
+        self.ring = torch.zeros((nh, cfg.window + 1), dtype=torch.int32, device=dev)
+        self.inter = torch.zeros((nh,), dtype=torch.int32, device=dev)
+        self.flag = torch.zeros((nh,), dtype=torch.int32, device=dev)
+        self.out = torch.zeros((B, spec.Hq, D), dtype=torch.float32, device=dev)
+        self.lse = torch.zeros((B, spec.Hq), dtype=torch.float32, device=dev)
+        with torch.cuda.device(dev):
+            self.handle = hc.hc_layer_create(ctx.handle, descs)
+        self.n_reps = hc.hc_layer_num_reps(self.handle)
+        self.rep_logits, self.scores = ctx.scratch(self.n_reps)
+        self.ev_topk = torch.cuda.Event()
+        self.ev_done = torch.cuda.Event()
+        self._gather_pending = False
+
+    def rep_slot(self, b: int, h: int) -> int:
+        return hc.hc_layer_rep_slot(self.handle, b, h)
+
+    # -- the three calls ------------------------------------------------------------------------
+    def attn(self, q: torch.Tensor, monitor: bool = True, stream=None) -> None:
+        hc.hc_decode_attn(self.ctx.handle, self.handle, self.arena, q, self.out, self.lse,
+                          self.rep_logits if (monitor and self.n_reps) else None, stream)
+
+    def monitor(self, scores_given: bool = False, stream=None) -> None:
+        hc.hc_rep_topk_drift(self.ctx.handle, self.handle, self.rep_logits, self.lse, self.scores, scores_given,
+                             self.topk_idx, self.base_idx, self.ring, self.inter, self.flag, stream)
+
+    def gather(self, stream=None, wait_event=None, done_event=None) -> None:
+        hc.hc_gather_retrieve(self.ctx.handle, self.handle, self.tier, self.topk_idx, self.flag, self.arena,
+                              stream, wait_event, done_event)
+
+    def step(self, q: torch.Tensor, side: Optional[torch.cuda.Stream] = None) -> None:
+        """One decode step of this layer on the current stream; the gather goes to ``side`` (or stays
+        on the current stream).  A refill decided now is visible to the next step's attention."""
+        main = torch.cuda.current_stream()
+        if self._gather_pending:
+            main.wait_event(self.ev_done)
+            self._gather_pending = False
+        self.attn(q)
+        if not self.n_reps:
+            return
+        self.monitor()
+        if side is None or self.tier is None:
+            if self.tier is not None:
+                self.gather()
+        else:
+            self.ev_topk.record(main)
+            self.gather(stream=side, wait_event=self.ev_topk, done_event=self.ev_done)
+            self._gather_pending = True
+
+    def close(self):
+        if self.handle:
+            hc.hc_layer_destroy(self.handle)
+            self.handle = None
