@@ -1,0 +1,232 @@
+#!/usr/bin/env python3
+"""Benchmark of the HeteroCache decode hot path on one MI355X.
+
+A "step" is one decode step of the whole stack: for every layer, attention over the heterogeneous
+cache (hc_decode_attn), the pivot drift monitor (hc_rep_topk_drift) and the device-predicated
+host-tier gather (hc_gather_retrieve, on a side stream).  The default workload is synthetic config 4:
+32 layers, batch 1, 32 query / 8 KV heads, head_dim 128, 224K context; per layer 2 full KV heads and
+6 compressed heads with budgets {8192, 4096, 4096, 2048, 2048, 1024}; bf16 K/V resident in HBM, the
+satellites' full K/V in pinned host memory; the query jumps every 16 steps so that every pivot
+triggers a refill then.
+
+Prints ONE JSON line.  `value` = microseconds per decode step per layer (wall clock over the timed
+steps / steps / layers).  `roofline` times the split-pass attention kernel alone with HIP events
+recorded by the library around that kernel, on the stream it is launched on.  `cpu_baseline` times
+the CPU oracle on a small sample of the same workload (a reported baseline, not a target).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "µs per decode step per layer + achieved HBM GB/s at 224K context, 1 GPU"
+HBM_PEAK_GBPS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=48)
+    ap.add_argument("--warmup", type=int, default=4)
+    ap.add_argument("--config", type=int, default=4, choices=[2, 3, 4])
+    ap.add_argument("--layers", type=int, default=0, help="0 = the config's own layer count")
+    ap.add_argument("--ctx", type=int, default=0, help="override the context length (testing)")
+    ap.add_argument("--mode", default="graph", choices=["graph", "eager"])
+    ap.add_argument("--dense", action="store_true", help="uncompressed comparison: all 8 KV heads full")
+    ap.add_argument("--no-tier", action="store_true", help="no host tier / gather (attention + monitor only)")
+    ap.add_argument("--wg-per-cu", type=int, default=0)
+    ap.add_argument("--attn-only", action="store_true", help="time hc_decode_attn alone (no monitor, no gather)")
+    ap.add_argument("--oracle-seconds", type=float, default=15.0)
+    ap.add_argument("--no-oracle", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2601_13684_amd import binding as hc
+    from paper_2601_13684_amd import inputs as I
+    from paper_2601_13684_amd import runtime as R
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    L = args.layers or I.CONFIG_LAYERS[args.config]
+    K, W = args.steps, args.warmup
+    T_total = W + 2 * K + 1           # warm-up, timed pass, kernel-timing pass
+    t_setup = time.time()
+
+    # ---- build the stack, layer by layer (masters are dropped once packed) ----
+    layers, scheds, keep = [], [], {}
+    ctx = None
+    for l in range(L):
+        w = I.make_workload(args.config, layer=l, device=dev, N=args.ctx or None)
+        spec = w.spec
+        if args.dense:
+            spec = I.spec_dense(spec.ctx[0])
+        if ctx is None:
+            ctx = R.Context(R.make_config(spec), dev, workgroups_per_cu=args.wg_per_cu or None)
+        retrieved, base = I.initial_lists(spec)
+        layers.append(R.LayerRuntime(ctx, spec, w.data, retrieved, base, host_tier=not args.no_tier))
+        scheds.append(w.schedule)
+        if l < 2 and not args.no_oracle:
+            keep[l] = (spec, I.LayerData({k: v.cpu() for k, v in w.data.K.items()},
+                                         {k: v.cpu() for k, v in w.data.V.items()}, {}), retrieved, base)
+        del w
+        print(f"[bench] layer {l + 1}/{L} packed ({time.time() - t_setup:.0f}s)", file=sys.stderr, flush=True)
+    spec0 = layers[0].spec
+    kv_bytes = spec0.kv_bytes()
+    Q_all = torch.stack([torch.stack([s.next() for s in scheds]) for _ in range(T_total)]).contiguous()   # [T,L,B,Hq,D]
+    q_cur = Q_all[0].clone()
+    t_dev = torch.zeros((1,), dtype=torch.long, device=dev)
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    setup_s = time.time() - t_setup
+
+    def load_q():
+        q_cur.copy_(Q_all.index_select(0, t_dev)[0])
+        t_dev.add_(1)
+
+    def step_eager():
+        load_q()
+        for l, lay in enumerate(layers):
+            if args.attn_only:
+                lay.attn(q_cur[l], monitor=False)
+            else:
+                lay.step(q_cur[l], side=side if lay.tier is not None else None)
+
+    def step_for_capture():
+        # same calls; all gathers are joined back before the step ends so that the captured graph is
+        # closed and a refill decided in this step is complete before the next replay starts
+        load_q()
+        main = torch.cuda.current_stream()
+        for l, lay in enumerate(layers):
+            lay.attn(q_cur[l], monitor=not args.attn_only)
+            if lay.n_reps and not args.attn_only:
+                lay.monitor()
+                if lay.tier is not None:
+                    lay.ev_topk.record(main)
+                    lay.gather(stream=side, wait_event=lay.ev_topk, done_event=lay.ev_done)
+        for lay in layers:
+            if lay.n_reps and lay.tier is not None and not args.attn_only:
+                main.wait_event(lay.ev_done)
+
+    # ---- warm-up (eager) + optional parity spot check against the oracle on layer 0 ----
+    flags_hist = []
+    snap = {}
+    for t in range(W):
+        step_eager()
+        torch.cuda.synchronize()
+        flags_hist.append(int(sum(int(lay.flag.sum()) for lay in layers)))
+        if t < 4 and 0 in keep:
+            snap[t] = (layers[0].out.cpu().double().numpy(), layers[0].lse.cpu().double().numpy())
+
+    # ---- timed region ----
+    graph = None
+    if args.mode == "graph":
+        cap = torch.cuda.Stream()
+        cap.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        t_keep = t_dev.clone()
+        with torch.cuda.stream(cap):
+            with torch.cuda.graph(graph, stream=cap):
+                step_for_capture()
+        t_dev.copy_(t_keep)               # capture does not execute; keep the schedule position
+        torch.cuda.synchronize()
+        run = graph.replay
+    else:
+        run = step_eager
+    trig_before = None
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        run()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+    us_per_layer = ms_per_step * 1e3 / L
+
+    # ---- kernel-timing pass: the same steps, eager, with the library's event hook around the split kernel ----
+    n_pairs = K * L
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_pairs)]
+    for a, b in evs:
+        a.record()
+        b.record()
+    torch.cuda.synchronize()
+    i = 0
+    for _ in range(K):
+        load_q()
+        for l, lay in enumerate(layers):
+            hc.hc_set_timing_events(ctx.handle, evs[i][0], evs[i][1])
+            if args.attn_only:
+                lay.attn(q_cur[l], monitor=False)
+            else:
+                lay.step(q_cur[l], side=side if lay.tier is not None else None)
+            i += 1
+    hc.hc_set_timing_events(ctx.handle, None, None)
+    torch.cuda.synchronize()
+    kern_ms = np.array([a.elapsed_time(b) for a, b in evs])
+    kern_us = float(kern_ms.mean() * 1e3)
+    achieved = kv_bytes / (kern_us * 1e-6) / 1e9
+
+    # ---- CPU oracle on a bounded sample: layers 0..1, first steps (the same inputs as warm-up) ----
+    cpu = None
+    parity = None
+    if keep and not args.no_oracle:
+        from oracle import ref
+        sample_t, n_ls = [], 0
+        worst = 0.0
+        t_or = time.perf_counter()
+        for l, (sp, data, retrieved, base) in keep.items():
+            orc = ref.RefLayer(sp, data, retrieved, base)
+            for t in range(min(W, 4)):
+                ts = time.perf_counter()
+                rec = orc.step(Q_all[t, l].cpu())
+                sample_t.append(time.perf_counter() - ts)
+                n_ls += 1
+                if l == 0 and t in snap:
+                    err = np.abs(snap[t][0] - rec["out"]).max(-1) / np.sqrt((rec["out"] ** 2).mean(-1))
+                    worst = max(worst, float(err.max()))
+                    assert err.max() < 1e-2 and np.abs(snap[t][1] - rec["lse"]).max() < 1e-4, "GPU/oracle mismatch in bench"
+                if time.perf_counter() - t_or > args.oracle_seconds:
+                    break
+            if time.perf_counter() - t_or > args.oracle_seconds:
+                break
+        cpu = {"value": float(np.mean(sample_t) * 1e6), "unit": "us per decode step per layer",
+               "cores": ref.threads(), "kind": "oracle",
+               "sample": f"{n_ls} layer-steps (layers 0..{len(keep) - 1}, first steps) of the same workload, "
+                         f"{sum(sample_t):.1f}s of CPU time"}
+        parity = worst
+
+    out = {
+        "metric": METRIC, "value": us_per_layer, "unit": "us per decode step per layer",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step, "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"config{args.config}{' dense' if args.dense else ''}: {spec0.ctx[0]} ctx, {L} layers, "
+                               f"B={spec0.B}, {spec0.Hq}q/{spec0.Hkv}kv heads, D=128",
+                   "layers": L, "context": spec0.ctx[0], "mode": args.mode, "host_tier": not args.no_tier,
+                   "kv_bytes_per_layer_step": kv_bytes,
+                   "split_workgroups": hc.hc_layer_num_workgroups(layers[0].handle),
+                   "split_partials": hc.hc_layer_num_partials(layers[0].handle)},
+        "tokens_per_s": spec0.B / (ms_per_step * 1e-3),
+        "step_GBps": kv_bytes * L / (ms_per_step * 1e-3) / 1e9,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "kernel": "attn_split_kernel", "kernel_us_mean": kern_us,
+                     "kernel_us_median": float(np.median(kern_ms) * 1e3), "kernel_us_p95": float(np.percentile(kern_ms, 95) * 1e3),
+                     "launches_timed": n_pairs},
+        "cpu_baseline": cpu,
+        "parity_max_err_over_rms": parity,
+        "warmup_flags": flags_hist,
+        "setup_s": setup_s,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

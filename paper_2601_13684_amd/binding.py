@@ -13,14 +13,14 @@ from typing import Optional, Sequence, Union
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libhc.so")
+LIB_PATH = os.environ.get("HC_LIB") or os.path.join(_HERE, "libhc.so")   # HC_LIB: load another build of the same ABI
 
 HC_OK, HC_EINVAL, HC_ESHAPE, HC_ENOMEM, HC_EHIP, HC_ESTATE = range(6)
 HC_MAX_WINDOW, HC_MAX_K_PER_REP = 64, 8
 
 EXPORTS = ["hc_create", "hc_destroy", "hc_strerror", "hc_last_error", "hc_layer_create", "hc_layer_destroy",
            "hc_layer_num_reps", "hc_layer_rep_slot", "hc_layer_num_workgroups", "hc_layer_num_partials",
-           "hc_set_split", "hc_plan_describe", "hc_decode_attn", "hc_rep_topk_drift", "hc_gather_retrieve"]
+           "hc_set_split", "hc_set_timing_events", "hc_plan_describe", "hc_decode_attn", "hc_rep_topk_drift", "hc_gather_retrieve"]
 
 
 class hc_config(C.Structure):
@@ -72,6 +72,7 @@ def lib():
         L.hc_layer_rep_slot.argtypes = [vp, i32, i32]
         L.hc_layer_rep_slot.restype = i32
         L.hc_set_split.argtypes = [vp, i32, i32]
+        L.hc_set_timing_events.argtypes = [vp, vp, vp]
         L.hc_plan_describe.argtypes = [C.POINTER(hc_config), C.POINTER(hc_head_desc), i32, i32,
                                        C.POINTER(hc_plan_info), C.c_char_p, i32]
         L.hc_decode_attn.argtypes = [vp] * 8
@@ -116,7 +117,10 @@ def _event(e) -> Optional[int]:
     if e is None:
         return None
     if isinstance(e, torch.cuda.Event):
-        return e.cuda_event
+        h = e.cuda_event
+        if not h:
+            raise ValueError("torch.cuda.Event has no HIP event yet: record it once before handing it to the C ABI")
+        return h
     return int(e)
 
 
@@ -136,8 +140,12 @@ def hc_destroy(ctx: int) -> None:
     _check(lib().hc_destroy(ctx), "hc_destroy")
 
 
-def hc_set_split(ctx: int, workgroups_per_cu: int, compute_units: int = 0) -> None:
+def hc_set_split(ctx: int, workgroups_per_cu: int = 2, compute_units: int = 0) -> None:
     _check(lib().hc_set_split(ctx, workgroups_per_cu, compute_units), "hc_set_split", ctx)
+
+
+def hc_set_timing_events(ctx: int, ev_begin=None, ev_end=None) -> None:
+    _check(lib().hc_set_timing_events(ctx, _event(ev_begin), _event(ev_end)), "hc_set_timing_events", ctx)
 
 
 def hc_plan_describe(cfg: hc_config, heads: Sequence[hc_head_desc], compute_units: int = 256,

@@ -12,11 +12,29 @@
 // computes (after a 3-step DPP all-reduce over the 8 column lanes) is already where p.V needs it.
 //
 // The running maximum is kept wave-uniform and updated lazily (only when some logit exceeds it by
-// more than 2^16): partial sums of different lanes then share one reference and merge by plain
-// addition.  A workgroup (4 wavefronts) owns a contiguous share of the layer's rows (split-K over
+// more than 2^16, which leaves the streaming loop): partial sums of different lanes then share one
+// reference and merge by plain addition.  A workgroup (4 wavefronts) owns a contiguous share of the layer's rows (split-K over
 // ragged per-head lengths) and writes one partial (max, sum, acc[G][D]) per head it touches; a
-// second kernel combines the partials.
+// second kernel combines the partials.  Loads are double-buffered in registers: the next group of
+// row steps is in flight while the current one is being reduced.
+#include <hip/hip_ext.h>
+
 #include "hc_internal.h"
+#ifdef HC_TUNE
+#include <stdio.h>
+#include <stdlib.h>
+#endif
+
+#ifdef HC_TUNE
+__device__ unsigned long long hc_dbg[4096 * 8];
+extern "C" int hc_debug_read(unsigned long long* host, int n)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(hc_dbg), sizeof(unsigned long long) * n);
+}
+#define HC_STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x < 4096) hc_dbg[blockIdx.x * 8 + (i)] = __builtin_amdgcn_s_memrealtime(); } while (0)
+#else
+#define HC_STAMP(i) do { } while (0)
+#endif
 
 namespace {
 
@@ -51,6 +69,7 @@ __device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 
 
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
+constexpr float INV_SQRT_D = 0.08838834764831845f;   // 1/sqrt(128)
 constexpr float LAZY_SLACK = 16.0f;     // log2 units: exp2 of at most 2^16 before the reference moves
 constexpr float M_INIT = -1.0e30f;      // finite, so that (old - new) never is inf - inf
 
@@ -61,77 +80,227 @@ struct WaveState {
     float acc[G][16];    // sum of exp2(t - m) * V[row][d] for the lane's 16 columns
 };
 
-// One row step: the wave's 8 rows [row0, row0+8).  k0,k1 / v0,v1 are the lane's two 16-byte chunks.
-template <int G, bool MASKED>
-__device__ __forceinline__ void row_step(WaveState<G>& st, const uint32_t (&qreg)[G][8], const uint4& k0,
-                                         const uint4& k1, const uint4& v0, const uint4& v1, bool valid,
-                                         float* __restrict__ rep_row, int max_ctx, int c)
+// One row step of a wave (its 8 rows): the lane's two 16-byte chunks of its K row and of its V row.
+struct Tile {
+    uint4 k0, k1, v0, v1;
+};
+
+// Kb / Vb: the head's K and V blocks (wave-uniform byte pointers); off: the lane's byte offset of its
+// first chunk (row * 256 + c * 16, below 4 GiB because contexts are capped at 2^24 rows).
+__device__ __forceinline__ void load_tile(Tile& t, const char* __restrict__ Kb, const char* __restrict__ Vb, uint32_t off)
 {
-    float s[G];
+    t.k0 = *reinterpret_cast<const uint4*>(Kb + off);
+    t.k1 = *reinterpret_cast<const uint4*>(Kb + off + 128);
+    t.v0 = *reinterpret_cast<const uint4*>(Vb + off);
+    t.v1 = *reinterpret_cast<const uint4*>(Vb + off + 128);
+}
+
+// q.K of the lane's row for the G query heads: partial dot products over the lane's 16 columns,
+// then summed over the 8 column lanes (every lane of the row ends up with the full sums).
+template <int G>
+__device__ __forceinline__ void qk(const uint32_t (&qreg)[G][8], const Tile& t, float (&s)[G])
+{
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         float a = 0.f;
-        a = dot2(k0.x, qreg[g][0], a);
-        a = dot2(k0.y, qreg[g][1], a);
-        a = dot2(k0.z, qreg[g][2], a);
-        a = dot2(k0.w, qreg[g][3], a);
-        a = dot2(k1.x, qreg[g][4], a);
-        a = dot2(k1.y, qreg[g][5], a);
-        a = dot2(k1.z, qreg[g][6], a);
-        a = dot2(k1.w, qreg[g][7], a);
+        a = dot2(t.k0.x, qreg[g][0], a);
+        a = dot2(t.k0.y, qreg[g][1], a);
+        a = dot2(t.k0.z, qreg[g][2], a);
+        a = dot2(t.k0.w, qreg[g][3], a);
+        a = dot2(t.k1.x, qreg[g][4], a);
+        a = dot2(t.k1.y, qreg[g][5], a);
+        a = dot2(t.k1.z, qreg[g][6], a);
+        a = dot2(t.k1.w, qreg[g][7], a);
         s[g] = sum8(a);
     }
-    if (rep_row) {   // pivot head: keep the scaled logits for the drift monitor
-        float mine = s[0];
+}
+
+// Pivot heads keep their scaled logits for the drift monitor: column lane g stores head g's logit.
+template <int G>
+__device__ __forceinline__ void store_rep(float* __restrict__ rep_row, const float (&s)[G], int max_ctx, int c, bool valid)
+{
+    // select s[c] with a tree over the bits of c (a chain of compares would be turned into a stack array)
+    float sel[G];
 #pragma unroll
-        for (int g = 1; g < G; ++g) mine = (c == g) ? s[g] : mine;
-        if (c < G && (!MASKED || valid)) rep_row[(size_t)c * max_ctx] = mine * 0.08838834764831845f;   // 1/sqrt(128)
+    for (int g = 0; g < G; ++g) sel[g] = s[g];
+#pragma unroll
+    for (int bit = 1; bit < G; bit <<= 1) {
+#pragma unroll
+        for (int g = 0; g + bit < G; g += 2 * bit) sel[g] = (c & bit) ? sel[g + bit] : sel[g];
     }
-    float t[G];
-    bool over = false;
+    if (c < G && valid) rep_row[(size_t)c * max_ctx] = sel[0] * INV_SQRT_D;
+}
+
+// Exponents of the softmax weights relative to the reference, x[g] = log2(e)/sqrt(D) s[g] - m[g]
+// (-inf for a masked row).  Returns the wave's mask of lanes in which some exponent exceeds the slack:
+// non-zero means the reference has to move before this row step may be accumulated.
+template <int G>
+__device__ __forceinline__ uint64_t exponents(const WaveState<G>& st, const float (&s)[G], float (&x)[G], bool valid)
+{
+    float mx = -INFINITY;
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-        t[g] = s[g] * (LOG2E * 0.08838834764831845f);
-        if (MASKED && !valid) t[g] = -INFINITY;
-        over |= t[g] > st.m[g] + LAZY_SLACK;
+        x[g] = valid ? fmaf(s[g], LOG2E * INV_SQRT_D, -st.m[g]) : -INFINITY;
+        mx = fmaxf(mx, x[g]);
     }
-    if (__builtin_amdgcn_ballot_w64(over) != 0) {   // rare: move the reference maximum
+    return __builtin_amdgcn_ballot_w64(mx > LAZY_SLACK);
+}
+
+// Rare: raise the reference to the largest logit of this row step and recompute the exponents.
+// Returns, per head, the factor 2^(old reference - new reference) by which everything accumulated so
+// far has to be multiplied.
+template <int G>
+__device__ __forceinline__ void move_reference(WaveState<G>& st, const float (&s)[G], float (&x)[G], float (&alpha)[G],
+                                               bool valid)
+{
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            float x = t[g];
-            x = fmaxf(x, dpp<DPP_ROR8>(x));
-            x = fmaxf(x, __shfl_xor(x, 16));
-            x = fmaxf(x, __shfl_xor(x, 32));
-            const float mn = fmaxf(st.m[g], x);
-            const float alpha = __builtin_amdgcn_exp2f(st.m[g] - mn);
-            st.m[g] = mn;
-            st.Z[g] *= alpha;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) st.acc[g][i] *= alpha;
-        }
+    for (int g = 0; g < G; ++g) {
+        const float t = valid ? s[g] * (LOG2E * INV_SQRT_D) : -INFINITY;
+        float hi = t;
+        hi = fmaxf(hi, dpp<DPP_ROR8>(hi));
+        hi = fmaxf(hi, __shfl_xor(hi, 16));
+        hi = fmaxf(hi, __shfl_xor(hi, 32));
+        const float mn = fmaxf(st.m[g], hi);
+        alpha[g] = __builtin_amdgcn_exp2f(st.m[g] - mn);
+        st.m[g] = mn;
+        x[g] = t - mn;
     }
+}
+
+// Multiplies the accumulators of one head by alpha if (and only if) the wave-uniform mask is non-zero.
+// Written as one opaque block with tied operands so that the accumulators keep their registers on both
+// paths: expressed as an ordinary branch, the register allocator copies all of them on the common path.
+__device__ __forceinline__ void scale_if(uint64_t mask, float alpha, float& z, float (&a)[16])
+{
+    asm volatile(
+        "s_cmp_eq_u64 %[m], 0\n\t"
+        "s_cbranch_scc1 1f\n\t"
+        "v_mul_f32 %[z], %[al], %[z]\n\t"
+        "v_mul_f32 %[a0], %[al], %[a0]\n\t"
+        "v_mul_f32 %[a1], %[al], %[a1]\n\t"
+        "v_mul_f32 %[a2], %[al], %[a2]\n\t"
+        "v_mul_f32 %[a3], %[al], %[a3]\n\t"
+        "v_mul_f32 %[a4], %[al], %[a4]\n\t"
+        "v_mul_f32 %[a5], %[al], %[a5]\n\t"
+        "v_mul_f32 %[a6], %[al], %[a6]\n\t"
+        "v_mul_f32 %[a7], %[al], %[a7]\n\t"
+        "v_mul_f32 %[a8], %[al], %[a8]\n\t"
+        "v_mul_f32 %[a9], %[al], %[a9]\n\t"
+        "v_mul_f32 %[a10], %[al], %[a10]\n\t"
+        "v_mul_f32 %[a11], %[al], %[a11]\n\t"
+        "v_mul_f32 %[a12], %[al], %[a12]\n\t"
+        "v_mul_f32 %[a13], %[al], %[a13]\n\t"
+        "v_mul_f32 %[a14], %[al], %[a14]\n\t"
+        "v_mul_f32 %[a15], %[al], %[a15]\n"
+        "1:"
+        : [z] "+v"(z), [a0] "+v"(a[0]), [a1] "+v"(a[1]), [a2] "+v"(a[2]), [a3] "+v"(a[3]), [a4] "+v"(a[4]),
+          [a5] "+v"(a[5]), [a6] "+v"(a[6]), [a7] "+v"(a[7]), [a8] "+v"(a[8]), [a9] "+v"(a[9]), [a10] "+v"(a[10]),
+          [a11] "+v"(a[11]), [a12] "+v"(a[12]), [a13] "+v"(a[13]), [a14] "+v"(a[14]), [a15] "+v"(a[15])
+        : [m] "s"(mask), [al] "v"(alpha)
+        : "scc");
+}
+
+// p.V: weights 2^x[g], accumulated into the lane's 16 columns.
+template <int G>
+__device__ __forceinline__ void pv(WaveState<G>& st, const float (&x)[G], const Tile& t)
+{
     float vf[16];
-    vf[0] = bf_lo(v0.x); vf[1] = bf_hi(v0.x); vf[2] = bf_lo(v0.y); vf[3] = bf_hi(v0.y);
-    vf[4] = bf_lo(v0.z); vf[5] = bf_hi(v0.z); vf[6] = bf_lo(v0.w); vf[7] = bf_hi(v0.w);
-    vf[8] = bf_lo(v1.x); vf[9] = bf_hi(v1.x); vf[10] = bf_lo(v1.y); vf[11] = bf_hi(v1.y);
-    vf[12] = bf_lo(v1.z); vf[13] = bf_hi(v1.z); vf[14] = bf_lo(v1.w); vf[15] = bf_hi(v1.w);
+    vf[0] = bf_lo(t.v0.x); vf[1] = bf_hi(t.v0.x); vf[2] = bf_lo(t.v0.y); vf[3] = bf_hi(t.v0.y);
+    vf[4] = bf_lo(t.v0.z); vf[5] = bf_hi(t.v0.z); vf[6] = bf_lo(t.v0.w); vf[7] = bf_hi(t.v0.w);
+    vf[8] = bf_lo(t.v1.x); vf[9] = bf_hi(t.v1.x); vf[10] = bf_lo(t.v1.y); vf[11] = bf_hi(t.v1.y);
+    vf[12] = bf_lo(t.v1.z); vf[13] = bf_hi(t.v1.z); vf[14] = bf_lo(t.v1.w); vf[15] = bf_hi(t.v1.w);
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-        const float p = __builtin_amdgcn_exp2f(t[g] - st.m[g]);
+        const float p = __builtin_amdgcn_exp2f(x[g]);
         st.Z[g] += p;
 #pragma unroll
         for (int i = 0; i < 16; ++i) st.acc[g][i] = fmaf(p, vf[i], st.acc[g][i]);
     }
 }
 
-template <int G, int U, int WG_PER_CU>
+#ifdef HC_TUNE
+template <int G>
+__device__ __forceinline__ void consume(WaveState<G>& st, const Tile& t)   // streaming-only probe
+{
+    const uint32_t x = t.k0.x ^ t.k0.y ^ t.k0.z ^ t.k0.w ^ t.k1.x ^ t.k1.y ^ t.k1.z ^ t.k1.w ^ t.v0.x ^ t.v0.y ^ t.v0.z ^
+                       t.v0.w ^ t.v1.x ^ t.v1.y ^ t.v1.z ^ t.v1.w;
+    st.Z[0] += __uint_as_float(x & 0x3f800000u);
+}
+#endif
+
+// One row step: logits, (pivot) logit store, reference check, accumulate.
+template <int G>
+__device__ __forceinline__ void row_step(WaveState<G>& st, const uint32_t (&qreg)[G][8], const Tile& t,
+                                         float* __restrict__ rep_row, int max_ctx, int c, bool valid)
+{
+    float s[G], x[G], alpha[G];
+    qk<G>(qreg, t, s);
+    if (rep_row) store_rep<G>(rep_row, s, max_ctx, c, valid);
+    const uint64_t over = exponents<G>(st, s, x, valid);
+#pragma unroll
+    for (int g = 0; g < G; ++g) alpha[g] = 1.0f;
+    if (over) move_reference<G>(st, s, x, alpha, valid);
+#pragma unroll
+    for (int g = 0; g < G; ++g) scale_if(over, alpha[g], st.Z[g], st.acc[g]);
+    pv<G>(st, x, t);
+}
+
+// Streams rows [row_begin, row_end) of one head through the wave state.  The wave takes the row steps
+// row_begin + 8*w + 32*i.  Full row steps are double-buffered in registers (tile B is in flight while
+// tile A is reduced, and vice versa); the ragged last row step is clamped for the load and masked.
+template <int G, int MODE>
+__device__ __forceinline__ void process_rows(WaveState<G>& st, const uint32_t (&qreg)[G][8],
+                                             const char* __restrict__ Kb, const char* __restrict__ Vb,
+                                             float* __restrict__ rep_base, int row_begin, int row_end, int w, int r,
+                                             int c, int max_ctx)
+{
+    const int wave_row0 = row_begin + 8 * w;
+    int row = wave_row0 + r;                                                        // this lane's row
+    const int nfull = wave_row0 + 8 <= row_end ? (row_end - 8 - wave_row0) / 32 + 1 : 0;   // unmasked row steps
+    uint32_t off = (uint32_t)row * 256u + (uint32_t)c * 16u;                        // byte offset of the lane's first chunk
+    constexpr uint32_t STEP = 32u * 256u;                                           // one row step further for this wave
+    Tile A, B;
+    int i = 0;
+    if (nfull > 0) load_tile(A, Kb, Vb, off);
+#ifdef HC_TUNE
+    if (MODE == 1) {
+        for (; i + 2 <= nfull; i += 2, off += 2 * STEP) {
+            load_tile(B, Kb, Vb, off + STEP);
+            consume<G>(st, A);
+            if (i + 2 < nfull) load_tile(A, Kb, Vb, off + 2 * STEP);
+            consume<G>(st, B);
+        }
+        if (i < nfull) consume<G>(st, A);
+        return;
+    }
+#endif
+#pragma unroll 1
+    for (; i + 2 <= nfull; i += 2, row += 64, off += 2 * STEP) {
+        load_tile(B, Kb, Vb, off + STEP);
+        row_step<G>(st, qreg, A, rep_base ? rep_base + row : nullptr, max_ctx, c, true);
+        if (i + 2 < nfull) load_tile(A, Kb, Vb, off + 2 * STEP);
+        row_step<G>(st, qreg, B, rep_base ? rep_base + row + 32 : nullptr, max_ctx, c, true);
+    }
+    if (i < nfull) {
+        row_step<G>(st, qreg, A, rep_base ? rep_base + row : nullptr, max_ctx, c, true);
+        row += 32;
+    }
+#pragma unroll 1
+    for (; row - r < row_end; row += 32) {
+        const bool valid = row < row_end;
+        load_tile(A, Kb, Vb, (uint32_t)(valid ? row : row_end - 1) * 256u + (uint32_t)c * 16u);
+        row_step<G>(st, qreg, A, rep_base ? rep_base + row : nullptr, max_ctx, c, valid);
+    }
+}
+
+template <int G, int U, int WG_PER_CU, int MODE = 0>
 __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16_t* __restrict__ arena,
-                                                            const uint16_t* __restrict__ q,
-                                                            const HeadDev* __restrict__ heads,
-                                                            const SegDev* __restrict__ segs,
-                                                            const int32_t* __restrict__ blk_seg,
-                                                            float* __restrict__ part_acc, float* __restrict__ part_ml,
-                                                            float* __restrict__ rep_logits, int max_ctx)
+                                                                    const uint16_t* __restrict__ q,
+                                                                    const BlkDev* __restrict__ blks,
+                                                                    const SegDev* __restrict__ segs,
+                                                                    float* __restrict__ part_acc,
+                                                                    float* __restrict__ part_ml,
+                                                                    float* __restrict__ rep_logits, int max_ctx)
 {
     __shared__ float sm_m[4][G];
     __shared__ float sm_Z[8][G];
@@ -143,13 +312,23 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
     const int r = lane >> 3;     // row inside a row step
     const int c = lane & 7;      // column lane
 
-    const int seg_end = blk_seg[blockIdx.x + 1];
-    for (int si = blk_seg[blockIdx.x]; si < seg_end; ++si) {
-        const SegDev seg = segs[si];
-        const HeadDev hd = heads[seg.bh];
-        const uint16_t* __restrict__ Kp = arena + hd.k_off;
-        const uint16_t* __restrict__ Vp = arena + hd.v_off;
-        float* rep_base = (rep_logits && hd.rep_slot >= 0) ? rep_logits + (size_t)hd.rep_slot * G * max_ctx : nullptr;
+    HC_STAMP(0);
+#ifdef HC_TUNE
+    if (threadIdx.x == 0 && blockIdx.x < 4096) {
+        hc_dbg[blockIdx.x * 8 + 5] = __builtin_amdgcn_s_getreg((3 << 11) | 20);     // XCC_ID
+        hc_dbg[blockIdx.x * 8 + 6] = __builtin_amdgcn_s_getreg((31 << 11) | 4);     // HW_ID
+    }
+#endif
+    const BlkDev blk = blks[blockIdx.x];
+    SegDev seg = blk.first;
+    int next_extra = blk.extra_begin;
+#ifdef HC_TUNE
+    if (seg.row_end > 0) HC_STAMP(1);
+#endif
+    for (;;) {
+        const char* __restrict__ Kp = reinterpret_cast<const char*>(arena + seg.k_off);
+        const char* __restrict__ Vp = reinterpret_cast<const char*>(arena + seg.v_off);
+        float* rep_base = (rep_logits && seg.rep_slot >= 0) ? rep_logits + (size_t)seg.rep_slot * G * max_ctx : nullptr;
 
         uint32_t qreg[G][8];
 #pragma unroll
@@ -168,38 +347,15 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
             for (int i = 0; i < 16; ++i) st.acc[g][i] = 0.f;
         }
 
-        // Row steps of this wave: rows seg.row_begin + 8*(w + 4*i), i = 0, 1, ...
-        int row0 = seg.row_begin + 8 * w;
-        // full groups of U row steps, no bounds checks
-        for (; row0 + 32 * (U - 1) + 8 <= seg.row_end; row0 += 32 * U) {
-            uint4 k0[U], k1[U], v0[U], v1[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const size_t off = (size_t)(row0 + 32 * u + r) * HC_D;
-                const uint4* kp = reinterpret_cast<const uint4*>(Kp + off);
-                const uint4* vp = reinterpret_cast<const uint4*>(Vp + off);
-                k0[u] = kp[c];
-                k1[u] = kp[8 + c];
-                v0[u] = vp[c];
-                v1[u] = vp[8 + c];
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                row_step<G, false>(st, qreg, k0[u], k1[u], v0[u], v1[u], true,
-                                   rep_base ? rep_base + row0 + 32 * u + r : nullptr, max_ctx, c);
-        }
-        // remaining row steps one at a time; rows past the end are clamped for the load and masked
-        for (; row0 < seg.row_end; row0 += 32) {
-            const int row = row0 + r;
-            const bool valid = row < seg.row_end;
-            const size_t off = (size_t)(valid ? row : seg.row_end - 1) * HC_D;
-            const uint4* kp = reinterpret_cast<const uint4*>(Kp + off);
-            const uint4* vp = reinterpret_cast<const uint4*>(Vp + off);
-            const uint4 k0 = kp[c], k1 = kp[8 + c], v0 = vp[c], v1 = vp[8 + c];
-            row_step<G, true>(st, qreg, k0, k1, v0, v1, valid, rep_base ? rep_base + row : nullptr, max_ctx, c);
-        }
+        process_rows<G, MODE>(st, qreg, Kp, Vp, rep_base, seg.row_begin, seg.row_end, w, r, c, max_ctx);
+#ifdef HC_TUNE
+        if (st.Z[0] >= 0.f) HC_STAMP(2);
+#endif
 
         // ---- merge the 4 waves x 8 row lanes into one partial (4 row lanes in registers, the rest in LDS) ----
+#ifdef HC_TUNE
+        if (st.Z[0] >= 0.f) HC_STAMP(3);
+#endif
         if (lane == 0) {
 #pragma unroll
             for (int g = 0; g < G; ++g) sm_m[w][g] = st.m[g];
@@ -247,12 +403,16 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
             part_ml[((size_t)seg.slot * G + tid) * 2 + 0] = M[tid];
             part_ml[((size_t)seg.slot * G + tid) * 2 + 1] = z;
         }
+        HC_STAMP(4);
+        if (next_extra >= blk.extra_end) break;
         __syncthreads();
+        seg = segs[next_extra++];
     }
 }
 
 // Second pass: out = sum_s 2^(m_s - M) acc_s / sum_s 2^(m_s - M) Z_s over the partials of one head.
-// One workgroup of 1024 threads per (b, query head): 8 partial lanes x 128 columns.
+// One workgroup of 1024 threads per (b, query head): 32 partial lanes x 32 column quads; every
+// thread's loads are independent and issued together.
 template <int G>
 __global__ __launch_bounds__(1024) void attn_combine_kernel(const HeadDev* __restrict__ heads,
                                                             const float* __restrict__ part_acc,
@@ -260,15 +420,17 @@ __global__ __launch_bounds__(1024) void attn_combine_kernel(const HeadDev* __res
                                                             float* __restrict__ out, float* __restrict__ lse)
 {
     __shared__ float sm_max[16];
-    __shared__ float sm_acc[8][HC_D];
-    __shared__ float sm_z[8];
+    __shared__ float4 sm_acc[32][32];
+    __shared__ float sm_z[32];
     const int bh = blockIdx.x / G, g = blockIdx.x % G;
     const HeadDev hd = heads[bh];
-    const int tid = threadIdx.x, d = tid & 127, pl = tid >> 7;
+    const int tid = threadIdx.x, dq = tid & 31, pl = tid >> 5;
     const int n = hd.part_count;
+    const float2* ml = reinterpret_cast<const float2*>(part_ml);
+    const float4* pa = reinterpret_cast<const float4*>(part_acc);
 
     float mx = M_INIT;
-    for (int s = tid; s < n; s += 1024) mx = fmaxf(mx, part_ml[((size_t)(hd.part_begin + s) * G + g) * 2]);
+    for (int s = tid; s < n; s += 1024) mx = fmaxf(mx, ml[(size_t)(hd.part_begin + s) * G + g].x);
     for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
     if ((tid & 63) == 0) sm_max[tid >> 6] = mx;
     __syncthreads();
@@ -276,40 +438,72 @@ __global__ __launch_bounds__(1024) void attn_combine_kernel(const HeadDev* __res
 #pragma unroll
     for (int i = 1; i < 16; ++i) M = fmaxf(M, sm_max[i]);
 
-    float acc = 0.f, z = 0.f;
-    for (int s = pl; s < n; s += 8) {
-        const size_t slot = (size_t)(hd.part_begin + s);
-        const float wgt = __builtin_amdgcn_exp2f(part_ml[(slot * G + g) * 2] - M);
-        z += wgt * part_ml[(slot * G + g) * 2 + 1];
-        acc += wgt * part_acc[(slot * G + g) * HC_D + d];
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float z = 0.f;
+    for (int s0 = pl; s0 < n; s0 += 128) {
+        float2 mz[4];
+        float4 a[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int s = s0 + 32 * u;
+            const size_t slot = (size_t)(hd.part_begin + (s < n ? s : pl));
+            mz[u] = ml[slot * G + g];
+            a[u] = pa[(slot * G + g) * (HC_D / 4) + dq];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float wgt = (s0 + 32 * u < n) ? __builtin_amdgcn_exp2f(mz[u].x - M) : 0.f;
+            z += wgt * mz[u].y;
+            acc.x += wgt * a[u].x;
+            acc.y += wgt * a[u].y;
+            acc.z += wgt * a[u].z;
+            acc.w += wgt * a[u].w;
+        }
     }
-    sm_acc[pl][d] = acc;
-    if (d == 0) sm_z[pl] = z;
+    sm_acc[pl][dq] = acc;
+    if (dq == 0) sm_z[pl] = z;
     __syncthreads();
-    if (pl == 0) {
+    if (tid < HC_D) {     // column tid: quad tid/4, component tid%4
+        const float* col = reinterpret_cast<const float*>(&sm_acc[0][0]) + tid;
         float a = 0.f, zz = 0.f;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            a += sm_acc[i][d];
+        for (int i = 0; i < 32; ++i) {
+            a += col[i * HC_D];
             zz += sm_z[i];
         }
-        out[(size_t)blockIdx.x * HC_D + d] = a / zz;
-        if (d == 0) lse[blockIdx.x] = (M + __builtin_amdgcn_logf(zz)) * LN2;
+        out[(size_t)blockIdx.x * HC_D + tid] = a / zz;
+        if (tid == 0) lse[blockIdx.x] = (M + __builtin_amdgcn_logf(zz)) * LN2;
     }
 }
 
-// Rows in flight per wave (U row steps of 8 rows, 4 KB each) against registers: the group-of-4 case
-// holds 32 query + 64 accumulator registers and takes U = 4 at two workgroups per compute unit.
-template <int G> struct Tune { static constexpr int U = 4, WG = 2; };
-template <> struct Tune<8> { static constexpr int U = 1, WG = 2; };
+// Rows in flight per wave (two tiles of U row steps of 8 rows, 4 KB each) against registers: the
+// group-of-4 case holds 32 query + 64 accumulator registers; U = 1 at two workgroups per compute unit
+// keeps 64 KB in flight per compute unit, which measurement shows is enough.
+template <int G> struct Tune { static constexpr int U = 1, WG = 2; };
+template <> struct Tune<8> { static constexpr int U = 1, WG = 1; };
 
 template <int G>
 hc_status launch(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* q, float* out, float* lse,
                  float* rep_logits, hipStream_t st)
 {
-    attn_split_kernel<G, Tune<G>::U, Tune<G>::WG><<<dim3(L->n_blocks), dim3(256), 0, st>>>(
-        (const uint16_t*)arena, (const uint16_t*)q, L->heads, L->segs, L->blk_seg, ctx->part_acc, ctx->part_ml,
-        rep_logits, ctx->cfg.max_ctx);
+    // The optional timing events are attached to the kernel's own dispatch, so that their distance is the
+    // kernel's execution time (what a profiler's kernel trace reports), not launch latency plus execution.
+#define HC_LAUNCH(KERNEL)                                                                                         \
+    hipExtLaunchKernelGGL(KERNEL, dim3(L->n_blocks), dim3(256), 0, st, ctx->ev_begin, ctx->ev_end, 0,            \
+                          (const uint16_t*)arena, (const uint16_t*)q, (const BlkDev*)L->blks,                    \
+                          (const SegDev*)L->segs, ctx->part_acc, ctx->part_ml, rep_logits, ctx->cfg.max_ctx)
+#ifdef HC_TUNE
+    if (G == 4 && getenv("HC_VARIANT")) {
+        int u = 4, wg = 2, mode = 0;
+        sscanf(getenv("HC_VARIANT"), "%d,%d,%d", &u, &wg, &mode);
+#define HC_V(UU, WW, MM) if (u == UU && wg == WW && mode == MM) { HC_LAUNCH((attn_split_kernel<4, UU, WW, MM>)); } else
+        HC_V(1, 2, 0) HC_V(2, 2, 0) HC_V(2, 1, 0) HC_V(4, 1, 0) HC_V(1, 2, 1) HC_V(2, 2, 1) HC_V(2, 1, 1) HC_V(4, 1, 1)
+        return hc_fail(ctx, HC_EINVAL, "unknown HC_VARIANT");
+#undef HC_V
+    } else
+#endif
+    HC_LAUNCH((attn_split_kernel<G, Tune<G>::U, Tune<G>::WG>));
+#undef HC_LAUNCH
     HC_HIP(ctx, hipGetLastError());
     attn_combine_kernel<G><<<dim3(L->n_heads * G), dim3(1024), 0, st>>>(L->heads, ctx->part_acc, ctx->part_ml, out, lse);
     HC_HIP(ctx, hipGetLastError());

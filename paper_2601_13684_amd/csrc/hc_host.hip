@@ -140,6 +140,16 @@ extern "C" hc_status hc_set_split(hc_ctx* ctx, int32_t workgroups_per_cu, int32_
     return HC_OK;
 }
 
+extern "C" hc_status hc_set_timing_events(hc_ctx* ctx, void* ev_begin, void* ev_end)
+{
+    if (!ctx_ok(ctx)) return HC_ESTATE;
+    if ((ev_begin == nullptr) != (ev_end == nullptr))
+        return hc_fail(ctx, HC_EINVAL, "hc_set_timing_events: give both events or neither");
+    ctx->ev_begin = (hipEvent_t)ev_begin;
+    ctx->ev_end = (hipEvent_t)ev_end;
+    return HC_OK;
+}
+
 static hc_status ensure_partials(hc_ctx* ctx, size_t slots)
 {
     if (slots <= ctx->part_slots) return HC_OK;
@@ -168,7 +178,7 @@ static void layer_free(hc_layer* L)
 {
     (void)hipFree(L->heads);
     (void)hipFree(L->segs);
-    (void)hipFree(L->blk_seg);
+    (void)hipFree(L->blks);
     (void)hipFree(L->reps);
     (void)hipFree(L->outs);
     (void)hipFree(L->sats);
@@ -181,6 +191,7 @@ struct Plan {
     std::vector<HeadDev> heads;
     std::vector<SegDev> segs;
     std::vector<int32_t> blk_seg;
+    std::vector<BlkDev> blks;
     std::vector<RepDev> reps;
     std::vector<OutDev> outs;
     std::vector<SatDev> sats;
@@ -305,10 +316,12 @@ static hc_status make_plan(const hc_config& cfg, const hc_head_desc* hd, int n_c
         }
     }
 
-    // ---- split-K plan: the rows of all heads, in granules of HC_UNIT_ROWS, are cut into equal
+    // ---- split-K plan.  The rows of all heads, in granules of HC_UNIT_ROWS, are cut into equal
     // contiguous shares, one per workgroup; a share that crosses a head boundary becomes several
     // segments, each producing its own partial result.
     P.heads.resize(nh);
+    const int64_t max_blocks = (int64_t)wg_per_cu * n_cu;
+    const int64_t min_units = 4;
     int64_t total_units = 0;
     for (int i = 0; i < nh; ++i) {
         total_units += (hd[i].len + HC_UNIT_ROWS - 1) / HC_UNIT_ROWS;
@@ -324,8 +337,6 @@ static hc_status make_plan(const hc_config& cfg, const hc_head_desc* hd, int n_c
         H.part_count = 0;
         H.pad = 0;
     }
-    const int64_t max_blocks = (int64_t)wg_per_cu * n_cu;
-    const int64_t min_units = 4;
     const int nb = (int)std::max<int64_t>(1, std::min<int64_t>(max_blocks, total_units / min_units));
     P.n_blocks = nb;
     P.blk_seg.assign(nb + 1, 0);
@@ -345,6 +356,10 @@ static hc_status make_plan(const hc_config& cfg, const hc_head_desc* hd, int n_c
             }
             const int64_t take_end = std::min(u1, head_first_unit + head_units);
             SegDev sg;
+            sg.k_off = hd[head].k_off;
+            sg.v_off = hd[head].v_off;
+            sg.rep_slot = P.rep_slot_of[head];
+            sg.pad = 0;
             sg.bh = head;
             sg.row_begin = (int32_t)((u0 - head_first_unit) * HC_UNIT_ROWS);
             sg.row_end = (int32_t)std::min<int64_t>((take_end - head_first_unit) * HC_UNIT_ROWS, hd[head].len);
@@ -356,6 +371,22 @@ static hc_status make_plan(const hc_config& cfg, const hc_head_desc* hd, int n_c
         }
     }
     P.blk_seg[nb] = (int32_t)P.segs.size();
+
+    // Placement.  On MI355X a workgroup's index modulo 8 is the die (XCD) it runs on, and with two
+    // workgroups per compute unit the second half of the indices are the second ones dispatched; dies
+    // and dispatch slots stream at measurably different speeds.  Share l = 16 j + 2 x + slot runs as
+    // workgroup slot * nb/2 + 8 j + x, so that neighbouring stretches of rows (in particular the two
+    // ends of a head) are spread over all dies and both slots instead of falling on the same kind.
+    P.blks.resize(nb);
+    for (int l = 0; l < nb; ++l) {
+        int p = l;
+        if (nb % 16 == 0) p = (l % 2) * (nb / 2) + (l / 16) * 8 + (l % 16) / 2;
+        BlkDev& B = P.blks[p];
+        B.first = P.segs[P.blk_seg[l]];
+        B.extra_begin = P.blk_seg[l] + 1;
+        B.extra_end = P.blk_seg[l + 1];
+        B.pad0 = B.pad1 = 0;
+    }
     return HC_OK;
 }
 
@@ -421,7 +452,7 @@ extern "C" hc_status hc_layer_create(hc_ctx* ctx, const hc_head_desc* hd, hc_lay
     st = ensure_partials(ctx, P.segs.size());
     if (st == HC_OK) st = upload(ctx, P.heads, &L->heads);
     if (st == HC_OK) st = upload(ctx, P.segs, &L->segs);
-    if (st == HC_OK) st = upload(ctx, P.blk_seg, &L->blk_seg);
+    if (st == HC_OK) st = upload(ctx, P.blks, &L->blks);
     if (st == HC_OK) st = upload(ctx, P.reps, &L->reps);
     if (st == HC_OK) st = upload(ctx, P.outs, &L->outs);
     if (st == HC_OK) st = upload(ctx, P.sats, &L->sats);

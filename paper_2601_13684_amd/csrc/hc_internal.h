@@ -22,10 +22,22 @@ struct HeadDev {
     int32_t pad;
 };
 
-// A contiguous run of rows of one head handled by one workgroup of the split pass.
+// A contiguous run of rows of one head handled by one workgroup of the split pass; self-contained so
+// that a workgroup can start streaming after a single descriptor read.
 struct SegDev {
+    int64_t k_off, v_off;          // element offsets of the head's K and V blocks in the arena
     int32_t bh, row_begin, row_end, slot;
+    int32_t rep_slot;
+    int32_t pad;
 };
+
+// What workgroup b of the split pass does: its first segment inline, any further ones (when its
+// share of rows crosses a head boundary) in segs[extra_begin, extra_end).
+struct BlkDev {
+    SegDev first;
+    int32_t extra_begin, extra_end, pad0, pad1;
+};
+static_assert(sizeof(SegDev) == 40 && sizeof(BlkDev) == 56, "descriptor layout");
 
 // One pivot of the layer.
 struct RepDev {
@@ -55,6 +67,7 @@ struct hc_ctx {
     int wg_per_cu;
     int device;
     char err[512];
+    hipEvent_t ev_begin = nullptr, ev_end = nullptr;   // optional timing hook around the split pass
     // split-K partial workspace
     float* part_acc = nullptr;   // [slots][G][D]
     float* part_ml = nullptr;    // [slots][G][2]  (running max in log2 units, sum)
@@ -81,7 +94,7 @@ struct hc_layer {
     std::vector<int32_t> rep_slot_of;   // [B*Hkv]
     HeadDev* heads = nullptr;
     SegDev* segs = nullptr;
-    int32_t* blk_seg = nullptr;    // [n_blocks+1]
+    BlkDev* blks = nullptr;        // [n_blocks]
     RepDev* reps = nullptr;
     OutDev* outs = nullptr;
     SatDev* sats = nullptr;

@@ -131,8 +131,12 @@ class LayerRuntime:
             self.handle = hc.hc_layer_create(ctx.handle, descs)
         self.n_reps = hc.hc_layer_num_reps(self.handle)
         self.rep_logits, self.scores = ctx.scratch(self.n_reps)
+        # torch creates the HIP event lazily at the first record: do it now, the C ABI needs the handle
         self.ev_topk = torch.cuda.Event()
         self.ev_done = torch.cuda.Event()
+        with torch.cuda.device(dev):
+            self.ev_topk.record()
+            self.ev_done.record()
         self._gather_pending = False
 
     def rep_slot(self, b: int, h: int) -> int:

@@ -357,6 +357,7 @@ def test_gather_moves_exactly_the_listed_rows_and_respects_the_flag():
     p.gpu.flag[1] = 0
     side = torch.cuda.Stream()
     ev0, ev1 = torch.cuda.Event(), torch.cuda.Event()
+    ev1.record()
     ev0.record()
     p.gpu.gather(stream=side, wait_event=ev0, done_event=ev1)
     torch.cuda.current_stream().wait_event(ev1)
