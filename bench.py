@@ -36,13 +36,16 @@ def main():
     ap.add_argument("--config", type=int, default=4, choices=[2, 3, 4])
     ap.add_argument("--layers", type=int, default=0, help="0 = the config's own layer count")
     ap.add_argument("--ctx", type=int, default=0, help="override the context length (testing)")
-    ap.add_argument("--mode", default="graph", choices=["graph", "eager"])
+    ap.add_argument("--mode", default="step", choices=["step", "graph", "eager"],
+                    help="step: hc_decode_step (native launch loop, two streams); graph: captured HIP graph; eager: Python loop")
     ap.add_argument("--dense", action="store_true", help="uncompressed comparison: all 8 KV heads full")
     ap.add_argument("--no-tier", action="store_true", help="no host tier / gather (attention + monitor only)")
     ap.add_argument("--wg-per-cu", type=int, default=0)
+    ap.add_argument("--serial", action="store_true", help="monitor and gather on the main stream (no overlap)")
     ap.add_argument("--attn-only", action="store_true", help="time hc_decode_attn alone (no monitor, no gather)")
     ap.add_argument("--oracle-seconds", type=float, default=15.0)
     ap.add_argument("--no-oracle", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true", help="skip the eager pass that times the split kernel")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
@@ -72,7 +75,7 @@ def main():
         if ctx is None:
             ctx = R.Context(R.make_config(spec), dev, workgroups_per_cu=args.wg_per_cu or None)
         retrieved, base = I.initial_lists(spec)
-        layers.append(R.LayerRuntime(ctx, spec, w.data, retrieved, base, host_tier=not args.no_tier))
+        layers.append(R.LayerRuntime(ctx, spec, w.data, retrieved, base, host_tier=not args.no_tier, own_scratch=True))
         scheds.append(w.schedule)
         if l < 2 and not args.no_oracle:
             keep[l] = (spec, I.LayerData({k: v.cpu() for k, v in w.data.K.items()},
@@ -98,23 +101,29 @@ def main():
             if args.attn_only:
                 lay.attn(q_cur[l], monitor=False)
             else:
-                lay.step(q_cur[l], side=side if lay.tier is not None else None)
+                lay.step(q_cur[l], side=None if args.serial else side)
 
     def step_for_capture():
-        # same calls; all gathers are joined back before the step ends so that the captured graph is
-        # closed and a refill decided in this step is complete before the next replay starts
+        # the same calls; every layer's side-stream work (monitor, gather) is joined back before the step
+        # ends, so that the captured graph is closed and a refill decided in this step is complete before
+        # the next replay starts
         load_q()
         main = torch.cuda.current_stream()
         for l, lay in enumerate(layers):
             lay.attn(q_cur[l], monitor=not args.attn_only)
             if lay.n_reps and not args.attn_only:
-                lay.monitor()
-                if lay.tier is not None:
+                if args.serial:
+                    lay.monitor()
+                    if lay.tier is not None:
+                        lay.gather()
+                else:
                     lay.ev_topk.record(main)
-                    lay.gather(stream=side, wait_event=lay.ev_topk, done_event=lay.ev_done)
-        for lay in layers:
-            if lay.n_reps and lay.tier is not None and not args.attn_only:
-                main.wait_event(lay.ev_done)
+                    side.wait_event(lay.ev_topk)
+                    lay.monitor(stream=side)
+                    if lay.tier is not None:
+                        lay.gather(stream=side)
+        if not args.attn_only and not args.serial:
+            main.wait_stream(side)
 
     # ---- warm-up (eager) + optional parity spot check against the oracle on layer 0 ----
     flags_hist = []
@@ -128,7 +137,14 @@ def main():
 
     # ---- timed region ----
     graph = None
-    if args.mode == "graph":
+    if args.mode == "step":
+        io = R.make_step_io(layers, q_cur, monitor=not args.attn_only)
+        main_s = torch.cuda.current_stream()
+
+        def run():
+            load_q()
+            hc.hc_decode_step(ctx.handle, io, L, main_s, None if (args.serial or args.attn_only) else side)
+    elif args.mode == "graph":
         cap = torch.cuda.Stream()
         cap.wait_stream(torch.cuda.current_stream())
         graph = torch.cuda.CUDAGraph()
@@ -152,25 +168,25 @@ def main():
     us_per_layer = ms_per_step * 1e3 / L
 
     # ---- kernel-timing pass: the same steps, eager, with the library's event hook around the split kernel ----
-    n_pairs = K * L
+    n_pairs = 0 if args.no_kernel_timing else K * L
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_pairs)]
     for a, b in evs:
         a.record()
         b.record()
     torch.cuda.synchronize()
     i = 0
-    for _ in range(K):
+    for _ in range(K if n_pairs else 0):
         load_q()
         for l, lay in enumerate(layers):
             hc.hc_set_timing_events(ctx.handle, evs[i][0], evs[i][1])
             if args.attn_only:
                 lay.attn(q_cur[l], monitor=False)
             else:
-                lay.step(q_cur[l], side=side if lay.tier is not None else None)
+                lay.step(q_cur[l], side=None if args.serial else side)
             i += 1
     hc.hc_set_timing_events(ctx.handle, None, None)
     torch.cuda.synchronize()
-    kern_ms = np.array([a.elapsed_time(b) for a, b in evs])
+    kern_ms = np.array([a.elapsed_time(b) for a, b in evs]) if n_pairs else np.array([float("nan")])
     kern_us = float(kern_ms.mean() * 1e3)
     achieved = kv_bytes / (kern_us * 1e-6) / 1e9
 
@@ -209,7 +225,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"config{args.config}{' dense' if args.dense else ''}: {spec0.ctx[0]} ctx, {L} layers, "
                                f"B={spec0.B}, {spec0.Hq}q/{spec0.Hkv}kv heads, D=128",
-                   "layers": L, "context": spec0.ctx[0], "mode": args.mode, "host_tier": not args.no_tier,
+                   "layers": L, "context": spec0.ctx[0], "mode": args.mode, "host_tier": not args.no_tier, "overlap_monitor": not args.serial,
                    "kv_bytes_per_layer_step": kv_bytes,
                    "split_workgroups": hc.hc_layer_num_workgroups(layers[0].handle),
                    "split_partials": hc.hc_layer_num_partials(layers[0].handle)},

@@ -149,7 +149,7 @@ hc_status hc_plan_describe(const hc_config* cfg, const hc_head_desc* heads_host,
  *   q           dev, bf16 [B][Hq][D]
  *   out         dev, f32  [B][Hq][D]
  *   lse         dev, f32  [B][Hq]
- *   rep_logits  dev, f32  [num_reps][G][max_ctx], or NULL.  If given, the scaled logits of
+ *   rep_logits  dev, f32  [num_reps][max_ctx][G], or NULL.  If given, the scaled logits of
  *               every pivot's query group over all ctx positions are stored for the monitor.
  *   stream      hipStream_t (NULL = default stream)
  * bf16 inputs, fp32 accumulation; split over the token axis with a second combine pass. */
@@ -158,7 +158,7 @@ hc_status hc_decode_attn(hc_ctx* ctx, const hc_layer* layer, const void* kv_aren
 
 /* Pivot drift monitor (Sec. 4.3, Eq. 9-10; Algorithm 1, the block under "t mod W = 0" with the
  * window read as sliding and tested every step once it holds W values).  For every pivot p:
- *   1. score s[j] = (1/G) sum_g exp(rep_logits[p][g][j] - lse[b, pG+g])        (agg = PROB)
+ *   1. score s[j] = (1/G) sum_g exp(rep_logits[p][j][g] - lse[b, pG+g])        (agg = PROB)
  *      for the candidates j in [sink, ctx-recent); stored to scores (f32 [num_reps][max_ctx]).
  *      With scores_given != 0 this step is skipped and scores is an INPUT.
  *   2. for k = k_mon and every satellite's r: T_k = the k candidates that come first under
@@ -186,6 +186,33 @@ hc_status hc_rep_topk_drift(hc_ctx* ctx, const hc_layer* layer, const float* rep
 hc_status hc_gather_retrieve(hc_ctx* ctx, const hc_layer* layer, const void* host_tier,
                              const int32_t* topk_idx, const int32_t* flag, void* kv_arena,
                              void* stream, void* wait_event, void* done_event);
+
+/* One decode step over a stack of layers (Algorithm 1, the body of the loop over t, for every layer):
+ * for each layer in order, hc_decode_attn on main_stream, then hc_rep_topk_drift and hc_gather_retrieve
+ * on side_stream (NULL = on main_stream, no overlap).  The side work of a layer overlaps the attention of
+ * the following layers; the attention of a layer at the next call waits for that layer's side work of
+ * this call, so a refill decided at step t is used from step t+1.  Launching from native code keeps the
+ * host ahead of the GPU (ten small launches per layer).  All buffers are the caller's, as in the three
+ * calls; scores == NULL (or a layer without pivots) skips monitor and gather for that layer; host_tier ==
+ * NULL skips the gather.  Layers whose monitors overlap other layers' attention need their own
+ * rep_logits, scores, lse, out.  Enqueue-only; not meant for graph capture (it uses per-layer events). */
+typedef struct {
+    hc_layer* layer;
+    const void* kv_arena;     /* dev; also written by the gather */
+    const void* host_tier;    /* pinned, or NULL */
+    const void* q;            /* dev bf16 [B][Hq][D] */
+    float* out;               /* dev [B][Hq][D] */
+    float* lse;               /* dev [B][Hq] */
+    float* rep_logits;        /* dev [num_reps][max_ctx][G] */
+    float* scores;            /* dev [num_reps][max_ctx], or NULL */
+    int32_t* topk_idx;
+    int32_t* base_idx;
+    int32_t* ring;
+    int32_t* inter;
+    int32_t* flag;
+} hc_layer_io;
+hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* layers, int32_t n_layers, void* main_stream,
+                         void* side_stream);
 
 #ifdef __cplusplus
 }

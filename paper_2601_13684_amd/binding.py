@@ -20,7 +20,7 @@ HC_MAX_WINDOW, HC_MAX_K_PER_REP = 64, 8
 
 EXPORTS = ["hc_create", "hc_destroy", "hc_strerror", "hc_last_error", "hc_layer_create", "hc_layer_destroy",
            "hc_layer_num_reps", "hc_layer_rep_slot", "hc_layer_num_workgroups", "hc_layer_num_partials",
-           "hc_set_split", "hc_set_timing_events", "hc_plan_describe", "hc_decode_attn", "hc_rep_topk_drift", "hc_gather_retrieve"]
+           "hc_set_split", "hc_set_timing_events", "hc_plan_describe", "hc_decode_attn", "hc_rep_topk_drift", "hc_gather_retrieve", "hc_decode_step"]
 
 
 class hc_config(C.Structure):
@@ -38,6 +38,11 @@ class hc_plan_info(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_workgroups", "n_partials", "n_reps", "n_lists", "n_satellites",
                                          "max_rows_per_workgroup", "min_rows_per_workgroup", "reserved")] + \
                [("total_rows", C.c_int64), ("rows_covered", C.c_int64)]
+
+
+class hc_layer_io(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("layer", "kv_arena", "host_tier", "q", "out", "lse", "rep_logits", "scores",
+                                          "topk_idx", "base_idx", "ring", "inter", "flag")]
 
 
 class HcError(RuntimeError):
@@ -78,6 +83,7 @@ def lib():
         L.hc_decode_attn.argtypes = [vp] * 8
         L.hc_rep_topk_drift.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
         L.hc_gather_retrieve.argtypes = [vp] * 9
+        L.hc_decode_step.argtypes = [vp, C.POINTER(hc_layer_io), i32, vp, vp]
         for n in EXPORTS:
             if n not in ("hc_strerror", "hc_last_error", "hc_layer_num_reps", "hc_layer_rep_slot",
                          "hc_layer_num_workgroups", "hc_layer_num_partials"):
@@ -204,3 +210,9 @@ def hc_gather_retrieve(ctx: int, layer: int, host_tier: Ptr, topk_idx: Ptr, flag
     _check(lib().hc_gather_retrieve(ctx, layer, _p(host_tier), _p(topk_idx), _p(flag), _p(kv_arena),
                                     _stream(stream), _event(wait_event), _event(done_event)),
            "hc_gather_retrieve", ctx)
+
+
+def hc_decode_step(ctx: int, io, n_layers: int, main_stream=None, side_stream=None) -> None:
+    """io: a ctypes array of hc_layer_io (build it once and reuse it: the q pointers may stay fixed)."""
+    _check(lib().hc_decode_step(ctx, io, n_layers, _stream(main_stream), None if side_stream is None else _stream(side_stream)),
+           "hc_decode_step", ctx)

@@ -115,20 +115,22 @@ __device__ __forceinline__ void qk(const uint32_t (&qreg)[G][8], const Tile& t, 
     }
 }
 
-// Pivot heads keep their scaled logits for the drift monitor: column lane g stores head g's logit.
+// Pivot heads keep their scaled logits for the drift monitor, laid out [position][G]: the first column lane
+// of each row stores the group's G logits as one vector, so a row step writes 8 x 4G contiguous bytes.
 template <int G>
-__device__ __forceinline__ void store_rep(float* __restrict__ rep_row, const float (&s)[G], int max_ctx, int c, bool valid)
+__device__ __forceinline__ void store_rep(float* __restrict__ rep_row, const float (&s)[G], int c, bool valid)
 {
-    // select s[c] with a tree over the bits of c (a chain of compares would be turned into a stack array)
-    float sel[G];
+    if (c != 0 || !valid) return;
+    if (G == 1) {
+        rep_row[0] = s[0] * INV_SQRT_D;
+    } else if (G == 2) {
+        *reinterpret_cast<float2*>(rep_row) = make_float2(s[0] * INV_SQRT_D, s[1] * INV_SQRT_D);
+    } else {
 #pragma unroll
-    for (int g = 0; g < G; ++g) sel[g] = s[g];
-#pragma unroll
-    for (int bit = 1; bit < G; bit <<= 1) {
-#pragma unroll
-        for (int g = 0; g + bit < G; g += 2 * bit) sel[g] = (c & bit) ? sel[g + bit] : sel[g];
+        for (int q = 0; q < G / 4; ++q)
+            reinterpret_cast<float4*>(rep_row)[q] = make_float4(s[4 * q] * INV_SQRT_D, s[4 * q + 1] * INV_SQRT_D,
+                                                                s[4 * q + 2] * INV_SQRT_D, s[4 * q + 3] * INV_SQRT_D);
     }
-    if (c < G && valid) rep_row[(size_t)c * max_ctx] = sel[0] * INV_SQRT_D;
 }
 
 // Exponents of the softmax weights relative to the reference, x[g] = log2(e)/sqrt(D) s[g] - m[g]
@@ -235,7 +237,7 @@ __device__ __forceinline__ void row_step(WaveState<G>& st, const uint32_t (&qreg
 {
     float s[G], x[G], alpha[G];
     qk<G>(qreg, t, s);
-    if (rep_row) store_rep<G>(rep_row, s, max_ctx, c, valid);
+    if (rep_row) store_rep<G>(rep_row, s, c, valid);
     const uint64_t over = exponents<G>(st, s, x, valid);
 #pragma unroll
     for (int g = 0; g < G; ++g) alpha[g] = 1.0f;
@@ -277,19 +279,19 @@ __device__ __forceinline__ void process_rows(WaveState<G>& st, const uint32_t (&
 #pragma unroll 1
     for (; i + 2 <= nfull; i += 2, row += 64, off += 2 * STEP) {
         load_tile(B, Kb, Vb, off + STEP);
-        row_step<G>(st, qreg, A, rep_base ? rep_base + row : nullptr, max_ctx, c, true);
+        row_step<G>(st, qreg, A, rep_base ? rep_base + (size_t)row * G : nullptr, max_ctx, c, true);
         if (i + 2 < nfull) load_tile(A, Kb, Vb, off + 2 * STEP);
-        row_step<G>(st, qreg, B, rep_base ? rep_base + row + 32 : nullptr, max_ctx, c, true);
+        row_step<G>(st, qreg, B, rep_base ? rep_base + (size_t)(row + 32) * G : nullptr, max_ctx, c, true);
     }
     if (i < nfull) {
-        row_step<G>(st, qreg, A, rep_base ? rep_base + row : nullptr, max_ctx, c, true);
+        row_step<G>(st, qreg, A, rep_base ? rep_base + (size_t)row * G : nullptr, max_ctx, c, true);
         row += 32;
     }
 #pragma unroll 1
     for (; row - r < row_end; row += 32) {
         const bool valid = row < row_end;
         load_tile(A, Kb, Vb, (uint32_t)(valid ? row : row_end - 1) * 256u + (uint32_t)c * 16u);
-        row_step<G>(st, qreg, A, rep_base ? rep_base + row : nullptr, max_ctx, c, valid);
+        row_step<G>(st, qreg, A, rep_base ? rep_base + (size_t)row * G : nullptr, max_ctx, c, valid);
     }
 }
 

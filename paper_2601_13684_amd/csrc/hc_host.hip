@@ -104,8 +104,9 @@ extern "C" hc_status hc_create(const hc_config* cfg, hc_ctx** out)
     const size_t misc_w = (size_t)c->max_reps * 4;
     const size_t cnt_w = (size_t)c->max_reps * HC_MAX_K_PER_REP * c->max_chunks * 2;
     const size_t bm_w = (size_t)c->max_reps * (cfg->max_ctx / 32);
+    const size_t hits_w = (size_t)c->max_reps * (c->max_chunks + 1);
     uint32_t* base = nullptr;
-    e = hipMalloc((void**)&base, (hist_w + sel_w + misc_w + cnt_w + bm_w) * sizeof(uint32_t));
+    e = hipMalloc((void**)&base, (hist_w + sel_w + misc_w + cnt_w + bm_w + hits_w) * sizeof(uint32_t));
     if (e != hipSuccess) {
         delete c;
         return e == hipErrorOutOfMemory ? HC_ENOMEM : HC_EHIP;
@@ -115,6 +116,7 @@ extern "C" hc_status hc_create(const hc_config* cfg, hc_ctx** out)
     c->misc = c->sel + sel_w;
     c->cnt = c->misc + misc_w;
     c->bitmap = c->cnt + cnt_w;
+    c->hits = c->bitmap + bm_w;
     *out = c;
     return HC_OK;
 }
@@ -182,6 +184,8 @@ static void layer_free(hc_layer* L)
     (void)hipFree(L->reps);
     (void)hipFree(L->outs);
     (void)hipFree(L->sats);
+    if (L->ev_attn) (void)hipEventDestroy(L->ev_attn);
+    if (L->ev_side) (void)hipEventDestroy(L->ev_side);
     L->magic = 0;
     delete L;
 }
@@ -443,6 +447,8 @@ extern "C" hc_status hc_layer_create(hc_ctx* ctx, const hc_head_desc* hd, hc_lay
     L->rep_slot_of = P.rep_slot_of;
     L->max_r = P.max_r;
     L->max_nchunk = P.max_nchunk;
+    L->max_nk = 1;
+    for (const RepDev& r : P.reps) L->max_nk = std::max(L->max_nk, r.nk);
     L->n_reps = (int)P.reps.size();
     L->n_outs = (int)P.outs.size();
     L->n_sats = (int)P.sats.size();
@@ -456,6 +462,8 @@ extern "C" hc_status hc_layer_create(hc_ctx* ctx, const hc_head_desc* hd, hc_lay
     if (st == HC_OK) st = upload(ctx, P.reps, &L->reps);
     if (st == HC_OK) st = upload(ctx, P.outs, &L->outs);
     if (st == HC_OK) st = upload(ctx, P.sats, &L->sats);
+    if (st == HC_OK && hipEventCreateWithFlags(&L->ev_attn, hipEventDisableTiming) != hipSuccess) st = hc_fail(ctx, HC_EHIP, "hipEventCreate failed");
+    if (st == HC_OK && hipEventCreateWithFlags(&L->ev_side, hipEventDisableTiming) != hipSuccess) st = hc_fail(ctx, HC_EHIP, "hipEventCreate failed");
     if (st != HC_OK) {
         layer_free(L);
         return st;
@@ -530,5 +538,47 @@ extern "C" hc_status hc_gather_retrieve(hc_ctx* ctx, const hc_layer* layer, cons
         if (s != HC_OK) return s;
     }
     if (done_event) HC_HIP(ctx, hipEventRecord((hipEvent_t)done_event, st));
+    return HC_OK;
+}
+
+// One decode step over a stack of layers, launched from native code so that the host keeps ahead of the
+// GPU (a layer is ten small launches).  Per layer: attention on the main stream; then, on the side
+// stream, the monitor and the gather, which thereby overlap the next layers' attention.  The attention of
+// a layer waits for that layer's side work of the previous step (a refill decided at step t is used from
+// step t+1; it also keeps rep_logits / lse from being overwritten while the monitor reads them).
+extern "C" hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* io, int32_t n_layers, void* main_stream,
+                                    void* side_stream)
+{
+    if (!ctx_ok(ctx)) return HC_ESTATE;
+    if (!io || n_layers < 0) return hc_fail(ctx, HC_EINVAL, "hc_decode_step: null argument");
+    hipStream_t ms = (hipStream_t)main_stream, ss = (hipStream_t)side_stream;
+    for (int l = 0; l < n_layers; ++l) {
+        const hc_layer_io& x = io[l];
+        hc_layer* L = x.layer;
+        if (!layer_ok(L) || L->ctx != ctx) return hc_fail(ctx, HC_ESTATE, "hc_decode_step: layer %d does not belong to this context", l);
+        if (L->side_pending) {
+            HC_HIP(ctx, hipStreamWaitEvent(ms, L->ev_side, 0));
+            L->side_pending = false;
+        }
+        const bool mon = L->n_reps > 0 && x.scores != nullptr;
+        hc_status st = hc_decode_attn(ctx, L, x.kv_arena, x.q, x.out, x.lse, mon ? x.rep_logits : nullptr, ms);
+        if (st != HC_OK) return st;
+        if (!mon) continue;
+        hipStream_t run = ss ? ss : ms;
+        if (ss) {
+            HC_HIP(ctx, hipEventRecord(L->ev_attn, ms));
+            HC_HIP(ctx, hipStreamWaitEvent(ss, L->ev_attn, 0));
+        }
+        st = hc_rep_topk_drift(ctx, L, x.rep_logits, x.lse, x.scores, 0, x.topk_idx, x.base_idx, x.ring, x.inter, x.flag, run);
+        if (st != HC_OK) return st;
+        if (x.host_tier) {
+            st = hc_gather_retrieve(ctx, L, x.host_tier, x.topk_idx, x.flag, const_cast<void*>(x.kv_arena), run, nullptr, nullptr);
+            if (st != HC_OK) return st;
+        }
+        if (ss) {
+            HC_HIP(ctx, hipEventRecord(L->ev_side, ss));
+            L->side_pending = true;
+        }
+    }
     return HC_OK;
 }

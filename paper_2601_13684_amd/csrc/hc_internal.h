@@ -9,7 +9,7 @@
 
 constexpr int HC_D = 128;            // head dimension the kernels are written for
 constexpr int HC_UNIT_ROWS = 32;     // split-K granule: 4 waves x 8 rows
-constexpr int HC_SEL_CHUNK = 4096;   // candidates per workgroup in the selection passes
+constexpr int HC_SEL_CHUNK = 1024;   // candidates per workgroup in the selection passes
 constexpr int HC_RADIX_BINS = 2048;  // 11-bit digits (11 + 11 + 10 bits of the 32-bit key)
 
 // One KV head as the kernels see it.
@@ -78,7 +78,8 @@ struct hc_ctx {
     uint32_t* sel = nullptr;       // [max_reps][HC_MAX_K_PER_REP][4]: prefix, remaining k, (tau, need)
     uint32_t* cnt = nullptr;       // [max_reps][HC_MAX_K_PER_REP][max_chunks][2]: greater, equal
     uint32_t* bitmap = nullptr;    // [max_reps][max_ctx/32]
-    uint32_t* misc = nullptr;      // [max_reps][4]: intersection accumulator, ticket
+    uint32_t* misc = nullptr;      // [max_reps][4]: spare
+    uint32_t* hits = nullptr;      // [max_reps][max_chunks+1]: per-chunk |T ∩ baseline|
     int max_chunks = 0;
     size_t zero_words = 0;         // words of the contiguous region cleared at the start of a monitor call
 };
@@ -91,6 +92,7 @@ struct hc_layer {
     int n_reps, n_outs, n_sats;
     int max_r;                     // largest r among satellites
     int max_nchunk;
+    int max_nk;                    // largest number of distinct set sizes of a pivot
     std::vector<int32_t> rep_slot_of;   // [B*Hkv]
     HeadDev* heads = nullptr;
     SegDev* segs = nullptr;
@@ -98,6 +100,9 @@ struct hc_layer {
     RepDev* reps = nullptr;
     OutDev* outs = nullptr;
     SatDev* sats = nullptr;
+    hipEvent_t ev_attn = nullptr;  // hc_decode_step: this layer's attention has been enqueued / its side work is done
+    hipEvent_t ev_side = nullptr;
+    bool side_pending = false;
 };
 
 constexpr uint32_t HC_CTX_MAGIC = 0x48435458u;    // "HCTX"

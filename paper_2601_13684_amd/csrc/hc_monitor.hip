@@ -9,21 +9,31 @@
 // (score descending, index ascending).  The lists are emitted in ascending index order by an
 // ordered compaction (per-chunk counts, then prefix sums).
 //
+// The work is latency-bound, not bandwidth-bound (a few MB, L2-resident), so every kernel is shaped to
+// have few dependent memory round trips: four candidates per thread fetched with one 16-byte load, all set
+// sizes of a pivot handled in the same pass over the scores, no local arrays (no scratch memory) and no
+// device-wide fences (the decision has a kernel of its own instead).  Workgroups are 256 threads with few
+// registers so that they can share compute units with the attention pass of the next layer when the
+// caller runs the monitor on a side stream.
+//
 // Kernels, all on the caller's stream:
 //   mon_prep        clear histograms, selection state, accumulators and the baseline bitmap
 //   mon_score_hist  score + first-digit histogram; scatter the baseline list into the bitmap
-//   mon_hist<2>     find the first digit of every set size; histogram of the second digit
-//   mon_hist<3>     find the second digit; histogram of the third digit
+//   mon_hist<2>     find the first digit of every set size; histograms of the second digit
+//   mon_hist<3>     find the second digit; histograms of the third digit
 //   mon_count       find the threshold key; per-chunk counts of greater / equal keys
-//   mon_write       ordered compaction into topk_idx; |T ∩ baseline| through the bitmap; the last
-//                   workgroup of a pivot's monitored list takes the trigger decision (exact integer
-//                   form of Eq. 10), writes inter / flag / ring and, on a trigger, the new baseline.
+//   mon_write       ordered compaction into topk_idx; |T ∩ baseline| through the bitmap
+//   mon_decide      window update and trigger decision (exact integer form of Eq. 10): writes inter, flag,
+//                   ring and, on a trigger, the new baseline
 #include "hc_internal.h"
 
 namespace {
 
-constexpr int BLK = 256;
-constexpr int PER_THREAD = HC_SEL_CHUNK / BLK;   // 16
+constexpr int BLK = 256;     // small workgroups: they fit beside the attention pass's waves on a compute unit
+constexpr int PER_THREAD = HC_SEL_CHUNK / BLK;   // 4 consecutive candidates per thread
+static_assert(PER_THREAD == 4, "one 16-byte load per thread");
+constexpr int NWAVE = BLK / 64;
+static_assert(NWAVE == 4, "reductions below add four wave sums");
 
 __device__ __forceinline__ uint32_t score_key(float s)
 {
@@ -44,7 +54,7 @@ struct RepWs {
 };
 
 struct Ws {
-    uint32_t *hist, *sel, *misc, *cnt, *bitmap;
+    uint32_t *hist, *sel, *misc, *cnt, *bitmap, *hits;
     int max_chunks, max_ctx;
     __device__ RepWs rep(int r) const
     {
@@ -61,84 +71,130 @@ struct Ws {
     }
 };
 
-// Exclusive prefix sum over the 256 threads of the workgroup; also returns the total.
-__device__ __forceinline__ uint32_t block_exscan(uint32_t v, uint32_t* sm /*[5]*/, uint32_t& total)
+__device__ __forceinline__ uint32_t wave_exscan(uint32_t v, uint32_t& total)
 {
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
     uint32_t inc = v;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
         const uint32_t t = __shfl_up(inc, o);
         if (lane >= o) inc += t;
     }
-    __syncthreads();
-    if (lane == 63) sm[w] = inc;
-    __syncthreads();
-    uint32_t base = 0, tot = 0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const uint32_t x = sm[i];
-        if (i < w) base += x;
-        tot += x;
-    }
-    total = tot;
-    return base + inc - v;
+    total = __shfl(inc, 63);
+    return inc - v;
 }
 
-// In a histogram of `nbins` (<= 2048) digit counts, walking from the highest digit down, find the
-// digit in which the k-th largest element falls and how many of that digit's elements are still
-// needed.  All threads return the same result.
-__device__ __forceinline__ void find_digit(const uint32_t* __restrict__ hist, int nbins, uint32_t k,
-                                           uint32_t* sm /*[8]*/, uint32_t& digit, uint32_t& remaining)
+// Exclusive prefix sum over the workgroup's threads.  sm: NWAVE words.
+__device__ __forceinline__ uint32_t block_exscan(uint32_t v, uint32_t* sm)
 {
-    // thread t owns the 8 digits nbins-1-8t ... nbins-8-8t (descending)
-    uint32_t h[8];
-    uint32_t local = 0;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int b = nbins - 1 - (threadIdx.x * 8 + i);
-        h[i] = (b >= 0) ? hist[b] : 0u;
-        local += h[i];
-    }
-    uint32_t total;
-    uint32_t above = block_exscan(local, sm, total);     // elements in higher digits than mine
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    uint32_t wtot;
+    const uint32_t ex = wave_exscan(v, wtot);
     __syncthreads();
-    if (above < k && k <= above + local) {
+    if (lane == 0) sm[w] = wtot;
+    __syncthreads();
+    uint32_t base = 0;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            if (above < k && k <= above + h[i]) {
-                sm[5] = (uint32_t)(nbins - 1 - (threadIdx.x * 8 + i));
-                sm[6] = k - above;
+    for (int i = 0; i < NWAVE; ++i)
+        if (i < w) base += sm[i];
+    return base + ex;
+}
+
+// In a histogram of nbins (<= 2048) digit counts, walking from the highest digit down, find the digit
+// in which the k-th largest element falls and how many of that digit's elements are still needed.
+// Done by ONE wave (lane l owns 32 consecutive digits); result valid in all its lanes.
+template <int nbins>
+__device__ __forceinline__ void find_digit_wave(const uint32_t* __restrict__ hist, uint32_t k, uint32_t& digit,
+                                                uint32_t& remaining)
+{
+    const int lane = threadIdx.x & 63;
+    constexpr int per = nbins / 64;               // 32 or 16
+    // lane l owns digits nbins-1-l*per ... nbins-(l+1)*per (descending)
+    uint32_t local = 0;
+    const uint4* h4 = reinterpret_cast<const uint4*>(hist + (nbins - (lane + 1) * per));
+    uint4 v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        if (i < per / 4) {
+            v[i] = h4[i];
+            local += v[i].x + v[i].y + v[i].z + v[i].w;
+        }
+    uint32_t tot;
+    uint32_t above = wave_exscan(local, tot);      // elements in higher digits than this lane's
+    const bool mine = above < k && k <= above + local;
+    uint32_t d = 0, rem = 0;
+    if (mine) {
+        // walk this lane's digits from the highest (last word of its span) down
+#pragma unroll
+        for (int i = per - 1; i >= 0; --i) {
+            const uint4 q = v[i >> 2];
+            const uint32_t c = (i & 3) == 0 ? q.x : (i & 3) == 1 ? q.y : (i & 3) == 2 ? q.z : q.w;
+            if (above < k && k <= above + c) {
+                d = (uint32_t)(nbins - (lane + 1) * per + i);
+                rem = k - above;
             }
-            above += h[i];
+            above += c;
         }
     }
-    __syncthreads();
-    digit = sm[5];
-    remaining = sm[6];
-    __syncthreads();
+    const uint64_t who = __builtin_amdgcn_ballot_w64(mine);
+    const int src = who ? __builtin_ctzll(who) : 0;
+    digit = __shfl(d, src);
+    remaining = __shfl(rem, src);
 }
 
-__global__ __launch_bounds__(BLK) void mon_prep(Ws ws, const RepDev* __restrict__ reps)
+__global__ __launch_bounds__(256) void mon_prep(Ws ws, const RepDev* __restrict__ reps)
 {
     const int rep = blockIdx.y;
     const RepWs w = ws.rep(rep);
     const size_t hist_words = (size_t)(1 + 2 * HC_MAX_K_PER_REP) * HC_RADIX_BINS;
     const size_t bm_words = (size_t)(reps[rep].hi + 31) / 32;
-    const size_t stride = (size_t)gridDim.x * BLK;
-    for (size_t i = (size_t)blockIdx.x * BLK + threadIdx.x; i < hist_words; i += stride) w.h1[i] = 0u;
-    for (size_t i = (size_t)blockIdx.x * BLK + threadIdx.x; i < bm_words; i += stride) w.bitmap[i] = 0u;
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < hist_words; i += stride) w.h1[i] = 0u;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < bm_words; i += stride) w.bitmap[i] = 0u;
     if (blockIdx.x == 0) {
         if (threadIdx.x < HC_MAX_K_PER_REP * 4) w.sel[threadIdx.x] = 0u;
         if (threadIdx.x < 4) w.misc[threadIdx.x] = 0u;
     }
 }
 
+// Score of candidate j from the G scaled logits of its row (rep_logits is [ctx][G] per pivot).
+template <int G>
+__device__ __forceinline__ float score_of(const float* __restrict__ lrow, int j, const float (&lse)[G], int agg)
+{
+    float l[G];
+    if (G == 1) {
+        l[0] = lrow[j];
+    } else if (G == 2) {
+        const float2 v = reinterpret_cast<const float2*>(lrow)[j];
+        l[0] = v.x; l[1] = v.y;
+    } else {
+#pragma unroll
+        for (int q = 0; q < G / 4; ++q) {
+            const float4 v = reinterpret_cast<const float4*>(lrow)[(size_t)j * (G / 4) + q];
+            l[4 * q] = v.x; l[4 * q + 1] = v.y; l[4 * q + 2] = v.z; l[4 * q + 3] = v.w;
+        }
+    }
+    float a;
+    if (agg == HC_AGG_PROB) {
+        a = 0.f;
+#pragma unroll
+        for (int g = 0; g < G; ++g) a += expf(l[g] - lse[g]);
+    } else if (G == 4) {
+        a = (l[0] + l[1]) + (l[2] + l[3]);
+    } else {
+        a = 0.f;
+#pragma unroll
+        for (int g = 0; g < G; ++g) a += l[g];
+    }
+    return a * (1.0f / (float)G);
+}
+
+template <int G>
 __global__ __launch_bounds__(BLK) void mon_score_hist(Ws ws, const RepDev* __restrict__ reps,
                                                       const float* __restrict__ rep_logits,
                                                       const float* __restrict__ lse, float* __restrict__ scores,
-                                                      int scores_given, int G, int agg,
-                                                      const int32_t* __restrict__ base_idx, int max_k)
+                                                      int scores_given, int agg, const int32_t* __restrict__ base_idx,
+                                                      int max_k)
 {
     __shared__ uint32_t sh[HC_RADIX_BINS];
     const int rep = blockIdx.y;
@@ -157,125 +213,153 @@ __global__ __launch_bounds__(BLK) void mon_score_hist(Ws ws, const RepDev* __res
 
     float* srow = scores + (size_t)rep * ws.max_ctx;
     const float* lrow = rep_logits ? rep_logits + (size_t)rep * G * ws.max_ctx : nullptr;
-    float l[8];
-    if (!scores_given && agg == HC_AGG_PROB)
-        for (int g = 0; g < G; ++g) l[g] = lse[(size_t)rd.bh * G + g];
-    const float invG = 1.0f / (float)G;
+    float l[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) l[g] = (!scores_given && agg == HC_AGG_PROB) ? lse[(size_t)rd.bh * G + g] : 0.f;
     const int first = rd.lo + blockIdx.x * HC_SEL_CHUNK;
+    float s[PER_THREAD];
+#pragma unroll
+    for (int i = 0; i < PER_THREAD; ++i) {       // candidate first + i*BLK + t: coalesced, loads independent
+        const int j = first + i * BLK + threadIdx.x;
+        s[i] = 0.f;
+        if (j < rd.hi) s[i] = scores_given ? srow[j] : score_of<G>(lrow, j, l, agg);
+    }
+#pragma unroll
     for (int i = 0; i < PER_THREAD; ++i) {
         const int j = first + i * BLK + threadIdx.x;
-        if (j >= rd.hi) break;
-        float s;
-        if (scores_given) {
-            s = srow[j];
-        } else {
-            float a = 0.f;
-            if (agg == HC_AGG_PROB) {
-                for (int g = 0; g < G; ++g) a += expf(lrow[(size_t)g * ws.max_ctx + j] - l[g]);
-            } else if (G == 4) {
-                a = (lrow[j] + lrow[(size_t)ws.max_ctx + j]) + (lrow[(size_t)2 * ws.max_ctx + j] + lrow[(size_t)3 * ws.max_ctx + j]);
-            } else {
-                for (int g = 0; g < G; ++g) a += lrow[(size_t)g * ws.max_ctx + j];
-            }
-            s = a * invG;
-            srow[j] = s;
+        if (j < rd.hi) {
+            if (!scores_given) srow[j] = s[i];
+            atomicAdd(&sh[score_key(s[i]) >> 21], 1u);
         }
-        atomicAdd(&sh[score_key(s) >> 21], 1u);
     }
     __syncthreads();
     for (int i = threadIdx.x; i < HC_RADIX_BINS; i += BLK)
         if (sh[i]) atomicAdd(&w.h1[i], sh[i]);
 }
 
+// The four candidates of a thread: positions first4 .. first4+3 (first4 a multiple of 4, so one
+// 16-byte load), of which those inside [lo, hi) count.
+__device__ __forceinline__ void load_keys(const float* __restrict__ srow, int first4, int lo, int hi, uint32_t (&key)[4],
+                                          bool (&in)[4])
+{
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (first4 < hi) v = *reinterpret_cast<const float4*>(srow + first4);     // row stride is a multiple of 64: in bounds
+    const float f[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        in[i] = first4 + i >= lo && first4 + i < hi;
+        key[i] = score_key(f[i]);
+    }
+}
+
 // PASS 2: digit two (bits 20..10) among keys whose first digit matches; PASS 3: digit three (bits 9..0)
-// among keys whose upper 22 bits match.
+// among keys whose upper 22 bits match.  One workgroup handles every set size of its pivot: wave ks
+// finds the digit of set size ks, then all waves histogram their candidates for each set size.
 template <int PASS>
 __global__ __launch_bounds__(BLK) void mon_hist(Ws ws, const RepDev* __restrict__ reps, const float* __restrict__ scores)
 {
-    __shared__ uint32_t sh[HC_RADIX_BINS];
-    __shared__ uint32_t sm[8];
-    const int rep = blockIdx.y / HC_MAX_K_PER_REP, ks = blockIdx.y % HC_MAX_K_PER_REP;
+    extern __shared__ uint32_t sh[];              // [nk][HC_RADIX_BINS]
+    __shared__ uint32_t sm_prefix[HC_MAX_K_PER_REP];
+    const int rep = blockIdx.y;
     const RepDev rd = reps[rep];
-    if (ks >= rd.nk || (int)blockIdx.x >= rd.nchunk) return;
+    const int lo4 = rd.lo & ~3;
+    const int nchunk = (rd.hi - lo4 + HC_SEL_CHUNK - 1) / HC_SEL_CHUNK;
+    if ((int)blockIdx.x >= nchunk) return;
     const RepWs w = ws.rep(rep);
-    for (int i = threadIdx.x; i < HC_RADIX_BINS; i += BLK) sh[i] = 0u;
+    for (int i = threadIdx.x; i < rd.nk * HC_RADIX_BINS; i += BLK) sh[i] = 0u;
 
-    uint32_t prefix, remaining;
-    if (PASS == 2) {
-        find_digit(w.h1, HC_RADIX_BINS, (uint32_t)rd.k[ks], sm, prefix, remaining);
-    } else {
-        uint32_t d2;
-        find_digit(w.h2 + (size_t)ks * HC_RADIX_BINS, HC_RADIX_BINS, w.sel[ks * 4 + 1], sm, d2, remaining);
-        prefix = (w.sel[ks * 4 + 0] << 11) | d2;
-    }
-    if (blockIdx.x == 0 && threadIdx.x == 0) {   // state for the next pass (same value from every workgroup)
+    for (int ks = threadIdx.x >> 6; ks < rd.nk; ks += NWAVE) {     // one wave per set size
+        uint32_t prefix, remaining;
         if (PASS == 2) {
-            w.sel[ks * 4 + 0] = prefix;
-            w.sel[ks * 4 + 1] = remaining;
+            find_digit_wave<HC_RADIX_BINS>(w.h1, (uint32_t)reps[rep].k[ks], prefix, remaining);   // (indexing the register copy would spill it)
         } else {
-            w.sel[ks * 4 + 2] = prefix;
-            w.sel[ks * 4 + 3] = remaining;
+            uint32_t d2;
+            find_digit_wave<HC_RADIX_BINS>(w.h2 + (size_t)ks * HC_RADIX_BINS, w.sel[ks * 4 + 1], d2, remaining);
+            prefix = (w.sel[ks * 4 + 0] << 11) | d2;
+        }
+        if ((threadIdx.x & 63) == 0) {
+            sm_prefix[ks] = prefix;
+            if (blockIdx.x == 0) {   // state for the next pass (every workgroup computes the same value)
+                w.sel[ks * 4 + (PASS == 2 ? 0 : 2)] = prefix;
+                w.sel[ks * 4 + (PASS == 2 ? 1 : 3)] = remaining;
+            }
         }
     }
-    const float* srow = scores + (size_t)rep * ws.max_ctx;
-    const int first = rd.lo + blockIdx.x * HC_SEL_CHUNK;
-    for (int i = 0; i < PER_THREAD; ++i) {
-        const int j = first + i * BLK + threadIdx.x;
-        if (j >= rd.hi) break;
-        const uint32_t key = score_key(srow[j]);
-        if (PASS == 2) {
-            if ((key >> 21) == prefix) atomicAdd(&sh[(key >> 10) & 0x7ffu], 1u);
-        } else {
-            if ((key >> 10) == prefix) atomicAdd(&sh[key & 0x3ffu], 1u);
+    uint32_t key[4];
+    bool in[4];
+    load_keys(scores + (size_t)rep * ws.max_ctx, lo4 + blockIdx.x * HC_SEL_CHUNK + threadIdx.x * 4, rd.lo, rd.hi, key, in);
+    __syncthreads();
+    for (int ks = 0; ks < rd.nk; ++ks) {
+        const uint32_t prefix = sm_prefix[ks];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (!in[i]) continue;
+            if (PASS == 2) {
+                if ((key[i] >> 21) == prefix) atomicAdd(&sh[ks * HC_RADIX_BINS + ((key[i] >> 10) & 0x7ffu)], 1u);
+            } else {
+                if ((key[i] >> 10) == prefix) atomicAdd(&sh[ks * HC_RADIX_BINS + (key[i] & 0x3ffu)], 1u);
+            }
         }
     }
     __syncthreads();
-    uint32_t* gh = (PASS == 2 ? w.h2 : w.h3) + (size_t)ks * HC_RADIX_BINS;
-    for (int i = threadIdx.x; i < HC_RADIX_BINS; i += BLK)
+    uint32_t* gh = PASS == 2 ? w.h2 : w.h3;
+    for (int i = threadIdx.x; i < rd.nk * HC_RADIX_BINS; i += BLK)
         if (sh[i]) atomicAdd(&gh[i], sh[i]);
 }
 
 __global__ __launch_bounds__(BLK) void mon_count(Ws ws, const RepDev* __restrict__ reps, const float* __restrict__ scores)
 {
-    __shared__ uint32_t sm[8];
-    __shared__ uint32_t red[2][4];
-    const int rep = blockIdx.y / HC_MAX_K_PER_REP, ks = blockIdx.y % HC_MAX_K_PER_REP;
+    __shared__ uint32_t sm_tau[HC_MAX_K_PER_REP];
+    __shared__ uint32_t red[HC_MAX_K_PER_REP][2][NWAVE];
+    const int rep = blockIdx.y;
     const RepDev rd = reps[rep];
-    if (ks >= rd.nk || (int)blockIdx.x >= rd.nchunk) return;
+    const int lo4 = rd.lo & ~3;
+    const int nchunk = (rd.hi - lo4 + HC_SEL_CHUNK - 1) / HC_SEL_CHUNK;
+    if ((int)blockIdx.x >= nchunk) return;
     const RepWs w = ws.rep(rep);
-    uint32_t d3, need;
-    find_digit(w.h3 + (size_t)ks * HC_RADIX_BINS, 1024, w.sel[ks * 4 + 3], sm, d3, need);
-    const uint32_t tau = (w.sel[ks * 4 + 2] << 10) | d3;
-    const float* srow = scores + (size_t)rep * ws.max_ctx;
-    const int first = rd.lo + blockIdx.x * HC_SEL_CHUNK;
-    uint32_t gt = 0, eq = 0;
-    for (int i = 0; i < PER_THREAD; ++i) {
-        const int j = first + i * BLK + threadIdx.x;
-        if (j >= rd.hi) break;
-        const uint32_t key = score_key(srow[j]);
-        gt += key > tau;
-        eq += key == tau;
+    const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int ks = wv; ks < rd.nk; ks += NWAVE) {
+        uint32_t d3, need;
+        find_digit_wave<1024>(w.h3 + (size_t)ks * HC_RADIX_BINS, w.sel[ks * 4 + 3], d3, need);
+        const uint32_t tau = (w.sel[ks * 4 + 2] << 10) | d3;
+        if (lane == 0) {
+            sm_tau[ks] = tau;
+            // The first workgroup leaves tau / need for mon_write in the first two words, which this
+            // kernel does not read (words 2 and 3 are still being read by the other workgroups).
+            if (blockIdx.x == 0) {
+                w.sel[ks * 4 + 0] = tau;
+                w.sel[ks * 4 + 1] = need;
+            }
+        }
     }
-    for (int o = 32; o > 0; o >>= 1) {
-        gt += __shfl_xor(gt, o);
-        eq += __shfl_xor(eq, o);
-    }
-    if ((threadIdx.x & 63) == 0) {
-        red[0][threadIdx.x >> 6] = gt;
-        red[1][threadIdx.x >> 6] = eq;
+    uint32_t key[4];
+    bool in[4];
+    load_keys(scores + (size_t)rep * ws.max_ctx, lo4 + blockIdx.x * HC_SEL_CHUNK + threadIdx.x * 4, rd.lo, rd.hi, key, in);
+    __syncthreads();
+    for (int ks = 0; ks < rd.nk; ++ks) {
+        const uint32_t tau = sm_tau[ks];
+        uint32_t gt = 0, eq = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            gt += in[i] && key[i] > tau;
+            eq += in[i] && key[i] == tau;
+        }
+        for (int o = 32; o > 0; o >>= 1) {
+            gt += __shfl_xor(gt, o);
+            eq += __shfl_xor(eq, o);
+        }
+        if (lane == 0) {
+            red[ks][0][wv] = gt;
+            red[ks][1][wv] = eq;
+        }
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t* c = w.cnt + ((size_t)ks * ws.max_chunks + blockIdx.x) * 2;
-        c[0] = red[0][0] + red[0][1] + red[0][2] + red[0][3];
-        c[1] = red[1][0] + red[1][1] + red[1][2] + red[1][3];
-    }
-    // The first workgroup leaves tau / need for mon_write.  It must not overwrite sel[2..3] before
-    // every other workgroup of this launch has read them, so the pair goes to the (now dead) first
-    // two words, which this kernel does not read.
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        w.sel[ks * 4 + 0] = tau;
-        w.sel[ks * 4 + 1] = need;
+    if (threadIdx.x < rd.nk * 2) {
+        const int ks = threadIdx.x >> 1, which = threadIdx.x & 1;
+        uint32_t t = 0;
+#pragma unroll
+        for (int i = 0; i < NWAVE; ++i) t += red[ks][which][i];
+        w.cnt[((size_t)ks * ws.max_chunks + blockIdx.x) * 2 + which] = t;
     }
 }
 
@@ -285,64 +369,60 @@ struct DriftCfg {
 
 __global__ __launch_bounds__(BLK) void mon_write(Ws ws, const RepDev* __restrict__ reps, const OutDev* __restrict__ outs,
                                                  const float* __restrict__ scores, int32_t* __restrict__ topk_idx,
-                                                 int32_t* __restrict__ base_idx, int32_t* __restrict__ ring,
-                                                 int32_t* __restrict__ inter_out, int32_t* __restrict__ flag_out,
                                                  DriftCfg cfg)
 {
-    __shared__ uint32_t sm[8];
+    __shared__ uint32_t sm[NWAVE];
     __shared__ uint32_t sm_off[2];
-    __shared__ uint32_t sm_last;
     const OutDev od = outs[blockIdx.y];
     const RepDev rd = reps[od.rep];
     const int chunk = blockIdx.x;
-    if (chunk >= rd.nchunk) return;
+    const int lo4 = rd.lo & ~3;
+    const int nchunk = (rd.hi - lo4 + HC_SEL_CHUNK - 1) / HC_SEL_CHUNK;
+    if (chunk >= nchunk) return;
     const RepWs w = ws.rep(od.rep);
     const int ks = od.kslot;
     const uint32_t tau = w.sel[ks * 4 + 0], need = w.sel[ks * 4 + 1];
-    const int k = rd.k[ks];
+    const int k = reps[od.rep].k[ks];
 
-    // Prefix over the chunks before mine: equal-keyed candidates seen, and list entries emitted.
-    // A chunk emits all its greater keys plus as many equal keys as are still needed.
-    {
+    uint32_t key[4];
+    bool in[4];
+    const int first4 = lo4 + chunk * HC_SEL_CHUNK + threadIdx.x * 4;
+    load_keys(scores + (size_t)od.rep * ws.max_ctx, first4, rd.lo, rd.hi, key, in);
+
+    // Prefix over the chunks before mine: equal-keyed candidates seen, and list entries emitted.  A chunk
+    // emits all its greater keys plus as many equal keys as are still needed.  Wave 0 scans the chunk
+    // counts, 64 at a time.
+    if (threadIdx.x < 64) {
         const uint32_t* cnt = w.cnt + (size_t)ks * ws.max_chunks * 2;
-        // equal-key prefix is sequential in nature; chunks are few (<= max_ctx/4096), so one thread walks them
+        uint32_t eq_before = 0, emitted = 0;
+        for (int c0 = 0; c0 < chunk; c0 += 64) {
+            const int c = c0 + threadIdx.x;
+            const uint32_t g = c < chunk ? cnt[c * 2] : 0u, e = c < chunk ? cnt[c * 2 + 1] : 0u;
+            uint32_t etot;
+            const uint32_t eprev = eq_before + wave_exscan(e, etot);
+            const uint32_t left = need > eprev ? need - eprev : 0u;
+            uint32_t mine = g + (e < left ? e : left);
+            for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o);
+            emitted += mine;
+            eq_before += etot;
+        }
         if (threadIdx.x == 0) {
-            uint32_t eq_before = 0, emitted = 0;
-            for (int c = 0; c < chunk; ++c) {
-                const uint32_t g = cnt[c * 2], e = cnt[c * 2 + 1];
-                const uint32_t left = need > eq_before ? need - eq_before : 0u;
-                emitted += g + (e < left ? e : left);
-                eq_before += e;
-            }
             sm_off[0] = eq_before;
             sm_off[1] = emitted;
         }
-        __syncthreads();
     }
-    const uint32_t eq_before_chunk = sm_off[0];
-    const uint32_t out_base = sm_off[1];
-
-    // each thread owns 16 consecutive candidates so that the compaction keeps index order
-    const float* srow = scores + (size_t)od.rep * ws.max_ctx;
-    const int first = rd.lo + chunk * HC_SEL_CHUNK + threadIdx.x * PER_THREAD;
-    uint32_t keys[PER_THREAD];
     uint32_t my_eq = 0;
 #pragma unroll
-    for (int i = 0; i < PER_THREAD; ++i) {
-        const int j = first + i;
-        keys[i] = (j < rd.hi) ? score_key(srow[j]) : 0u;
-        if (j < rd.hi && keys[i] == tau) ++my_eq;
-    }
-    uint32_t tot;
-    uint32_t eq_rank = eq_before_chunk + block_exscan(my_eq, sm, tot);
-    __syncthreads();
+    for (int i = 0; i < 4; ++i) my_eq += in[i] && key[i] == tau;
+    const uint32_t eq_local = block_exscan(my_eq, sm);       // its barriers also publish sm_off
+    uint32_t eq_rank = sm_off[0] + eq_local;
+    const uint32_t out_base = sm_off[1];
     uint32_t selmask = 0, my_sel = 0;
 #pragma unroll
-    for (int i = 0; i < PER_THREAD; ++i) {
-        const int j = first + i;
-        if (j >= rd.hi) break;
-        bool s = keys[i] > tau;
-        if (keys[i] == tau) {
+    for (int i = 0; i < 4; ++i) {
+        if (!in[i]) continue;
+        bool s = key[i] > tau;
+        if (key[i] == tau) {
             s = eq_rank < need;
             ++eq_rank;
         }
@@ -351,72 +431,96 @@ __global__ __launch_bounds__(BLK) void mon_write(Ws ws, const RepDev* __restrict
             ++my_sel;
         }
     }
-    uint32_t pos = out_base + block_exscan(my_sel, sm, tot);
+    uint32_t pos = out_base + block_exscan(my_sel, sm);
     int32_t* dst = topk_idx + (size_t)od.row * cfg.max_k;
     uint32_t hits = 0;
 #pragma unroll
-    for (int i = 0; i < PER_THREAD; ++i) {
+    for (int i = 0; i < 4; ++i) {
         if (selmask & (1u << i)) {
-            const int j = first + i;
+            const int j = first4 + i;
             if (pos < (uint32_t)k) dst[pos] = j;     // pos < k always holds; the guard keeps a corrupt state in bounds
             ++pos;
             if (od.is_mon) hits += (w.bitmap[j >> 5] >> (j & 31)) & 1u;
         }
     }
     if (!od.is_mon) return;
-
-    // ---- monitored list only: intersection size, then the decision by the last workgroup ----
+    // per-chunk hit counts, summed by mon_decide (hundreds of atomics on one word would serialise)
     for (int o = 32; o > 0; o >>= 1) hits += __shfl_xor(hits, o);
-    if ((threadIdx.x & 63) == 0 && hits) atomicAdd(&w.misc[0], hits);
-    __threadfence();          // my list entries and my hits are visible before my ticket
     __syncthreads();
-    if (threadIdx.x == 0) sm_last = (atomicAdd(&w.misc[1], 1u) == (uint32_t)rd.nchunk - 1u);
+    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = hits;
     __syncthreads();
-    if (!sm_last) return;
-    __threadfence();          // see what the other workgroups wrote
+    if (threadIdx.x == 0) ws.hits[(size_t)od.rep * (ws.max_chunks + 1) + chunk] = sm[0] + sm[1] + sm[2] + sm[3];
+}
+
+// One workgroup per pivot, after mon_write has completed (the kernel boundary makes its lists and the
+// intersection count visible): window update, decision, baseline update.
+__global__ __launch_bounds__(BLK) void mon_decide(Ws ws, const RepDev* __restrict__ reps, const int32_t* __restrict__ topk_idx,
+                                                  int32_t* __restrict__ base_idx, int32_t* __restrict__ ring,
+                                                  int32_t* __restrict__ inter_out, int32_t* __restrict__ flag_out,
+                                                  DriftCfg cfg)
+{
+    // The lower median is found by ranking (no local arrays: they would live in scratch memory, and a
+    // kernel that needs scratch is far slower to launch).
+    __shared__ int32_t sm_ring[HC_MAX_WINDOW];
+    __shared__ int32_t sm_med;
+    __shared__ int32_t sm_trig;
+    const RepDev rd = reps[blockIdx.x];
+    const int k = rd.k[0];
+    int32_t* rg = ring + (size_t)rd.bh * (cfg.window + 1);
+    int n = rg[0];
+    if (n < 0 || n > cfg.window) n = 0;
+    const int drop = n == cfg.window ? 1 : 0;        // sliding window: the oldest value leaves
+    __shared__ uint32_t sm_hits[NWAVE];
+    {
+        const int lo4 = rd.lo & ~3;
+        const int nchunk = (rd.hi - lo4 + HC_SEL_CHUNK - 1) / HC_SEL_CHUNK;
+        uint32_t h = 0;
+        for (int c = threadIdx.x; c < nchunk; c += BLK) h += ws.hits[(size_t)blockIdx.x * (ws.max_chunks + 1) + c];
+        for (int o = 32; o > 0; o >>= 1) h += __shfl_xor(h, o);
+        if ((threadIdx.x & 63) == 0) sm_hits[threadIdx.x >> 6] = h;
+        __syncthreads();
+    }
+    const int32_t inter = (int32_t)(sm_hits[0] + sm_hits[1] + sm_hits[2] + sm_hits[3]);
+    const int m = n - drop + 1;                      // values in the window after the push
+    if ((int)threadIdx.x < m) sm_ring[threadIdx.x] = (int)threadIdx.x == m - 1 ? inter : rg[1 + drop + threadIdx.x];
+    __syncthreads();
+    if ((int)threadIdx.x < m) {
+        const int32_t v = sm_ring[threadIdx.x];
+        int rank = 0;
+        for (int j = 0; j < m; ++j) rank += sm_ring[j] < v || (sm_ring[j] == v && j < (int)threadIdx.x);
+        if (rank == (m - 1) / 2) sm_med = v;         // lower median
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < m) rg[1 + threadIdx.x] = sm_ring[threadIdx.x];
     if (threadIdx.x == 0) {
-        const int32_t inter = (int32_t)__hip_atomic_load(&w.misc[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        int32_t* rg = ring + (size_t)rd.bh * (cfg.window + 1);
-        int n = rg[0];
-        if (n < 0 || n > cfg.window) n = 0;
-        if (n == cfg.window) {                       // sliding window: drop the oldest value
-            for (int i = 1; i < cfg.window; ++i) rg[i] = rg[i + 1];
-            n = cfg.window - 1;
-        }
-        rg[1 + n] = inter;
-        ++n;
         int trig = 0;
-        if (n == cfg.window) {
-            int32_t tmp[HC_MAX_WINDOW];
-            for (int i = 0; i < n; ++i) tmp[i] = rg[1 + i];
-            for (int i = 1; i < n; ++i) {            // insertion sort, W <= 64
-                const int32_t v = tmp[i];
-                int p = i - 1;
-                while (p >= 0 && tmp[p] > v) {
-                    tmp[p + 1] = tmp[p];
-                    --p;
-                }
-                tmp[p + 1] = v;
-            }
-            const long long med = tmp[(n - 1) / 2];  // lower median
+        if (m == cfg.window) {
+            const long long med = sm_med;
             const long long kk = k;
             if (cfg.metric == HC_METRIC_OVERLAP)
                 trig = med * cfg.tau_den < (long long)cfg.tau_num * kk;                     // med/k < tau
             else
                 trig = med * cfg.tau_den < (long long)cfg.tau_num * (2 * kk - med);         // med/(2k-med) < tau
         }
-        if (trig) n = 0;                             // the window restarts after a retrieval
-        rg[0] = n;
+        rg[0] = trig ? 0 : m;                        // the window restarts after a retrieval
         inter_out[rd.bh] = inter;
         flag_out[rd.bh] = trig;
-        sm[7] = (uint32_t)trig;
+        sm_trig = trig;
     }
     __syncthreads();
-    if (sm[7]) {                                     // K_base <- K_t
+    if (sm_trig) {                                   // K_base <- K_t
+        const int32_t* src = topk_idx + (size_t)rd.bh * cfg.max_k;
         int32_t* base = base_idx + (size_t)rd.bh * cfg.max_k;
-        for (int i = threadIdx.x; i < k; i += BLK)
-            base[i] = __hip_atomic_load(&dst[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int i = threadIdx.x; i < k; i += BLK) base[i] = src[i];
     }
+}
+
+template <int G>
+void launch_score_hist(Ws ws, const hc_layer* L, const float* rep_logits, const float* lse, float* scores,
+                       int scores_given, int agg, const int32_t* base_idx, int max_k, hipStream_t st)
+{
+    mon_score_hist<G><<<dim3(L->max_nchunk, L->n_reps), dim3(BLK), 0, st>>>(ws, L->reps, rep_logits, lse, scores,
+                                                                            scores_given, agg, base_idx, max_k);
 }
 
 }   // namespace
@@ -425,24 +529,30 @@ hc_status hc_launch_monitor(hc_ctx* ctx, const hc_layer* L, const float* rep_log
                             int scores_given, int32_t* topk_idx, int32_t* base_idx, int32_t* ring, int32_t* inter,
                             int32_t* flag, hipStream_t st)
 {
-    Ws ws{ctx->hist, ctx->sel, ctx->misc, ctx->cnt, ctx->bitmap, ctx->max_chunks, ctx->cfg.max_ctx};
+    Ws ws{ctx->hist, ctx->sel, ctx->misc, ctx->cnt, ctx->bitmap, ctx->hits, ctx->max_chunks, ctx->cfg.max_ctx};
     const hc_config& c = ctx->cfg;
-    const dim3 blk(BLK);
-    mon_prep<<<dim3(16, L->n_reps), blk, 0, st>>>(ws, L->reps);
+    mon_prep<<<dim3(16, L->n_reps), dim3(256), 0, st>>>(ws, L->reps);
     HC_HIP(ctx, hipGetLastError());
-    mon_score_hist<<<dim3(L->max_nchunk, L->n_reps), blk, 0, st>>>(ws, L->reps, rep_logits, lse, scores, scores_given,
-                                                                   ctx->G, c.agg, base_idx, c.max_k);
+    switch (ctx->G) {
+    case 1: launch_score_hist<1>(ws, L, rep_logits, lse, scores, scores_given, c.agg, base_idx, c.max_k, st); break;
+    case 2: launch_score_hist<2>(ws, L, rep_logits, lse, scores, scores_given, c.agg, base_idx, c.max_k, st); break;
+    case 4: launch_score_hist<4>(ws, L, rep_logits, lse, scores, scores_given, c.agg, base_idx, c.max_k, st); break;
+    default: launch_score_hist<8>(ws, L, rep_logits, lse, scores, scores_given, c.agg, base_idx, c.max_k, st); break;
+    }
     HC_HIP(ctx, hipGetLastError());
-    const dim3 gk(L->max_nchunk, L->n_reps * HC_MAX_K_PER_REP);
-    mon_hist<2><<<gk, blk, 0, st>>>(ws, L->reps, scores);
+    // the later passes start at a multiple of 4 positions, which can add one chunk
+    const dim3 gk(L->max_nchunk + 1, L->n_reps);
+    const size_t hist_lds = (size_t)L->max_nk * HC_RADIX_BINS * sizeof(uint32_t);
+    mon_hist<2><<<gk, dim3(BLK), hist_lds, st>>>(ws, L->reps, scores);
     HC_HIP(ctx, hipGetLastError());
-    mon_hist<3><<<gk, blk, 0, st>>>(ws, L->reps, scores);
+    mon_hist<3><<<gk, dim3(BLK), hist_lds, st>>>(ws, L->reps, scores);
     HC_HIP(ctx, hipGetLastError());
-    mon_count<<<gk, blk, 0, st>>>(ws, L->reps, scores);
+    mon_count<<<gk, dim3(BLK), 0, st>>>(ws, L->reps, scores);
     HC_HIP(ctx, hipGetLastError());
     DriftCfg dc{c.window, c.metric, c.tau_num, c.tau_den, c.max_k};
-    mon_write<<<dim3(L->max_nchunk, L->n_outs), blk, 0, st>>>(ws, L->reps, L->outs, scores, topk_idx, base_idx, ring,
-                                                             inter, flag, dc);
+    mon_write<<<dim3(L->max_nchunk + 1, L->n_outs), dim3(BLK), 0, st>>>(ws, L->reps, L->outs, scores, topk_idx, dc);
+    HC_HIP(ctx, hipGetLastError());
+    mon_decide<<<dim3(L->n_reps), dim3(BLK), 0, st>>>(ws, L->reps, topk_idx, base_idx, ring, inter, flag, dc);
     HC_HIP(ctx, hipGetLastError());
     return HC_OK;
 }

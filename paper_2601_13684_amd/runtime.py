@@ -68,10 +68,10 @@ class Context:
         self._scratch: Dict[int, Tuple[torch.Tensor, torch.Tensor]] = {}
 
     def scratch(self, n_reps: int) -> Tuple[torch.Tensor, torch.Tensor]:
-        """(rep_logits [n_reps,G,max_ctx] f32, scores [n_reps,max_ctx] f32), shared by layers."""
+        """(rep_logits [n_reps,max_ctx,G] f32, scores [n_reps,max_ctx] f32), shared by layers."""
         n = max(1, n_reps)
         if n not in self._scratch:
-            self._scratch[n] = (torch.zeros((n, self.G, self.cfg.max_ctx), dtype=torch.float32, device=self.device),
+            self._scratch[n] = (torch.zeros((n, self.cfg.max_ctx, self.G), dtype=torch.float32, device=self.device),
                                 torch.zeros((n, self.cfg.max_ctx), dtype=torch.float32, device=self.device))
         return self._scratch[n]
 
@@ -84,7 +84,7 @@ class Context:
 class LayerRuntime:
     def __init__(self, ctx: Context, spec: LayerSpec, data: LayerData,
                  retrieved: Dict[Tuple[int, int], torch.Tensor], base: Dict[Tuple[int, int], torch.Tensor],
-                 host_tier: bool = True):
+                 host_tier: bool = True, own_scratch: bool = False):
         self.ctx, self.spec = ctx, spec
         cfg, dev = ctx.cfg, ctx.device
         B, Hkv = spec.B, spec.Hkv
@@ -130,14 +130,19 @@ class LayerRuntime:
         with torch.cuda.device(dev):
             self.handle = hc.hc_layer_create(ctx.handle, descs)
         self.n_reps = hc.hc_layer_num_reps(self.handle)
-        self.rep_logits, self.scores = ctx.scratch(self.n_reps)
+        if own_scratch:     # needed when this layer's monitor overlaps the next layer's attention
+            n = max(1, self.n_reps)
+            self.rep_logits = torch.zeros((n, cfg.max_ctx, ctx.G), dtype=torch.float32, device=dev)
+            self.scores = torch.zeros((n, cfg.max_ctx), dtype=torch.float32, device=dev)
+        else:
+            self.rep_logits, self.scores = ctx.scratch(self.n_reps)
         # torch creates the HIP event lazily at the first record: do it now, the C ABI needs the handle
         self.ev_topk = torch.cuda.Event()
         self.ev_done = torch.cuda.Event()
         with torch.cuda.device(dev):
             self.ev_topk.record()
             self.ev_done.record()
-        self._gather_pending = False
+        self._side_pending = False
 
     def rep_slot(self, b: int, h: int) -> int:
         return hc.hc_layer_rep_slot(self.handle, b, h)
@@ -156,25 +161,48 @@ class LayerRuntime:
                               stream, wait_event, done_event)
 
     def step(self, q: torch.Tensor, side: Optional[torch.cuda.Stream] = None) -> None:
-        """One decode step of this layer on the current stream; the gather goes to ``side`` (or stays
-        on the current stream).  A refill decided now is visible to the next step's attention."""
+        """One decode step of this layer.  Attention runs on the current stream; with ``side`` the monitor
+        and the gather run there (so that they overlap whatever the current stream does next), otherwise
+        they follow on the current stream.  A refill decided now is visible to the next step's attention:
+        that attention waits for this step's side-stream work first (which also protects rep_logits,
+        scores and lse of this layer from being overwritten while the monitor reads them)."""
         main = torch.cuda.current_stream()
-        if self._gather_pending:
+        if self._side_pending:
             main.wait_event(self.ev_done)
-            self._gather_pending = False
+            self._side_pending = False
         self.attn(q)
         if not self.n_reps:
             return
-        self.monitor()
-        if side is None or self.tier is None:
+        if side is None:
+            self.monitor()
             if self.tier is not None:
                 self.gather()
+            return
+        self.ev_topk.record(main)                   # attention of this layer is enqueued
+        side.wait_event(self.ev_topk)
+        self.monitor(stream=side)
+        if self.tier is not None:
+            self.gather(stream=side, done_event=self.ev_done)
         else:
-            self.ev_topk.record(main)
-            self.gather(stream=side, wait_event=self.ev_topk, done_event=self.ev_done)
-            self._gather_pending = True
+            self.ev_done.record(side)
+        self._side_pending = True
 
     def close(self):
         if self.handle:
             hc.hc_layer_destroy(self.handle)
             self.handle = None
+
+
+def make_step_io(layers: List[LayerRuntime], q_per_layer: torch.Tensor, monitor: bool = True):
+    """ctypes array for hc_decode_step: q_per_layer [L,B,Hq,D] bf16 is a fixed device buffer the caller
+    refills before every step."""
+    arr = (hc.hc_layer_io * len(layers))()
+    for l, lay in enumerate(layers):
+        arr[l] = hc.hc_layer_io(layer=lay.handle, kv_arena=lay.arena.data_ptr(),
+                                host_tier=lay.tier.data_ptr() if lay.tier is not None else None,
+                                q=q_per_layer[l].data_ptr(), out=lay.out.data_ptr(), lse=lay.lse.data_ptr(),
+                                rep_logits=lay.rep_logits.data_ptr(),
+                                scores=lay.scores.data_ptr() if monitor else None,
+                                topk_idx=lay.topk_idx.data_ptr(), base_idx=lay.base_idx.data_ptr(),
+                                ring=lay.ring.data_ptr(), inter=lay.inter.data_ptr(), flag=lay.flag.data_ptr())
+    return arr

@@ -112,7 +112,7 @@ def test_attention_batched_ragged_contexts():
     rec = p.ref.step(q, monitor=True)
     for (b, h), lg in rec["logits"].items():
         slot = p.gpu.rep_slot(b, h)
-        got = p.gpu.rep_logits[slot, :, :spec.ctx[b]].cpu().double().numpy()
+        got = p.gpu.rep_logits[slot, :spec.ctx[b], :].T.cpu().double().numpy()
         assert np.abs(got - lg).max() < 2e-5, (b, h, np.abs(got - lg).max())
     p.close()
 
@@ -506,3 +506,44 @@ def test_config4_full_size_single_layer():
             resync(p, rec)
         assert p.slots_equal_oracle()
     p.close()
+
+
+# ------------------------------------------------------------------------------------------
+# hc_decode_step: the native launch loop over a stack of layers, monitor and gather on a side stream
+# ------------------------------------------------------------------------------------------
+def test_decode_step_stack_of_layers_matches_oracle():
+    say("hc_decode_step, 3 layers, 6 steps, side stream")
+    ws = [I.make_workload(2, layer=l, N=8192, scale=0.25) for l in range(3)]
+    ctx = R.Context(R.make_config(ws[0].spec), DEV)
+    pairs = []
+    for w in ws:
+        retrieved, base = I.initial_lists(w.spec)
+        gpu = R.LayerRuntime(ctx, w.spec, w.data, retrieved, base, own_scratch=True)
+        pairs.append((gpu, ref.RefLayer(w.spec, w.data, retrieved, base), w))
+    layers = [p[0] for p in pairs]
+    q_cur = torch.zeros((3, 1, 32, 128), dtype=torch.bfloat16, device=DEV)
+    io = R.make_step_io(layers, q_cur)
+    side = torch.cuda.Stream()
+    triggers = 0
+    for t in range(6):
+        qs = [w.schedule.next() for _, _, w in pairs]
+        q_cur.copy_(torch.stack(qs).to(DEV))
+        hc.hc_decode_step(ctx.handle, io, 3, None, side)
+        torch.cuda.synchronize()
+        for l, (gpu, orc, w) in enumerate(pairs):
+            rec = orc.step(qs[l])
+            U.check_attention(gpu.out, gpu.lse, rec, f"step {t} layer {l}")
+            topk = gpu.topk_idx.cpu().numpy()
+            for (b, h), T in rec["topk"].items():
+                assert U.check_set_valid(topk[b * 8 + h, :T.size], T, rec["scores"][(b, h if h in w.spec.reps(b) else w.spec.heads[b][h].rep)], 1e-4) == 0
+            for (b, pv), f in rec["flag"].items():
+                assert int(gpu.flag[pv]) == f and int(gpu.inter[pv]) == rec["inter"][(b, pv)]
+                triggers += f
+            p = U.Pair.__new__(U.Pair)
+            p.spec, p.gpu, p.ref = w.spec, gpu, orc
+            assert p.slots_equal_oracle(), f"slots differ at step {t} layer {l}"
+    say("  triggers", triggers)
+    assert triggers >= 6
+    for gpu, _, _ in pairs:
+        gpu.close()
+    ctx.close()
