@@ -189,9 +189,11 @@ hc_status hc_gather_retrieve(hc_ctx* ctx, const hc_layer* layer, const void* hos
 
 /* One decode step over a stack of layers (Algorithm 1, the body of the loop over t, for every layer):
  * for each layer in order, hc_decode_attn on main_stream, then hc_rep_topk_drift and hc_gather_retrieve
- * on side_stream (NULL = on main_stream, no overlap).  The side work of a layer overlaps the attention of
- * the following layers; the attention of a layer at the next call waits for that layer's side work of
- * this call, so a refill decided at step t is used from step t+1.  Launching from native code keeps the
+ * on side_stream (NULL = on main_stream, no overlap).  Layers are handled in groups of layers_per_group
+ * (>= 1; 4 is a good value): a group's attentions, then one cross-stream event, then the group's monitors
+ * and gathers, which overlap the attention of the following groups.  The attention of a layer at the
+ * next call waits for that layer's side work of this call, so a refill decided at step t is used from
+ * step t+1.  Launching from native code keeps the
  * host ahead of the GPU (ten small launches per layer).  All buffers are the caller's, as in the three
  * calls; scores == NULL (or a layer without pivots) skips monitor and gather for that layer; host_tier ==
  * NULL skips the gather.  Layers whose monitors overlap other layers' attention need their own
@@ -211,8 +213,8 @@ typedef struct {
     int32_t* inter;
     int32_t* flag;
 } hc_layer_io;
-hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* layers, int32_t n_layers, void* main_stream,
-                         void* side_stream);
+hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* layers, int32_t n_layers, int32_t layers_per_group,
+                         void* main_stream, void* side_stream);
 
 #ifdef __cplusplus
 }

@@ -83,7 +83,7 @@ def lib():
         L.hc_decode_attn.argtypes = [vp] * 8
         L.hc_rep_topk_drift.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
         L.hc_gather_retrieve.argtypes = [vp] * 9
-        L.hc_decode_step.argtypes = [vp, C.POINTER(hc_layer_io), i32, vp, vp]
+        L.hc_decode_step.argtypes = [vp, C.POINTER(hc_layer_io), i32, i32, vp, vp]
         for n in EXPORTS:
             if n not in ("hc_strerror", "hc_last_error", "hc_layer_num_reps", "hc_layer_rep_slot",
                          "hc_layer_num_workgroups", "hc_layer_num_partials"):
@@ -212,7 +212,7 @@ def hc_gather_retrieve(ctx: int, layer: int, host_tier: Ptr, topk_idx: Ptr, flag
            "hc_gather_retrieve", ctx)
 
 
-def hc_decode_step(ctx: int, io, n_layers: int, main_stream=None, side_stream=None) -> None:
+def hc_decode_step(ctx: int, io, n_layers: int, main_stream=None, side_stream=None, layers_per_group: int = 4) -> None:
     """io: a ctypes array of hc_layer_io (build it once and reuse it: the q pointers may stay fixed)."""
-    _check(lib().hc_decode_step(ctx, io, n_layers, _stream(main_stream), None if side_stream is None else _stream(side_stream)),
-           "hc_decode_step", ctx)
+    _check(lib().hc_decode_step(ctx, io, n_layers, layers_per_group, _stream(main_stream),
+                                None if side_stream is None else _stream(side_stream)), "hc_decode_step", ctx)

@@ -5,13 +5,17 @@
 // to learn which pivots fired: the predicate (flag of the satellite's pivot) is read on the device
 // and workgroups of untriggered satellites leave at once.  32 lanes move one position: lanes 0-15
 // the K row, lanes 16-31 the V row, 16 bytes each.
+#include <algorithm>
+
 #include "hc_internal.h"
 
 namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int ROWS_PER_BLOCK = 64;   // positions per workgroup: 8 per pass, 8 passes
+constexpr int ROWS_PER_PASS = 64;    // positions a workgroup has in flight: 8 per sub-pass, 8 sub-passes
+constexpr int BLOCKS_PER_SAT = 16;   // workgroups per satellite: 1024 positions (512 KB) in flight per satellite;
+                                     // few enough that an untriggered call costs next to nothing
 
 __global__ __launch_bounds__(256) void gather_kernel(const SatDev* __restrict__ sats, const HeadDev* __restrict__ heads,
                                                      const uint16_t* __restrict__ tier,
@@ -21,33 +25,33 @@ __global__ __launch_bounds__(256) void gather_kernel(const SatDev* __restrict__ 
 {
     const SatDev sd = sats[blockIdx.y];
     if (flag[sd.rep_bh] == 0) return;
-    const int row_first = blockIdx.x * ROWS_PER_BLOCK;
-    if (row_first >= sd.r) return;
     const HeadDev hd = heads[sd.bh];
     const int32_t* list = topk_idx + (size_t)sd.bh * max_k;
-    const int sub = threadIdx.x >> 5;          // which of the 8 positions of a pass
+    const int sub = threadIdx.x >> 5;          // which of the 8 positions of a sub-pass
     const int l32 = threadIdx.x & 31;
     const int is_v = l32 >> 4;                 // lanes 16..31 move the V row
     const int chunk = l32 & 15;                // 16-byte chunk of the 256-byte row
     const u32x4* src_base = reinterpret_cast<const u32x4*>(tier + hd.tier_off);
     u32x4* dst_base = reinterpret_cast<u32x4*>(arena + (is_v ? hd.v_off : hd.k_off));
-    u32x4 buf[ROWS_PER_BLOCK / 8];
-    int slot[ROWS_PER_BLOCK / 8];
+    for (int row_first = blockIdx.x * ROWS_PER_PASS; row_first < sd.r; row_first += gridDim.x * ROWS_PER_PASS) {
+        u32x4 buf[ROWS_PER_PASS / 8];
+        int slot[ROWS_PER_PASS / 8];
 #pragma unroll
-    for (int p = 0; p < ROWS_PER_BLOCK / 8; ++p) {     // issue every host read first: they are latency-bound
-        const int i = row_first + p * 8 + sub;
-        slot[p] = -1;
-        if (i < sd.r) {
-            const int j = list[i];
-            if (j >= 0 && j < hd.ctx) {                // a corrupt list entry must not leave the tier block
-                buf[p] = __builtin_nontemporal_load(src_base + (size_t)j * 32 + is_v * 16 + chunk);
-                slot[p] = sd.first_slot + i;
+        for (int p = 0; p < ROWS_PER_PASS / 8; ++p) {      // issue every host read first: they are latency-bound
+            const int i = row_first + p * 8 + sub;
+            slot[p] = -1;
+            if (i < sd.r) {
+                const int j = list[i];
+                if (j >= 0 && j < hd.ctx) {                // a corrupt list entry must not leave the tier block
+                    buf[p] = __builtin_nontemporal_load(src_base + (size_t)j * 32 + is_v * 16 + chunk);
+                    slot[p] = sd.first_slot + i;
+                }
             }
         }
-    }
 #pragma unroll
-    for (int p = 0; p < ROWS_PER_BLOCK / 8; ++p)
-        if (slot[p] >= 0) dst_base[(size_t)slot[p] * 16 + chunk] = buf[p];
+        for (int p = 0; p < ROWS_PER_PASS / 8; ++p)
+            if (slot[p] >= 0) dst_base[(size_t)slot[p] * 16 + chunk] = buf[p];
+    }
 }
 
 }   // namespace
@@ -55,7 +59,7 @@ __global__ __launch_bounds__(256) void gather_kernel(const SatDev* __restrict__ 
 hc_status hc_launch_gather(hc_ctx* ctx, const hc_layer* L, const void* tier, const int32_t* topk_idx,
                            const int32_t* flag, void* arena, hipStream_t st)
 {
-    const dim3 grid((L->max_r + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK, L->n_sats);
+    const dim3 grid(std::min(BLOCKS_PER_SAT, (L->max_r + ROWS_PER_PASS - 1) / ROWS_PER_PASS), L->n_sats);
     gather_kernel<<<grid, dim3(256), 0, st>>>(L->sats, L->heads, (const uint16_t*)tier, topk_idx, flag,
                                              (uint16_t*)arena, ctx->cfg.max_k);
     HC_HIP(ctx, hipGetLastError());

@@ -542,42 +542,61 @@ extern "C" hc_status hc_gather_retrieve(hc_ctx* ctx, const hc_layer* layer, cons
 }
 
 // One decode step over a stack of layers, launched from native code so that the host keeps ahead of the
-// GPU (a layer is ten small launches).  Per layer: attention on the main stream; then, on the side
-// stream, the monitor and the gather, which thereby overlap the next layers' attention.  The attention of
-// a layer waits for that layer's side work of the previous step (a refill decided at step t is used from
-// step t+1; it also keeps rep_logits / lse from being overwritten while the monitor reads them).
-extern "C" hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* io, int32_t n_layers, void* main_stream,
-                                    void* side_stream)
+// GPU (a layer is ten small launches).  Layers are taken in groups: the attention of a group's layers on
+// the main stream; then, on the side stream, their monitors and gathers, which thereby overlap the
+// attention of the following groups.  One event pair per group (not per layer) keeps the host cost of the
+// cross-stream ordering small.  The attention of a layer waits for that layer's side work of the
+// previous step (a refill decided at step t is used from step t+1; it also keeps rep_logits / lse from
+// being overwritten while the monitor reads them).
+extern "C" hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* io, int32_t n_layers, int32_t layers_per_group,
+                                    void* main_stream, void* side_stream)
 {
     if (!ctx_ok(ctx)) return HC_ESTATE;
-    if (!io || n_layers < 0) return hc_fail(ctx, HC_EINVAL, "hc_decode_step: null argument");
+    if (!io || n_layers < 0 || layers_per_group < 1) return hc_fail(ctx, HC_EINVAL, "hc_decode_step: bad argument");
     hipStream_t ms = (hipStream_t)main_stream, ss = (hipStream_t)side_stream;
-    for (int l = 0; l < n_layers; ++l) {
-        const hc_layer_io& x = io[l];
-        hc_layer* L = x.layer;
-        if (!layer_ok(L) || L->ctx != ctx) return hc_fail(ctx, HC_ESTATE, "hc_decode_step: layer %d does not belong to this context", l);
-        if (L->side_pending) {
-            HC_HIP(ctx, hipStreamWaitEvent(ms, L->ev_side, 0));
-            L->side_pending = false;
-        }
-        const bool mon = L->n_reps > 0 && x.scores != nullptr;
-        hc_status st = hc_decode_attn(ctx, L, x.kv_arena, x.q, x.out, x.lse, mon ? x.rep_logits : nullptr, ms);
-        if (st != HC_OK) return st;
-        if (!mon) continue;
-        hipStream_t run = ss ? ss : ms;
-        if (ss) {
-            HC_HIP(ctx, hipEventRecord(L->ev_attn, ms));
-            HC_HIP(ctx, hipStreamWaitEvent(ss, L->ev_attn, 0));
-        }
-        st = hc_rep_topk_drift(ctx, L, x.rep_logits, x.lse, x.scores, 0, x.topk_idx, x.base_idx, x.ring, x.inter, x.flag, run);
-        if (st != HC_OK) return st;
-        if (x.host_tier) {
-            st = hc_gather_retrieve(ctx, L, x.host_tier, x.topk_idx, x.flag, const_cast<void*>(x.kv_arena), run, nullptr, nullptr);
+    for (int l = 0; l < n_layers; ++l)
+        if (!layer_ok(io[l].layer) || io[l].layer->ctx != ctx)
+            return hc_fail(ctx, HC_ESTATE, "hc_decode_step: layer %d does not belong to this context", l);
+    hipEvent_t last_waited = nullptr;
+    for (int g0 = 0; g0 < n_layers; g0 += layers_per_group) {
+        const int g1 = std::min(n_layers, g0 + layers_per_group);
+        bool any_side = false;
+        for (int l = g0; l < g1; ++l) {
+            const hc_layer_io& x = io[l];
+            hc_layer* L = x.layer;
+            if (L->pending_ev) {
+                if (L->pending_ev != last_waited) HC_HIP(ctx, hipStreamWaitEvent(ms, L->pending_ev, 0));
+                last_waited = L->pending_ev;
+                L->pending_ev = nullptr;
+            }
+            const bool mon = L->n_reps > 0 && x.scores != nullptr;
+            any_side |= mon;
+            const hc_status st = hc_decode_attn(ctx, L, x.kv_arena, x.q, x.out, x.lse, mon ? x.rep_logits : nullptr, ms);
             if (st != HC_OK) return st;
         }
+        if (!any_side) continue;
+        hc_layer* Lg = io[g1 - 1].layer;          // the group's events live in its last layer
+        hipStream_t run = ss ? ss : ms;
         if (ss) {
-            HC_HIP(ctx, hipEventRecord(L->ev_side, ss));
-            L->side_pending = true;
+            HC_HIP(ctx, hipEventRecord(Lg->ev_attn, ms));
+            HC_HIP(ctx, hipStreamWaitEvent(ss, Lg->ev_attn, 0));
+        }
+        for (int l = g0; l < g1; ++l) {
+            const hc_layer_io& x = io[l];
+            hc_layer* L = x.layer;
+            if (!(L->n_reps > 0 && x.scores != nullptr)) continue;
+            hc_status st = hc_rep_topk_drift(ctx, L, x.rep_logits, x.lse, x.scores, 0, x.topk_idx, x.base_idx, x.ring,
+                                             x.inter, x.flag, run);
+            if (st != HC_OK) return st;
+            if (x.host_tier) {
+                st = hc_gather_retrieve(ctx, L, x.host_tier, x.topk_idx, x.flag, const_cast<void*>(x.kv_arena), run,
+                                        nullptr, nullptr);
+                if (st != HC_OK) return st;
+            }
+        }
+        if (ss) {
+            HC_HIP(ctx, hipEventRecord(Lg->ev_side, ss));
+            for (int l = g0; l < g1; ++l) io[l].layer->pending_ev = Lg->ev_side;
         }
     }
     return HC_OK;

@@ -81,6 +81,7 @@ struct hc_ctx {
     uint32_t* misc = nullptr;      // [max_reps][4]: spare
     uint32_t* hits = nullptr;      // [max_reps][max_chunks+1]: per-chunk |T ∩ baseline|
     int max_chunks = 0;
+    bool monitor_dirty = true;     // histograms / bitmap not known to be clear (first call, or a call that failed midway)
     size_t zero_words = 0;         // words of the contiguous region cleared at the start of a monitor call
 };
 
@@ -102,7 +103,7 @@ struct hc_layer {
     SatDev* sats = nullptr;
     hipEvent_t ev_attn = nullptr;  // hc_decode_step: this layer's attention has been enqueued / its side work is done
     hipEvent_t ev_side = nullptr;
-    bool side_pending = false;
+    hipEvent_t pending_ev = nullptr;   // side work of the previous hc_decode_step that this layer's attention must wait for
 };
 
 constexpr uint32_t HC_CTX_MAGIC = 0x48435458u;    // "HCTX"

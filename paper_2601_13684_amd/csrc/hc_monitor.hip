@@ -17,14 +17,15 @@
 // caller runs the monitor on a side stream.
 //
 // Kernels, all on the caller's stream:
-//   mon_prep        clear histograms, selection state, accumulators and the baseline bitmap
+//   (mon_prep       clear the digit histograms and the baseline bitmap: only after a failed call; normally
+//                   they are left clear by the previous call's last kernel)
 //   mon_score_hist  score + first-digit histogram; scatter the baseline list into the bitmap
 //   mon_hist<2>     find the first digit of every set size; histograms of the second digit
 //   mon_hist<3>     find the second digit; histograms of the third digit
 //   mon_count       find the threshold key; per-chunk counts of greater / equal keys
 //   mon_write       ordered compaction into topk_idx; |T ∩ baseline| through the bitmap
 //   mon_decide      window update and trigger decision (exact integer form of Eq. 10): writes inter, flag,
-//                   ring and, on a trigger, the new baseline
+//                   ring and, on a trigger, the new baseline; clears histograms and bitmap for the next call
 #include "hc_internal.h"
 
 namespace {
@@ -142,19 +143,14 @@ __device__ __forceinline__ void find_digit_wave(const uint32_t* __restrict__ his
     remaining = __shfl(rem, src);
 }
 
-__global__ __launch_bounds__(256) void mon_prep(Ws ws, const RepDev* __restrict__ reps)
+__global__ __launch_bounds__(256) void mon_prep(Ws ws, int max_ctx)
 {
-    const int rep = blockIdx.y;
-    const RepWs w = ws.rep(rep);
+    const RepWs w = ws.rep(blockIdx.y);
     const size_t hist_words = (size_t)(1 + 2 * HC_MAX_K_PER_REP) * HC_RADIX_BINS;
-    const size_t bm_words = (size_t)(reps[rep].hi + 31) / 32;
+    const size_t bm_words = (size_t)max_ctx / 32;
     const size_t stride = (size_t)gridDim.x * 256;
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < hist_words; i += stride) w.h1[i] = 0u;
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < bm_words; i += stride) w.bitmap[i] = 0u;
-    if (blockIdx.x == 0) {
-        if (threadIdx.x < HC_MAX_K_PER_REP * 4) w.sel[threadIdx.x] = 0u;
-        if (threadIdx.x < 4) w.misc[threadIdx.x] = 0u;
-    }
 }
 
 // Score of candidate j from the G scaled logits of its row (rep_logits is [ctx][G] per pivot).
@@ -513,6 +509,11 @@ __global__ __launch_bounds__(BLK) void mon_decide(Ws ws, const RepDev* __restric
         int32_t* base = base_idx + (size_t)rd.bh * cfg.max_k;
         for (int i = threadIdx.x; i < k; i += BLK) base[i] = src[i];
     }
+    // every other kernel of this call is done with the histograms and the bitmap: leave them clear
+    const RepWs w = ws.rep(blockIdx.x);
+    uint4* h4 = reinterpret_cast<uint4*>(w.h1);
+    for (int i = threadIdx.x; i < (1 + 2 * HC_MAX_K_PER_REP) * HC_RADIX_BINS / 4; i += BLK) h4[i] = make_uint4(0u, 0u, 0u, 0u);
+    for (int i = threadIdx.x; i < (rd.hi + 31) / 32; i += BLK) w.bitmap[i] = 0u;
 }
 
 template <int G>
@@ -531,8 +532,11 @@ hc_status hc_launch_monitor(hc_ctx* ctx, const hc_layer* L, const float* rep_log
 {
     Ws ws{ctx->hist, ctx->sel, ctx->misc, ctx->cnt, ctx->bitmap, ctx->hits, ctx->max_chunks, ctx->cfg.max_ctx};
     const hc_config& c = ctx->cfg;
-    mon_prep<<<dim3(16, L->n_reps), dim3(256), 0, st>>>(ws, L->reps);
-    HC_HIP(ctx, hipGetLastError());
+    if (ctx->monitor_dirty) {     // a previous call did not run to its last kernel
+        mon_prep<<<dim3(16, ctx->max_reps), dim3(256), 0, st>>>(ws, ctx->cfg.max_ctx);
+        HC_HIP(ctx, hipGetLastError());
+    }
+    ctx->monitor_dirty = true;
     switch (ctx->G) {
     case 1: launch_score_hist<1>(ws, L, rep_logits, lse, scores, scores_given, c.agg, base_idx, c.max_k, st); break;
     case 2: launch_score_hist<2>(ws, L, rep_logits, lse, scores, scores_given, c.agg, base_idx, c.max_k, st); break;
@@ -554,5 +558,6 @@ hc_status hc_launch_monitor(hc_ctx* ctx, const hc_layer* L, const float* rep_log
     HC_HIP(ctx, hipGetLastError());
     mon_decide<<<dim3(L->n_reps), dim3(BLK), 0, st>>>(ws, L->reps, topk_idx, base_idx, ring, inter, flag, dc);
     HC_HIP(ctx, hipGetLastError());
+    ctx->monitor_dirty = false;   // everything enqueued: the workspace will be clear again when this call completes
     return HC_OK;
 }
