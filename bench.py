@@ -26,6 +26,10 @@ if ROOT not in sys.path:
 
 METRIC = "µs per decode step per layer + achieved HBM GB/s at 224K context, 1 GPU"
 HBM_PEAK_GBPS = 8000.0
+# HBM traffic of one launch of the split kernel (bytes), from the hardware counters FETCH_SIZE and
+# WRITE_SIZE of profiler runs of this script, scaled by what the same counters read for the streaming
+# kernel of --calibrate-copy; keyed by (config, dense).  The runs and factors are in profiles/.
+MEASURED_TRAFFIC = {(4, False): 254697052}
 
 
 def main():
@@ -46,7 +50,10 @@ def main():
     ap.add_argument("--attn-only", action="store_true", help="time hc_decode_attn alone (no monitor, no gather)")
     ap.add_argument("--oracle-seconds", type=float, default=12.0)
     ap.add_argument("--no-oracle", action="store_true")
-    ap.add_argument("--no-kernel-timing", action="store_true", help="skip the eager pass that times the split kernel")
+    ap.add_argument("--no-kernel-timing", action="store_true", help="skip the pass that times the split kernel")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
+                    help="first run 8 plain streaming kernels (out = in + 1 over MiB of fp32 in, MiB out) so that a "
+                         "counter run can scale FETCH_SIZE / WRITE_SIZE by a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
@@ -60,6 +67,14 @@ def main():
 
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        n = args.calibrate_copy * (1 << 20) // 4
+        src = torch.ones((n,), dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(8):
+            torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
     L = args.layers or I.CONFIG_LAYERS[args.config]
     K, W = args.steps, args.warmup
     T_total = W + 2 * K + 1           # warm-up, timed pass, kernel-timing pass
@@ -170,24 +185,20 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / K
     us_per_layer = ms_per_step * 1e3 / L
 
-    # ---- kernel-timing pass: the same steps, eager, with the library's event hook around the split kernel ----
+    # ---- kernel-timing pass: the same steps launched the same way, with one event pair attached to every
+    # split-pass dispatch by the library (a captured graph cannot carry them: that mode is timed eagerly) ----
     n_pairs = 0 if args.no_kernel_timing else K * L
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_pairs)]
     for a, b in evs:
         a.record()
         b.record()
     torch.cuda.synchronize()
-    i = 0
-    for _ in range(K if n_pairs else 0):
-        load_q()
-        for l, lay in enumerate(layers):
-            hc.hc_set_timing_events(ctx.handle, evs[i][0], evs[i][1])
-            if args.attn_only:
-                lay.attn(q_cur[l], monitor=False)
-            else:
-                lay.step(q_cur[l], side=None if args.serial else side)
-            i += 1
-    hc.hc_set_timing_events(ctx.handle, None, None)
+    if n_pairs:
+        hc.hc_set_timing_events(ctx.handle, [a for a, _ in evs], [b for _, b in evs])
+        timed_run = step_eager if args.mode == "graph" else run
+        for _ in range(K):
+            timed_run()
+        hc.hc_set_timing_events(ctx.handle)
     torch.cuda.synchronize()
     kern_ms = np.array([a.elapsed_time(b) for a, b in evs]) if n_pairs else np.array([float("nan")])
     kern_us = float(kern_ms.mean() * 1e3)
@@ -236,7 +247,8 @@ def main():
         "tokens_per_s": spec0.B / (ms_per_step * 1e-3),
         "step_GBps": kv_bytes * L / (ms_per_step * 1e-3) / 1e9,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": MEASURED_TRAFFIC.get((args.config, args.dense)) if not args.ctx else None,
                      "kernel": "attn_split_kernel", "kernel_us_mean": kern_us,
                      "kernel_us_median": float(np.median(kern_ms) * 1e3), "kernel_us_p95": float(np.percentile(kern_ms, 95) * 1e3),
                      "launches_timed": n_pairs},

@@ -115,11 +115,12 @@ int32_t hc_layer_num_partials(const hc_layer* layer);
  * (default 2) and host override of the compute-unit count (0 = ask the device). */
 hc_status hc_set_split(hc_ctx* ctx, int32_t workgroups_per_cu, int32_t compute_units);
 
-/* Measurement hook: with two non-NULL hipEvent_t, the next hc_decode_attn calls record ev_begin
- * immediately before and ev_end immediately after their split-pass kernel, on the call's stream, so
- * that a benchmark can time that kernel alone with hipEventElapsedTime.  Two NULLs switch it off.
- * The events are the caller's; they are only recorded, never waited on or destroyed. */
-hc_status hc_set_timing_events(hc_ctx* ctx, void* ev_begin, void* ev_end);
+/* Measurement hook: hands the library n pairs of hipEvent_t (host arrays of handles, copied).  The
+ * next n launches of the split-pass kernel, from hc_decode_attn or hc_decode_step, attach pair i to
+ * their i-th dispatch, so that hipEventElapsedTime(ev_begin[i], ev_end[i]) is that kernel's execution
+ * time alone, as a profiler's kernel trace reports it.  After n launches, or with n = 0, no events
+ * are recorded.  The events are the caller's; they are only recorded, never waited on or destroyed. */
+hc_status hc_set_timing_events(hc_ctx* ctx, void* const* ev_begin, void* const* ev_end, int32_t n);
 
 /* Host-only dry run of hc_layer_create: validates the head table exactly as hc_layer_create does
  * and reports the plan it would build for a device with the given number of compute units.  Touches

@@ -77,7 +77,7 @@ def lib():
         L.hc_layer_rep_slot.argtypes = [vp, i32, i32]
         L.hc_layer_rep_slot.restype = i32
         L.hc_set_split.argtypes = [vp, i32, i32]
-        L.hc_set_timing_events.argtypes = [vp, vp, vp]
+        L.hc_set_timing_events.argtypes = [vp, vp, vp, i32]
         L.hc_plan_describe.argtypes = [C.POINTER(hc_config), C.POINTER(hc_head_desc), i32, i32,
                                        C.POINTER(hc_plan_info), C.c_char_p, i32]
         L.hc_decode_attn.argtypes = [vp] * 8
@@ -150,8 +150,14 @@ def hc_set_split(ctx: int, workgroups_per_cu: int = 2, compute_units: int = 0) -
     _check(lib().hc_set_split(ctx, workgroups_per_cu, compute_units), "hc_set_split", ctx)
 
 
-def hc_set_timing_events(ctx: int, ev_begin=None, ev_end=None) -> None:
-    _check(lib().hc_set_timing_events(ctx, _event(ev_begin), _event(ev_end)), "hc_set_timing_events", ctx)
+def hc_set_timing_events(ctx: int, ev_begin=(), ev_end=()) -> None:
+    """ev_begin / ev_end: equally long sequences of torch.cuda.Event (timing enabled, recorded once)."""
+    n = len(ev_begin)
+    if len(ev_end) != n:
+        raise ValueError("hc_set_timing_events: sequences of equal length")
+    arr_b = (C.c_void_p * max(n, 1))(*[_event(e) for e in ev_begin])
+    arr_e = (C.c_void_p * max(n, 1))(*[_event(e) for e in ev_end])
+    _check(lib().hc_set_timing_events(ctx, arr_b if n else None, arr_e if n else None, n), "hc_set_timing_events", ctx)
 
 
 def hc_plan_describe(cfg: hc_config, heads: Sequence[hc_head_desc], compute_units: int = 256,

@@ -490,8 +490,14 @@ hc_status launch(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* 
 {
     // The optional timing events are attached to the kernel's own dispatch, so that their distance is the
     // kernel's execution time (what a profiler's kernel trace reports), not launch latency plus execution.
+    hipEvent_t ev_begin = nullptr, ev_end = nullptr;
+    if (ctx->timing_next < ctx->timing.size()) {
+        ev_begin = ctx->timing[ctx->timing_next].first;
+        ev_end = ctx->timing[ctx->timing_next].second;
+        ++ctx->timing_next;
+    }
 #define HC_LAUNCH(KERNEL)                                                                                         \
-    hipExtLaunchKernelGGL(KERNEL, dim3(L->n_blocks), dim3(256), 0, st, ctx->ev_begin, ctx->ev_end, 0,            \
+    hipExtLaunchKernelGGL(KERNEL, dim3(L->n_blocks), dim3(256), 0, st, ev_begin, ev_end, 0,                      \
                           (const uint16_t*)arena, (const uint16_t*)q, (const BlkDev*)L->blks,                    \
                           (const SegDev*)L->segs, ctx->part_acc, ctx->part_ml, rep_logits, ctx->cfg.max_ctx)
 #ifdef HC_TUNE

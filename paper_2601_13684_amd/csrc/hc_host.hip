@@ -142,13 +142,17 @@ extern "C" hc_status hc_set_split(hc_ctx* ctx, int32_t workgroups_per_cu, int32_
     return HC_OK;
 }
 
-extern "C" hc_status hc_set_timing_events(hc_ctx* ctx, void* ev_begin, void* ev_end)
+extern "C" hc_status hc_set_timing_events(hc_ctx* ctx, void* const* ev_begin, void* const* ev_end, int32_t n)
 {
     if (!ctx_ok(ctx)) return HC_ESTATE;
-    if ((ev_begin == nullptr) != (ev_end == nullptr))
-        return hc_fail(ctx, HC_EINVAL, "hc_set_timing_events: give both events or neither");
-    ctx->ev_begin = (hipEvent_t)ev_begin;
-    ctx->ev_end = (hipEvent_t)ev_end;
+    if (n < 0 || (n > 0 && (ev_begin == nullptr || ev_end == nullptr)))
+        return hc_fail(ctx, HC_EINVAL, "hc_set_timing_events: n >= 0 and two arrays of n events");
+    for (int i = 0; i < n; ++i)
+        if (ev_begin[i] == nullptr || ev_end[i] == nullptr)
+            return hc_fail(ctx, HC_EINVAL, "hc_set_timing_events: pair %d has a NULL event", i);
+    ctx->timing.clear();
+    ctx->timing_next = 0;
+    for (int i = 0; i < n; ++i) ctx->timing.emplace_back((hipEvent_t)ev_begin[i], (hipEvent_t)ev_end[i]);
     return HC_OK;
 }
 

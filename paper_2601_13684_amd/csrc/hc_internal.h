@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <utility>
 #include <vector>
 
 #include "../../include/hc.h"
@@ -67,7 +68,8 @@ struct hc_ctx {
     int wg_per_cu;
     int device;
     char err[512];
-    hipEvent_t ev_begin = nullptr, ev_end = nullptr;   // optional timing hook around the split pass
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> timing;   // optional timing hook: one pair per split-pass launch
+    size_t timing_next = 0;
     // split-K partial workspace
     float* part_acc = nullptr;   // [slots][G][D]
     float* part_ml = nullptr;    // [slots][G][2]  (running max in log2 units, sum)
