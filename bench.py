@@ -45,7 +45,7 @@ def main():
     ap.add_argument("--dense", action="store_true", help="uncompressed comparison: all 8 KV heads full")
     ap.add_argument("--no-tier", action="store_true", help="no host tier / gather (attention + monitor only)")
     ap.add_argument("--wg-per-cu", type=int, default=0)
-    ap.add_argument("--group", type=int, default=4, help="layers per cross-stream sync group in step mode")
+    ap.add_argument("--group", type=int, default=8, help="layers per cross-stream sync group in step mode")
     ap.add_argument("--serial", action="store_true", help="monitor and gather on the main stream (no overlap)")
     ap.add_argument("--attn-only", action="store_true", help="time hc_decode_attn alone (no monitor, no gather)")
     ap.add_argument("--oracle-seconds", type=float, default=12.0)
@@ -239,7 +239,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"config{args.config}{' dense' if args.dense else ''}: {spec0.ctx[0]} ctx, {L} layers, "
                                f"B={spec0.B}, {spec0.Hq}q/{spec0.Hkv}kv heads, D=128",
-                   "layers": L, "context": spec0.ctx[0], "mode": args.mode, "host_tier": not args.no_tier, "overlap_monitor": not args.serial,
+                   "layers": L, "context": spec0.ctx[0], "mode": args.mode, "host_tier": not args.no_tier, "overlap_monitor": not args.serial, "layers_per_group": args.group,
                    "kv_bytes_per_layer_step": kv_bytes,
                    "split_workgroups": hc.hc_layer_num_workgroups(layers[0].handle),
                    "split_partials": hc.hc_layer_num_partials(layers[0].handle)},

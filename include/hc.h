@@ -55,7 +55,7 @@ typedef enum {
 enum { HC_ROLE_FULL = 0, HC_ROLE_SATELLITE = 1, HC_ROLE_ANCHOR = 2 };
 enum { HC_METRIC_OVERLAP = 0, HC_METRIC_JACCARD = 1 };
 enum { HC_AGG_PROB = 0, HC_AGG_LOGIT = 1 };
-enum { HC_MAX_WINDOW = 64, HC_MAX_K_PER_REP = 8 };
+enum { HC_MAX_WINDOW = 64, HC_MAX_K_PER_REP = 8, HC_MAX_GROUP = 8 };
 
 typedef struct {
     int32_t B;         /* sequences in the batch (>= 1)                                         */
@@ -191,14 +191,17 @@ hc_status hc_gather_retrieve(hc_ctx* ctx, const hc_layer* layer, const void* hos
 /* One decode step over a stack of layers (Algorithm 1, the body of the loop over t, for every layer):
  * for each layer in order, hc_decode_attn on main_stream, then hc_rep_topk_drift and hc_gather_retrieve
  * on side_stream (NULL = on main_stream, no overlap).  Layers are handled in groups of layers_per_group
- * (>= 1; 4 is a good value): a group's attentions, then one cross-stream event, then the group's monitors
- * and gathers, which overlap the attention of the following groups.  The attention of a layer at the
- * next call waits for that layer's side work of this call, so a refill decided at step t is used from
- * step t+1.  Launching from native code keeps the
- * host ahead of the GPU (ten small launches per layer).  All buffers are the caller's, as in the three
- * calls; scores == NULL (or a layer without pivots) skips monitor and gather for that layer; host_tier ==
- * NULL skips the gather.  Layers whose monitors overlap other layers' attention need their own
- * rep_logits, scores, lse, out.  Enqueue-only; not meant for graph capture (it uses per-layer events). */
+ * (1..HC_MAX_GROUP; 4 is a good value): a group's attentions, then one cross-stream event, then ONE
+ * batched monitor and ONE batched gather for the whole group (the launches, and nearly the GPU time, of
+ * a single layer: those kernels are latency-bound), which overlap the attention of the following
+ * groups.  The attention of a layer at the next call waits for that layer's side work of this call, so
+ * a refill decided at step t is used from step t+1.  Launching from native code keeps the host ahead
+ * of the GPU.  All buffers are the caller's, as in the three calls; scores == NULL (or a layer without
+ * pivots) skips monitor and gather for that layer; host_tier == NULL skips the gather.  Layers whose
+ * monitors overlap other layers' attention need their own rep_logits, scores, lse, out.  The context
+ * holds one selection workspace per position in a group; hc_rep_topk_drift uses the first, so a direct
+ * call must be stream-ordered with this call's side work.  Enqueue-only; not meant for graph capture
+ * (it uses per-layer events). */
 typedef struct {
     hc_layer* layer;
     const void* kv_arena;     /* dev; also written by the gather */

@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("HC_LIB") or os.path.join(_HERE, "libhc.so")   # HC_LIB: load another build of the same ABI
 
 HC_OK, HC_EINVAL, HC_ESHAPE, HC_ENOMEM, HC_EHIP, HC_ESTATE = range(6)
-HC_MAX_WINDOW, HC_MAX_K_PER_REP = 64, 8
+HC_MAX_WINDOW, HC_MAX_K_PER_REP, HC_MAX_GROUP = 64, 8, 8
 
 EXPORTS = ["hc_create", "hc_destroy", "hc_strerror", "hc_last_error", "hc_layer_create", "hc_layer_destroy",
            "hc_layer_num_reps", "hc_layer_rep_slot", "hc_layer_num_workgroups", "hc_layer_num_partials",

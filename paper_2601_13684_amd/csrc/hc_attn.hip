@@ -115,21 +115,23 @@ __device__ __forceinline__ void qk(const uint32_t (&qreg)[G][8], const Tile& t, 
     }
 }
 
-// Pivot heads keep their scaled logits for the drift monitor, laid out [position][G]: the first column lane
-// of each row stores the group's G logits as one vector, so a row step writes 8 x 4G contiguous bytes.
+// The G scaled logits of the lane's row, kept for the drift monitor.  Only column lane 0 holds them after
+// the reduction.  They go to a staging buffer in LDS first (stash points at the row's G floats there) and
+// reach memory in long contiguous runs: 128-byte stores scattered through a pass that streams reads at
+// full rate cost several times their share of the traffic.
 template <int G>
-__device__ __forceinline__ void store_rep(float* __restrict__ rep_row, const float (&s)[G], int c, bool valid)
+__device__ __forceinline__ void stash_rep(float* stash, const float (&s)[G], int c, bool valid)
 {
     if (c != 0 || !valid) return;
     if (G == 1) {
-        rep_row[0] = s[0] * INV_SQRT_D;
+        stash[0] = s[0] * INV_SQRT_D;
     } else if (G == 2) {
-        *reinterpret_cast<float2*>(rep_row) = make_float2(s[0] * INV_SQRT_D, s[1] * INV_SQRT_D);
+        *reinterpret_cast<float2*>(stash) = make_float2(s[0] * INV_SQRT_D, s[1] * INV_SQRT_D);
     } else {
 #pragma unroll
         for (int q = 0; q < G / 4; ++q)
-            reinterpret_cast<float4*>(rep_row)[q] = make_float4(s[4 * q] * INV_SQRT_D, s[4 * q + 1] * INV_SQRT_D,
-                                                                s[4 * q + 2] * INV_SQRT_D, s[4 * q + 3] * INV_SQRT_D);
+            reinterpret_cast<float4*>(stash)[q] = make_float4(s[4 * q] * INV_SQRT_D, s[4 * q + 1] * INV_SQRT_D,
+                                                              s[4 * q + 2] * INV_SQRT_D, s[4 * q + 3] * INV_SQRT_D);
     }
 }
 
@@ -220,24 +222,14 @@ __device__ __forceinline__ void pv(WaveState<G>& st, const float (&x)[G], const 
     }
 }
 
-#ifdef HC_TUNE
+// One row step: logits, (pivot) logit stash, reference check, accumulate.
 template <int G>
-__device__ __forceinline__ void consume(WaveState<G>& st, const Tile& t)   // streaming-only probe
-{
-    const uint32_t x = t.k0.x ^ t.k0.y ^ t.k0.z ^ t.k0.w ^ t.k1.x ^ t.k1.y ^ t.k1.z ^ t.k1.w ^ t.v0.x ^ t.v0.y ^ t.v0.z ^
-                       t.v0.w ^ t.v1.x ^ t.v1.y ^ t.v1.z ^ t.v1.w;
-    st.Z[0] += __uint_as_float(x & 0x3f800000u);
-}
-#endif
-
-// One row step: logits, (pivot) logit store, reference check, accumulate.
-template <int G>
-__device__ __forceinline__ void row_step(WaveState<G>& st, const uint32_t (&qreg)[G][8], const Tile& t,
-                                         float* __restrict__ rep_row, int max_ctx, int c, bool valid)
+__device__ __forceinline__ void row_step(WaveState<G>& st, const uint32_t (&qreg)[G][8], const Tile& t, float* stash,
+                                         int c, bool valid)
 {
     float s[G], x[G], alpha[G];
     qk<G>(qreg, t, s);
-    if (rep_row) store_rep<G>(rep_row, s, c, valid);
+    if (stash) stash_rep<G>(stash, s, c, valid);
     const uint64_t over = exponents<G>(st, s, x, valid);
 #pragma unroll
     for (int g = 0; g < G; ++g) alpha[g] = 1.0f;
@@ -247,55 +239,76 @@ __device__ __forceinline__ void row_step(WaveState<G>& st, const uint32_t (&qreg
     pv<G>(st, x, t);
 }
 
+constexpr int REP_STASH_FLOATS = 4096;   // one staging buffer: 16 KB, i.e. 1024 positions of a group of 4 (measured: the
+                                         // longer the runs, the cheaper the stores; two workgroups' buffers still fit a CU's LDS)
+
 // Streams rows [row_begin, row_end) of one head through the wave state.  The wave takes the row steps
 // row_begin + 8*w + 32*i.  Full row steps are double-buffered in registers (tile B is in flight while
 // tile A is reduced, and vice versa); the ragged last row step is clamped for the load and masked.
-template <int G, int MODE>
+//
+// For a pivot (rep_base != nullptr) the rows are taken in chunks of REP_STASH_FLOATS / G positions: the
+// waves stash their logits in LDS, and at the end of a chunk the workgroup writes the chunk's logits to
+// rep_base as one contiguous run.  Two staging buffers alternate, so one barrier per chunk is enough;
+// the number of chunks depends only on the segment, so every wave reaches every barrier.  The register
+// pipeline of loads runs on across chunk boundaries.
+template <int G>
 __device__ __forceinline__ void process_rows(WaveState<G>& st, const uint32_t (&qreg)[G][8],
                                              const char* __restrict__ Kb, const char* __restrict__ Vb,
-                                             float* __restrict__ rep_base, int row_begin, int row_end, int w, int r,
-                                             int c, int max_ctx)
+                                             float* __restrict__ rep_base, float (&stash)[2][REP_STASH_FLOATS],
+                                             int row_begin, int row_end, int w, int r, int c)
 {
+    constexpr int CAP = REP_STASH_FLOATS / G;      // positions per chunk
+    constexpr int STEPS = CAP / 32;                // row steps of one wave per chunk
+    static_assert(STEPS % 2 == 0, "chunks hold whole pairs of row steps");
+    constexpr uint32_t STEP = 32u * 256u;          // bytes from one row step of this wave to the next
     const int wave_row0 = row_begin + 8 * w;
-    int row = wave_row0 + r;                                                        // this lane's row
     const int nfull = wave_row0 + 8 <= row_end ? (row_end - 8 - wave_row0) / 32 + 1 : 0;   // unmasked row steps
-    uint32_t off = (uint32_t)row * 256u + (uint32_t)c * 16u;                        // byte offset of the lane's first chunk
-    constexpr uint32_t STEP = 32u * 256u;                                           // one row step further for this wave
+    uint32_t off = (uint32_t)(wave_row0 + r) * 256u + (uint32_t)c * 16u;                   // the lane's first chunk of its row
+    const int nchunk = rep_base ? (row_end - row_begin + CAP - 1) / CAP : 1;
     Tile A, B;
     int i = 0;
     if (nfull > 0) load_tile(A, Kb, Vb, off);
-#ifdef HC_TUNE
-    if (MODE == 1) {
-        for (; i + 2 <= nfull; i += 2, off += 2 * STEP) {
+#pragma unroll 1
+    for (int ch = 0; ch < nchunk; ++ch) {
+        const bool last = ch == nchunk - 1;
+        const int i_hi = last ? nfull : (ch + 1) * STEPS;          // a chunk before the last holds full row steps only
+        float* sp = rep_base ? &stash[ch & 1][(8 * w + r) * G] : nullptr;
+#pragma unroll 1
+        for (; i + 2 <= i_hi; i += 2, off += 2 * STEP) {
             load_tile(B, Kb, Vb, off + STEP);
-            consume<G>(st, A);
+            row_step<G>(st, qreg, A, sp, c, true);
             if (i + 2 < nfull) load_tile(A, Kb, Vb, off + 2 * STEP);
-            consume<G>(st, B);
+            row_step<G>(st, qreg, B, sp ? sp + 32 * G : nullptr, c, true);
+            if (sp) sp += 64 * G;
         }
-        if (i < nfull) consume<G>(st, A);
-        return;
-    }
-#endif
-#pragma unroll 1
-    for (; i + 2 <= nfull; i += 2, row += 64, off += 2 * STEP) {
-        load_tile(B, Kb, Vb, off + STEP);
-        row_step<G>(st, qreg, A, rep_base ? rep_base + (size_t)row * G : nullptr, max_ctx, c, true);
-        if (i + 2 < nfull) load_tile(A, Kb, Vb, off + 2 * STEP);
-        row_step<G>(st, qreg, B, rep_base ? rep_base + (size_t)(row + 32) * G : nullptr, max_ctx, c, true);
-    }
-    if (i < nfull) {
-        row_step<G>(st, qreg, A, rep_base ? rep_base + (size_t)row * G : nullptr, max_ctx, c, true);
-        row += 32;
-    }
-#pragma unroll 1
-    for (; row - r < row_end; row += 32) {
-        const bool valid = row < row_end;
-        load_tile(A, Kb, Vb, (uint32_t)(valid ? row : row_end - 1) * 256u + (uint32_t)c * 16u);
-        row_step<G>(st, qreg, A, rep_base ? rep_base + (size_t)row * G : nullptr, max_ctx, c, valid);
+        if (last) {
+            if (i < nfull) {
+                row_step<G>(st, qreg, A, sp, c, true);
+                if (sp) sp += 32 * G;
+                ++i;
+            }
+            const int row = wave_row0 + 32 * i + r;                 // at most one ragged row step is left
+            if (row - r < row_end) {
+                const bool valid = row < row_end;
+                load_tile(A, Kb, Vb, (uint32_t)(valid ? row : row_end - 1) * 256u + (uint32_t)c * 16u);
+                row_step<G>(st, qreg, A, sp, c, valid);
+            }
+        }
+        if (rep_base) {
+            __syncthreads();
+            const int first = row_begin + ch * CAP;
+            const int nf = (row_end - first < CAP ? row_end - first : CAP) * G;     // floats of this chunk
+            const float* src = stash[ch & 1];
+            float* dst = rep_base + (size_t)first * G;                              // 128-byte aligned: first is a multiple of 32
+            typedef float f4v __attribute__((ext_vector_type(4)));
+            for (int f = (int)threadIdx.x * 4; f + 4 <= nf; f += 1024)      // streaming stores: nothing here reads them back
+                __builtin_nontemporal_store(*reinterpret_cast<const f4v*>(src + f), reinterpret_cast<f4v*>(dst + f));
+            for (int f = (nf & ~3) + (int)threadIdx.x; f < nf; f += 256) dst[f] = src[f];
+        }
     }
 }
 
-template <int G, int U, int WG_PER_CU, int MODE = 0>
+template <int G, int WG_PER_CU>
 __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16_t* __restrict__ arena,
                                                                     const uint16_t* __restrict__ q,
                                                                     const BlkDev* __restrict__ blks,
@@ -307,6 +320,7 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
     __shared__ float sm_m[4][G];
     __shared__ float sm_Z[8][G];
     __shared__ float sm_red[8][G * HC_D];
+    __shared__ __attribute__((aligned(16))) float sm_stash[2][REP_STASH_FLOATS];
 
     const int tid = threadIdx.x;
     const int w = tid >> 6;
@@ -349,7 +363,7 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
             for (int i = 0; i < 16; ++i) st.acc[g][i] = 0.f;
         }
 
-        process_rows<G, MODE>(st, qreg, Kp, Vp, rep_base, seg.row_begin, seg.row_end, w, r, c, max_ctx);
+        process_rows<G>(st, qreg, Kp, Vp, rep_base, sm_stash, seg.row_begin, seg.row_end, w, r, c);
 #ifdef HC_TUNE
         if (st.Z[0] >= 0.f) HC_STAMP(2);
 #endif
@@ -478,11 +492,11 @@ __global__ __launch_bounds__(1024) void attn_combine_kernel(const HeadDev* __res
     }
 }
 
-// Rows in flight per wave (two tiles of U row steps of 8 rows, 4 KB each) against registers: the
-// group-of-4 case holds 32 query + 64 accumulator registers; U = 1 at two workgroups per compute unit
-// keeps 64 KB in flight per compute unit, which measurement shows is enough.
-template <int G> struct Tune { static constexpr int U = 1, WG = 2; };
-template <> struct Tune<8> { static constexpr int U = 1, WG = 1; };
+// Workgroups per compute unit the kernel is compiled for.  A wave keeps two tiles of 8 rows (4 KB each) in
+// flight; the group-of-4 case holds 32 query + 64 accumulator registers, and two workgroups (8 waves)
+// per compute unit keep 64 KB in flight there, which measurement shows is enough.
+template <int G> struct Tune { static constexpr int WG = 2; };
+template <> struct Tune<8> { static constexpr int WG = 1; };
 
 template <int G>
 hc_status launch(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* q, float* out, float* lse,
@@ -500,17 +514,7 @@ hc_status launch(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* 
     hipExtLaunchKernelGGL(KERNEL, dim3(L->n_blocks), dim3(256), 0, st, ev_begin, ev_end, 0,                      \
                           (const uint16_t*)arena, (const uint16_t*)q, (const BlkDev*)L->blks,                    \
                           (const SegDev*)L->segs, ctx->part_acc, ctx->part_ml, rep_logits, ctx->cfg.max_ctx)
-#ifdef HC_TUNE
-    if (G == 4 && getenv("HC_VARIANT")) {
-        int u = 4, wg = 2, mode = 0;
-        sscanf(getenv("HC_VARIANT"), "%d,%d,%d", &u, &wg, &mode);
-#define HC_V(UU, WW, MM) if (u == UU && wg == WW && mode == MM) { HC_LAUNCH((attn_split_kernel<4, UU, WW, MM>)); } else
-        HC_V(1, 2, 0) HC_V(2, 2, 0) HC_V(2, 1, 0) HC_V(4, 1, 0) HC_V(1, 2, 1) HC_V(2, 2, 1) HC_V(2, 1, 1) HC_V(4, 1, 1)
-        return hc_fail(ctx, HC_EINVAL, "unknown HC_VARIANT");
-#undef HC_V
-    } else
-#endif
-    HC_LAUNCH((attn_split_kernel<G, Tune<G>::U, Tune<G>::WG>));
+    HC_LAUNCH((attn_split_kernel<G, Tune<G>::WG>));
 #undef HC_LAUNCH
     HC_HIP(ctx, hipGetLastError());
     attn_combine_kernel<G><<<dim3(L->n_heads * G), dim3(1024), 0, st>>>(L->heads, ctx->part_acc, ctx->part_ml, out, lse);

@@ -17,14 +17,30 @@ constexpr int ROWS_PER_PASS = 64;    // positions a workgroup has in flight: 8 p
 constexpr int BLOCKS_PER_SAT = 16;   // workgroups per satellite: 1024 positions (512 KB) in flight per satellite;
                                      // few enough that an untriggered call costs next to nothing
 
-__global__ __launch_bounds__(256) void gather_kernel(const SatDev* __restrict__ sats, const HeadDev* __restrict__ heads,
-                                                     const uint16_t* __restrict__ tier,
-                                                     const int32_t* __restrict__ topk_idx,
-                                                     const int32_t* __restrict__ flag, uint16_t* __restrict__ arena,
-                                                     int max_k)
+// One layer of a batched call (blockIdx.z picks the layer).
+struct GatherItem {
+    const SatDev* sats;
+    const HeadDev* heads;
+    const uint16_t* tier;
+    const int32_t* topk_idx;
+    const int32_t* flag;
+    uint16_t* arena;
+    int n_sats, pad;
+};
+struct GatherBatch {
+    GatherItem it[HC_MAX_GROUP];
+};
+
+__global__ __launch_bounds__(256) void gather_kernel(GatherBatch B, int max_k)
 {
-    const SatDev sd = sats[blockIdx.y];
-    if (flag[sd.rep_bh] == 0) return;
+    const GatherItem& it = B.it[blockIdx.z];
+    if ((int)blockIdx.y >= it.n_sats) return;
+    const HeadDev* __restrict__ heads = it.heads;
+    const uint16_t* __restrict__ tier = it.tier;
+    const int32_t* __restrict__ topk_idx = it.topk_idx;
+    uint16_t* __restrict__ arena = it.arena;
+    const SatDev sd = it.sats[blockIdx.y];
+    if (it.flag[sd.rep_bh] == 0) return;
     const HeadDev hd = heads[sd.bh];
     const int32_t* list = topk_idx + (size_t)sd.bh * max_k;
     const int sub = threadIdx.x >> 5;          // which of the 8 positions of a sub-pass
@@ -56,12 +72,21 @@ __global__ __launch_bounds__(256) void gather_kernel(const SatDev* __restrict__ 
 
 }   // namespace
 
-hc_status hc_launch_gather(hc_ctx* ctx, const hc_layer* L, const void* tier, const int32_t* topk_idx,
-                           const int32_t* flag, void* arena, hipStream_t st)
+hc_status hc_launch_gather(hc_ctx* ctx, int n, const hc_gather_call* calls, hipStream_t st)
 {
-    const dim3 grid(std::min(BLOCKS_PER_SAT, (L->max_r + ROWS_PER_PASS - 1) / ROWS_PER_PASS), L->n_sats);
-    gather_kernel<<<grid, dim3(256), 0, st>>>(L->sats, L->heads, (const uint16_t*)tier, topk_idx, flag,
-                                             (uint16_t*)arena, ctx->cfg.max_k);
+    if (n < 1 || n > HC_MAX_GROUP) return hc_fail(ctx, HC_EINVAL, "gather batch of %d layers", n);
+    GatherBatch B{};
+    int max_r = 0, max_sats = 0;
+    for (int i = 0; i < n; ++i) {
+        const hc_gather_call& x = calls[i];
+        B.it[i] = GatherItem{x.L->sats, x.L->heads, (const uint16_t*)x.tier, x.topk_idx, x.flag, (uint16_t*)x.arena,
+                             x.L->n_sats, 0};
+        max_r = std::max(max_r, x.L->max_r);
+        max_sats = std::max(max_sats, x.L->n_sats);
+    }
+    if (max_sats == 0 || max_r == 0) return HC_OK;
+    const dim3 grid(std::min(BLOCKS_PER_SAT, (max_r + ROWS_PER_PASS - 1) / ROWS_PER_PASS), max_sats, n);
+    gather_kernel<<<grid, dim3(256), 0, st>>>(B, ctx->cfg.max_k);
     HC_HIP(ctx, hipGetLastError());
     return HC_OK;
 }

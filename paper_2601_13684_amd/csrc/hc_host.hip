@@ -105,18 +105,24 @@ extern "C" hc_status hc_create(const hc_config* cfg, hc_ctx** out)
     const size_t cnt_w = (size_t)c->max_reps * HC_MAX_K_PER_REP * c->max_chunks * 2;
     const size_t bm_w = (size_t)c->max_reps * (cfg->max_ctx / 32);
     const size_t hits_w = (size_t)c->max_reps * (c->max_chunks + 1);
+    const size_t lane_w = hist_w + sel_w + misc_w + cnt_w + bm_w + hits_w;
     uint32_t* base = nullptr;
-    e = hipMalloc((void**)&base, (hist_w + sel_w + misc_w + cnt_w + bm_w + hits_w) * sizeof(uint32_t));
+    e = hipMalloc((void**)&base, HC_MAX_GROUP * lane_w * sizeof(uint32_t));
     if (e != hipSuccess) {
         delete c;
         return e == hipErrorOutOfMemory ? HC_ENOMEM : HC_EHIP;
     }
-    c->hist = base;
-    c->sel = c->hist + hist_w;
-    c->misc = c->sel + sel_w;
-    c->cnt = c->misc + misc_w;
-    c->bitmap = c->cnt + cnt_w;
-    c->hits = c->bitmap + bm_w;
+    c->ws_base = base;
+    for (int i = 0; i < HC_MAX_GROUP; ++i) {
+        hc_monitor_ws& w = c->ws[i];
+        w.hist = base + (size_t)i * lane_w;
+        w.sel = w.hist + hist_w;
+        w.misc = w.sel + sel_w;
+        w.cnt = w.misc + misc_w;
+        w.bitmap = w.cnt + cnt_w;
+        w.hits = w.bitmap + bm_w;
+        w.dirty = true;
+    }
     *out = c;
     return HC_OK;
 }
@@ -124,7 +130,7 @@ extern "C" hc_status hc_create(const hc_config* cfg, hc_ctx** out)
 extern "C" hc_status hc_destroy(hc_ctx* ctx)
 {
     if (!ctx_ok(ctx)) return HC_ESTATE;
-    (void)hipFree(ctx->hist);
+    (void)hipFree(ctx->ws_base);
     (void)hipFree(ctx->part_acc);
     (void)hipFree(ctx->part_ml);
     ctx->magic = 0;
@@ -508,11 +514,10 @@ extern "C" hc_status hc_decode_attn(hc_ctx* ctx, const hc_layer* layer, const vo
     return hc_launch_attn(ctx, layer, kv_arena, q, out, lse, rep_logits, (hipStream_t)stream);
 }
 
-extern "C" hc_status hc_rep_topk_drift(hc_ctx* ctx, const hc_layer* layer, const float* rep_logits, const float* lse,
-                                       float* scores, int32_t scores_given, int32_t* topk_idx, int32_t* base_idx,
-                                       int32_t* ring, int32_t* inter, int32_t* flag, void* stream)
+static hc_status monitor_check(hc_ctx* ctx, const hc_layer* layer, const float* rep_logits, const float* lse,
+                               const float* scores, int32_t scores_given, const int32_t* topk_idx,
+                               const int32_t* base_idx, const int32_t* ring, const int32_t* inter, const int32_t* flag)
 {
-    if (!ctx_ok(ctx)) return HC_ESTATE;
     if (!layer_ok(layer) || layer->ctx != ctx) return hc_fail(ctx, HC_ESTATE, "hc_rep_topk_drift: layer does not belong to this context");
     if (!scores || !topk_idx || !base_idx || !ring || !inter || !flag)
         return hc_fail(ctx, HC_EINVAL, "hc_rep_topk_drift: null pointer");
@@ -520,9 +525,30 @@ extern "C" hc_status hc_rep_topk_drift(hc_ctx* ctx, const hc_layer* layer, const
         return hc_fail(ctx, HC_EINVAL, "hc_rep_topk_drift: rep_logits and lse are needed unless scores are given");
     if (((uintptr_t)scores | (uintptr_t)rep_logits) & 15)
         return hc_fail(ctx, HC_EINVAL, "hc_rep_topk_drift: scores and rep_logits must be 16-byte aligned");
+    return HC_OK;
+}
+
+extern "C" hc_status hc_rep_topk_drift(hc_ctx* ctx, const hc_layer* layer, const float* rep_logits, const float* lse,
+                                       float* scores, int32_t scores_given, int32_t* topk_idx, int32_t* base_idx,
+                                       int32_t* ring, int32_t* inter, int32_t* flag, void* stream)
+{
+    if (!ctx_ok(ctx)) return HC_ESTATE;
+    const hc_status st = monitor_check(ctx, layer, rep_logits, lse, scores, scores_given, topk_idx, base_idx, ring, inter, flag);
+    if (st != HC_OK) return st;
     if (layer->n_reps == 0) return HC_OK;
-    return hc_launch_monitor(ctx, layer, rep_logits, lse, scores, scores_given != 0, topk_idx, base_idx, ring,
-                             inter, flag, (hipStream_t)stream);
+    const hc_monitor_call call{layer, rep_logits, lse, scores, topk_idx, base_idx, ring, inter, flag};
+    return hc_launch_monitor(ctx, 1, &call, scores_given != 0, (hipStream_t)stream);
+}
+
+static hc_status gather_check(hc_ctx* ctx, const hc_layer* layer, const void* host_tier, const int32_t* topk_idx,
+                              const int32_t* flag, const void* kv_arena)
+{
+    if (!layer_ok(layer) || layer->ctx != ctx) return hc_fail(ctx, HC_ESTATE, "hc_gather_retrieve: layer does not belong to this context");
+    if (!topk_idx || !flag || !kv_arena || (!host_tier && layer->n_sats > 0))
+        return hc_fail(ctx, HC_EINVAL, "hc_gather_retrieve: null pointer");
+    if (((uintptr_t)kv_arena | (uintptr_t)host_tier) & 15)
+        return hc_fail(ctx, HC_EINVAL, "hc_gather_retrieve: kv_arena and host_tier must be 16-byte aligned");
+    return HC_OK;
 }
 
 extern "C" hc_status hc_gather_retrieve(hc_ctx* ctx, const hc_layer* layer, const void* host_tier,
@@ -530,15 +556,13 @@ extern "C" hc_status hc_gather_retrieve(hc_ctx* ctx, const hc_layer* layer, cons
                                         void* stream, void* wait_event, void* done_event)
 {
     if (!ctx_ok(ctx)) return HC_ESTATE;
-    if (!layer_ok(layer) || layer->ctx != ctx) return hc_fail(ctx, HC_ESTATE, "hc_gather_retrieve: layer does not belong to this context");
-    if (!topk_idx || !flag || !kv_arena || (!host_tier && layer->n_sats > 0))
-        return hc_fail(ctx, HC_EINVAL, "hc_gather_retrieve: null pointer");
-    if (((uintptr_t)kv_arena | (uintptr_t)host_tier) & 15)
-        return hc_fail(ctx, HC_EINVAL, "hc_gather_retrieve: kv_arena and host_tier must be 16-byte aligned");
+    const hc_status chk = gather_check(ctx, layer, host_tier, topk_idx, flag, kv_arena);
+    if (chk != HC_OK) return chk;
     hipStream_t st = (hipStream_t)stream;
     if (wait_event) HC_HIP(ctx, hipStreamWaitEvent(st, (hipEvent_t)wait_event, 0));
     if (layer->n_sats > 0) {
-        hc_status s = hc_launch_gather(ctx, layer, host_tier, topk_idx, flag, kv_arena, st);
+        const hc_gather_call call{layer, host_tier, topk_idx, flag, kv_arena};
+        const hc_status s = hc_launch_gather(ctx, 1, &call, st);
         if (s != HC_OK) return s;
     }
     if (done_event) HC_HIP(ctx, hipEventRecord((hipEvent_t)done_event, st));
@@ -546,25 +570,30 @@ extern "C" hc_status hc_gather_retrieve(hc_ctx* ctx, const hc_layer* layer, cons
 }
 
 // One decode step over a stack of layers, launched from native code so that the host keeps ahead of the
-// GPU (a layer is ten small launches).  Layers are taken in groups: the attention of a group's layers on
-// the main stream; then, on the side stream, their monitors and gathers, which thereby overlap the
-// attention of the following groups.  One event pair per group (not per layer) keeps the host cost of the
-// cross-stream ordering small.  The attention of a layer waits for that layer's side work of the
-// previous step (a refill decided at step t is used from step t+1; it also keeps rep_logits / lse from
-// being overwritten while the monitor reads them).
+// GPU.  Layers are taken in groups: the attention of a group's layers on the main stream; then, on the
+// side stream, ONE batched monitor and ONE batched gather for the whole group (seven launches per group
+// instead of seven per layer: these kernels are latency-bound, so a batch costs little more GPU time than
+// one layer, and the host stays ahead).  They overlap the attention of the following groups.  One event
+// pair per group keeps the host cost of the cross-stream ordering small.  The attention of a layer
+// waits for that layer's side work of the previous step (a refill decided at step t is used from step
+// t+1; it also keeps rep_logits / lse from being overwritten while the monitor reads them).
 extern "C" hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* io, int32_t n_layers, int32_t layers_per_group,
                                     void* main_stream, void* side_stream)
 {
     if (!ctx_ok(ctx)) return HC_ESTATE;
-    if (!io || n_layers < 0 || layers_per_group < 1) return hc_fail(ctx, HC_EINVAL, "hc_decode_step: bad argument");
+    if (!io || n_layers < 0 || layers_per_group < 1 || layers_per_group > HC_MAX_GROUP)
+        return hc_fail(ctx, HC_EINVAL, "hc_decode_step: bad argument (layers_per_group 1..%d)", (int)HC_MAX_GROUP);
     hipStream_t ms = (hipStream_t)main_stream, ss = (hipStream_t)side_stream;
+    if (side_stream != nullptr && ss == ms) return hc_fail(ctx, HC_EINVAL, "hc_decode_step: side_stream must differ from main_stream");
     for (int l = 0; l < n_layers; ++l)
         if (!layer_ok(io[l].layer) || io[l].layer->ctx != ctx)
             return hc_fail(ctx, HC_ESTATE, "hc_decode_step: layer %d does not belong to this context", l);
     hipEvent_t last_waited = nullptr;
     for (int g0 = 0; g0 < n_layers; g0 += layers_per_group) {
         const int g1 = std::min(n_layers, g0 + layers_per_group);
-        bool any_side = false;
+        hc_monitor_call mon[HC_MAX_GROUP];
+        hc_gather_call gat[HC_MAX_GROUP];
+        int n_mon = 0, n_gat = 0;
         for (int l = g0; l < g1; ++l) {
             const hc_layer_io& x = io[l];
             hc_layer* L = x.layer;
@@ -573,35 +602,36 @@ extern "C" hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* io, int32_t 
                 last_waited = L->pending_ev;
                 L->pending_ev = nullptr;
             }
-            const bool mon = L->n_reps > 0 && x.scores != nullptr;
-            any_side |= mon;
-            const hc_status st = hc_decode_attn(ctx, L, x.kv_arena, x.q, x.out, x.lse, mon ? x.rep_logits : nullptr, ms);
+            const bool side = L->n_reps > 0 && x.scores != nullptr;
+            if (side) {
+                hc_status st = monitor_check(ctx, L, x.rep_logits, x.lse, x.scores, 0, x.topk_idx, x.base_idx, x.ring, x.inter, x.flag);
+                if (st != HC_OK) return st;
+                mon[n_mon++] = hc_monitor_call{L, x.rep_logits, x.lse, x.scores, x.topk_idx, x.base_idx, x.ring, x.inter, x.flag};
+                if (x.host_tier && L->n_sats > 0) {
+                    st = gather_check(ctx, L, x.host_tier, x.topk_idx, x.flag, x.kv_arena);
+                    if (st != HC_OK) return st;
+                    gat[n_gat++] = hc_gather_call{L, x.host_tier, x.topk_idx, x.flag, const_cast<void*>(x.kv_arena)};
+                }
+            }
+            const hc_status st = hc_decode_attn(ctx, L, x.kv_arena, x.q, x.out, x.lse, side ? x.rep_logits : nullptr, ms);
             if (st != HC_OK) return st;
         }
-        if (!any_side) continue;
+        if (n_mon == 0) continue;
         hc_layer* Lg = io[g1 - 1].layer;          // the group's events live in its last layer
         hipStream_t run = ss ? ss : ms;
         if (ss) {
             HC_HIP(ctx, hipEventRecord(Lg->ev_attn, ms));
             HC_HIP(ctx, hipStreamWaitEvent(ss, Lg->ev_attn, 0));
         }
-        for (int l = g0; l < g1; ++l) {
-            const hc_layer_io& x = io[l];
-            hc_layer* L = x.layer;
-            if (!(L->n_reps > 0 && x.scores != nullptr)) continue;
-            hc_status st = hc_rep_topk_drift(ctx, L, x.rep_logits, x.lse, x.scores, 0, x.topk_idx, x.base_idx, x.ring,
-                                             x.inter, x.flag, run);
-            if (st != HC_OK) return st;
-            if (x.host_tier) {
-                st = hc_gather_retrieve(ctx, L, x.host_tier, x.topk_idx, x.flag, const_cast<void*>(x.kv_arena), run,
-                                        nullptr, nullptr);
-                if (st != HC_OK) return st;
-            }
-        }
+        hc_status st = hc_launch_monitor(ctx, n_mon, mon, 0, run);
+        if (st == HC_OK && n_gat > 0) st = hc_launch_gather(ctx, n_gat, gat, run);
         if (ss) {
-            HC_HIP(ctx, hipEventRecord(Lg->ev_side, ss));
-            for (int l = g0; l < g1; ++l) io[l].layer->pending_ev = Lg->ev_side;
+            // recorded even after a failed launch, so that no later call waits on a stale event
+            const hipError_t e = hipEventRecord(Lg->ev_side, ss);
+            for (int i = 0; i < n_mon; ++i) const_cast<hc_layer*>(mon[i].L)->pending_ev = Lg->ev_side;
+            if (st == HC_OK) HC_HIP(ctx, e);
         }
+        if (st != HC_OK) return st;
     }
     return HC_OK;
 }

@@ -60,6 +60,16 @@ struct SatDev {
     int32_t bh, rep_bh, r, first_slot;   // first_slot = sink + recent
 };
 
+struct hc_monitor_ws {
+    uint32_t* hist = nullptr;      // [max_reps][HC_MAX_K_PER_REP][3][HC_RADIX_BINS]
+    uint32_t* sel = nullptr;       // [max_reps][HC_MAX_K_PER_REP][4]: prefix, remaining k, (tau, need)
+    uint32_t* misc = nullptr;      // [max_reps][4]: spare
+    uint32_t* cnt = nullptr;       // [max_reps][HC_MAX_K_PER_REP][max_chunks][2]: greater, equal
+    uint32_t* bitmap = nullptr;    // [max_reps][max_ctx/32]
+    uint32_t* hits = nullptr;      // [max_reps][max_chunks+1]: per-chunk |T ∩ baseline|
+    bool dirty = true;             // histograms / bitmap not known to be clear (first call, or a call that failed midway)
+};
+
 struct hc_ctx {
     uint32_t magic;
     hc_config cfg;
@@ -74,17 +84,11 @@ struct hc_ctx {
     float* part_acc = nullptr;   // [slots][G][D]
     float* part_ml = nullptr;    // [slots][G][2]  (running max in log2 units, sum)
     size_t part_slots = 0;
-    // selection workspace, sized for max_reps pivots
+    // selection workspace, sized for max_reps pivots; one copy per layer of a batched monitor call
     int max_reps = 0;
-    uint32_t* hist = nullptr;      // [max_reps][HC_MAX_K_PER_REP][3][HC_RADIX_BINS]
-    uint32_t* sel = nullptr;       // [max_reps][HC_MAX_K_PER_REP][4]: prefix, remaining k, (tau, need)
-    uint32_t* cnt = nullptr;       // [max_reps][HC_MAX_K_PER_REP][max_chunks][2]: greater, equal
-    uint32_t* bitmap = nullptr;    // [max_reps][max_ctx/32]
-    uint32_t* misc = nullptr;      // [max_reps][4]: spare
-    uint32_t* hits = nullptr;      // [max_reps][max_chunks+1]: per-chunk |T ∩ baseline|
+    uint32_t* ws_base = nullptr;   // the one allocation behind all lanes
+    hc_monitor_ws ws[HC_MAX_GROUP];
     int max_chunks = 0;
-    bool monitor_dirty = true;     // histograms / bitmap not known to be clear (first call, or a call that failed midway)
-    size_t zero_words = 0;         // words of the contiguous region cleared at the start of a monitor call
 };
 
 struct hc_layer {
@@ -120,11 +124,23 @@ hc_status hc_hip_fail(hc_ctx* ctx, hipError_t e, const char* what);
         if (e_ != hipSuccess) return hc_hip_fail((ctx), e_, #call);   \
     } while (0)
 
-// kernel launchers (one translation unit each)
+// kernel launchers (one translation unit each).  Monitor and gather take a batch of 1..HC_MAX_GROUP
+// layers and handle it with the launches of one layer.
+struct hc_monitor_call {
+    const hc_layer* L;
+    const float* rep_logits;
+    const float* lse;
+    float* scores;
+    int32_t *topk_idx, *base_idx, *ring, *inter, *flag;
+};
+struct hc_gather_call {
+    const hc_layer* L;
+    const void* tier;
+    const int32_t* topk_idx;
+    const int32_t* flag;
+    void* arena;
+};
 hc_status hc_launch_attn(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* q, float* out,
                          float* lse, float* rep_logits, hipStream_t st);
-hc_status hc_launch_monitor(hc_ctx* ctx, const hc_layer* L, const float* rep_logits, const float* lse,
-                            float* scores, int scores_given, int32_t* topk_idx, int32_t* base_idx,
-                            int32_t* ring, int32_t* inter, int32_t* flag, hipStream_t st);
-hc_status hc_launch_gather(hc_ctx* ctx, const hc_layer* L, const void* tier, const int32_t* topk_idx,
-                           const int32_t* flag, void* arena, hipStream_t st);
+hc_status hc_launch_monitor(hc_ctx* ctx, int n, const hc_monitor_call* calls, int scores_given, hipStream_t st);
+hc_status hc_launch_gather(hc_ctx* ctx, int n, const hc_gather_call* calls, hipStream_t st);

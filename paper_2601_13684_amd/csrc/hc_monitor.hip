@@ -72,6 +72,27 @@ struct Ws {
     }
 };
 
+// One layer of a batched call: its workspace copy, its plan and the caller's buffers.  A launch handles
+// up to HC_MAX_GROUP layers (blockIdx.z picks the layer), so that a group of layers costs the launches
+// and the launch latencies of one.
+struct MonItem {
+    Ws ws;
+    const RepDev* reps;
+    const OutDev* outs;
+    const float* rep_logits;
+    const float* lse;
+    float* scores;
+    int32_t* topk_idx;
+    int32_t* base_idx;
+    int32_t* ring;
+    int32_t* inter;
+    int32_t* flag;
+    int n_reps, n_outs;
+};
+struct MonBatch {
+    MonItem it[HC_MAX_GROUP];
+};
+
 __device__ __forceinline__ uint32_t wave_exscan(uint32_t v, uint32_t& total)
 {
     const int lane = threadIdx.x & 63;
@@ -186,14 +207,18 @@ __device__ __forceinline__ float score_of(const float* __restrict__ lrow, int j,
 }
 
 template <int G>
-__global__ __launch_bounds__(BLK) void mon_score_hist(Ws ws, const RepDev* __restrict__ reps,
-                                                      const float* __restrict__ rep_logits,
-                                                      const float* __restrict__ lse, float* __restrict__ scores,
-                                                      int scores_given, int agg, const int32_t* __restrict__ base_idx,
-                                                      int max_k)
+__global__ __launch_bounds__(BLK) void mon_score_hist(MonBatch B, int scores_given, int agg, int max_k)
 {
     __shared__ uint32_t sh[HC_RADIX_BINS];
+    const MonItem& it = B.it[blockIdx.z];
     const int rep = blockIdx.y;
+    if (rep >= it.n_reps) return;
+    const Ws ws = it.ws;
+    const RepDev* __restrict__ reps = it.reps;
+    const float* __restrict__ rep_logits = it.rep_logits;
+    const float* __restrict__ lse = it.lse;
+    float* __restrict__ scores = it.scores;
+    const int32_t* __restrict__ base_idx = it.base_idx;
     const RepDev rd = reps[rep];
     if ((int)blockIdx.x >= rd.nchunk) return;
     const RepWs w = ws.rep(rep);
@@ -252,11 +277,16 @@ __device__ __forceinline__ void load_keys(const float* __restrict__ srow, int fi
 // among keys whose upper 22 bits match.  One workgroup handles every set size of its pivot: wave ks
 // finds the digit of set size ks, then all waves histogram their candidates for each set size.
 template <int PASS>
-__global__ __launch_bounds__(BLK) void mon_hist(Ws ws, const RepDev* __restrict__ reps, const float* __restrict__ scores)
+__global__ __launch_bounds__(BLK) void mon_hist(MonBatch B)
 {
     extern __shared__ uint32_t sh[];              // [nk][HC_RADIX_BINS]
     __shared__ uint32_t sm_prefix[HC_MAX_K_PER_REP];
+    const MonItem& it = B.it[blockIdx.z];
     const int rep = blockIdx.y;
+    if (rep >= it.n_reps) return;
+    const Ws ws = it.ws;
+    const RepDev* __restrict__ reps = it.reps;
+    const float* __restrict__ scores = it.scores;
     const RepDev rd = reps[rep];
     const int lo4 = rd.lo & ~3;
     const int nchunk = (rd.hi - lo4 + HC_SEL_CHUNK - 1) / HC_SEL_CHUNK;
@@ -303,11 +333,16 @@ __global__ __launch_bounds__(BLK) void mon_hist(Ws ws, const RepDev* __restrict_
         if (sh[i]) atomicAdd(&gh[i], sh[i]);
 }
 
-__global__ __launch_bounds__(BLK) void mon_count(Ws ws, const RepDev* __restrict__ reps, const float* __restrict__ scores)
+__global__ __launch_bounds__(BLK) void mon_count(MonBatch B)
 {
     __shared__ uint32_t sm_tau[HC_MAX_K_PER_REP];
     __shared__ uint32_t red[HC_MAX_K_PER_REP][2][NWAVE];
+    const MonItem& it = B.it[blockIdx.z];
     const int rep = blockIdx.y;
+    if (rep >= it.n_reps) return;
+    const Ws ws = it.ws;
+    const RepDev* __restrict__ reps = it.reps;
+    const float* __restrict__ scores = it.scores;
     const RepDev rd = reps[rep];
     const int lo4 = rd.lo & ~3;
     const int nchunk = (rd.hi - lo4 + HC_SEL_CHUNK - 1) / HC_SEL_CHUNK;
@@ -363,13 +398,17 @@ struct DriftCfg {
     int window, metric, tau_num, tau_den, max_k;
 };
 
-__global__ __launch_bounds__(BLK) void mon_write(Ws ws, const RepDev* __restrict__ reps, const OutDev* __restrict__ outs,
-                                                 const float* __restrict__ scores, int32_t* __restrict__ topk_idx,
-                                                 DriftCfg cfg)
+__global__ __launch_bounds__(BLK) void mon_write(MonBatch B, DriftCfg cfg)
 {
     __shared__ uint32_t sm[NWAVE];
     __shared__ uint32_t sm_off[2];
-    const OutDev od = outs[blockIdx.y];
+    const MonItem& it = B.it[blockIdx.z];
+    if ((int)blockIdx.y >= it.n_outs) return;
+    const Ws ws = it.ws;
+    const RepDev* __restrict__ reps = it.reps;
+    const float* __restrict__ scores = it.scores;
+    int32_t* __restrict__ topk_idx = it.topk_idx;
+    const OutDev od = it.outs[blockIdx.y];
     const RepDev rd = reps[od.rep];
     const int chunk = blockIdx.x;
     const int lo4 = rd.lo & ~3;
@@ -450,11 +489,17 @@ __global__ __launch_bounds__(BLK) void mon_write(Ws ws, const RepDev* __restrict
 
 // One workgroup per pivot, after mon_write has completed (the kernel boundary makes its lists and the
 // intersection count visible): window update, decision, baseline update.
-__global__ __launch_bounds__(BLK) void mon_decide(Ws ws, const RepDev* __restrict__ reps, const int32_t* __restrict__ topk_idx,
-                                                  int32_t* __restrict__ base_idx, int32_t* __restrict__ ring,
-                                                  int32_t* __restrict__ inter_out, int32_t* __restrict__ flag_out,
-                                                  DriftCfg cfg)
+__global__ __launch_bounds__(BLK) void mon_decide(MonBatch B, DriftCfg cfg)
 {
+    const MonItem& it = B.it[blockIdx.y];
+    if ((int)blockIdx.x >= it.n_reps) return;
+    const Ws ws = it.ws;
+    const RepDev* __restrict__ reps = it.reps;
+    const int32_t* __restrict__ topk_idx = it.topk_idx;
+    int32_t* __restrict__ base_idx = it.base_idx;
+    int32_t* __restrict__ ring = it.ring;
+    int32_t* __restrict__ inter_out = it.inter;
+    int32_t* __restrict__ flag_out = it.flag;
     // The lower median is found by ranking (no local arrays: they would live in scratch memory, and a
     // kernel that needs scratch is far slower to launch).
     __shared__ int32_t sm_ring[HC_MAX_WINDOW];
@@ -516,48 +561,65 @@ __global__ __launch_bounds__(BLK) void mon_decide(Ws ws, const RepDev* __restric
     for (int i = threadIdx.x; i < (rd.hi + 31) / 32; i += BLK) w.bitmap[i] = 0u;
 }
 
-template <int G>
-void launch_score_hist(Ws ws, const hc_layer* L, const float* rep_logits, const float* lse, float* scores,
-                       int scores_given, int agg, const int32_t* base_idx, int max_k, hipStream_t st)
-{
-    mon_score_hist<G><<<dim3(L->max_nchunk, L->n_reps), dim3(BLK), 0, st>>>(ws, L->reps, rep_logits, lse, scores,
-                                                                            scores_given, agg, base_idx, max_k);
-}
-
 }   // namespace
 
-hc_status hc_launch_monitor(hc_ctx* ctx, const hc_layer* L, const float* rep_logits, const float* lse, float* scores,
-                            int scores_given, int32_t* topk_idx, int32_t* base_idx, int32_t* ring, int32_t* inter,
-                            int32_t* flag, hipStream_t st)
+hc_status hc_launch_monitor(hc_ctx* ctx, int n, const hc_monitor_call* calls, int scores_given, hipStream_t st)
 {
-    Ws ws{ctx->hist, ctx->sel, ctx->misc, ctx->cnt, ctx->bitmap, ctx->hits, ctx->max_chunks, ctx->cfg.max_ctx};
+    if (n < 1 || n > HC_MAX_GROUP) return hc_fail(ctx, HC_EINVAL, "monitor batch of %d layers", n);
     const hc_config& c = ctx->cfg;
-    if (ctx->monitor_dirty) {     // a previous call did not run to its last kernel
-        mon_prep<<<dim3(16, ctx->max_reps), dim3(256), 0, st>>>(ws, ctx->cfg.max_ctx);
-        HC_HIP(ctx, hipGetLastError());
+    MonBatch B{};
+    int max_reps = 0, max_outs = 0, max_nchunk = 0, max_nk = 0;
+    for (int i = 0; i < n; ++i) {
+        const hc_monitor_call& x = calls[i];
+        hc_monitor_ws& m = ctx->ws[i];
+        MonItem& it = B.it[i];
+        it.ws = Ws{m.hist, m.sel, m.misc, m.cnt, m.bitmap, m.hits, ctx->max_chunks, c.max_ctx};
+        it.reps = x.L->reps;
+        it.outs = x.L->outs;
+        it.rep_logits = x.rep_logits;
+        it.lse = x.lse;
+        it.scores = x.scores;
+        it.topk_idx = x.topk_idx;
+        it.base_idx = x.base_idx;
+        it.ring = x.ring;
+        it.inter = x.inter;
+        it.flag = x.flag;
+        it.n_reps = x.L->n_reps;
+        it.n_outs = x.L->n_outs;
+        max_reps = std::max(max_reps, x.L->n_reps);
+        max_outs = std::max(max_outs, x.L->n_outs);
+        max_nchunk = std::max(max_nchunk, x.L->max_nchunk);
+        max_nk = std::max(max_nk, x.L->max_nk);
+        if (m.dirty) {     // a previous call that used this workspace copy did not run to its last kernel
+            mon_prep<<<dim3(16, ctx->max_reps), dim3(256), 0, st>>>(it.ws, c.max_ctx);
+            HC_HIP(ctx, hipGetLastError());
+        }
+        m.dirty = true;
     }
-    ctx->monitor_dirty = true;
+    if (max_reps == 0) return HC_OK;
+    const dim3 g1(max_nchunk, max_reps, n);
     switch (ctx->G) {
-    case 1: launch_score_hist<1>(ws, L, rep_logits, lse, scores, scores_given, c.agg, base_idx, c.max_k, st); break;
-    case 2: launch_score_hist<2>(ws, L, rep_logits, lse, scores, scores_given, c.agg, base_idx, c.max_k, st); break;
-    case 4: launch_score_hist<4>(ws, L, rep_logits, lse, scores, scores_given, c.agg, base_idx, c.max_k, st); break;
-    default: launch_score_hist<8>(ws, L, rep_logits, lse, scores, scores_given, c.agg, base_idx, c.max_k, st); break;
+    case 1: mon_score_hist<1><<<g1, dim3(BLK), 0, st>>>(B, scores_given, c.agg, c.max_k); break;
+    case 2: mon_score_hist<2><<<g1, dim3(BLK), 0, st>>>(B, scores_given, c.agg, c.max_k); break;
+    case 4: mon_score_hist<4><<<g1, dim3(BLK), 0, st>>>(B, scores_given, c.agg, c.max_k); break;
+    default: mon_score_hist<8><<<g1, dim3(BLK), 0, st>>>(B, scores_given, c.agg, c.max_k); break;
     }
     HC_HIP(ctx, hipGetLastError());
     // the later passes start at a multiple of 4 positions, which can add one chunk
-    const dim3 gk(L->max_nchunk + 1, L->n_reps);
-    const size_t hist_lds = (size_t)L->max_nk * HC_RADIX_BINS * sizeof(uint32_t);
-    mon_hist<2><<<gk, dim3(BLK), hist_lds, st>>>(ws, L->reps, scores);
+    const dim3 gk(max_nchunk + 1, max_reps, n);
+    const size_t hist_lds = (size_t)max_nk * HC_RADIX_BINS * sizeof(uint32_t);
+    mon_hist<2><<<gk, dim3(BLK), hist_lds, st>>>(B);
     HC_HIP(ctx, hipGetLastError());
-    mon_hist<3><<<gk, dim3(BLK), hist_lds, st>>>(ws, L->reps, scores);
+    mon_hist<3><<<gk, dim3(BLK), hist_lds, st>>>(B);
     HC_HIP(ctx, hipGetLastError());
-    mon_count<<<gk, dim3(BLK), 0, st>>>(ws, L->reps, scores);
+    mon_count<<<gk, dim3(BLK), 0, st>>>(B);
     HC_HIP(ctx, hipGetLastError());
     DriftCfg dc{c.window, c.metric, c.tau_num, c.tau_den, c.max_k};
-    mon_write<<<dim3(L->max_nchunk + 1, L->n_outs), dim3(BLK), 0, st>>>(ws, L->reps, L->outs, scores, topk_idx, dc);
+    mon_write<<<dim3(max_nchunk + 1, max_outs, n), dim3(BLK), 0, st>>>(B, dc);
     HC_HIP(ctx, hipGetLastError());
-    mon_decide<<<dim3(L->n_reps), dim3(BLK), 0, st>>>(ws, L->reps, topk_idx, base_idx, ring, inter, flag, dc);
+    mon_decide<<<dim3(max_reps, n), dim3(BLK), 0, st>>>(B, dc);
     HC_HIP(ctx, hipGetLastError());
-    ctx->monitor_dirty = false;   // everything enqueued: the workspace will be clear again when this call completes
+    // everything enqueued: the workspace copies will be clear again when this call completes
+    for (int i = 0; i < n; ++i) ctx->ws[i].dirty = false;
     return HC_OK;
 }

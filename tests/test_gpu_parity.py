@@ -511,9 +511,10 @@ def test_config4_full_size_single_layer():
 # ------------------------------------------------------------------------------------------
 # hc_decode_step: the native launch loop over a stack of layers, monitor and gather on a side stream
 # ------------------------------------------------------------------------------------------
-def test_decode_step_stack_of_layers_matches_oracle():
-    say("hc_decode_step, 3 layers, 6 steps, side stream")
-    ws = [I.make_workload(2, layer=l, N=8192, scale=0.25) for l in range(3)]
+@pytest.mark.parametrize("n_layers,n_side,group", [(3, 1, 4), (5, 0, 4), (5, 1, 2), (5, 1, 1), (10, 1, 8)])
+def test_decode_step_stack_of_layers_matches_oracle(n_layers, n_side, group):
+    say(f"hc_decode_step, {n_layers} layers, 6 steps, {n_side} side streams, groups of {group}")
+    ws = [I.make_workload(2, layer=l, N=8192, scale=0.25) for l in range(n_layers)]
     ctx = R.Context(R.make_config(ws[0].spec), DEV)
     pairs = []
     for w in ws:
@@ -521,14 +522,14 @@ def test_decode_step_stack_of_layers_matches_oracle():
         gpu = R.LayerRuntime(ctx, w.spec, w.data, retrieved, base, own_scratch=True)
         pairs.append((gpu, ref.RefLayer(w.spec, w.data, retrieved, base), w))
     layers = [p[0] for p in pairs]
-    q_cur = torch.zeros((3, 1, 32, 128), dtype=torch.bfloat16, device=DEV)
+    q_cur = torch.zeros((n_layers, 1, 32, 128), dtype=torch.bfloat16, device=DEV)
     io = R.make_step_io(layers, q_cur)
-    side = torch.cuda.Stream()
+    sides = [torch.cuda.Stream() for _ in range(n_side)]
     triggers = 0
     for t in range(6):
         qs = [w.schedule.next() for _, _, w in pairs]
         q_cur.copy_(torch.stack(qs).to(DEV))
-        hc.hc_decode_step(ctx.handle, io, 3, None, side)
+        hc.hc_decode_step(ctx.handle, io, n_layers, None, sides[0] if sides else None, group)
         torch.cuda.synchronize()
         for l, (gpu, orc, w) in enumerate(pairs):
             rec = orc.step(qs[l])
@@ -543,7 +544,7 @@ def test_decode_step_stack_of_layers_matches_oracle():
             p.spec, p.gpu, p.ref = w.spec, gpu, orc
             assert p.slots_equal_oracle(), f"slots differ at step {t} layer {l}"
     say("  triggers", triggers)
-    assert triggers >= 6
+    assert triggers >= 2 * n_layers
     for gpu, _, _ in pairs:
         gpu.close()
     ctx.close()
