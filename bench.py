@@ -45,6 +45,7 @@ def main():
     ap.add_argument("--dense", action="store_true", help="uncompressed comparison: all 8 KV heads full")
     ap.add_argument("--no-tier", action="store_true", help="no host tier / gather (attention + monitor only)")
     ap.add_argument("--wg-per-cu", type=int, default=0)
+    ap.add_argument("--share-weights", default="", help="16 comma-separated share weights [die*2+slot] (tuning)")
     ap.add_argument("--group", type=int, default=8, help="layers per cross-stream sync group in step mode")
     ap.add_argument("--serial", action="store_true", help="monitor and gather on the main stream (no overlap)")
     ap.add_argument("--attn-only", action="store_true", help="time hc_decode_attn alone (no monitor, no gather)")
@@ -90,6 +91,8 @@ def main():
             spec = I.spec_dense(spec.ctx[0])
         if ctx is None:
             ctx = R.Context(R.make_config(spec), dev, workgroups_per_cu=args.wg_per_cu or None)
+            if args.share_weights:
+                hc.hc_set_share_weights(ctx.handle, [float(x) for x in args.share_weights.split(",")])
         retrieved, base = I.initial_lists(spec)
         layers.append(R.LayerRuntime(ctx, spec, w.data, retrieved, base, host_tier=not args.no_tier, own_scratch=True))
         scheds.append(w.schedule)

@@ -114,6 +114,12 @@ int32_t hc_layer_num_partials(const hc_layer* layer);
 /* Tuning knob (before hc_layer_create): target workgroups per compute unit of the split pass
  * (default 2) and host override of the compute-unit count (0 = ask the device). */
 hc_status hc_set_split(hc_ctx* ctx, int32_t workgroups_per_cu, int32_t compute_units);
+/* Tuning knob (before hc_layer_create): relative size of the share of rows that a workgroup of the
+ * split pass gets, by the die it runs on (workgroup index mod 8) and its dispatch slot (first or
+ * second half of the indices): weights16[die * 2 + slot], each in 0.25..4; NULL restores the built-in
+ * defaults (measured on MI355X: a launch reaches the dies up to ~2 us apart, and they stream at
+ * slightly different rates).  Used when the number of workgroups is a multiple of 16. */
+hc_status hc_set_share_weights(hc_ctx* ctx, const float* weights16);
 
 /* Measurement hook: hands the library n pairs of hipEvent_t (host arrays of handles, copied).  The
  * next n launches of the split-pass kernel, from hc_decode_attn or hc_decode_step, attach pair i to

@@ -14,6 +14,16 @@
 
 #include "hc_internal.h"
 
+// Relative share of rows of a split-pass workgroup by die (workgroup index mod 8) and dispatch slot
+// (first / second half of the indices): [die * 2 + slot].  Measured on MI355X with equal shares at the
+// 224K-context shape (about 940 rows per workgroup): a launch reaches dies 0-1 first, dies 2-3 about
+// 1.4 us and dies 4-7 about 1.5-2.3 us later; the second workgroup on a compute unit streams about 5 %
+// slower than the first, odd dies about 3 % slower than even ones.  These weights equalise the mean
+// finish time of the 16 classes there (worth about 1 % of the pass); they are applied only to passes
+// long enough for such small corrections to be meaningful.
+static const float DEFAULT_SHARE_WEIGHTS[16] = {1.11f, 1.04f, 1.07f, 0.99f, 1.04f, 0.97f, 1.00f, 0.92f,
+                                                1.04f, 0.98f, 0.96f, 0.90f, 1.07f, 0.99f, 1.00f, 0.93f};
+
 hc_status hc_fail(hc_ctx* ctx, hc_status st, const char* fmt, ...)
 {
     if (ctx) {
@@ -87,6 +97,7 @@ extern "C" hc_status hc_create(const hc_config* cfg, hc_ctx** out)
     c->cfg = *cfg;
     c->G = G;
     c->wg_per_cu = 2;
+    for (int i = 0; i < 16; ++i) c->share_weights[i] = DEFAULT_SHARE_WEIGHTS[i];
     c->err[0] = 0;
     hipDeviceProp_t prop;
     hipError_t e = hipGetDevice(&c->device);
@@ -145,6 +156,17 @@ extern "C" hc_status hc_set_split(hc_ctx* ctx, int32_t workgroups_per_cu, int32_
         return hc_fail(ctx, HC_EINVAL, "hc_set_split: workgroups_per_cu 1..16, compute_units 0..4096");
     ctx->wg_per_cu = workgroups_per_cu;
     if (compute_units > 0) ctx->n_cu = compute_units;
+    return HC_OK;
+}
+
+extern "C" hc_status hc_set_share_weights(hc_ctx* ctx, const float* weights16)
+{
+    if (!ctx_ok(ctx)) return HC_ESTATE;
+    for (int i = 0; i < 16; ++i) {
+        const float w = weights16 ? weights16[i] : DEFAULT_SHARE_WEIGHTS[i];
+        if (!(w >= 0.25f && w <= 4.0f)) return hc_fail(ctx, HC_EINVAL, "hc_set_share_weights: weight %d outside 0.25..4", i);
+        ctx->share_weights[i] = w;
+    }
     return HC_OK;
 }
 
@@ -229,8 +251,8 @@ struct ErrBuf {
     }
 };
 
-static hc_status make_plan(const hc_config& cfg, const hc_head_desc* hd, int n_cu, int wg_per_cu, Plan& P,
-                           const ErrBuf& E)
+static hc_status make_plan(const hc_config& cfg, const hc_head_desc* hd, int n_cu, int wg_per_cu, const float* share_weights,
+                           Plan& P, const ErrBuf& E)
 {
     const int nh = cfg.B * cfg.Hkv;
     const int max_reps = std::max(1, nh / 2);
@@ -357,9 +379,23 @@ static hc_status make_plan(const hc_config& cfg, const hc_head_desc* hd, int n_c
     int head = 0;
     int64_t head_first_unit = 0;      // global index of the current head's first granule
     int slot = 0;
+    // Share boundaries in granules: equal shares, or, when the placement below applies, shares weighted by
+    // the die and dispatch slot the share will run on (share l runs on die (l % 16) / 2, slot l % 2).
+    std::vector<int64_t> bound(nb + 1, 0);
+    {
+        const bool weighted = share_weights && nb % 16 == 0 && total_units >= 16 * (int64_t)nb;   // >= 512 rows per workgroup
+        double total_w = 0;
+        for (int l = 0; l < nb; ++l) total_w += weighted ? share_weights[((l % 16) / 2) * 2 + l % 2] : 1.0;
+        double acc_w = 0;
+        for (int l = 0; l < nb; ++l) {
+            acc_w += weighted ? share_weights[((l % 16) / 2) * 2 + l % 2] : 1.0;
+            bound[l + 1] = l + 1 == nb ? total_units : (int64_t)((double)total_units * acc_w / total_w + 0.5);
+            if (bound[l + 1] < bound[l]) bound[l + 1] = bound[l];
+        }
+    }
     for (int blk = 0; blk < nb; ++blk) {
-        int64_t u0 = total_units * blk / nb;
-        const int64_t u1 = total_units * (blk + 1) / nb;
+        int64_t u0 = bound[blk];
+        const int64_t u1 = bound[blk + 1];
         P.blk_seg[blk] = (int32_t)P.segs.size();
         while (u0 < u1) {
             int64_t head_units = (hd[head].len + HC_UNIT_ROWS - 1) / HC_UNIT_ROWS;
@@ -413,7 +449,7 @@ extern "C" hc_status hc_plan_describe(const hc_config* cfg, const hc_head_desc* 
     if (cs != HC_OK) return cs;
     if (compute_units < 1 || compute_units > 4096 || workgroups_per_cu < 1 || workgroups_per_cu > 16) return HC_EINVAL;
     Plan P;
-    const hc_status st = make_plan(*cfg, heads_host, compute_units, workgroups_per_cu, P,
+    const hc_status st = make_plan(*cfg, heads_host, compute_units, workgroups_per_cu, DEFAULT_SHARE_WEIGHTS, P,
                                    ErrBuf{err, err_len > 0 ? (size_t)err_len : 0});
     if (st != HC_OK) return st;
     memset(info, 0, sizeof *info);
@@ -446,7 +482,7 @@ extern "C" hc_status hc_layer_create(hc_ctx* ctx, const hc_head_desc* hd, hc_lay
     if (!hd || !out) return hc_fail(ctx, HC_EINVAL, "hc_layer_create: null argument");
     *out = nullptr;
     Plan P;
-    hc_status st = make_plan(ctx->cfg, hd, ctx->n_cu, ctx->wg_per_cu, P, ErrBuf{ctx->err, sizeof ctx->err});
+    hc_status st = make_plan(ctx->cfg, hd, ctx->n_cu, ctx->wg_per_cu, ctx->share_weights, P, ErrBuf{ctx->err, sizeof ctx->err});
     if (st != HC_OK) return st;
 
     hc_layer* L = new (std::nothrow) hc_layer();

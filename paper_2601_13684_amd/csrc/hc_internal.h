@@ -76,6 +76,7 @@ struct hc_ctx {
     int G;
     int n_cu;
     int wg_per_cu;
+    float share_weights[16];     // by die and dispatch slot, see hc_set_share_weights
     int device;
     char err[512];
     std::vector<std::pair<hipEvent_t, hipEvent_t>> timing;   // optional timing hook: one pair per split-pass launch

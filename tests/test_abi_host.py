@@ -118,9 +118,10 @@ def test_plan_of_the_224k_layer_is_balanced_and_covers_every_row():
     assert info.total_rows == 2 * 229376 + 21504 == info.rows_covered
     assert info.n_reps == 2 and info.n_satellites == 6 and info.n_lists == 8
     assert info.n_partials <= 512 + 8
-    # equal shares up to one 32-row granule (+ the ragged tails of the heads a share crosses)
-    assert info.max_rows_per_workgroup - info.min_rows_per_workgroup <= 64
-    assert info.max_rows_per_workgroup <= 480256 // 512 + 64
+    # shares are equal up to the built-in die / dispatch-slot weights (0.90 .. 1.11 of the mean) and one
+    # 32-row granule (+ the ragged tails of the heads a share crosses)
+    mean = 480256 / 512
+    assert 0.90 * mean - 64 <= info.min_rows_per_workgroup <= info.max_rows_per_workgroup <= 1.11 * mean + 64
 
 
 @pytest.mark.parametrize("cus,wg", [(1, 1), (8, 2), (256, 2), (256, 8), (304, 4)])
