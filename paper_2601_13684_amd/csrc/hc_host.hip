@@ -376,44 +376,66 @@ static hc_status make_plan(const hc_config& cfg, const hc_head_desc* hd, int n_c
     const int nb = (int)std::max<int64_t>(1, std::min<int64_t>(max_blocks, total_units / min_units));
     P.n_blocks = nb;
     P.blk_seg.assign(nb + 1, 0);
-    int head = 0;
-    int64_t head_first_unit = 0;      // global index of the current head's first granule
-    int slot = 0;
-    // Share boundaries in granules: equal shares, or, when the placement below applies, shares weighted by
-    // the die and dispatch slot the share will run on (share l runs on die (l % 16) / 2, slot l % 2).
-    std::vector<int64_t> bound(nb + 1, 0);
+    // Long passes whose workgroups come in whole groups of one per die and dispatch slot get shares
+    // weighted by the class the share runs on (share l runs on die (l % 16) / 2, slot l % 2).
+    const bool weighted = share_weights != nullptr && nb % 16 == 0 && total_units >= 16 * (int64_t)nb;   // >= 512 rows per workgroup
+
+    std::vector<int64_t> head_first(nh + 1, 0);        // first granule of every head
+    for (int i = 0; i < nh; ++i) head_first[i + 1] = head_first[i] + (hd[i].len + HC_UNIT_ROWS - 1) / HC_UNIT_ROWS;
+    auto head_of_unit = [&](int64_t u) {
+        return (int)(std::upper_bound(head_first.begin(), head_first.end(), u) - head_first.begin()) - 1;
+    };
+
+    // Shares are cut on a cost axis: one per granule, plus SEG_COST granules at every head boundary, because a
+    // workgroup whose share crosses a boundary closes one state (merge of its waves, partial result
+    // written) and opens another (new query rows, load pipeline refilled), which costs it the time of
+    // about 100 rows.  cost_start[h] is where head h's boundary cost begins; its granules follow it.
+    // (Measured at the 224K shape: the workgroups that cross a boundary were the last to finish by 2 us.)
+    const int64_t SEG_COST = total_units >= 16 * (int64_t)nb ? 3 : 0;
+    std::vector<int64_t> cost_start(nh + 1, 0);
+    for (int i = 1; i <= nh; ++i) cost_start[i] = head_first[i] + SEG_COST * (i - 1);
+    const int64_t total_cost = cost_start[nh];            // = total_units + SEG_COST * (nh - 1)
+    auto unit_of_cost = [&](int64_t cst) {                 // first granule at or after this point of the cost axis
+        if (cst >= total_cost) return total_units;
+        const int h = (int)(std::upper_bound(cost_start.begin(), cost_start.begin() + nh, cst) - cost_start.begin()) - 1;
+        const int64_t into = cst - cost_start[h] - (h > 0 ? SEG_COST : 0);
+        return head_first[h] + std::max<int64_t>(0, into);
+    };
+
+    // share boundaries [lo, hi) in granules
+    std::vector<int64_t> lo(nb), hi(nb);
     {
-        const bool weighted = share_weights && nb % 16 == 0 && total_units >= 16 * (int64_t)nb;   // >= 512 rows per workgroup
         double total_w = 0;
-        for (int l = 0; l < nb; ++l) total_w += weighted ? share_weights[((l % 16) / 2) * 2 + l % 2] : 1.0;
+        for (int l = 0; l < nb; ++l) total_w += weighted ? share_weights[l % 16] : 1.0;
         double acc_w = 0;
+        int64_t prev = 0;
         for (int l = 0; l < nb; ++l) {
-            acc_w += weighted ? share_weights[((l % 16) / 2) * 2 + l % 2] : 1.0;
-            bound[l + 1] = l + 1 == nb ? total_units : (int64_t)((double)total_units * acc_w / total_w + 0.5);
-            if (bound[l + 1] < bound[l]) bound[l + 1] = bound[l];
+            acc_w += weighted ? share_weights[l % 16] : 1.0;
+            int64_t end = l + 1 == nb ? total_units : unit_of_cost((int64_t)((double)total_cost * acc_w / total_w + 0.5));
+            end = std::min(std::max(end, prev), total_units);
+            lo[l] = prev;
+            hi[l] = end;
+            prev = end;
         }
     }
+
+    // segments of the shares, one partial-result slot each
     for (int blk = 0; blk < nb; ++blk) {
-        int64_t u0 = bound[blk];
-        const int64_t u1 = bound[blk + 1];
+        int64_t u0 = lo[blk];
+        const int64_t u1 = hi[blk];
         P.blk_seg[blk] = (int32_t)P.segs.size();
         while (u0 < u1) {
-            int64_t head_units = (hd[head].len + HC_UNIT_ROWS - 1) / HC_UNIT_ROWS;
-            while (u0 >= head_first_unit + head_units) {
-                head_first_unit += head_units;
-                ++head;
-                head_units = (hd[head].len + HC_UNIT_ROWS - 1) / HC_UNIT_ROWS;
-            }
-            const int64_t take_end = std::min(u1, head_first_unit + head_units);
+            const int head = head_of_unit(u0);
+            const int64_t take_end = std::min(u1, head_first[head + 1]);
             SegDev sg;
             sg.k_off = hd[head].k_off;
             sg.v_off = hd[head].v_off;
             sg.rep_slot = P.rep_slot_of[head];
             sg.pad = 0;
             sg.bh = head;
-            sg.row_begin = (int32_t)((u0 - head_first_unit) * HC_UNIT_ROWS);
-            sg.row_end = (int32_t)std::min<int64_t>((take_end - head_first_unit) * HC_UNIT_ROWS, hd[head].len);
-            sg.slot = slot++;
+            sg.row_begin = (int32_t)((u0 - head_first[head]) * HC_UNIT_ROWS);
+            sg.row_end = (int32_t)std::min<int64_t>((take_end - head_first[head]) * HC_UNIT_ROWS, hd[head].len);
+            sg.slot = (int32_t)P.segs.size();
             if (P.heads[head].part_count == 0) P.heads[head].part_begin = sg.slot;
             P.heads[head].part_count++;
             P.segs.push_back(sg);
@@ -421,6 +443,8 @@ static hc_status make_plan(const hc_config& cfg, const hc_head_desc* hd, int n_c
         }
     }
     P.blk_seg[nb] = (int32_t)P.segs.size();
+    for (int blk = 0; blk < nb; ++blk)
+        if (P.blk_seg[blk] == P.blk_seg[blk + 1]) return E.fail(HC_ESTATE, "internal: workgroup %d has no rows", blk);
 
     // Placement.  On MI355X a workgroup's index modulo 8 is the die (XCD) it runs on, and with two
     // workgroups per compute unit the second half of the indices are the second ones dispatched; dies

@@ -117,6 +117,38 @@ def test_attention_batched_ragged_contexts():
     p.close()
 
 
+@pytest.mark.parametrize("cus,wg", [(16, 1), (32, 2), (8, 2), (64, 2)])
+def test_attention_with_few_workgroups_and_weighted_shares(cus, wg):
+    """A plan with few workgroups, so that a small batch gets the long-pass treatment (shares weighted by
+    die and dispatch slot, head boundaries charged): shares crossing several small heads, pivots' logits
+    staged across chunk boundaries; three calls in a row."""
+    say("attention, few workgroups", cus, wg)
+    spec = I.spec_ragged(41, B=6, lo=1500, hi=7000, budgets=(96, 160, 352))
+    for b in range(spec.B):
+        spec.heads[b] = [h if h.role == I.ROLE_FULL else I.HeadSpec(h.role, rep=h.rep, sink=16, recent=32, budget=h.budget)
+                         for h in spec.heads[b]]
+    q0 = I.draw_q(spec, 42)
+    data = I.draw_layer(spec, q0, 43, heavy_frac=0.01)
+    ctx = R.Context(R.make_config(spec), DEV)
+    hc.hc_set_split(ctx.handle, wg, cus)
+    p = U.Pair(spec, data, DEV, ctx=ctx, host_tier=False)
+    assert hc.hc_layer_num_workgroups(p.gpu.handle) == cus * wg
+    rec = p.ref.step(q0.to(torch.bfloat16), monitor=True)
+    for call in range(3):
+        p.gpu.out.zero_()
+        p.gpu.lse.zero_()
+        p.gpu.rep_logits.zero_()
+        p.gpu.attn(q0.to(torch.bfloat16).to(DEV))
+        torch.cuda.synchronize()
+        worst, lerr = U.check_attention(p.gpu.out, p.gpu.lse, rec, f"call {call}")
+        for (b, h), lg in rec["logits"].items():
+            got = p.gpu.rep_logits[p.gpu.rep_slot(b, h), :spec.ctx[b], :].T.cpu().double().numpy()
+            assert np.abs(got - lg).max() < 2e-5, (call, b, h, np.abs(got - lg).max())
+    say("  max err/rms", worst, "lse err", lerr, "partials", hc.hc_layer_num_partials(p.gpu.handle))
+    p.close()
+    ctx.close()
+
+
 # ------------------------------------------------------------------------------------------
 # A6-A7 on given scores: integer work, bit-exact
 # ------------------------------------------------------------------------------------------
