@@ -117,8 +117,8 @@ hc_status hc_set_split(hc_ctx* ctx, int32_t workgroups_per_cu, int32_t compute_u
 /* Tuning knob (before hc_layer_create): relative size of the share of rows that a workgroup of the
  * split pass gets, by the die it runs on (workgroup index mod 8) and its dispatch slot (first or
  * second half of the indices): weights16[die * 2 + slot], each in 0.25..4; NULL restores the built-in
- * defaults (measured on MI355X: a launch reaches the dies up to ~2 us apart, and they stream at
- * slightly different rates).  Used when the number of workgroups is a multiple of 16. */
+ * defaults (measured on MI355X: the second workgroup on a compute unit and the workgroups on odd
+ * dies stream a few per cent slower).  Used when the number of workgroups is a multiple of 16. */
 hc_status hc_set_share_weights(hc_ctx* ctx, const float* weights16);
 
 /* Measurement hook: hands the library n pairs of hipEvent_t (host arrays of handles, copied).  The

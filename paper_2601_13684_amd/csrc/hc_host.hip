@@ -16,13 +16,12 @@
 
 // Relative share of rows of a split-pass workgroup by die (workgroup index mod 8) and dispatch slot
 // (first / second half of the indices): [die * 2 + slot].  Measured on MI355X with equal shares at the
-// 224K-context shape (about 940 rows per workgroup): a launch reaches dies 0-1 first, dies 2-3 about
-// 1.4 us and dies 4-7 about 1.5-2.3 us later; the second workgroup on a compute unit streams about 5 %
-// slower than the first, odd dies about 3 % slower than even ones.  These weights equalise the mean
-// finish time of the 16 classes there (worth about 1 % of the pass); they are applied only to passes
-// long enough for such small corrections to be meaningful.
-static const float DEFAULT_SHARE_WEIGHTS[16] = {1.11f, 1.04f, 1.07f, 0.99f, 1.04f, 0.97f, 1.00f, 0.92f,
-                                                1.04f, 0.98f, 0.96f, 0.90f, 1.07f, 0.99f, 1.00f, 0.93f};
+// 224K-context shape (about 940 rows per workgroup), in back-to-back launches: the second workgroup on
+// a compute unit finishes about 2 us (6 %) after the first, and workgroups on odd dies about 2.5 us (7 %)
+// after those on even dies.  These weights equalise the mean finish time of the 16 classes there (the pass
+// ends about 1.5 us earlier); they are applied only to passes long enough for such corrections to matter.
+static const float DEFAULT_SHARE_WEIGHTS[16] = {1.07f, 0.99f, 1.02f, 0.95f, 1.06f, 0.99f, 0.99f, 0.92f,
+                                                1.06f, 0.99f, 0.99f, 0.92f, 1.08f, 1.01f, 1.02f, 0.95f};
 
 hc_status hc_fail(hc_ctx* ctx, hc_status st, const char* fmt, ...)
 {
