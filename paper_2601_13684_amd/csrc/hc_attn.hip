@@ -56,6 +56,21 @@ constexpr int DPP_XOR2 = 0x4E;         // quad_perm [2,3,0,1]
 constexpr int DPP_HALF_MIRROR = 0x141; // lane i <-> 7-i inside each group of 8
 constexpr int DPP_ROR8 = 0x128;        // lane i <-> i^8 inside a row of 16
 
+// Lane-swap instructions of gfx950.  swap_rows16: the odd rows of 16 lanes of x change places with the even
+// rows of y (x becomes [x.row0, y.row0, x.row2, y.row2], y becomes [x.row1, y.row1, x.row3, y.row3]);
+// swap_halves32: the upper 32 lanes of x change places with the lower 32 lanes of y.  Written as assembly
+// because the compiler folds "first result + second result" of the corresponding builtins into twice the
+// first (checked on ROCm 7.2); the s_nop covers the wait states the instruction needs after a vector write
+// of its operands.
+__device__ __forceinline__ void swap_rows16(float& x, float& y)
+{
+    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(x), "+v"(y));
+}
+__device__ __forceinline__ void swap_halves32(float& x, float& y)
+{
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(x), "+v"(y));
+}
+
 __device__ __forceinline__ float sum8(float x)   // sum over the 8 column lanes, result in all of them
 {
     x += dpp<DPP_XOR1>(x);
@@ -325,8 +340,8 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
                                                                     float* __restrict__ rep_logits, int max_ctx)
 {
     __shared__ float sm_m[4][G];
-    __shared__ float sm_Z[8][G];
-    __shared__ float sm_red[8][G * HC_D];
+    __shared__ float sm_Z[16][G];
+    __shared__ __attribute__((aligned(16))) float sm_red[4][G * HC_D];
     __shared__ __attribute__((aligned(16))) float sm_stash[2][REP_STASH_FLOATS];
 
     const int tid = threadIdx.x;
@@ -375,55 +390,68 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
         if (st.Z[0] >= 0.f) HC_STAMP(2);
 #endif
 
-        // ---- merge the 4 waves x 8 row lanes into one partial (4 row lanes in registers, the rest in LDS) ----
-#ifdef HC_TUNE
-        if (st.Z[0] >= 0.f) HC_STAMP(3);
-#endif
+        // ---- merge the 4 waves x 8 row lanes into one partial ----
+        // Inside a wave the 16 G accumulators of a lane are summed over the wave's 8 row lanes in registers:
+        // lanes 8 apart by a DPP rotate, then rows of 16 lanes and halves of 32 lanes by the lane-swap
+        // instructions, which reduce TWO registers at a time (afterwards the lanes with lane bit 4 clear
+        // hold the sums of the first register, those with it set the sums of the second; bit 5 likewise), so
+        // the 16 G registers shrink to 4 G and every lane is left with a quarter of the (head, column) sums:
+        // flat index e + 4 G * [bit 5] + 8 G * [bit 4], e < 4 G, of acc[flat / 16][flat % 16].
+        // The four waves' sums, each still relative to its own reference maximum, meet in LDS; one barrier.
+        constexpr int NA = 16 * G;
+        float red[NA / 4];
+        {
+            float half[NA / 2];
+#pragma unroll
+            for (int e = 0; e < NA / 2; ++e) {
+                float x = st.acc[e / 16][e % 16], y = st.acc[(e + NA / 2) / 16][(e + NA / 2) % 16];
+                x += dpp<DPP_ROR8>(x);
+                y += dpp<DPP_ROR8>(y);
+                swap_rows16(x, y);
+                half[e] = x + y;
+            }
+#pragma unroll
+            for (int e = 0; e < NA / 4; ++e) {
+                float x = half[e], y = half[e + NA / 4];
+                swap_halves32(x, y);
+                red[e] = x + y;
+            }
+        }
+        const int sel = ((lane >> 4) & 1) * 2 + (lane >> 5);          // [bit 4] * 2 + [bit 5]
+        if ((lane & 8) == 0) {                                          // lanes 8 apart hold the same sums
+            const int flat0 = (NA / 4) * sel;
+#pragma unroll
+            for (int e = 0; e < NA / 4; e += 4) {
+                const int flat = flat0 + e, g = flat / 16, i = flat % 16;
+                *reinterpret_cast<float4*>(&sm_red[w][g * HC_D + 64 * (i / 8) + 8 * c + (i % 8)]) =
+                    make_float4(red[e], red[e + 1], red[e + 2], red[e + 3]);
+            }
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            float z = st.Z[g];
+            z += dpp<DPP_ROR8>(z);
+            if ((lane & 15) == 0) sm_Z[w * 4 + sel][g] = z;            // one lane per row pair: c == 0, bit 3 clear
+        }
         if (lane == 0) {
 #pragma unroll
             for (int g = 0; g < G; ++g) sm_m[w][g] = st.m[g];
         }
         __syncthreads();
-        float M[G];
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            M[g] = fmaxf(fmaxf(sm_m[0][g], sm_m[1][g]), fmaxf(sm_m[2][g], sm_m[3][g]));
-            const float sc = __builtin_amdgcn_exp2f(st.m[g] - M[g]);
-            float z = st.Z[g] * sc;
-            z += dpp<DPP_ROR8>(z);
-            z += __shfl_xor(z, 16);
-            if ((lane & 31) == 0) sm_Z[w * 2 + (lane >> 5)][g] = z;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                float a = st.acc[g][i] * sc;
-                a += dpp<DPP_ROR8>(a);
-                a += __shfl_xor(a, 16);
-                st.acc[g][i] = a;
-            }
-        }
-        if ((lane & 24) == 0) {
-            float* dst = sm_red[w * 2 + (lane >> 5)];
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    dst[g * HC_D + 8 * c + i] = st.acc[g][i];
-                    dst[g * HC_D + 64 + 8 * c + i] = st.acc[g][8 + i];
-                }
-            }
-        }
-        __syncthreads();
         for (int o = tid; o < G * HC_D; o += 256) {
+            const int g = o / HC_D;
+            const float M = fmaxf(fmaxf(sm_m[0][g], sm_m[1][g]), fmaxf(sm_m[2][g], sm_m[3][g]));
             float a = 0.f;
 #pragma unroll
-            for (int p = 0; p < 8; ++p) a += sm_red[p][o];
+            for (int p = 0; p < 4; ++p) a += sm_red[p][o] * __builtin_amdgcn_exp2f(sm_m[p][g] - M);
             part_acc[(size_t)seg.slot * G * HC_D + o] = a;
         }
         if (tid < G) {
+            const float M = fmaxf(fmaxf(sm_m[0][tid], sm_m[1][tid]), fmaxf(sm_m[2][tid], sm_m[3][tid]));
             float z = 0.f;
 #pragma unroll
-            for (int p = 0; p < 8; ++p) z += sm_Z[p][tid];
-            part_ml[((size_t)seg.slot * G + tid) * 2 + 0] = M[tid];
+            for (int p = 0; p < 16; ++p) z += sm_Z[p][tid] * __builtin_amdgcn_exp2f(sm_m[p / 4][tid] - M);
+            part_ml[((size_t)seg.slot * G + tid) * 2 + 0] = M;
             part_ml[((size_t)seg.slot * G + tid) * 2 + 1] = z;
         }
         HC_STAMP(4);
