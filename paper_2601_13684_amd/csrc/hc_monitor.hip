@@ -106,22 +106,6 @@ __device__ __forceinline__ uint32_t wave_exscan(uint32_t v, uint32_t& total)
     return inc - v;
 }
 
-// Exclusive prefix sum over the workgroup's threads.  sm: NWAVE words.
-__device__ __forceinline__ uint32_t block_exscan(uint32_t v, uint32_t* sm)
-{
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    uint32_t wtot;
-    const uint32_t ex = wave_exscan(v, wtot);
-    __syncthreads();
-    if (lane == 0) sm[w] = wtot;
-    __syncthreads();
-    uint32_t base = 0;
-#pragma unroll
-    for (int i = 0; i < NWAVE; ++i)
-        if (i < w) base += sm[i];
-    return base + ex;
-}
-
 // In a histogram of nbins (<= 2048) digit counts, walking from the highest digit down, find the digit
 // in which the k-th largest element falls and how many of that digit's elements are still needed.
 // Done by ONE wave (lane l owns 32 consecutive digits); result valid in all its lanes.
@@ -206,8 +190,12 @@ __device__ __forceinline__ float score_of(const float* __restrict__ lrow, int j,
     return a * (1.0f / (float)G);
 }
 
+// A workgroup of the selection passes takes `span` consecutive chunks of HC_SEL_CHUNK candidates: 1 when a
+// single layer is handled (many small workgroups: latency), more when a batch of layers is (the histograms
+// in LDS are cleared and flushed once per workgroup, so fewer, longer workgroups do far less work in total
+// and a batch fits a small part of the GPU).
 template <int G>
-__global__ __launch_bounds__(BLK) void mon_score_hist(MonBatch B, int scores_given, int agg, int max_k)
+__global__ __launch_bounds__(BLK) void mon_score_hist(MonBatch B, int scores_given, int agg, int max_k, int span)
 {
     __shared__ uint32_t sh[HC_RADIX_BINS];
     const MonItem& it = B.it[blockIdx.z];
@@ -220,13 +208,15 @@ __global__ __launch_bounds__(BLK) void mon_score_hist(MonBatch B, int scores_giv
     float* __restrict__ scores = it.scores;
     const int32_t* __restrict__ base_idx = it.base_idx;
     const RepDev rd = reps[rep];
-    if ((int)blockIdx.x >= rd.nchunk) return;
+    const int c0 = blockIdx.x * span, c1 = min(c0 + span, rd.nchunk);
+    if (c0 >= rd.nchunk) return;
     const RepWs w = ws.rep(rep);
     for (int i = threadIdx.x; i < HC_RADIX_BINS; i += BLK) sh[i] = 0u;
 
     // baseline list -> bitmap (each workgroup takes a slice of the list)
     const int32_t* base = base_idx + (size_t)rd.bh * max_k;
-    for (int i = blockIdx.x * BLK + threadIdx.x; i < rd.k[0]; i += rd.nchunk * BLK) {
+    const int nblk = (rd.nchunk + span - 1) / span;
+    for (int i = blockIdx.x * BLK + threadIdx.x; i < rd.k[0]; i += nblk * BLK) {
         const int j = base[i];
         if (j >= rd.lo && j < rd.hi) atomicOr(&w.bitmap[j >> 5], 1u << (j & 31));
     }
@@ -237,20 +227,22 @@ __global__ __launch_bounds__(BLK) void mon_score_hist(MonBatch B, int scores_giv
     float l[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) l[g] = (!scores_given && agg == HC_AGG_PROB) ? lse[(size_t)rd.bh * G + g] : 0.f;
-    const int first = rd.lo + blockIdx.x * HC_SEL_CHUNK;
-    float s[PER_THREAD];
+    for (int ch = c0; ch < c1; ++ch) {
+        const int first = rd.lo + ch * HC_SEL_CHUNK;
+        float s[PER_THREAD];
 #pragma unroll
-    for (int i = 0; i < PER_THREAD; ++i) {       // candidate first + i*BLK + t: coalesced, loads independent
-        const int j = first + i * BLK + threadIdx.x;
-        s[i] = 0.f;
-        if (j < rd.hi) s[i] = scores_given ? srow[j] : score_of<G>(lrow, j, l, agg);
-    }
+        for (int i = 0; i < PER_THREAD; ++i) {       // candidate first + i*BLK + t: coalesced, loads independent
+            const int j = first + i * BLK + threadIdx.x;
+            s[i] = 0.f;
+            if (j < rd.hi) s[i] = scores_given ? srow[j] : score_of<G>(lrow, j, l, agg);
+        }
 #pragma unroll
-    for (int i = 0; i < PER_THREAD; ++i) {
-        const int j = first + i * BLK + threadIdx.x;
-        if (j < rd.hi) {
-            if (!scores_given) srow[j] = s[i];
-            atomicAdd(&sh[score_key(s[i]) >> 21], 1u);
+        for (int i = 0; i < PER_THREAD; ++i) {
+            const int j = first + i * BLK + threadIdx.x;
+            if (j < rd.hi) {
+                if (!scores_given) srow[j] = s[i];
+                atomicAdd(&sh[score_key(s[i]) >> 21], 1u);
+            }
         }
     }
     __syncthreads();
@@ -273,11 +265,17 @@ __device__ __forceinline__ void load_keys(const float* __restrict__ srow, int fi
     }
 }
 
+// The later passes work on chunks that start at a multiple of 4 positions (lo4), which can add one chunk.
+__device__ __forceinline__ int chunks_from_lo4(const RepDev& rd)
+{
+    return (rd.hi - (rd.lo & ~3) + HC_SEL_CHUNK - 1) / HC_SEL_CHUNK;
+}
+
 // PASS 2: digit two (bits 20..10) among keys whose first digit matches; PASS 3: digit three (bits 9..0)
 // among keys whose upper 22 bits match.  One workgroup handles every set size of its pivot: wave ks
 // finds the digit of set size ks, then all waves histogram their candidates for each set size.
 template <int PASS>
-__global__ __launch_bounds__(BLK) void mon_hist(MonBatch B)
+__global__ __launch_bounds__(BLK) void mon_hist(MonBatch B, int span)
 {
     extern __shared__ uint32_t sh[];              // [nk][HC_RADIX_BINS]
     __shared__ uint32_t sm_prefix[HC_MAX_K_PER_REP];
@@ -289,8 +287,9 @@ __global__ __launch_bounds__(BLK) void mon_hist(MonBatch B)
     const float* __restrict__ scores = it.scores;
     const RepDev rd = reps[rep];
     const int lo4 = rd.lo & ~3;
-    const int nchunk = (rd.hi - lo4 + HC_SEL_CHUNK - 1) / HC_SEL_CHUNK;
-    if ((int)blockIdx.x >= nchunk) return;
+    const int nchunk = chunks_from_lo4(rd);
+    const int c0 = blockIdx.x * span, c1 = min(c0 + span, nchunk);
+    if (c0 >= nchunk) return;
     const RepWs w = ws.rep(rep);
     for (int i = threadIdx.x; i < rd.nk * HC_RADIX_BINS; i += BLK) sh[i] = 0u;
 
@@ -311,19 +310,26 @@ __global__ __launch_bounds__(BLK) void mon_hist(MonBatch B)
             }
         }
     }
-    uint32_t key[4];
-    bool in[4];
-    load_keys(scores + (size_t)rep * ws.max_ctx, lo4 + blockIdx.x * HC_SEL_CHUNK + threadIdx.x * 4, rd.lo, rd.hi, key, in);
     __syncthreads();
-    for (int ks = 0; ks < rd.nk; ++ks) {
-        const uint32_t prefix = sm_prefix[ks];
+    const float* srow = scores + (size_t)rep * ws.max_ctx;
+    for (int ch = c0; ch < c1; ch += 2) {         // two chunks' loads in flight
+        uint32_t key[2][4];
+        bool in[2][4];
+        load_keys(srow, lo4 + ch * HC_SEL_CHUNK + threadIdx.x * 4, rd.lo, rd.hi, key[0], in[0]);
+        load_keys(srow, lo4 + (ch + 1) * HC_SEL_CHUNK + threadIdx.x * 4, rd.lo, ch + 1 < c1 ? rd.hi : 0, key[1], in[1]);
+        for (int ks = 0; ks < rd.nk; ++ks) {
+            const uint32_t prefix = sm_prefix[ks];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            if (!in[i]) continue;
-            if (PASS == 2) {
-                if ((key[i] >> 21) == prefix) atomicAdd(&sh[ks * HC_RADIX_BINS + ((key[i] >> 10) & 0x7ffu)], 1u);
-            } else {
-                if ((key[i] >> 10) == prefix) atomicAdd(&sh[ks * HC_RADIX_BINS + (key[i] & 0x3ffu)], 1u);
+            for (int u = 0; u < 2; ++u) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (!in[u][i]) continue;
+                    if (PASS == 2) {
+                        if ((key[u][i] >> 21) == prefix) atomicAdd(&sh[ks * HC_RADIX_BINS + ((key[u][i] >> 10) & 0x7ffu)], 1u);
+                    } else {
+                        if ((key[u][i] >> 10) == prefix) atomicAdd(&sh[ks * HC_RADIX_BINS + (key[u][i] & 0x3ffu)], 1u);
+                    }
+                }
             }
         }
     }
@@ -333,10 +339,36 @@ __global__ __launch_bounds__(BLK) void mon_hist(MonBatch B)
         if (sh[i]) atomicAdd(&gh[i], sh[i]);
 }
 
-__global__ __launch_bounds__(BLK) void mon_count(MonBatch B)
+// Keys of the 16 consecutive candidates of a lane (positions first16 .. first16+15, first16 a multiple of 4:
+// four 16-byte loads) and the mask of those inside [lo, hi).  One wave covers a chunk this way, in position
+// order, so the ordered passes below need no workgroup barriers.
+__device__ __forceinline__ void load_keys16(const float* __restrict__ srow, int first16, int lo, int hi, uint32_t (&key)[16],
+                                            uint32_t& inmask)
+{
+    float4 v[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        v[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (first16 + 4 * q < hi) v[q] = *reinterpret_cast<const float4*>(srow + first16 + 4 * q);   // row stride is a multiple of 64: in bounds
+    }
+    inmask = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const float f[4] = {v[q].x, v[q].y, v[q].z, v[q].w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int j = first16 + 4 * q + i;
+            if (j >= lo && j < hi) inmask |= 1u << (4 * q + i);
+            key[4 * q + i] = score_key(f[i]);
+        }
+    }
+}
+
+// Finds the threshold key of every set size, then per chunk the counts of greater and of equal keys.
+// Wave v of the workgroup takes the chunks c0 + v, c0 + v + 4, ... of the workgroup's span.
+__global__ __launch_bounds__(BLK) void mon_count(MonBatch B, int span)
 {
     __shared__ uint32_t sm_tau[HC_MAX_K_PER_REP];
-    __shared__ uint32_t red[HC_MAX_K_PER_REP][2][NWAVE];
     const MonItem& it = B.it[blockIdx.z];
     const int rep = blockIdx.y;
     if (rep >= it.n_reps) return;
@@ -345,8 +377,9 @@ __global__ __launch_bounds__(BLK) void mon_count(MonBatch B)
     const float* __restrict__ scores = it.scores;
     const RepDev rd = reps[rep];
     const int lo4 = rd.lo & ~3;
-    const int nchunk = (rd.hi - lo4 + HC_SEL_CHUNK - 1) / HC_SEL_CHUNK;
-    if ((int)blockIdx.x >= nchunk) return;
+    const int nchunk = chunks_from_lo4(rd);
+    const int c0 = blockIdx.x * span, c1 = min(c0 + span, nchunk);
+    if (c0 >= nchunk) return;
     const RepWs w = ws.rep(rep);
     const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
     for (int ks = wv; ks < rd.nk; ks += NWAVE) {
@@ -363,34 +396,29 @@ __global__ __launch_bounds__(BLK) void mon_count(MonBatch B)
             }
         }
     }
-    uint32_t key[4];
-    bool in[4];
-    load_keys(scores + (size_t)rep * ws.max_ctx, lo4 + blockIdx.x * HC_SEL_CHUNK + threadIdx.x * 4, rd.lo, rd.hi, key, in);
     __syncthreads();
-    for (int ks = 0; ks < rd.nk; ++ks) {
-        const uint32_t tau = sm_tau[ks];
-        uint32_t gt = 0, eq = 0;
+    const float* srow = scores + (size_t)rep * ws.max_ctx;
+    for (int ch = c0 + wv; ch < c1; ch += NWAVE) {
+        uint32_t key[16], inmask;
+        load_keys16(srow, lo4 + ch * HC_SEL_CHUNK + lane * 16, rd.lo, rd.hi, key, inmask);
+        for (int ks = 0; ks < rd.nk; ++ks) {
+            const uint32_t tau = sm_tau[ks];
+            uint32_t gt = 0, eq = 0;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            gt += in[i] && key[i] > tau;
-            eq += in[i] && key[i] == tau;
+            for (int i = 0; i < 16; ++i) {
+                const bool in = (inmask >> i) & 1u;
+                gt += in && key[i] > tau;
+                eq += in && key[i] == tau;
+            }
+            for (int o = 32; o > 0; o >>= 1) {
+                gt += __shfl_xor(gt, o);
+                eq += __shfl_xor(eq, o);
+            }
+            if (lane == 0) {
+                w.cnt[((size_t)ks * ws.max_chunks + ch) * 2 + 0] = gt;
+                w.cnt[((size_t)ks * ws.max_chunks + ch) * 2 + 1] = eq;
+            }
         }
-        for (int o = 32; o > 0; o >>= 1) {
-            gt += __shfl_xor(gt, o);
-            eq += __shfl_xor(eq, o);
-        }
-        if (lane == 0) {
-            red[ks][0][wv] = gt;
-            red[ks][1][wv] = eq;
-        }
-    }
-    __syncthreads();
-    if (threadIdx.x < rd.nk * 2) {
-        const int ks = threadIdx.x >> 1, which = threadIdx.x & 1;
-        uint32_t t = 0;
-#pragma unroll
-        for (int i = 0; i < NWAVE; ++i) t += red[ks][which][i];
-        w.cnt[((size_t)ks * ws.max_chunks + blockIdx.x) * 2 + which] = t;
     }
 }
 
@@ -398,10 +426,10 @@ struct DriftCfg {
     int window, metric, tau_num, tau_den, max_k;
 };
 
-__global__ __launch_bounds__(BLK) void mon_write(MonBatch B, DriftCfg cfg)
+// Ordered compaction of one index list (blockIdx.y) into topk_idx, and |T ∩ baseline| for the monitored
+// list.  Wave v takes the chunks c0 + v, c0 + v + 4, ... of the workgroup's span; no workgroup barriers.
+__global__ __launch_bounds__(BLK) void mon_write(MonBatch B, DriftCfg cfg, int span)
 {
-    __shared__ uint32_t sm[NWAVE];
-    __shared__ uint32_t sm_off[2];
     const MonItem& it = B.it[blockIdx.z];
     if ((int)blockIdx.y >= it.n_outs) return;
     const Ws ws = it.ws;
@@ -410,29 +438,30 @@ __global__ __launch_bounds__(BLK) void mon_write(MonBatch B, DriftCfg cfg)
     int32_t* __restrict__ topk_idx = it.topk_idx;
     const OutDev od = it.outs[blockIdx.y];
     const RepDev rd = reps[od.rep];
-    const int chunk = blockIdx.x;
     const int lo4 = rd.lo & ~3;
-    const int nchunk = (rd.hi - lo4 + HC_SEL_CHUNK - 1) / HC_SEL_CHUNK;
-    if (chunk >= nchunk) return;
+    const int nchunk = chunks_from_lo4(rd);
+    const int c0 = blockIdx.x * span, c1 = min(c0 + span, nchunk);
+    if (c0 >= nchunk) return;
     const RepWs w = ws.rep(od.rep);
     const int ks = od.kslot;
     const uint32_t tau = w.sel[ks * 4 + 0], need = w.sel[ks * 4 + 1];
     const int k = reps[od.rep].k[ks];
+    const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const float* srow = scores + (size_t)od.rep * ws.max_ctx;
+    const uint32_t* cnt = w.cnt + (size_t)ks * ws.max_chunks * 2;
+    int32_t* dst = topk_idx + (size_t)od.row * cfg.max_k;
 
-    uint32_t key[4];
-    bool in[4];
-    const int first4 = lo4 + chunk * HC_SEL_CHUNK + threadIdx.x * 4;
-    load_keys(scores + (size_t)od.rep * ws.max_ctx, first4, rd.lo, rd.hi, key, in);
+    for (int chunk = c0 + wv; chunk < c1; chunk += NWAVE) {
+        uint32_t key[16], inmask;
+        const int first16 = lo4 + chunk * HC_SEL_CHUNK + lane * 16;
+        load_keys16(srow, first16, rd.lo, rd.hi, key, inmask);
 
-    // Prefix over the chunks before mine: equal-keyed candidates seen, and list entries emitted.  A chunk
-    // emits all its greater keys plus as many equal keys as are still needed.  Wave 0 scans the chunk
-    // counts, 64 at a time.
-    if (threadIdx.x < 64) {
-        const uint32_t* cnt = w.cnt + (size_t)ks * ws.max_chunks * 2;
+        // Prefix over the chunks before this one: equal-keyed candidates seen, and list entries emitted.  A
+        // chunk emits all its greater keys plus as many equal keys as are still needed.
         uint32_t eq_before = 0, emitted = 0;
-        for (int c0 = 0; c0 < chunk; c0 += 64) {
-            const int c = c0 + threadIdx.x;
-            const uint32_t g = c < chunk ? cnt[c * 2] : 0u, e = c < chunk ? cnt[c * 2 + 1] : 0u;
+        for (int b0 = 0; b0 < chunk; b0 += 64) {
+            const int b = b0 + lane;
+            const uint32_t g = b < chunk ? cnt[b * 2] : 0u, e = b < chunk ? cnt[b * 2 + 1] : 0u;
             uint32_t etot;
             const uint32_t eprev = eq_before + wave_exscan(e, etot);
             const uint32_t left = need > eprev ? need - eprev : 0u;
@@ -441,50 +470,42 @@ __global__ __launch_bounds__(BLK) void mon_write(MonBatch B, DriftCfg cfg)
             emitted += mine;
             eq_before += etot;
         }
-        if (threadIdx.x == 0) {
-            sm_off[0] = eq_before;
-            sm_off[1] = emitted;
+        uint32_t my_eq = 0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) my_eq += ((inmask >> i) & 1u) && key[i] == tau;
+        uint32_t tot;
+        uint32_t eq_rank = eq_before + wave_exscan(my_eq, tot);
+        uint32_t selmask = 0, my_sel = 0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            if (!((inmask >> i) & 1u)) continue;
+            bool sel = key[i] > tau;
+            if (key[i] == tau) {
+                sel = eq_rank < need;
+                ++eq_rank;
+            }
+            if (sel) {
+                selmask |= 1u << i;
+                ++my_sel;
+            }
+        }
+        uint32_t pos = emitted + wave_exscan(my_sel, tot);
+        uint32_t hits = 0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            if (selmask & (1u << i)) {
+                const int j = first16 + i;
+                if (pos < (uint32_t)k) dst[pos] = j;     // pos < k always holds; the guard keeps a corrupt state in bounds
+                ++pos;
+                if (od.is_mon) hits += (w.bitmap[j >> 5] >> (j & 31)) & 1u;
+            }
+        }
+        if (od.is_mon) {
+            // per-chunk hit counts, summed by mon_decide (hundreds of atomics on one word would serialise)
+            for (int o = 32; o > 0; o >>= 1) hits += __shfl_xor(hits, o);
+            if (lane == 0) ws.hits[(size_t)od.rep * (ws.max_chunks + 1) + chunk] = hits;
         }
     }
-    uint32_t my_eq = 0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) my_eq += in[i] && key[i] == tau;
-    const uint32_t eq_local = block_exscan(my_eq, sm);       // its barriers also publish sm_off
-    uint32_t eq_rank = sm_off[0] + eq_local;
-    const uint32_t out_base = sm_off[1];
-    uint32_t selmask = 0, my_sel = 0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        if (!in[i]) continue;
-        bool s = key[i] > tau;
-        if (key[i] == tau) {
-            s = eq_rank < need;
-            ++eq_rank;
-        }
-        if (s) {
-            selmask |= 1u << i;
-            ++my_sel;
-        }
-    }
-    uint32_t pos = out_base + block_exscan(my_sel, sm);
-    int32_t* dst = topk_idx + (size_t)od.row * cfg.max_k;
-    uint32_t hits = 0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        if (selmask & (1u << i)) {
-            const int j = first4 + i;
-            if (pos < (uint32_t)k) dst[pos] = j;     // pos < k always holds; the guard keeps a corrupt state in bounds
-            ++pos;
-            if (od.is_mon) hits += (w.bitmap[j >> 5] >> (j & 31)) & 1u;
-        }
-    }
-    if (!od.is_mon) return;
-    // per-chunk hit counts, summed by mon_decide (hundreds of atomics on one word would serialise)
-    for (int o = 32; o > 0; o >>= 1) hits += __shfl_xor(hits, o);
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = hits;
-    __syncthreads();
-    if (threadIdx.x == 0) ws.hits[(size_t)od.rep * (ws.max_chunks + 1) + chunk] = sm[0] + sm[1] + sm[2] + sm[3];
 }
 
 // One workgroup per pivot, after mon_write has completed (the kernel boundary makes its lists and the
@@ -597,25 +618,27 @@ hc_status hc_launch_monitor(hc_ctx* ctx, int n, const hc_monitor_call* calls, in
         m.dirty = true;
     }
     if (max_reps == 0) return HC_OK;
-    const dim3 g1(max_nchunk, max_reps, n);
+    // chunks per workgroup: aim at about 512 workgroups per launch, at most 8 chunks each
+    const int span = std::max(1, std::min(8, (n * max_reps * (max_nchunk + 1)) / 512));
+    const dim3 g1((max_nchunk + span - 1) / span, max_reps, n);
     switch (ctx->G) {
-    case 1: mon_score_hist<1><<<g1, dim3(BLK), 0, st>>>(B, scores_given, c.agg, c.max_k); break;
-    case 2: mon_score_hist<2><<<g1, dim3(BLK), 0, st>>>(B, scores_given, c.agg, c.max_k); break;
-    case 4: mon_score_hist<4><<<g1, dim3(BLK), 0, st>>>(B, scores_given, c.agg, c.max_k); break;
-    default: mon_score_hist<8><<<g1, dim3(BLK), 0, st>>>(B, scores_given, c.agg, c.max_k); break;
+    case 1: mon_score_hist<1><<<g1, dim3(BLK), 0, st>>>(B, scores_given, c.agg, c.max_k, span); break;
+    case 2: mon_score_hist<2><<<g1, dim3(BLK), 0, st>>>(B, scores_given, c.agg, c.max_k, span); break;
+    case 4: mon_score_hist<4><<<g1, dim3(BLK), 0, st>>>(B, scores_given, c.agg, c.max_k, span); break;
+    default: mon_score_hist<8><<<g1, dim3(BLK), 0, st>>>(B, scores_given, c.agg, c.max_k, span); break;
     }
     HC_HIP(ctx, hipGetLastError());
     // the later passes start at a multiple of 4 positions, which can add one chunk
-    const dim3 gk(max_nchunk + 1, max_reps, n);
+    const dim3 gk((max_nchunk + 1 + span - 1) / span, max_reps, n);
     const size_t hist_lds = (size_t)max_nk * HC_RADIX_BINS * sizeof(uint32_t);
-    mon_hist<2><<<gk, dim3(BLK), hist_lds, st>>>(B);
+    mon_hist<2><<<gk, dim3(BLK), hist_lds, st>>>(B, span);
     HC_HIP(ctx, hipGetLastError());
-    mon_hist<3><<<gk, dim3(BLK), hist_lds, st>>>(B);
+    mon_hist<3><<<gk, dim3(BLK), hist_lds, st>>>(B, span);
     HC_HIP(ctx, hipGetLastError());
-    mon_count<<<gk, dim3(BLK), 0, st>>>(B);
+    mon_count<<<gk, dim3(BLK), 0, st>>>(B, span);
     HC_HIP(ctx, hipGetLastError());
     DriftCfg dc{c.window, c.metric, c.tau_num, c.tau_den, c.max_k};
-    mon_write<<<dim3(max_nchunk + 1, max_outs, n), dim3(BLK), 0, st>>>(B, dc);
+    mon_write<<<dim3((max_nchunk + 1 + span - 1) / span, max_outs, n), dim3(BLK), 0, st>>>(B, dc, span);
     HC_HIP(ctx, hipGetLastError());
     mon_decide<<<dim3(max_reps, n), dim3(BLK), 0, st>>>(B, dc);
     HC_HIP(ctx, hipGetLastError());
