@@ -29,7 +29,7 @@ HBM_PEAK_GBPS = 8000.0
 # HBM traffic of one launch of the split kernel (bytes), from the hardware counters FETCH_SIZE and
 # WRITE_SIZE of profiler runs of this script, scaled by what the same counters read for the streaming
 # kernel of --calibrate-copy; keyed by (config, dense).  The runs and factors are in profiles/.
-MEASURED_TRAFFIC = {(4, False): 254697052}
+MEASURED_TRAFFIC = {(4, False): 254637133}
 
 
 def main():
@@ -78,7 +78,7 @@ def main():
         del src, dst
     L = args.layers or I.CONFIG_LAYERS[args.config]
     K, W = args.steps, args.warmup
-    T_total = W + 2 * K + 1           # warm-up, timed pass, kernel-timing pass
+    T_total = W + 2 * K + 9           # warm-up, timed pass, kernel-timing pass, comparison pass
     t_setup = time.time()
 
     # ---- build the stack, layer by layer (masters are dropped once packed) ----
@@ -207,6 +207,19 @@ def main():
     kern_us = float(kern_ms.mean() * 1e3)
     achieved = kv_bytes / (kern_us * 1e-6) / 1e9
 
+    # ---- for comparison: the same kernel with nothing else on the GPU (monitor and gather on the same stream,
+    # so that no other kernel shares HBM with it), a few steps ----
+    iso_us = None
+    if n_pairs and args.mode == "step" and not (args.serial or args.attn_only):
+        n_iso = min(K, 8)
+        hc.hc_set_timing_events(ctx.handle, [a for a, _ in evs[:n_iso * L]], [b for _, b in evs[:n_iso * L]])
+        for _ in range(n_iso):
+            load_q()
+            hc.hc_decode_step(ctx.handle, io, L, main_s, None, args.group)
+        hc.hc_set_timing_events(ctx.handle)
+        torch.cuda.synchronize()
+        iso_us = float(np.mean([a.elapsed_time(b) for a, b in evs[:n_iso * L]]) * 1e3)
+
     # ---- CPU oracle on a bounded sample: layers 0..1, first steps (the same inputs as warm-up) ----
     cpu = None
     parity = None
@@ -254,7 +267,9 @@ def main():
                      "traffic": MEASURED_TRAFFIC.get((args.config, args.dense)) if not args.ctx else None,
                      "kernel": "attn_split_kernel", "kernel_us_mean": kern_us,
                      "kernel_us_median": float(np.median(kern_ms) * 1e3), "kernel_us_p95": float(np.percentile(kern_ms, 95) * 1e3),
-                     "launches_timed": n_pairs},
+                     "launches_timed": n_pairs,
+                     "kernel_us_mean_without_overlap": iso_us,
+                     "frac_without_overlap": (kv_bytes / (iso_us * 1e-6) / 1e9 / HBM_PEAK_GBPS) if iso_us else None},
         "cpu_baseline": cpu,
         "parity_max_err_over_rms": parity,
         "warmup_flags": flags_hist,
