@@ -324,6 +324,7 @@ static hc_status make_plan(const hc_config& cfg, const hc_head_desc* hd, int n_c
             r.nk = 1;
             const int slot = (int)P.reps.size();
             if (slot >= max_reps) return E.fail(HC_ESHAPE, "more pivots than the context was sized for");
+            r.out_begin = (int32_t)P.outs.size();
             P.outs.push_back(OutDev{slot, 0, pi, 1});
             for (int si : mine) {
                 const hc_head_desc& h = hd[si];
@@ -344,6 +345,7 @@ static hc_status make_plan(const hc_config& cfg, const hc_head_desc* hd, int n_c
                 P.sats.push_back(SatDev{si, pi, rr, h.sink + h.recent});
                 P.max_r = std::max(P.max_r, rr);
             }
+            r.out_count = (int32_t)P.outs.size() - r.out_begin;
             r.nchunk = (r.hi - r.lo + HC_SEL_CHUNK - 1) / HC_SEL_CHUNK;
             P.max_nchunk = std::max(P.max_nchunk, r.nchunk);
             P.rep_slot_of[pi] = slot;

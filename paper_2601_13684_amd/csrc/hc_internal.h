@@ -47,7 +47,7 @@ struct RepDev {
     int32_t nk;                       // distinct set sizes
     int32_t k[HC_MAX_K_PER_REP];      // k[0] = k_mon
     int32_t nchunk;                   // ceil((hi-lo)/HC_SEL_CHUNK)
-    int32_t pad;
+    int32_t out_begin, out_count;     // this pivot's lists: outs[out_begin, out_begin + out_count)
 };
 
 // One index list to emit: row `row` of topk_idx gets T_k with k = rep.k[kslot].

@@ -426,84 +426,91 @@ struct DriftCfg {
     int window, metric, tau_num, tau_den, max_k;
 };
 
-// Ordered compaction of one index list (blockIdx.y) into topk_idx, and |T ∩ baseline| for the monitored
-// list.  Wave v takes the chunks c0 + v, c0 + v + 4, ... of the workgroup's span; no workgroup barriers.
+// Ordered compaction of the index lists of one pivot (blockIdx.y) into topk_idx, and |T ∩ baseline| for the
+// monitored list.  Wave v takes the chunks c0 + v, c0 + v + 4, ... of the workgroup's span and reads the
+// chunk's keys once for all set sizes; lists of equal size (satellites with the same budget) share the
+// selection and differ only in the row they are written to.  No workgroup barriers.
 __global__ __launch_bounds__(BLK) void mon_write(MonBatch B, DriftCfg cfg, int span)
 {
     const MonItem& it = B.it[blockIdx.z];
-    if ((int)blockIdx.y >= it.n_outs) return;
+    const int rep = blockIdx.y;
+    if (rep >= it.n_reps) return;
     const Ws ws = it.ws;
     const RepDev* __restrict__ reps = it.reps;
+    const OutDev* __restrict__ outs = it.outs;
     const float* __restrict__ scores = it.scores;
     int32_t* __restrict__ topk_idx = it.topk_idx;
-    const OutDev od = it.outs[blockIdx.y];
-    const RepDev rd = reps[od.rep];
+    const RepDev rd = reps[rep];
     const int lo4 = rd.lo & ~3;
     const int nchunk = chunks_from_lo4(rd);
     const int c0 = blockIdx.x * span, c1 = min(c0 + span, nchunk);
     if (c0 >= nchunk) return;
-    const RepWs w = ws.rep(od.rep);
-    const int ks = od.kslot;
-    const uint32_t tau = w.sel[ks * 4 + 0], need = w.sel[ks * 4 + 1];
-    const int k = reps[od.rep].k[ks];
+    const RepWs w = ws.rep(rep);
     const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const float* srow = scores + (size_t)od.rep * ws.max_ctx;
-    const uint32_t* cnt = w.cnt + (size_t)ks * ws.max_chunks * 2;
-    int32_t* dst = topk_idx + (size_t)od.row * cfg.max_k;
+    const float* srow = scores + (size_t)rep * ws.max_ctx;
 
     for (int chunk = c0 + wv; chunk < c1; chunk += NWAVE) {
         uint32_t key[16], inmask;
         const int first16 = lo4 + chunk * HC_SEL_CHUNK + lane * 16;
         load_keys16(srow, first16, rd.lo, rd.hi, key, inmask);
-
-        // Prefix over the chunks before this one: equal-keyed candidates seen, and list entries emitted.  A
-        // chunk emits all its greater keys plus as many equal keys as are still needed.
-        uint32_t eq_before = 0, emitted = 0;
-        for (int b0 = 0; b0 < chunk; b0 += 64) {
-            const int b = b0 + lane;
-            const uint32_t g = b < chunk ? cnt[b * 2] : 0u, e = b < chunk ? cnt[b * 2 + 1] : 0u;
-            uint32_t etot;
-            const uint32_t eprev = eq_before + wave_exscan(e, etot);
-            const uint32_t left = need > eprev ? need - eprev : 0u;
-            uint32_t mine = g + (e < left ? e : left);
-            for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o);
-            emitted += mine;
-            eq_before += etot;
-        }
-        uint32_t my_eq = 0;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) my_eq += ((inmask >> i) & 1u) && key[i] == tau;
-        uint32_t tot;
-        uint32_t eq_rank = eq_before + wave_exscan(my_eq, tot);
-        uint32_t selmask = 0, my_sel = 0;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            if (!((inmask >> i) & 1u)) continue;
-            bool sel = key[i] > tau;
-            if (key[i] == tau) {
-                sel = eq_rank < need;
-                ++eq_rank;
+        for (int ks = 0; ks < rd.nk; ++ks) {
+            const uint32_t tau = w.sel[ks * 4 + 0], need = w.sel[ks * 4 + 1];
+            const int k = reps[rep].k[ks];               // (indexing the register copy would spill it)
+            const uint32_t* cnt = w.cnt + (size_t)ks * ws.max_chunks * 2;
+            // Prefix over the chunks before this one: equal-keyed candidates seen, and list entries emitted.  A
+            // chunk emits all its greater keys plus as many equal keys as are still needed.
+            uint32_t eq_before = 0, emitted = 0;
+            for (int b0 = 0; b0 < chunk; b0 += 64) {
+                const int b = b0 + lane;
+                const uint32_t g = b < chunk ? cnt[b * 2] : 0u, e = b < chunk ? cnt[b * 2 + 1] : 0u;
+                uint32_t etot;
+                const uint32_t eprev = eq_before + wave_exscan(e, etot);
+                const uint32_t left = need > eprev ? need - eprev : 0u;
+                uint32_t mine = g + (e < left ? e : left);
+                for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o);
+                emitted += mine;
+                eq_before += etot;
             }
-            if (sel) {
-                selmask |= 1u << i;
-                ++my_sel;
-            }
-        }
-        uint32_t pos = emitted + wave_exscan(my_sel, tot);
-        uint32_t hits = 0;
+            uint32_t my_eq = 0;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            if (selmask & (1u << i)) {
-                const int j = first16 + i;
-                if (pos < (uint32_t)k) dst[pos] = j;     // pos < k always holds; the guard keeps a corrupt state in bounds
-                ++pos;
-                if (od.is_mon) hits += (w.bitmap[j >> 5] >> (j & 31)) & 1u;
+            for (int i = 0; i < 16; ++i) my_eq += ((inmask >> i) & 1u) && key[i] == tau;
+            uint32_t tot;
+            uint32_t eq_rank = eq_before + wave_exscan(my_eq, tot);
+            uint32_t selmask = 0, my_sel = 0;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                if (!((inmask >> i) & 1u)) continue;
+                bool sel = key[i] > tau;
+                if (key[i] == tau) {
+                    sel = eq_rank < need;
+                    ++eq_rank;
+                }
+                if (sel) {
+                    selmask |= 1u << i;
+                    ++my_sel;
+                }
             }
-        }
-        if (od.is_mon) {
-            // per-chunk hit counts, summed by mon_decide (hundreds of atomics on one word would serialise)
-            for (int o = 32; o > 0; o >>= 1) hits += __shfl_xor(hits, o);
-            if (lane == 0) ws.hits[(size_t)od.rep * (ws.max_chunks + 1) + chunk] = hits;
+            const uint32_t pos0 = emitted + wave_exscan(my_sel, tot);
+            for (int o = rd.out_begin; o < rd.out_begin + rd.out_count; ++o) {      // the rows this list goes to
+                const OutDev od = outs[o];
+                if (od.kslot != ks) continue;
+                int32_t* dst = topk_idx + (size_t)od.row * cfg.max_k;
+                uint32_t pos = pos0, hits = 0;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    if (selmask & (1u << i)) {
+                        const int j = first16 + i;
+                        if (pos < (uint32_t)k) dst[pos] = j;     // pos < k always holds; the guard keeps a corrupt state in bounds
+                        ++pos;
+                        if (od.is_mon) hits += (w.bitmap[j >> 5] >> (j & 31)) & 1u;
+                    }
+                }
+                if (od.is_mon) {
+                    // per-chunk hit counts, summed by mon_decide (hundreds of atomics on one word would serialise)
+                    for (int o2 = 32; o2 > 0; o2 >>= 1) hits += __shfl_xor(hits, o2);
+                    if (lane == 0) ws.hits[(size_t)rep * (ws.max_chunks + 1) + chunk] = hits;
+                }
+            }
         }
     }
 }
@@ -589,7 +596,7 @@ hc_status hc_launch_monitor(hc_ctx* ctx, int n, const hc_monitor_call* calls, in
     if (n < 1 || n > HC_MAX_GROUP) return hc_fail(ctx, HC_EINVAL, "monitor batch of %d layers", n);
     const hc_config& c = ctx->cfg;
     MonBatch B{};
-    int max_reps = 0, max_outs = 0, max_nchunk = 0, max_nk = 0;
+    int max_reps = 0, max_nchunk = 0, max_nk = 0;
     for (int i = 0; i < n; ++i) {
         const hc_monitor_call& x = calls[i];
         hc_monitor_ws& m = ctx->ws[i];
@@ -608,7 +615,6 @@ hc_status hc_launch_monitor(hc_ctx* ctx, int n, const hc_monitor_call* calls, in
         it.n_reps = x.L->n_reps;
         it.n_outs = x.L->n_outs;
         max_reps = std::max(max_reps, x.L->n_reps);
-        max_outs = std::max(max_outs, x.L->n_outs);
         max_nchunk = std::max(max_nchunk, x.L->max_nchunk);
         max_nk = std::max(max_nk, x.L->max_nk);
         if (m.dirty) {     // a previous call that used this workspace copy did not run to its last kernel
@@ -638,7 +644,9 @@ hc_status hc_launch_monitor(hc_ctx* ctx, int n, const hc_monitor_call* calls, in
     mon_count<<<gk, dim3(BLK), 0, st>>>(B, span);
     HC_HIP(ctx, hipGetLastError());
     DriftCfg dc{c.window, c.metric, c.tau_num, c.tau_den, c.max_k};
-    mon_write<<<dim3((max_nchunk + 1 + span - 1) / span, max_outs, n), dim3(BLK), 0, st>>>(B, dc, span);
+    // the write pass has no per-workgroup set-up to amortise: one chunk per wave
+    const int span_w = NWAVE;
+    mon_write<<<dim3((max_nchunk + 1 + span_w - 1) / span_w, max_reps, n), dim3(BLK), 0, st>>>(B, dc, span_w);
     HC_HIP(ctx, hipGetLastError());
     mon_decide<<<dim3(max_reps, n), dim3(BLK), 0, st>>>(B, dc);
     HC_HIP(ctx, hipGetLastError());
