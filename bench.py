@@ -44,6 +44,7 @@ def main():
                     help="step: hc_decode_step (native launch loop, two streams); graph: captured HIP graph; eager: Python loop")
     ap.add_argument("--dense", action="store_true", help="uncompressed comparison: all 8 KV heads full")
     ap.add_argument("--no-tier", action="store_true", help="no host tier / gather (attention + monitor only)")
+    ap.add_argument("--full-gather", action="store_true", help="refills fetch whole lists (no slot map: nothing is kept)")
     ap.add_argument("--wg-per-cu", type=int, default=0)
     ap.add_argument("--share-weights", default="", help="16 comma-separated share weights [die*2+slot] (tuning)")
     ap.add_argument("--group", type=int, default=8, help="layers per cross-stream sync group in step mode")
@@ -94,7 +95,8 @@ def main():
             if args.share_weights:
                 hc.hc_set_share_weights(ctx.handle, [float(x) for x in args.share_weights.split(",")])
         retrieved, base = I.initial_lists(spec)
-        layers.append(R.LayerRuntime(ctx, spec, w.data, retrieved, base, host_tier=not args.no_tier, own_scratch=True))
+        layers.append(R.LayerRuntime(ctx, spec, w.data, retrieved, base, host_tier=not args.no_tier, own_scratch=True,
+                                     delta_gather=not args.full_gather))
         scheds.append(w.schedule)
         if l < 2 and not args.no_oracle:
             keep[l] = (spec, I.LayerData({k: v.cpu() for k, v in w.data.K.items()},
@@ -255,7 +257,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"config{args.config}{' dense' if args.dense else ''}: {spec0.ctx[0]} ctx, {L} layers, "
                                f"B={spec0.B}, {spec0.Hq}q/{spec0.Hkv}kv heads, D=128",
-                   "layers": L, "context": spec0.ctx[0], "mode": args.mode, "host_tier": not args.no_tier, "overlap_monitor": not args.serial, "layers_per_group": args.group,
+                   "layers": L, "context": spec0.ctx[0], "mode": args.mode, "host_tier": not args.no_tier, "gather": "none" if args.no_tier else ("whole lists" if args.full_gather else "difference only"), "overlap_monitor": not args.serial, "layers_per_group": args.group,
                    "kv_bytes_per_layer_step": kv_bytes,
                    "split_workgroups": hc.hc_layer_num_workgroups(layers[0].handle),
                    "split_partials": hc.hc_layer_num_partials(layers[0].handle)},

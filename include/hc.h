@@ -181,10 +181,21 @@ hc_status hc_rep_topk_drift(hc_ctx* ctx, const hc_layer* layer, const float* rep
                             int32_t* topk_idx, int32_t* base_idx, int32_t* ring,
                             int32_t* inter, int32_t* flag, void* stream);
 
-/* AsyncUpdate (Algorithm 1; Sec. 4.3): for every satellite s whose pivot has flag != 0, slot
- * sink+recent+i of its K and V rows in the arena <- host-tier rows at position topk_idx[s][i],
- * i = 0..r-1.  Satellites of pivots with flag == 0 and anchors are not touched (the predicate is
- * evaluated on the device; the call always enqueues).
+/* AsyncUpdate (Algorithm 1; Sec. 4.3): for every satellite s whose pivot has flag != 0, the r retrieved
+ * slots (slots sink+recent .. sink+recent+r-1 of its K and V rows in the arena) are made to hold the
+ * host-tier rows of the positions topk_idx[s][0..r-1].  Satellites of pivots with flag == 0 and anchors are
+ * not touched (the predicate is evaluated on the device; the call always enqueues).
+ *   slot_pos    NULL: slot sink+recent+i <- position topk_idx[s][i] for every i (the whole list crosses
+ *               the host link, slots in ascending position order).
+ *               Otherwise dev int32 [B*Hkv][max_k], in/out: slot_pos[s][i] is the position that retrieved
+ *               slot i of satellite s holds (the caller initialises it with the initial lists).  Only
+ *               the difference moves: positions of the list that are not resident go into the slots of
+ *               resident positions that left the list, and slot_pos is updated.  Afterwards the resident
+ *               set is exactly the list; the slots are no longer in position order, which attention does
+ *               not depend on.  Rows that stay are not read again, so the bytes on the host link are
+ *               512 * |T_new \ T_old| per satellite.  A slot_pos row that does not hold r distinct
+ *               positions is repaired by a full refill.  (The paper replaces the whole satellite cache;
+ *               this gives the same resident set.)
  *   host_tier   pinned, bf16; the kernel reads it over the host link
  *   stream      stream to run the gather on (typically a side stream)
  *   wait_event  hipEvent_t or NULL: the stream waits for it first (record it after the monitor)
@@ -192,7 +203,7 @@ hc_status hc_rep_topk_drift(hc_ctx* ctx, const hc_layer* layer, const float* rep
  *               layer's arena must wait for it (a refill decided at step t is used from t+1). */
 hc_status hc_gather_retrieve(hc_ctx* ctx, const hc_layer* layer, const void* host_tier,
                              const int32_t* topk_idx, const int32_t* flag, void* kv_arena,
-                             void* stream, void* wait_event, void* done_event);
+                             int32_t* slot_pos, void* stream, void* wait_event, void* done_event);
 
 /* One decode step over a stack of layers (Algorithm 1, the body of the loop over t, for every layer):
  * for each layer in order, hc_decode_attn on main_stream, then hc_rep_topk_drift and hc_gather_retrieve
@@ -222,6 +233,7 @@ typedef struct {
     int32_t* ring;
     int32_t* inter;
     int32_t* flag;
+    int32_t* slot_pos;        /* dev [B*Hkv][max_k] in/out, or NULL: see hc_gather_retrieve */
 } hc_layer_io;
 hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* layers, int32_t n_layers, int32_t layers_per_group,
                          void* main_stream, void* side_stream);

@@ -42,7 +42,7 @@ class hc_plan_info(C.Structure):
 
 class hc_layer_io(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("layer", "kv_arena", "host_tier", "q", "out", "lse", "rep_logits", "scores",
-                                          "topk_idx", "base_idx", "ring", "inter", "flag")]
+                                          "topk_idx", "base_idx", "ring", "inter", "flag", "slot_pos")]
 
 
 class HcError(RuntimeError):
@@ -83,7 +83,7 @@ def lib():
                                        C.POINTER(hc_plan_info), C.c_char_p, i32]
         L.hc_decode_attn.argtypes = [vp] * 8
         L.hc_rep_topk_drift.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
-        L.hc_gather_retrieve.argtypes = [vp] * 9
+        L.hc_gather_retrieve.argtypes = [vp] * 10
         L.hc_decode_step.argtypes = [vp, C.POINTER(hc_layer_io), i32, i32, vp, vp]
         for n in EXPORTS:
             if n not in ("hc_strerror", "hc_last_error", "hc_layer_num_reps", "hc_layer_rep_slot",
@@ -223,8 +223,8 @@ def hc_rep_topk_drift(ctx: int, layer: int, rep_logits: Ptr, lse: Ptr, scores: P
 
 
 def hc_gather_retrieve(ctx: int, layer: int, host_tier: Ptr, topk_idx: Ptr, flag: Ptr, kv_arena: Ptr,
-                       stream=None, wait_event=None, done_event=None) -> None:
-    _check(lib().hc_gather_retrieve(ctx, layer, _p(host_tier), _p(topk_idx), _p(flag), _p(kv_arena),
+                       slot_pos: Ptr = None, stream=None, wait_event=None, done_event=None) -> None:
+    _check(lib().hc_gather_retrieve(ctx, layer, _p(host_tier), _p(topk_idx), _p(flag), _p(kv_arena), _p(slot_pos),
                                     _stream(stream), _event(wait_event), _event(done_event)),
            "hc_gather_retrieve", ctx)
 

@@ -123,6 +123,21 @@ extern "C" hc_status hc_create(const hc_config* cfg, hc_ctx** out)
         return e == hipErrorOutOfMemory ? HC_ENOMEM : HC_EHIP;
     }
     c->ws_base = base;
+    {
+        const size_t rows = (size_t)cfg->B * cfg->Hkv;
+        const size_t pair_w = (size_t)HC_MAX_GROUP * rows * cfg->max_k;
+        int32_t* g = nullptr;
+        e = hipMalloc((void**)&g, (2 * pair_w + (size_t)HC_MAX_GROUP * rows) * sizeof(int32_t));
+        if (e != hipSuccess) {
+            (void)hipFree(base);
+            delete c;
+            return e == hipErrorOutOfMemory ? HC_ENOMEM : HC_EHIP;
+        }
+        c->pair_slot = g;
+        c->pair_pos = g + pair_w;
+        c->npairs = g + 2 * pair_w;
+        (void)hc_gather_set_lds_limit();
+    }
     for (int i = 0; i < HC_MAX_GROUP; ++i) {
         hc_monitor_ws& w = c->ws[i];
         w.hist = base + (size_t)i * lane_w;
@@ -141,6 +156,7 @@ extern "C" hc_status hc_destroy(hc_ctx* ctx)
 {
     if (!ctx_ok(ctx)) return HC_ESTATE;
     (void)hipFree(ctx->ws_base);
+    (void)hipFree(ctx->pair_slot);
     (void)hipFree(ctx->part_acc);
     (void)hipFree(ctx->part_ml);
     ctx->magic = 0;
@@ -614,7 +630,7 @@ static hc_status gather_check(hc_ctx* ctx, const hc_layer* layer, const void* ho
 
 extern "C" hc_status hc_gather_retrieve(hc_ctx* ctx, const hc_layer* layer, const void* host_tier,
                                         const int32_t* topk_idx, const int32_t* flag, void* kv_arena,
-                                        void* stream, void* wait_event, void* done_event)
+                                        int32_t* slot_pos, void* stream, void* wait_event, void* done_event)
 {
     if (!ctx_ok(ctx)) return HC_ESTATE;
     const hc_status chk = gather_check(ctx, layer, host_tier, topk_idx, flag, kv_arena);
@@ -622,7 +638,7 @@ extern "C" hc_status hc_gather_retrieve(hc_ctx* ctx, const hc_layer* layer, cons
     hipStream_t st = (hipStream_t)stream;
     if (wait_event) HC_HIP(ctx, hipStreamWaitEvent(st, (hipEvent_t)wait_event, 0));
     if (layer->n_sats > 0) {
-        const hc_gather_call call{layer, host_tier, topk_idx, flag, kv_arena};
+        const hc_gather_call call{layer, host_tier, topk_idx, flag, kv_arena, slot_pos};
         const hc_status s = hc_launch_gather(ctx, 1, &call, st);
         if (s != HC_OK) return s;
     }
@@ -671,7 +687,7 @@ extern "C" hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* io, int32_t 
                 if (x.host_tier && L->n_sats > 0) {
                     st = gather_check(ctx, L, x.host_tier, x.topk_idx, x.flag, x.kv_arena);
                     if (st != HC_OK) return st;
-                    gat[n_gat++] = hc_gather_call{L, x.host_tier, x.topk_idx, x.flag, const_cast<void*>(x.kv_arena)};
+                    gat[n_gat++] = hc_gather_call{L, x.host_tier, x.topk_idx, x.flag, const_cast<void*>(x.kv_arena), x.slot_pos};
                 }
             }
             const hc_status st = hc_decode_attn(ctx, L, x.kv_arena, x.q, x.out, x.lse, side ? x.rep_logits : nullptr, ms);

@@ -90,6 +90,10 @@ struct hc_ctx {
     uint32_t* ws_base = nullptr;   // the one allocation behind all lanes
     hc_monitor_ws ws[HC_MAX_GROUP];
     int max_chunks = 0;
+    // gather workspace, one copy per layer of a batched call: the (slot, position) pairs of a refill
+    int32_t* pair_slot = nullptr;  // [HC_MAX_GROUP][B*Hkv][max_k]
+    int32_t* pair_pos = nullptr;   // [HC_MAX_GROUP][B*Hkv][max_k]
+    int32_t* npairs = nullptr;     // [HC_MAX_GROUP][B*Hkv]
 };
 
 struct hc_layer {
@@ -140,8 +144,10 @@ struct hc_gather_call {
     const int32_t* topk_idx;
     const int32_t* flag;
     void* arena;
+    int32_t* slot_pos;     // or nullptr
 };
 hc_status hc_launch_attn(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* q, float* out,
                          float* lse, float* rep_logits, hipStream_t st);
 hc_status hc_launch_monitor(hc_ctx* ctx, int n, const hc_monitor_call* calls, int scores_given, hipStream_t st);
 hc_status hc_launch_gather(hc_ctx* ctx, int n, const hc_gather_call* calls, hipStream_t st);
+hc_status hc_gather_set_lds_limit();     // once per process, at context creation

@@ -84,7 +84,7 @@ class Context:
 class LayerRuntime:
     def __init__(self, ctx: Context, spec: LayerSpec, data: LayerData,
                  retrieved: Dict[Tuple[int, int], torch.Tensor], base: Dict[Tuple[int, int], torch.Tensor],
-                 host_tier: bool = True, own_scratch: bool = False):
+                 host_tier: bool = True, own_scratch: bool = False, delta_gather: bool = True):
         self.ctx, self.spec = ctx, spec
         cfg, dev = ctx.cfg, ctx.device
         B, Hkv = spec.B, spec.Hkv
@@ -122,6 +122,13 @@ class LayerRuntime:
         self.base_idx = torch.full((nh, cfg.max_k), -1, dtype=torch.int32, device=dev)
         for (b, p), lst in base.items():
             self.base_idx[b * Hkv + p, :lst.numel()] = lst.to(dev, torch.int32)
+        # which position every retrieved slot of a satellite holds (None: refills replace whole lists)
+        self.slot_pos = None
+        if delta_gather:
+            self.slot_pos = torch.full((nh, cfg.max_k), -1, dtype=torch.int32, device=dev)
+            for (b, h), lst in retrieved.items():
+                if spec.heads[b][h].role == ROLE_SATELLITE:
+                    self.slot_pos[b * Hkv + h, :lst.numel()] = lst.to(dev, torch.int32)
         self.ring = torch.zeros((nh, cfg.window + 1), dtype=torch.int32, device=dev)
         self.inter = torch.zeros((nh,), dtype=torch.int32, device=dev)
         self.flag = torch.zeros((nh,), dtype=torch.int32, device=dev)
@@ -158,7 +165,7 @@ class LayerRuntime:
 
     def gather(self, stream=None, wait_event=None, done_event=None) -> None:
         hc.hc_gather_retrieve(self.ctx.handle, self.handle, self.tier, self.topk_idx, self.flag, self.arena,
-                              stream, wait_event, done_event)
+                              self.slot_pos, stream, wait_event, done_event)
 
     def step(self, q: torch.Tensor, side: Optional[torch.cuda.Stream] = None) -> None:
         """One decode step of this layer.  Attention runs on the current stream; with ``side`` the monitor
@@ -204,5 +211,6 @@ def make_step_io(layers: List[LayerRuntime], q_per_layer: torch.Tensor, monitor:
                                 rep_logits=lay.rep_logits.data_ptr(),
                                 scores=lay.scores.data_ptr() if monitor else None,
                                 topk_idx=lay.topk_idx.data_ptr(), base_idx=lay.base_idx.data_ptr(),
-                                ring=lay.ring.data_ptr(), inter=lay.inter.data_ptr(), flag=lay.flag.data_ptr())
+                                ring=lay.ring.data_ptr(), inter=lay.inter.data_ptr(), flag=lay.flag.data_ptr(),
+                                slot_pos=lay.slot_pos.data_ptr() if lay.slot_pos is not None else None)
     return arr

@@ -54,26 +54,40 @@ def check_set_valid(T_gpu: np.ndarray, T_ref: np.ndarray, s_ref: np.ndarray, rel
 class Pair:
     """One layer on the GPU and its oracle twin, fed the same inputs."""
 
-    def __init__(self, spec, data, device="cuda:0", ctx=None, host_tier=True, wg_per_cu=None):
+    def __init__(self, spec, data, device="cuda:0", ctx=None, host_tier=True, wg_per_cu=None, delta_gather=True):
         self.spec, self.data = spec, data
         retrieved, base = I.initial_lists(spec)
         self.own_ctx = ctx is None
         self.ctx = ctx or R.Context(R.make_config(spec), device, workgroups_per_cu=wg_per_cu)
-        self.gpu = R.LayerRuntime(self.ctx, spec, data, retrieved, base, host_tier=host_tier)
+        self.gpu = R.LayerRuntime(self.ctx, spec, data, retrieved, base, host_tier=host_tier, delta_gather=delta_gather)
         cpu = I.LayerData({k: v.cpu() for k, v in data.K.items()}, {k: v.cpu() for k, v in data.V.items()}, {})
         self.ref = ref.RefLayer(spec, cpu, retrieved, base)
 
     def slots_equal_oracle(self):
-        """Byte-exact comparison of every compressed head's K/V slots with the oracle's rows."""
+        """Byte-exact comparison of every compressed head's K/V slots with the oracle's rows.  With a slot
+        map the retrieved slots may be in any order: the map must be a permutation of the oracle's list,
+        and every slot must hold the rows of the position the map names."""
         arena = self.gpu.arena.cpu().view(torch.int16).numpy().view(np.uint16)
+        slot_pos = self.gpu.slot_pos.cpu().numpy() if self.gpu.slot_pos is not None else None
         for b in range(self.spec.B):
             for h in range(self.spec.Hkv):
-                if self.spec.heads[b][h].role == I.ROLE_FULL:
+                hs = self.spec.heads[b][h]
+                if hs.role == I.ROLE_FULL:
                     continue
                 d = self.gpu.descs[b * self.spec.Hkv + h]
                 Kr, Vr = self.ref.slot_rows(b, h)
-                if not (np.array_equal(arena[d.k_off:d.k_off + d.len * 128].reshape(-1, 128), Kr)
-                        and np.array_equal(arena[d.v_off:d.v_off + d.len * 128].reshape(-1, 128), Vr)):
+                Kg = arena[d.k_off:d.k_off + d.len * 128].reshape(-1, 128)
+                Vg = arena[d.v_off:d.v_off + d.len * 128].reshape(-1, 128)
+                fixed = hs.sink + hs.recent
+                r = d.len - fixed
+                if slot_pos is not None and hs.role == I.ROLE_SATELLITE and r > 0:
+                    sp = slot_pos[b * self.spec.Hkv + h, :r]
+                    order = np.argsort(sp, kind="stable")
+                    if not np.array_equal(sp[order], self.ref.resident(b, h)[fixed:]):
+                        return False
+                    Kg = np.concatenate([Kg[:fixed], Kg[fixed:][order]])
+                    Vg = np.concatenate([Vg[:fixed], Vg[fixed:][order]])
+                if not (np.array_equal(Kg, Kr) and np.array_equal(Vg, Vr)):
                     return False
         return True
 

@@ -68,7 +68,7 @@ def test_null_arguments():
     assert hc.lib().hc_layer_destroy(None) == hc.HC_ESTATE
     assert hc.lib().hc_decode_attn(None, None, None, None, None, None, None, None) == hc.HC_ESTATE
     assert hc.lib().hc_rep_topk_drift(None, None, None, None, None, 0, None, None, None, None, None, None) == hc.HC_ESTATE
-    assert hc.lib().hc_gather_retrieve(None, None, None, None, None, None, None, None, None) == hc.HC_ESTATE
+    assert hc.lib().hc_gather_retrieve(None, None, None, None, None, None, None, None, None, None) == hc.HC_ESTATE
     assert hc.lib().hc_layer_num_reps(None) == -1
 
 

@@ -366,8 +366,9 @@ def test_integer_inputs_are_bit_exact_end_to_end():
 # ------------------------------------------------------------------------------------------
 # A8: gather
 # ------------------------------------------------------------------------------------------
-def test_gather_moves_exactly_the_listed_rows_and_respects_the_flag():
-    say("gather")
+@pytest.mark.parametrize("delta", [False, True])
+def test_gather_moves_exactly_the_listed_rows_and_respects_the_flag(delta):
+    say("gather", "with slot map" if delta else "whole lists")
     heads = [I.HeadSpec(I.ROLE_FULL), I.HeadSpec(I.ROLE_FULL),
              I.HeadSpec(I.ROLE_SATELLITE, rep=0, sink=16, recent=32, budget=16 + 32 + 500),
              I.HeadSpec(I.ROLE_SATELLITE, rep=1, sink=16, recent=32, budget=16 + 32 + 77),
@@ -376,7 +377,7 @@ def test_gather_moves_exactly_the_listed_rows_and_respects_the_flag():
     spec = I.LayerSpec(B=1, Hq=24, Hkv=6, D=128, ctx=[3000], heads=[heads])
     q0 = I.draw_q(spec, 1)
     data = I.draw_layer(spec, q0, 2)
-    p = U.Pair(spec, data, DEV)
+    p = U.Pair(spec, data, DEV, delta_gather=delta)
     before = p.gpu.arena.clone()
     rng = np.random.default_rng(4)
     lists = {}
@@ -405,6 +406,76 @@ def test_gather_moves_exactly_the_listed_rows_and_respects_the_flag():
         for off in (d.k_off, d.v_off):
             mask[off + 48 * 128: off + d.len * 128] = False
     assert torch.equal(after[mask], before[mask])
+    p.close()
+
+
+def test_gather_with_slot_map_moves_only_the_difference():
+    """Rows that stay resident are not fetched again (their slots keep a marker written over them), the
+    fresh positions land in the slots of the positions that left, the map ends up a permutation of the
+    list; an untriggered call changes nothing; a corrupt map is repaired by a full refill."""
+    say("gather, difference only")
+    heads = [I.HeadSpec(I.ROLE_FULL), I.HeadSpec(I.ROLE_SATELLITE, rep=0, sink=16, recent=32, budget=16 + 32 + 3000),
+             I.HeadSpec(I.ROLE_SATELLITE, rep=0, sink=16, recent=32, budget=16 + 32 + 640)]
+    spec = I.LayerSpec(B=1, Hq=12, Hkv=3, D=128, ctx=[9000], heads=[heads])
+    q0 = I.draw_q(spec, 11)
+    data = I.draw_layer(spec, q0, 12)
+    p = U.Pair(spec, data, DEV)
+    g = p.gpu
+    rng = np.random.default_rng(5)
+    cand = np.arange(16, 9000 - 32)
+    for rnd in range(3):
+        new_lists, kept_slots = {}, {}
+        for h in (1, 2):
+            r = spec.r(0, h)
+            old = g.slot_pos[h, :r].cpu().numpy()
+            stay = rng.choice(old, int(0.6 * r), replace=False)
+            fresh = rng.choice(np.setdiff1d(cand, old), r - stay.size, replace=False)
+            new_lists[h] = np.sort(np.concatenate([stay, fresh])).astype(np.int32)
+            g.topk_idx[h, :r] = torch.from_numpy(new_lists[h]).to(DEV)
+            kept_slots[h] = np.nonzero(np.isin(old, stay))[0]
+            d = g.descs[h]
+            for off in (d.k_off, d.v_off):       # marker over the rows that must not be fetched again
+                rows = g.arena[off:off + d.len * 128].view(-1, 128)
+                rows[48 + torch.from_numpy(kept_slots[h]).to(DEV)] = 7.0
+        g.flag[0] = 1
+        g.gather()
+        torch.cuda.synchronize()
+        for h in (1, 2):
+            r = spec.r(0, h)
+            d = g.descs[h]
+            sp = g.slot_pos[h, :r].cpu().numpy()
+            assert np.array_equal(np.sort(sp), new_lists[h]), "the map is not a permutation of the list"
+            for off, full in ((d.k_off, data.K[(0, h)]), (d.v_off, data.V[(0, h)])):
+                rows = g.arena[off:off + d.len * 128].view(-1, 128)[48:].cpu()
+                kept = np.zeros(r, dtype=bool)
+                kept[kept_slots[h]] = True
+                assert (rows[torch.from_numpy(kept)] == 7.0).all(), "a resident row was fetched again"
+                want = full.cpu()[torch.from_numpy(sp[~kept]).long()]
+                assert torch.equal(rows[torch.from_numpy(~kept)], want), "a fresh row is wrong"
+                # put the true rows back under the markers for the next round
+                g.arena[off:off + d.len * 128].view(-1, 128)[48:][torch.from_numpy(kept).to(DEV)] = \
+                    full[torch.from_numpy(sp[kept]).long().to(full.device)].to(DEV)
+            p.ref.retrieved[(0, h)] = new_lists[h]
+        assert p.slots_equal_oracle()
+    # untriggered: nothing moves
+    before, map_before = g.arena.clone(), g.slot_pos.clone()
+    g.topk_idx[1, :3000] = torch.arange(100, 3100, dtype=torch.int32, device=DEV)
+    g.flag[0] = 0
+    g.gather()
+    torch.cuda.synchronize()
+    assert torch.equal(g.arena, before) and torch.equal(g.slot_pos, map_before)
+    # a map that holds a listed position twice (so it cannot describe r distinct positions) is repaired by a
+    # full refill in list order
+    g.flag[0] = 1
+    g.gather()
+    torch.cuda.synchronize()
+    assert torch.equal(torch.sort(g.slot_pos[1, :3000]).values.cpu(), torch.arange(100, 3100, dtype=torch.int32))
+    g.slot_pos[1, 5] = g.slot_pos[1, 6]
+    g.gather()
+    torch.cuda.synchronize()
+    p.ref.retrieved[(0, 1)] = np.arange(100, 3100, dtype=np.int32)
+    assert torch.equal(g.slot_pos[1, :3000].cpu(), torch.arange(100, 3100, dtype=torch.int32))
+    assert p.slots_equal_oracle()
     p.close()
 
 
