@@ -482,12 +482,16 @@ def test_gather_with_slot_map_moves_only_the_difference():
 # ------------------------------------------------------------------------------------------
 # Multi-step integration (Algorithm 1, stage 3 loop)
 # ------------------------------------------------------------------------------------------
-def run_steps(p, sched, steps, side=None, rel_band=1e-4, tag=""):
+def run_steps(p, sched, steps, side=None, rel_band=1e-4, tag="", stepper=None):
+    """stepper(q): runs one decode step of p.gpu (default: LayerRuntime.step)."""
     sp = p.spec
     resyncs = triggers = 0
     for t in range(steps):
         q = sched.next()
-        p.gpu.step(q.to(DEV), side=side)
+        if stepper is None:
+            p.gpu.step(q.to(DEV), side=side)
+        else:
+            stepper(q.to(DEV))
         torch.cuda.synchronize()
         rec = p.ref.step(q)
         worst, lerr = U.check_attention(p.gpu.out, p.gpu.lse, rec, f"{tag} step {t}")
@@ -549,6 +553,47 @@ def test_config1_tiny_multi_step_with_side_stream():
     say("  resyncs", resyncs, "triggers", triggers)
     assert triggers >= 2 and resyncs <= 1
     assert p.ref.n_tests == 12
+    p.close()
+
+
+def test_captured_graph_of_a_layer_step_replays_like_eager():
+    """attention + monitor + refill of one layer captured once into a HIP graph (the three calls only enqueue
+    kernels: no memsets, no allocations) and replayed for 10 steps, with unrelated eager work and
+    synchronisations between the replays; every replay is checked against the oracle, across triggers."""
+    say("captured graph, config 1, 10 replays")
+    w = I.make_workload(1)
+    p = U.Pair(w.spec, w.data, DEV)
+    q_buf = torch.zeros((w.spec.B, w.spec.Hq, 128), dtype=torch.bfloat16, device=DEV)
+
+    def one_step():
+        p.gpu.attn(q_buf)
+        p.gpu.monitor()
+        p.gpu.gather()
+
+    def eager(q):
+        q_buf.copy_(q)
+        one_step()
+
+    run_steps(p, w.schedule, 2, tag="eager", stepper=eager)       # also leaves the monitor workspace clean
+    cap = torch.cuda.Stream()
+    cap.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(cap):
+        with torch.cuda.graph(graph, stream=cap):
+            one_step()
+    torch.cuda.synchronize()
+    junk = torch.zeros((1 << 20,), device=DEV)
+
+    def replay(q):
+        q_buf.copy_(q)
+        junk.add_(1.0)                       # the program's own eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        junk.mul_(0.5)
+
+    resyncs, triggers = run_steps(p, w.schedule, 10, tag="graph", stepper=replay)
+    say("  resyncs", resyncs, "triggers", triggers)
+    assert triggers >= 2 and resyncs <= 1
     p.close()
 
 
