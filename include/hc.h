@@ -121,6 +121,11 @@ hc_status hc_set_split(hc_ctx* ctx, int32_t workgroups_per_cu, int32_t compute_u
  * dies stream a few per cent slower).  Used when the number of workgroups is a multiple of 16. */
 hc_status hc_set_share_weights(hc_ctx* ctx, const float* weights16);
 
+/* Tuning knob: how many 1024-candidate chunks a workgroup of the monitor's selection passes takes
+ * (1..64); 0 (default) lets every call choose: 1 for a single layer (many small workgroups, lowest
+ * latency), up to 8 for a batch of layers (histograms cleared and flushed once per workgroup). */
+hc_status hc_set_monitor_span(hc_ctx* ctx, int32_t span);
+
 /* Measurement hook: hands the library n pairs of hipEvent_t (host arrays of handles, copied).  The
  * next n launches of the split-pass kernel, from hc_decode_attn or hc_decode_step, attach pair i to
  * their i-th dispatch, so that hipEventElapsedTime(ev_begin[i], ev_end[i]) is that kernel's execution

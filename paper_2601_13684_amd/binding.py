@@ -20,7 +20,7 @@ HC_MAX_WINDOW, HC_MAX_K_PER_REP, HC_MAX_GROUP = 64, 8, 8
 
 EXPORTS = ["hc_create", "hc_destroy", "hc_strerror", "hc_last_error", "hc_layer_create", "hc_layer_destroy",
            "hc_layer_num_reps", "hc_layer_rep_slot", "hc_layer_num_workgroups", "hc_layer_num_partials",
-           "hc_set_split", "hc_set_share_weights", "hc_set_timing_events", "hc_plan_describe", "hc_decode_attn", "hc_rep_topk_drift", "hc_gather_retrieve", "hc_decode_step"]
+           "hc_set_split", "hc_set_share_weights", "hc_set_monitor_span", "hc_set_timing_events", "hc_plan_describe", "hc_decode_attn", "hc_rep_topk_drift", "hc_gather_retrieve", "hc_decode_step"]
 
 
 class hc_config(C.Structure):
@@ -78,6 +78,7 @@ def lib():
         L.hc_layer_rep_slot.restype = i32
         L.hc_set_split.argtypes = [vp, i32, i32]
         L.hc_set_share_weights.argtypes = [vp, C.POINTER(C.c_float)]
+        L.hc_set_monitor_span.argtypes = [vp, i32]
         L.hc_set_timing_events.argtypes = [vp, vp, vp, i32]
         L.hc_plan_describe.argtypes = [C.POINTER(hc_config), C.POINTER(hc_head_desc), i32, i32,
                                        C.POINTER(hc_plan_info), C.c_char_p, i32]
@@ -159,6 +160,10 @@ def hc_set_share_weights(ctx: int, weights=None) -> None:
             raise ValueError("hc_set_share_weights: 16 weights")
         arr = (C.c_float * 16)(*[float(w) for w in weights])
     _check(lib().hc_set_share_weights(ctx, arr), "hc_set_share_weights", ctx)
+
+
+def hc_set_monitor_span(ctx: int, span: int = 0) -> None:
+    _check(lib().hc_set_monitor_span(ctx, span), "hc_set_monitor_span", ctx)
 
 
 def hc_set_timing_events(ctx: int, ev_begin=(), ev_end=()) -> None:

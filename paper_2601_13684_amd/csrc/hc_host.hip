@@ -185,6 +185,14 @@ extern "C" hc_status hc_set_share_weights(hc_ctx* ctx, const float* weights16)
     return HC_OK;
 }
 
+extern "C" hc_status hc_set_monitor_span(hc_ctx* ctx, int32_t span)
+{
+    if (!ctx_ok(ctx)) return HC_ESTATE;
+    if (span < 0 || span > 64) return hc_fail(ctx, HC_EINVAL, "hc_set_monitor_span: 0 (automatic) or 1..64");
+    ctx->monitor_span = span;
+    return HC_OK;
+}
+
 extern "C" hc_status hc_set_timing_events(hc_ctx* ctx, void* const* ev_begin, void* const* ev_end, int32_t n)
 {
     if (!ctx_ok(ctx)) return HC_ESTATE;

@@ -90,6 +90,7 @@ struct hc_ctx {
     uint32_t* ws_base = nullptr;   // the one allocation behind all lanes
     hc_monitor_ws ws[HC_MAX_GROUP];
     int max_chunks = 0;
+    int monitor_span = 0;          // chunks per workgroup of the selection passes; 0: chosen per launch
     // gather workspace, one copy per layer of a batched call: the (slot, position) pairs of a refill
     int32_t* pair_slot = nullptr;  // [HC_MAX_GROUP][B*Hkv][max_k]
     int32_t* pair_pos = nullptr;   // [HC_MAX_GROUP][B*Hkv][max_k]

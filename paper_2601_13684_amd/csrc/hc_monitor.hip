@@ -625,7 +625,7 @@ hc_status hc_launch_monitor(hc_ctx* ctx, int n, const hc_monitor_call* calls, in
     }
     if (max_reps == 0) return HC_OK;
     // chunks per workgroup: aim at about 512 workgroups per launch, at most 8 chunks each
-    const int span = std::max(1, std::min(8, (n * max_reps * (max_nchunk + 1)) / 512));
+    const int span = ctx->monitor_span > 0 ? ctx->monitor_span : std::max(1, std::min(8, (n * max_reps * (max_nchunk + 1)) / 512));
     const dim3 g1((max_nchunk + span - 1) / span, max_reps, n);
     switch (ctx->G) {
     case 1: mon_score_hist<1><<<g1, dim3(BLK), 0, st>>>(B, scores_given, c.agg, c.max_k, span); break;

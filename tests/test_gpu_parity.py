@@ -152,9 +152,10 @@ def test_attention_with_few_workgroups_and_weighted_shares(cus, wg):
 # ------------------------------------------------------------------------------------------
 # A6-A7 on given scores: integer work, bit-exact
 # ------------------------------------------------------------------------------------------
-def monitor_case(spec, scores_by_rep, base_by_rep, ring_init=None):
+def monitor_case(spec, scores_by_rep, base_by_rep, ring_init=None, span=0):
     """Runs hc_rep_topk_drift with CPU-made fp32 scores and returns device tables + oracle results."""
     ctx = R.Context(R.make_config(spec), DEV)
+    hc.hc_set_monitor_span(ctx.handle, span)
     retrieved, base = I.initial_lists(spec)
     base.update(base_by_rep)
     data = I.LayerData({(b, h): torch.zeros((spec.ctx[b], 128), dtype=torch.bfloat16) for b in range(spec.B) for h in range(spec.Hkv)},
@@ -209,9 +210,10 @@ def compare_monitor(spec, gpu, s_by_rep, base, ring_init=None):
         assert ring[row, 0] == len(e_ring) and ring[row, 1:1 + len(e_ring)].tolist() == list(e_ring)
 
 
+@pytest.mark.parametrize("span", [0, 3, 8])
 @pytest.mark.parametrize("kind", ["uniform", "ties", "all_equal", "signed_zero", "negatives", "tiny_exponents"])
-def test_monitor_bit_exact_on_given_scores(kind):
-    say("monitor given scores", kind)
+def test_monitor_bit_exact_on_given_scores(kind, span):
+    say("monitor given scores", kind, "span", span)
     N = 20000
     spec = I.spec_llama(N, (4096, 2048, 2048, 1024, 1024, 512))
     rng = np.random.default_rng(11)
@@ -234,8 +236,32 @@ def test_monitor_bit_exact_on_given_scores(kind):
         s_by_rep[(0, p)] = s
         lo, hi = spec.cand_range(0, p)
         base[(0, p)] = torch.from_numpy(np.sort(rng.choice(np.arange(lo, hi), spec.k_mon(0, p), replace=False)).astype(np.int32))
-    ctx, gpu, base_all = monitor_case(spec, s_by_rep, base)
+    ctx, gpu, base_all = monitor_case(spec, s_by_rep, base, span=span)
     compare_monitor(spec, gpu, s_by_rep, base_all)
+    gpu.close()
+    ctx.close()
+
+
+@pytest.mark.parametrize("span", [0, 2])
+@pytest.mark.parametrize("N,sink,recent", [(2000, 16, 32), (1024 + 48, 16, 32), (4099, 3, 0), (1500, 0, 0)])
+def test_monitor_extreme_set_sizes(N, sink, recent, span):
+    """Set sizes 1 and "every candidate" side by side (the latter must come back as the whole candidate
+    range, whatever the scores), candidate ranges that start off a multiple of 4 and end off a chunk."""
+    say("monitor extreme set sizes", N, sink, recent, "span", span)
+    ncand = N - sink - recent
+    heads = [I.HeadSpec(I.ROLE_FULL), I.HeadSpec(I.ROLE_SATELLITE, rep=0, sink=sink, recent=recent, budget=N),
+             I.HeadSpec(I.ROLE_SATELLITE, rep=0, sink=sink, recent=recent, budget=sink + recent + 1),
+             I.HeadSpec(I.ROLE_SATELLITE, rep=0, sink=sink, recent=recent, budget=sink + recent + ncand // 2)]
+    spec = I.LayerSpec(B=1, Hq=16, Hkv=4, D=128, ctx=[N], heads=[heads])
+    rng = np.random.default_rng(N)
+    s = rng.normal(size=N).astype(np.float32)
+    s[rng.integers(0, N, 30)] = s.max()            # ties at the top
+    lo, hi = spec.cand_range(0, 0)
+    assert (lo, hi) == (sink, N - recent)
+    base = {(0, 0): torch.from_numpy(np.arange(lo, lo + spec.k_mon(0, 0), dtype=np.int32))}
+    ctx, gpu, base_all = monitor_case(spec, {(0, 0): s}, base, span=span)
+    compare_monitor(spec, gpu, {(0, 0): s}, base_all)
+    assert np.array_equal(gpu.topk_idx[1, :ncand].cpu().numpy(), np.arange(lo, hi))
     gpu.close()
     ctx.close()
 
