@@ -55,6 +55,7 @@ typedef enum {
 enum { HC_ROLE_FULL = 0, HC_ROLE_SATELLITE = 1, HC_ROLE_ANCHOR = 2 };
 enum { HC_METRIC_OVERLAP = 0, HC_METRIC_JACCARD = 1 };
 enum { HC_AGG_PROB = 0, HC_AGG_LOGIT = 1 };
+enum { HC_WINDOW_SLIDING = 0, HC_WINDOW_TUMBLING = 1 };
 enum { HC_MAX_WINDOW = 64, HC_MAX_K_PER_REP = 8, HC_MAX_GROUP = 8 };
 
 typedef struct {
@@ -71,6 +72,13 @@ typedef struct {
     int32_t tau_den;   /*   integers: statistic < tau  (strict, Eq. 10); tau_den >= 1           */
     int32_t agg;       /* HC_AGG_PROB: mean over the GQA group of softmax weights (App. C.1);
                           HC_AGG_LOGIT: mean of scaled logits (exactly reproducible test mode)  */
+    int32_t window_mode; /* HC_WINDOW_SLIDING: Eq. 10 as written, tested at every step once W overlaps are
+                          stored, the store emptied on a retrieval.  HC_WINDOW_TUMBLING: Algorithm 1's
+                          loop, tested when t mod W = 0 over the W steps since the last test, the store
+                          emptied after every test.  (Algorithm 1 re-scores the W buffered queries at
+                          that point; as long as the pivot's cache has not changed in between, that
+                          gives the overlaps already computed at those steps, which are what is
+                          stored.)                                                               */
 } hc_config;
 
 /* One KV head of one sequence; table of B*Hkv entries, row (b*Hkv + h), HOST memory. */
@@ -178,7 +186,8 @@ hc_status hc_decode_attn(hc_ctx* ctx, const hc_layer* layer, const void* kv_aren
  *      pivot (T_{k_mon}) and of each satellite (T_r).  NaN scores rank last; -0 equals +0.
  *   3. inter[p] = |T_{k_mon} ∩ base_idx row p| (entries < 0 in the baseline never match);
  *      pushed into ring[p]; once W values are stored, r_t = [lower-median statistic < tau];
- *      flag[p] = r_t.  On r_t = 1 the baseline row becomes T_{k_mon} and the ring is emptied.
+ *      flag[p] = r_t.  On r_t = 1 the baseline row becomes T_{k_mon} and the ring is emptied
+ *      (HC_WINDOW_TUMBLING: the ring is emptied after every test).
  * All of topk_idx, base_idx, ring, inter, flag are dev int32 tables as described above;
  * rows of heads that are not pivots (or their satellites, for topk_idx) are left untouched. */
 hc_status hc_rep_topk_drift(hc_ctx* ctx, const hc_layer* layer, const float* rep_logits, const float* lse,

@@ -209,7 +209,8 @@ class RefLayer:
                 if len(ring) > sp.window:
                     ring.pop(0)
                 flag = 0
-                if len(ring) == sp.window:
+                tested = len(ring) == sp.window
+                if tested:
                     self.n_tests += 1
                     flag = trigger(ring, kmon, sp.metric, sp.tau_num, sp.tau_den)
                 rec["flag"][(b, p)] = flag
@@ -218,5 +219,9 @@ class RefLayer:
                     for sat in sp.satellites(b, p):
                         self.retrieved[(b, sat)] = rec["topk"][(b, sat)].copy()
                     self.base[(b, p)] = T.copy()
+                    ring.clear()
+                elif tested and sp.window_mode == 1:
+                    # Algorithm 1: the buffer of the window is emptied after every test (t mod W = 0),
+                    # whether or not it led to a retrieval
                     ring.clear()
         return rec

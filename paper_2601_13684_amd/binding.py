@@ -25,7 +25,7 @@ EXPORTS = ["hc_create", "hc_destroy", "hc_strerror", "hc_last_error", "hc_layer_
 
 class hc_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("B", "Hq", "Hkv", "D", "max_ctx", "max_k", "window", "metric",
-                                         "tau_num", "tau_den", "agg")]
+                                         "tau_num", "tau_den", "agg", "window_mode")]
 
 
 class hc_head_desc(C.Structure):

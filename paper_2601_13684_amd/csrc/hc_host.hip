@@ -77,6 +77,7 @@ static hc_status check_config(const hc_config* cfg)
     if (cfg->window < 1 || cfg->window > HC_MAX_WINDOW) return HC_EINVAL;
     if (cfg->metric != HC_METRIC_OVERLAP && cfg->metric != HC_METRIC_JACCARD) return HC_EINVAL;
     if (cfg->agg != HC_AGG_PROB && cfg->agg != HC_AGG_LOGIT) return HC_EINVAL;
+    if (cfg->window_mode != HC_WINDOW_SLIDING && cfg->window_mode != HC_WINDOW_TUMBLING) return HC_EINVAL;
     if (cfg->tau_den < 1 || cfg->tau_num < 0) return HC_EINVAL;
     if ((int64_t)cfg->B * cfg->Hkv > (1 << 20)) return HC_ESHAPE;
     return HC_OK;

@@ -423,7 +423,7 @@ __global__ __launch_bounds__(BLK) void mon_count(MonBatch B, int span)
 }
 
 struct DriftCfg {
-    int window, metric, tau_num, tau_den, max_k;
+    int window, metric, tau_num, tau_den, max_k, tumbling;
 };
 
 // Ordered compaction of the index lists of one pivot (blockIdx.y) into topk_idx, and |T ∩ baseline| for the
@@ -571,7 +571,8 @@ __global__ __launch_bounds__(BLK) void mon_decide(MonBatch B, DriftCfg cfg)
             else
                 trig = med * cfg.tau_den < (long long)cfg.tau_num * (2 * kk - med);         // med/(2k-med) < tau
         }
-        rg[0] = trig ? 0 : m;                        // the window restarts after a retrieval
+        // the window restarts after a retrieval; a tumbling window after every test
+        rg[0] = (trig || (cfg.tumbling && m == cfg.window)) ? 0 : m;
         inter_out[rd.bh] = inter;
         flag_out[rd.bh] = trig;
         sm_trig = trig;
@@ -643,7 +644,7 @@ hc_status hc_launch_monitor(hc_ctx* ctx, int n, const hc_monitor_call* calls, in
     HC_HIP(ctx, hipGetLastError());
     mon_count<<<gk, dim3(BLK), 0, st>>>(B, span);
     HC_HIP(ctx, hipGetLastError());
-    DriftCfg dc{c.window, c.metric, c.tau_num, c.tau_den, c.max_k};
+    DriftCfg dc{c.window, c.metric, c.tau_num, c.tau_den, c.max_k, c.window_mode == HC_WINDOW_TUMBLING};
     // the write pass has no per-workgroup set-up to amortise: one chunk per wave
     const int span_w = NWAVE;
     mon_write<<<dim3((max_nchunk + 1 + span_w - 1) / span_w, max_reps, n), dim3(BLK), 0, st>>>(B, dc, span_w);

@@ -56,6 +56,7 @@ class LayerSpec:
     tau_num: int = 4                   # drift threshold tau = tau_num / tau_den
     tau_den: int = 5
     agg: int = AGG_PROB
+    window_mode: int = 0               # 0: sliding window (Eq. 10), 1: tumbling window (Algorithm 1)
 
     @property
     def G(self) -> int:

@@ -31,7 +31,7 @@ def make_config(spec: LayerSpec, max_ctx: Optional[int] = None, max_k: Optional[
             ks += [spec.r(b, s) for s in spec.satellites(b, p)]
     return hc.hc_config(B=spec.B, Hq=spec.Hq, Hkv=spec.Hkv, D=spec.D, max_ctx=mc, max_k=max_k or max(ks),
                         window=spec.window, metric=spec.metric, tau_num=spec.tau_num, tau_den=spec.tau_den,
-                        agg=spec.agg)
+                        agg=spec.agg, window_mode=spec.window_mode)
 
 
 def make_descs(spec: LayerSpec) -> Tuple[List[hc.hc_head_desc], int, int]:

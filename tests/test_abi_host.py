@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_sizes_match_the_header_layout():
-    assert C.sizeof(hc.hc_config) == 11 * 4
+    assert C.sizeof(hc.hc_config) == 12 * 4
     assert C.sizeof(hc.hc_head_desc) == 3 * 8 + 8 * 4
     assert C.sizeof(hc.hc_plan_info) == 8 * 4 + 2 * 8
 
@@ -50,6 +50,7 @@ def cfg_for(spec, **kw):
     ("D", 64, hc.HC_ESHAPE), ("Hq", 7, hc.HC_EINVAL), ("Hq", 32, hc.HC_ESHAPE),   # G = 16
     ("max_ctx", 100, hc.HC_ESHAPE), ("window", 0, hc.HC_EINVAL), ("window", 65, hc.HC_EINVAL),
     ("metric", 2, hc.HC_EINVAL), ("tau_den", 0, hc.HC_EINVAL), ("agg", 3, hc.HC_EINVAL), ("max_k", 0, hc.HC_EINVAL),
+    ("window_mode", 2, hc.HC_EINVAL),
 ])
 def test_bad_config_is_rejected_before_any_gpu_call(field, value, status):
     spec = I.spec_tiny(1024, budget=160, sink=16, recent=32)

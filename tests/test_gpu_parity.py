@@ -184,10 +184,11 @@ def expect_monitor(spec, s32, b, p, base_list, ring_vals):
     if len(ring) > spec.window:
         ring = ring[-spec.window:]
     flag = 0
-    if len(ring) == spec.window:
+    tested = len(ring) == spec.window
+    if tested:
         flag = ref.trigger(ring, kmon, spec.metric, spec.tau_num, spec.tau_den)
     new_base = T if flag else base_list
-    if flag:
+    if flag or (tested and spec.window_mode == 1):
         ring = []
     return lists, inter, flag, new_base, ring
 
@@ -292,17 +293,22 @@ def test_monitor_trigger_threshold_is_exact(metric, num, den):
 
 
 @pytest.mark.parametrize("W", [2, 3, 4])
-def test_monitor_window_lower_median_and_ring(W):
-    say("monitor window", W)
+@pytest.mark.parametrize("mode", [0, 1])
+def test_monitor_window_lower_median_and_ring(W, mode):
+    say("monitor window", W, "tumbling" if mode else "sliding")
     N = 4096
     spec = I.spec_tiny(N)
     spec.window = W
+    spec.window_mode = mode
     rng = np.random.default_rng(5)
     s = rng.random(N).astype(np.float32)
     lo, hi = spec.cand_range(0, 0)
     k = spec.k_mon(0, 0)
     base = torch.from_numpy(np.sort(rng.choice(np.arange(lo, hi), k, replace=False)).astype(np.int32))
-    for prior in ([], [k] * (W - 1), [0] * (W - 1), [k] * W, [0, k, 0, k][:W]):
+    priors = [[], [k] * (W - 1), [0] * (W - 1), [0, k, 0, k][:W - 1]]
+    if mode == 0:
+        priors += [[k] * W, [0, k, 0, k][:W]]      # a full ring only exists with a sliding window
+    for prior in priors:
         ctx, gpu, base_all = monitor_case(spec, {(0, 0): s}, {(0, 0): base}, ring_init={(0, 0): prior})
         compare_monitor(spec, gpu, {(0, 0): s}, base_all, ring_init={(0, 0): prior})
         gpu.close()
@@ -643,13 +649,17 @@ def test_config5_shape_batched_multi_step():
     p.close()
 
 
-def test_window_3_multi_step():
-    say("window 3")
+@pytest.mark.parametrize("mode", [0, 1])
+def test_window_3_multi_step(mode):
+    say("window 3", "tumbling" if mode else "sliding")
     w = I.make_workload(1)
     w.spec.window = 3
+    w.spec.window_mode = mode
     p = U.Pair(w.spec, w.data, DEV)
-    resyncs, triggers = run_steps(p, w.schedule, 9, tag="W3")
+    resyncs, triggers = run_steps(p, w.schedule, 12, tag="W3")
     assert triggers >= 1
+    if mode == 1:
+        assert p.ref.n_tests == 4           # steps 3, 6, 9, 12 only
     p.close()
 
 

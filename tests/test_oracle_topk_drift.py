@@ -213,6 +213,54 @@ def test_window_debounces_and_ring_clears_on_trigger():
     assert layer.n_tests == 3 and layer.n_triggers == 1
 
 
+def test_tumbling_window_tests_only_every_w_steps():
+    """Algorithm 1's loop: with W = 3 the signal is evaluated at steps 3, 6, 9, ... over the three steps
+    since the last evaluation.  Worked by hand for an unchanged query: the window of steps 1-3 (overlap
+    low: positional baseline) triggers and the baseline becomes the true top-k; steps 4-6 then see full
+    overlap and do not trigger; the sliding window of Eq. 10 evaluates at 3 (trigger), then at every step
+    from 6 on."""
+    spec, q0, data = small_workload(seed=6)
+    spec.window = 3
+    q = q0.to(torch.bfloat16)
+    tests = {}
+    for mode in (0, 1):
+        spec.window_mode = mode
+        retrieved, base = I.initial_lists(spec)
+        layer = ref.RefLayer(spec, data, retrieved, base)
+        flags = [layer.step(q)["flag"][(0, 0)] for _ in range(9)]
+        assert flags == [0, 0, 1, 0, 0, 0, 0, 0, 0]
+        tests[mode] = layer.n_tests
+    assert tests == {0: 1 + 4, 1: 3}          # sliding: steps 3, 6, 7, 8, 9; tumbling: steps 3, 6, 9
+
+
+def test_tumbling_window_misses_what_a_sliding_window_sees():
+    """Overlap sequence by construction (the baseline is swapped by hand): high at steps 1-2, low at steps
+    3-5, high afterwards; W = 3, lower median.  Sliding: {1,2,3} = h,h,l -> high; {2,3,4} = h,l,l -> low:
+    fires at step 4.  Tumbling: {1,2,3} -> high; {4,5,6} = l,l,h -> low: fires at step 6."""
+    spec, q0, data = small_workload(seed=7)
+    spec.window = 3
+    q = q0.to(torch.bfloat16)
+    fired = {}
+    for mode in (0, 1):
+        spec.window_mode = mode
+        retrieved, base = I.initial_lists(spec)
+        layer = ref.RefLayer(spec, data, retrieved, base)
+        true_top = ref.topk(layer.step(q, monitor=True)["scores"][(0, 0)].astype(np.float32),
+                            *spec.cand_range(0, 0), spec.k_mon(0, 0))
+        layer = ref.RefLayer(spec, data, retrieved, base)
+        good, bad = true_top.copy(), base[(0, 0)].numpy().copy()
+        flags = []
+        for t in range(1, 8):
+            layer.base[(0, 0)] = bad if t in (3, 4, 5) else good
+            before = layer.n_triggers
+            f = layer.step(q)["flag"][(0, 0)]
+            flags.append(f)
+            if layer.n_triggers > before:
+                break
+        fired[mode] = len(flags)
+    assert fired == {0: 4, 1: 6}
+
+
 def test_overlap_after_rotation_matches_bivariate_normal_expectation():
     """G = 1, keys ~ N(0,1): the logits of q and of q rotated by theta are jointly normal with
     correlation cos(theta), so E[overlap of the two top-k sets] = P(z>c, z'>c)/f, f = k/#candidates.
