@@ -141,11 +141,19 @@ class RefLayer:
     A compressed head is an index list into its master K/V: positions [0,sink), then
     [ctx-recent, ctx), then the r retrieved positions (slot order).  A refill decided at
     step t is used by the attention of step t+1.
+
+    The context may grow (append): the paper's ModelForward returns an updated cache (Algorithm 1)
+    without saying how the decode token enters compressed heads or the host tier.  Reading: every head's
+    master K/V (for a satellite, its host tier) grows by the token's row at position ctx; full heads
+    attend over all of it; a compressed head sees the token through its window of the last `recent`
+    positions, and the position that thereby leaves the window becomes an ordinary candidate of the
+    pivot's top-k, retrievable like any other.
     """
 
     def __init__(self, spec: LayerSpec, data: LayerData,
                  retrieved: Dict[Tuple[int, int], torch.Tensor], base: Dict[Tuple[int, int], torch.Tensor]):
         self.spec = spec
+        self.ctx = list(spec.ctx)              # current context length per sequence (grows with append)
         self.Kb = {k: _bits(v) for k, v in data.K.items()}
         self.Vb = {k: _bits(v) for k, v in data.V.items()}
         self.retrieved = {k: np.asarray(v, dtype=np.int32).copy() for k, v in retrieved.items()}
@@ -158,10 +166,26 @@ class RefLayer:
         hs = self.spec.heads[b][h]
         if hs.role == ROLE_FULL:
             return None
-        N = self.spec.ctx[b]
+        N = self.ctx[b]
         return np.concatenate([np.arange(0, hs.sink, dtype=np.int32),
                                np.arange(N - hs.recent, N, dtype=np.int32),
                                self.retrieved[(b, h)]]).astype(np.int32)
+
+    def cand_range(self, b: int, p: int) -> Tuple[int, int]:
+        """Candidate positions [lo, hi) of pivot p's top-k at the current context length."""
+        s0 = self.spec.heads[b][self.spec.satellites(b, p)[0]]
+        return s0.sink, self.ctx[b] - s0.recent
+
+    def append(self, k_new: torch.Tensor, v_new: torch.Tensor) -> None:
+        """k_new, v_new: bf16 [B, Hkv, D], the decode token's rows; they become position ctx_b of every
+        head of sequence b, and ctx_b grows by one.  Call before the step that attends over them."""
+        kb = _bits(k_new).reshape(self.spec.B, self.spec.Hkv, self.spec.D)
+        vb = _bits(v_new).reshape(self.spec.B, self.spec.Hkv, self.spec.D)
+        for b in range(self.spec.B):
+            for h in range(self.spec.Hkv):
+                self.Kb[(b, h)] = np.concatenate([self.Kb[(b, h)][:self.ctx[b]], kb[b, h][None, :]])
+                self.Vb[(b, h)] = np.concatenate([self.Vb[(b, h)][:self.ctx[b]], vb[b, h][None, :]])
+            self.ctx[b] += 1
 
     def slot_rows(self, b: int, h: int):
         """(K rows, V rows) as uint16 bit patterns in slot order: what HBM must hold."""
@@ -196,7 +220,7 @@ class RefLayer:
                 s = scores(lg, lse[b, p * G:(p + 1) * G], sp.agg)
                 rec["scores"][(b, p)] = s
                 s32 = s.astype(np.float32)          # the decision is taken on fp32 scores
-                lo, hi = sp.cand_range(b, p)
+                lo, hi = self.cand_range(b, p)
                 kmon = sp.k_mon(b, p)
                 T = topk(s32, lo, hi, kmon)
                 rec["topk"][(b, p)] = T

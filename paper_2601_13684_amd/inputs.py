@@ -122,6 +122,20 @@ def draw_q(spec: LayerSpec, seed: int, device: str = "cpu") -> torch.Tensor:
     return _randn((spec.B, spec.Hq, spec.D), g, device).double()
 
 
+def draw_token(spec: LayerSpec, seed: int, device: str = "cpu", toward: Optional[torch.Tensor] = None,
+               gain: float = 0.0) -> Tuple[torch.Tensor, torch.Tensor]:
+    """K and V rows of one generated token for every (sequence, KV head): bf16 [B, Hkv, D] ~ N(0,1); with
+    ``toward`` (a query [B, Hq, D]) and ``gain`` the key gets ``gain`` times the unit mean of the head's
+    query group added (a planted heavy token)."""
+    g = _gen(seed, device)
+    k = _randn((spec.B, spec.Hkv, spec.D), g, device)
+    v = _randn((spec.B, spec.Hkv, spec.D), g, device)
+    if toward is not None and gain:
+        u = toward.to(device).float().reshape(spec.B, spec.Hkv, spec.G, spec.D).mean(2)
+        k = k + gain * u / u.norm(dim=-1, keepdim=True)
+    return k.to(torch.bfloat16), v.to(torch.bfloat16)
+
+
 def draw_layer(spec: LayerSpec, q0: torch.Tensor, seed: int, device: str = "cpu",
                heavy_frac: float = 0.0, heavy_count: Optional[int] = None,
                heavy_gain: float = 3.0, heavy_noise: float = 0.3,
