@@ -83,11 +83,12 @@ typedef struct {
 
 /* One KV head of one sequence; table of B*Hkv entries, row (b*Hkv + h), HOST memory. */
 typedef struct {
-    int64_t k_off;     /* element (bf16) offset of this head's K rows [len][D] in the arena;
-                          multiple of 8                                                          */
-    int64_t v_off;     /* same for V rows [len][D]                                               */
+    int64_t k_off;     /* element (bf16) offset of this head's K rows [len][D] in the arena ([cap][D]
+                          for a full head that may grow); multiple of 8                          */
+    int64_t v_off;     /* same for V rows                                                        */
     int64_t tier_off;  /* satellites: element offset of this head's [ctx][2][D] block (K row then
-                          V row per position) in the host tier; multiple of 8; others: ignored   */
+                          V row per position; [cap][2][D] if it may grow) in the host tier;
+                          multiple of 8; others: ignored                                         */
     int32_t ctx;       /* N_b: context length of the sequence, 1..max_ctx                        */
     int32_t len;       /* resident rows: ctx for a full head, the budget l_i for a compressed one */
     int32_t role;      /* HC_ROLE_*                                                              */
@@ -98,7 +99,9 @@ typedef struct {
                           slots [sink+recent, len) are the r retrieved ones                      */
     int32_t k_mon;     /* pivot: size of the monitored set (L_base of Eq. 9); 0 = largest r of
                           its satellites                                                         */
-    int32_t reserved;  /* must be 0                                                              */
+    int32_t cap;       /* room to grow (hc_append_kv): rows that this head's K block, V block (full heads)
+                          and host-tier block (satellites) are laid out for; 0 = none (len resp. ctx);
+                          otherwise ctx <= cap <= max_ctx.  Compressed heads' K/V blocks stay [len][D]  */
 } hc_head_desc;
 
 /* ---- life cycle (these may allocate and synchronise; not for capture) -------------------- */
@@ -219,6 +222,27 @@ hc_status hc_gather_retrieve(hc_ctx* ctx, const hc_layer* layer, const void* hos
                              const int32_t* topk_idx, const int32_t* flag, void* kv_arena,
                              int32_t* slot_pos, void* stream, void* wait_event, void* done_event);
 
+/* Cache update of ModelForward (Algorithm 1: C_GPU is returned updated by ModelForward; Sec. 4.3 keeps the
+ * satellites' full K/V on the host): the decode token's rows k_new, v_new (dev bf16 [B][Hkv][D]) become
+ * position ctx_b of every head of every sequence b, and ctx_b grows by one.  The paper does not say how a
+ * generated token enters compressed heads or the host tier; here:
+ *   full heads        row ctx_b of their K and V blocks (which need cap > ctx_b);
+ *   compressed heads  the slot of their recent window that held position ctx_b - recent (the window is kept
+ *                     as a ring: slot sink + (position - initial ctx) mod recent), so they see the token
+ *                     at once; with recent == 0 they do not see it until it is retrieved;
+ *   satellites        also row ctx_b of their host-tier block (written by the kernel over the host link),
+ *                     so that the position can be retrieved once it has left the window;
+ *   pivots            the candidate range [sink, ctx_b - recent) of their top-k grows by the position that
+ *                     left the window.
+ * Call it before the hc_decode_attn that attends over the token, on the same stream, and after the layer's
+ * monitor and gather of the previous step have completed (they read the tables this call updates;
+ * hc_decode_step orders it so).  Every 64 appended tokens the split-K plan is rebalanced (a small
+ * host-to-device copy on the stream).  Fails with HC_ESHAPE when a head has no room left. */
+hc_status hc_append_kv(hc_ctx* ctx, hc_layer* layer, const void* k_new, const void* v_new, void* kv_arena,
+                       void* host_tier, void* stream);
+/* Current context length of sequence b of the layer (grows with hc_append_kv); -1 on a bad argument. */
+int32_t hc_layer_context(const hc_layer* layer, int32_t b);
+
 /* One decode step over a stack of layers (Algorithm 1, the body of the loop over t, for every layer):
  * for each layer in order, hc_decode_attn on main_stream, then hc_rep_topk_drift and hc_gather_retrieve
  * on side_stream (NULL = on main_stream, no overlap).  Layers are handled in groups of layers_per_group
@@ -248,6 +272,8 @@ typedef struct {
     int32_t* inter;
     int32_t* flag;
     int32_t* slot_pos;        /* dev [B*Hkv][max_k] in/out, or NULL: see hc_gather_retrieve */
+    const void* k_new;        /* dev bf16 [B][Hkv][D]: with v_new, the token to append before attention  */
+    const void* v_new;        /*   (hc_append_kv); both NULL: the context does not grow                  */
 } hc_layer_io;
 hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* layers, int32_t n_layers, int32_t layers_per_group,
                          void* main_stream, void* side_stream);

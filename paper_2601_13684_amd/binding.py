@@ -20,7 +20,7 @@ HC_MAX_WINDOW, HC_MAX_K_PER_REP, HC_MAX_GROUP = 64, 8, 8
 
 EXPORTS = ["hc_create", "hc_destroy", "hc_strerror", "hc_last_error", "hc_layer_create", "hc_layer_destroy",
            "hc_layer_num_reps", "hc_layer_rep_slot", "hc_layer_num_workgroups", "hc_layer_num_partials",
-           "hc_set_split", "hc_set_share_weights", "hc_set_monitor_span", "hc_set_timing_events", "hc_plan_describe", "hc_decode_attn", "hc_rep_topk_drift", "hc_gather_retrieve", "hc_decode_step"]
+           "hc_set_split", "hc_set_share_weights", "hc_set_monitor_span", "hc_set_timing_events", "hc_plan_describe", "hc_decode_attn", "hc_rep_topk_drift", "hc_gather_retrieve", "hc_append_kv", "hc_layer_context", "hc_decode_step"]
 
 
 class hc_config(C.Structure):
@@ -31,7 +31,7 @@ class hc_config(C.Structure):
 class hc_head_desc(C.Structure):
     _fields_ = [("k_off", C.c_int64), ("v_off", C.c_int64), ("tier_off", C.c_int64),
                 ("ctx", C.c_int32), ("len", C.c_int32), ("role", C.c_int32), ("rep", C.c_int32),
-                ("sink", C.c_int32), ("recent", C.c_int32), ("k_mon", C.c_int32), ("reserved", C.c_int32)]
+                ("sink", C.c_int32), ("recent", C.c_int32), ("k_mon", C.c_int32), ("cap", C.c_int32)]
 
 
 class hc_plan_info(C.Structure):
@@ -42,7 +42,7 @@ class hc_plan_info(C.Structure):
 
 class hc_layer_io(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("layer", "kv_arena", "host_tier", "q", "out", "lse", "rep_logits", "scores",
-                                          "topk_idx", "base_idx", "ring", "inter", "flag", "slot_pos")]
+                                          "topk_idx", "base_idx", "ring", "inter", "flag", "slot_pos", "k_new", "v_new")]
 
 
 class HcError(RuntimeError):
@@ -85,6 +85,9 @@ def lib():
         L.hc_decode_attn.argtypes = [vp] * 8
         L.hc_rep_topk_drift.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
         L.hc_gather_retrieve.argtypes = [vp] * 10
+        L.hc_append_kv.argtypes = [vp] * 7
+        L.hc_layer_context.argtypes = [vp, i32]
+        L.hc_layer_context.restype = i32
         L.hc_decode_step.argtypes = [vp, C.POINTER(hc_layer_io), i32, i32, vp, vp]
         for n in EXPORTS:
             if n not in ("hc_strerror", "hc_last_error", "hc_layer_num_reps", "hc_layer_rep_slot",
@@ -232,6 +235,15 @@ def hc_gather_retrieve(ctx: int, layer: int, host_tier: Ptr, topk_idx: Ptr, flag
     _check(lib().hc_gather_retrieve(ctx, layer, _p(host_tier), _p(topk_idx), _p(flag), _p(kv_arena), _p(slot_pos),
                                     _stream(stream), _event(wait_event), _event(done_event)),
            "hc_gather_retrieve", ctx)
+
+
+def hc_append_kv(ctx: int, layer: int, k_new: Ptr, v_new: Ptr, kv_arena: Ptr, host_tier: Ptr = None, stream=None) -> None:
+    _check(lib().hc_append_kv(ctx, layer, _p(k_new), _p(v_new), _p(kv_arena), _p(host_tier), _stream(stream)),
+           "hc_append_kv", ctx)
+
+
+def hc_layer_context(layer: int, b: int) -> int:
+    return lib().hc_layer_context(layer, b)
 
 
 def hc_decode_step(ctx: int, io, n_layers: int, main_stream=None, side_stream=None, layers_per_group: int = 4) -> None:

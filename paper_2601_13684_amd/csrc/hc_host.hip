@@ -223,10 +223,10 @@ static hc_status ensure_partials(hc_ctx* ctx, size_t slots)
 }
 
 template <class T>
-static hc_status upload(hc_ctx* ctx, const std::vector<T>& v, T** dev)
+static hc_status upload(hc_ctx* ctx, const std::vector<T>& v, T** dev, size_t capacity = 0)
 {
     *dev = nullptr;
-    const size_t n = std::max<size_t>(1, v.size());
+    const size_t n = std::max<size_t>(std::max<size_t>(1, v.size()), capacity);
     HC_HIP(ctx, hipMalloc((void**)dev, n * sizeof(T)));
     if (!v.empty()) HC_HIP(ctx, hipMemcpy(*dev, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice));
     return HC_OK;
@@ -286,7 +286,8 @@ static hc_status make_plan(const hc_config& cfg, const hc_head_desc* hd, int n_c
         const hc_head_desc& h = hd[i];
         if (h.role != HC_ROLE_FULL && h.role != HC_ROLE_SATELLITE && h.role != HC_ROLE_ANCHOR)
             return E.fail(HC_EINVAL, "head %d: bad role %d", i, h.role);
-        if (h.reserved != 0) return E.fail(HC_EINVAL, "head %d: reserved field must be 0", i);
+        if (h.cap != 0 && (h.cap < h.ctx || h.cap > cfg.max_ctx))
+            return E.fail(HC_EINVAL, "head %d: cap %d outside ctx..max_ctx", i, h.cap);
         if (h.ctx < 1 || h.ctx > cfg.max_ctx) return E.fail(HC_ESHAPE, "head %d: ctx %d outside 1..%d", i, h.ctx, cfg.max_ctx);
         if (h.ctx != hd[i - i % cfg.Hkv].ctx) return E.fail(HC_EINVAL, "head %d: ctx differs within its sequence", i);
         if (h.len < 1 || h.len > h.ctx) return E.fail(HC_ESHAPE, "head %d: len %d outside 1..ctx", i, h.len);
@@ -309,8 +310,9 @@ static hc_status make_plan(const hc_config& cfg, const hc_head_desc* hd, int n_c
     {
         std::vector<std::pair<int64_t, int64_t>> iv;
         for (int i = 0; i < nh; ++i) {
-            iv.push_back({hd[i].k_off, hd[i].k_off + (int64_t)hd[i].len * HC_D});
-            iv.push_back({hd[i].v_off, hd[i].v_off + (int64_t)hd[i].len * HC_D});
+            const int64_t rows = hd[i].role == HC_ROLE_FULL && hd[i].cap > hd[i].len ? hd[i].cap : hd[i].len;
+            iv.push_back({hd[i].k_off, hd[i].k_off + rows * HC_D});
+            iv.push_back({hd[i].v_off, hd[i].v_off + rows * HC_D});
         }
         std::sort(iv.begin(), iv.end());
         for (size_t i = 1; i < iv.size(); ++i)
@@ -397,6 +399,11 @@ static hc_status make_plan(const hc_config& cfg, const hc_head_desc* hd, int n_c
         H.rep_slot = P.rep_slot_of[i];
         H.part_begin = 0;
         H.part_count = 0;
+        H.role = hd[i].role;
+        H.sink = hd[i].sink;
+        H.recent = hd[i].recent;
+        H.ctx0 = hd[i].ctx;
+        H.tail_seg = H.tail_blk = -1;
         H.pad = 0;
     }
     const int nb = (int)std::max<int64_t>(1, std::min<int64_t>(max_blocks, total_units / min_units));
@@ -486,6 +493,14 @@ static hc_status make_plan(const hc_config& cfg, const hc_head_desc* hd, int n_c
         B.extra_begin = P.blk_seg[l] + 1;
         B.extra_end = P.blk_seg[l + 1];
         B.pad0 = B.pad1 = 0;
+        // a full head's last segment grows with appended tokens: remember where its copies live
+        for (int sg = P.blk_seg[l]; sg < P.blk_seg[l + 1]; ++sg) {
+            HeadDev& H = P.heads[P.segs[sg].bh];
+            if (hd[P.segs[sg].bh].role == HC_ROLE_FULL && P.segs[sg].row_end == hd[P.segs[sg].bh].len) {
+                H.tail_seg = sg;
+                H.tail_blk = sg == P.blk_seg[l] ? p : -1;
+            }
+        }
     }
     return HC_OK;
 }
@@ -550,10 +565,18 @@ extern "C" hc_status hc_layer_create(hc_ctx* ctx, const hc_head_desc* hd, hc_lay
     L->n_sats = (int)P.sats.size();
     L->n_blocks = P.n_blocks;
     L->n_segs = L->n_partials = (int)P.segs.size();
+    L->hd_host.assign(hd, hd + L->n_heads);
+    for (int i = 0; i < L->n_heads; ++i) L->ctx0_host.push_back(hd[i].ctx);
+    for (const RepDev& r : P.reps) {
+        L->rep_lo_host.push_back(r.lo);
+        L->rep_recent_host.push_back(hd[r.bh].ctx - r.hi);
+    }
+    // a plan has at most one segment per workgroup plus one per head boundary: room for any later plan
+    L->seg_capacity = P.n_blocks + L->n_heads;
 
-    st = ensure_partials(ctx, P.segs.size());
+    st = ensure_partials(ctx, (size_t)L->seg_capacity);
     if (st == HC_OK) st = upload(ctx, P.heads, &L->heads);
-    if (st == HC_OK) st = upload(ctx, P.segs, &L->segs);
+    if (st == HC_OK) st = upload(ctx, P.segs, &L->segs, (size_t)L->seg_capacity);
     if (st == HC_OK) st = upload(ctx, P.blks, &L->blks);
     if (st == HC_OK) st = upload(ctx, P.reps, &L->reps);
     if (st == HC_OK) st = upload(ctx, P.outs, &L->outs);
@@ -655,6 +678,72 @@ extern "C" hc_status hc_gather_retrieve(hc_ctx* ctx, const hc_layer* layer, cons
     return HC_OK;
 }
 
+extern "C" int32_t hc_layer_context(const hc_layer* layer, int32_t b)
+{
+    if (!layer_ok(layer) || b < 0 || b >= layer->ctx->cfg.B) return -1;
+    return layer->hd_host[(size_t)b * layer->ctx->cfg.Hkv].ctx;
+}
+
+// Rebuilds the split-K plan from the head table as it is now and copies it over the old one on `st`.
+// The workgroup count and the pivots do not change with the lengths; only shares, segments and slots do.
+static hc_status replan(hc_ctx* ctx, hc_layer* L, hipStream_t st)
+{
+    Plan P;
+    hc_status s = make_plan(ctx->cfg, L->hd_host.data(), ctx->n_cu, ctx->wg_per_cu, ctx->share_weights, P,
+                            ErrBuf{ctx->err, sizeof ctx->err});
+    if (s != HC_OK) return s;
+    if (P.n_blocks != L->n_blocks || (int)P.segs.size() > L->seg_capacity || (int)P.reps.size() != L->n_reps)
+        return hc_fail(ctx, HC_ESTATE, "internal: a rebalanced plan does not fit the layer");
+    for (int i = 0; i < L->n_heads; ++i) P.heads[i].ctx0 = L->ctx0_host[i];        // the ring of recent slots keeps its origin
+    HC_HIP(ctx, hipMemcpyAsync(L->heads, P.heads.data(), P.heads.size() * sizeof(HeadDev), hipMemcpyHostToDevice, st));
+    HC_HIP(ctx, hipMemcpyAsync(L->segs, P.segs.data(), P.segs.size() * sizeof(SegDev), hipMemcpyHostToDevice, st));
+    HC_HIP(ctx, hipMemcpyAsync(L->blks, P.blks.data(), P.blks.size() * sizeof(BlkDev), hipMemcpyHostToDevice, st));
+    HC_HIP(ctx, hipMemcpyAsync(L->reps, P.reps.data(), P.reps.size() * sizeof(RepDev), hipMemcpyHostToDevice, st));
+    HC_HIP(ctx, hipStreamSynchronize(st));        // the host vectors go away; rare (every 64 tokens)
+    L->n_segs = L->n_partials = (int)P.segs.size();
+    L->max_nchunk = P.max_nchunk;
+    L->appended_since_plan = 0;
+    return HC_OK;
+}
+
+extern "C" hc_status hc_append_kv(hc_ctx* ctx, hc_layer* layer, const void* k_new, const void* v_new, void* kv_arena,
+                                  void* host_tier, void* stream)
+{
+    if (!ctx_ok(ctx)) return HC_ESTATE;
+    if (!layer_ok(layer) || layer->ctx != ctx) return hc_fail(ctx, HC_ESTATE, "hc_append_kv: layer does not belong to this context");
+    if (!k_new || !v_new || !kv_arena) return hc_fail(ctx, HC_EINVAL, "hc_append_kv: null pointer");
+    if (((uintptr_t)k_new | (uintptr_t)v_new | (uintptr_t)kv_arena | (uintptr_t)host_tier) & 3)
+        return hc_fail(ctx, HC_EINVAL, "hc_append_kv: pointers must be 4-byte aligned");
+    hc_layer* L = layer;
+    for (int i = 0; i < L->n_heads; ++i) {
+        const hc_head_desc& h = L->hd_host[i];
+        const bool grows = h.role == HC_ROLE_FULL || h.role == HC_ROLE_SATELLITE;
+        if (h.ctx + 1 > ctx->cfg.max_ctx || (grows && h.ctx + 1 > (h.cap ? h.cap : h.ctx)))
+            return hc_fail(ctx, HC_ESHAPE, "hc_append_kv: head %d has no room for position %d (cap %d, max_ctx %d)", i, h.ctx,
+                           h.cap, ctx->cfg.max_ctx);
+        if (h.role == HC_ROLE_SATELLITE && !host_tier) return hc_fail(ctx, HC_EINVAL, "hc_append_kv: host_tier is needed for satellites");
+    }
+    hipStream_t st = (hipStream_t)stream;
+    const hc_status s = hc_launch_append(ctx, L, k_new, v_new, kv_arena, host_tier, st);
+    if (s != HC_OK) return s;
+    // the host's copy of the lengths follows what the kernel does to the device tables
+    for (int i = 0; i < L->n_heads; ++i) {
+        hc_head_desc& h = L->hd_host[i];
+        h.ctx += 1;
+        if (h.role == HC_ROLE_FULL) h.len += 1;
+    }
+    int max_nchunk = 1;
+    for (int i = 0; i < L->n_heads; ++i)
+        if (L->rep_slot_of[i] >= 0) {
+            const int slot = L->rep_slot_of[i];
+            const int lo = L->rep_lo_host[slot], hi = L->hd_host[i].ctx - L->rep_recent_host[slot];
+            max_nchunk = std::max(max_nchunk, (hi - lo + HC_SEL_CHUNK - 1) / HC_SEL_CHUNK);
+        }
+    L->max_nchunk = max_nchunk;
+    if (++L->appended_since_plan >= 64) return replan(ctx, L, st);
+    return HC_OK;
+}
+
 // One decode step over a stack of layers, launched from native code so that the host keeps ahead of the
 // GPU.  Layers are taken in groups: the attention of a group's layers on the main stream; then, on the
 // side stream, ONE batched monitor and ONE batched gather for the whole group (seven launches per group
@@ -698,6 +787,11 @@ extern "C" hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* io, int32_t 
                     if (st != HC_OK) return st;
                     gat[n_gat++] = hc_gather_call{L, x.host_tier, x.topk_idx, x.flag, const_cast<void*>(x.kv_arena), x.slot_pos};
                 }
+            }
+            if (x.k_new || x.v_new) {
+                const hc_status sa = hc_append_kv(ctx, L, x.k_new, x.v_new, const_cast<void*>(x.kv_arena),
+                                                  const_cast<void*>(x.host_tier), ms);
+                if (sa != HC_OK) return sa;
             }
             const hc_status st = hc_decode_attn(ctx, L, x.kv_arena, x.q, x.out, x.lse, side ? x.rep_logits : nullptr, ms);
             if (st != HC_OK) return st;

@@ -16,10 +16,15 @@ constexpr int HC_RADIX_BINS = 2048;  // 11-bit digits (11 + 11 + 10 bits of the 
 // One KV head as the kernels see it.
 struct HeadDev {
     int64_t k_off, v_off, tier_off;
-    int32_t len, ctx;
+    int32_t len, ctx;      // ctx (and len of a full head) grow on the device with every appended token
     int32_t rep_slot;      // >= 0: this full head is a pivot and owns that slot of rep_logits
     int32_t part_begin;    // first split-K partial of this head
     int32_t part_count;
+    int32_t role;          // HC_ROLE_*
+    int32_t sink, recent;  // compressed heads
+    int32_t ctx0;          // context length when the layer was created: anchors the ring of recent slots
+    int32_t tail_seg;      // full head: the segment that holds its last row, and the workgroup whose
+    int32_t tail_blk;      //   descriptor carries a copy of that segment (-1: none does)
     int32_t pad;
 };
 
@@ -107,6 +112,11 @@ struct hc_layer {
     int max_nchunk;
     int max_nk;                    // largest number of distinct set sizes of a pivot
     std::vector<int32_t> rep_slot_of;   // [B*Hkv]
+    std::vector<hc_head_desc> hd_host;  // the head table as it is now (lengths grow with appended tokens)
+    std::vector<int32_t> ctx0_host;     // [B*Hkv] context lengths at creation
+    std::vector<int32_t> rep_lo_host, rep_recent_host;   // per pivot: first candidate, recent slots of its satellites
+    int appended_since_plan = 0;
+    int seg_capacity = 0;               // device room in segs (a rebalanced plan may have a few more segments)
     HeadDev* heads = nullptr;
     SegDev* segs = nullptr;
     BlkDev* blks = nullptr;        // [n_blocks]
@@ -152,3 +162,5 @@ hc_status hc_launch_attn(hc_ctx* ctx, const hc_layer* L, const void* arena, cons
 hc_status hc_launch_monitor(hc_ctx* ctx, int n, const hc_monitor_call* calls, int scores_given, hipStream_t st);
 hc_status hc_launch_gather(hc_ctx* ctx, int n, const hc_gather_call* calls, hipStream_t st);
 hc_status hc_gather_set_lds_limit();     // once per process, at context creation
+hc_status hc_launch_append(hc_ctx* ctx, const hc_layer* L, const void* k_new, const void* v_new, void* arena, void* tier,
+                           hipStream_t st);

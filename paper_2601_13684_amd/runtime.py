@@ -16,13 +16,13 @@ from typing import Dict, List, Optional, Tuple
 import torch
 
 from . import binding as hc
-from .inputs import ROLE_FULL, ROLE_SATELLITE, LayerData, LayerSpec
+from .inputs import ROLE_ANCHOR, ROLE_FULL, ROLE_SATELLITE, LayerData, LayerSpec
 
 D = 128
 
 
-def make_config(spec: LayerSpec, max_ctx: Optional[int] = None, max_k: Optional[int] = None) -> hc.hc_config:
-    mc = max_ctx or max(spec.ctx)
+def make_config(spec: LayerSpec, max_ctx: Optional[int] = None, max_k: Optional[int] = None, growth: int = 0) -> hc.hc_config:
+    mc = max_ctx or (max(spec.ctx) + growth)
     mc = (mc + 63) // 64 * 64
     ks = [1]
     for b in range(spec.B):
@@ -34,8 +34,9 @@ def make_config(spec: LayerSpec, max_ctx: Optional[int] = None, max_k: Optional[
                         agg=spec.agg, window_mode=spec.window_mode)
 
 
-def make_descs(spec: LayerSpec) -> Tuple[List[hc.hc_head_desc], int, int]:
-    """Head table of a layer plus the arena and host-tier sizes in bf16 elements."""
+def make_descs(spec: LayerSpec, growth: int = 0) -> Tuple[List[hc.hc_head_desc], int, int]:
+    """Head table of a layer plus the arena and host-tier sizes in bf16 elements.  With ``growth`` the K / V
+    blocks of full heads and the host-tier blocks of satellites have room for that many appended tokens."""
     descs: List[hc.hc_head_desc] = []
     off = 0
     tier_off = 0
@@ -43,13 +44,15 @@ def make_descs(spec: LayerSpec) -> Tuple[List[hc.hc_head_desc], int, int]:
         for h in range(spec.Hkv):
             hs = spec.heads[b][h]
             ln = spec.resident(b, h)
-            d = hc.hc_head_desc(k_off=off, v_off=off + ln * D, tier_off=0, ctx=spec.ctx[b], len=ln, role=hs.role,
+            rows = ln + growth if hs.role == ROLE_FULL else ln          # rows the K and V blocks are laid out for
+            d = hc.hc_head_desc(k_off=off, v_off=off + rows * D, tier_off=0, ctx=spec.ctx[b], len=ln, role=hs.role,
                                 rep=hs.rep if hs.role == ROLE_SATELLITE else -1, sink=hs.sink, recent=hs.recent,
-                                k_mon=hs.k_mon if hs.role == ROLE_FULL else 0, reserved=0)
-            off += 2 * ln * D
+                                k_mon=hs.k_mon if hs.role == ROLE_FULL else 0,
+                                cap=spec.ctx[b] + growth if (growth and hs.role != ROLE_ANCHOR) else 0)
+            off += 2 * rows * D
             if hs.role == ROLE_SATELLITE:
                 d.tier_off = tier_off
-                tier_off += spec.ctx[b] * 2 * D
+                tier_off += (spec.ctx[b] + growth) * 2 * D
             descs.append(d)
     return descs, off, tier_off
 
@@ -84,11 +87,11 @@ class Context:
 class LayerRuntime:
     def __init__(self, ctx: Context, spec: LayerSpec, data: LayerData,
                  retrieved: Dict[Tuple[int, int], torch.Tensor], base: Dict[Tuple[int, int], torch.Tensor],
-                 host_tier: bool = True, own_scratch: bool = False, delta_gather: bool = True):
+                 host_tier: bool = True, own_scratch: bool = False, delta_gather: bool = True, growth: int = 0):
         self.ctx, self.spec = ctx, spec
         cfg, dev = ctx.cfg, ctx.device
         B, Hkv = spec.B, spec.Hkv
-        descs, off, tier_off = make_descs(spec)
+        descs, off, tier_off = make_descs(spec, growth)
         self.descs = descs
         # ---- arena ----
         self.arena = torch.zeros((off,), dtype=torch.bfloat16, device=dev)
@@ -162,6 +165,13 @@ class LayerRuntime:
     def monitor(self, scores_given: bool = False, stream=None) -> None:
         hc.hc_rep_topk_drift(self.ctx.handle, self.handle, self.rep_logits, self.lse, self.scores, scores_given,
                              self.topk_idx, self.base_idx, self.ring, self.inter, self.flag, stream)
+
+    def append(self, k_new: torch.Tensor, v_new: torch.Tensor, stream=None) -> None:
+        """The decode token's K/V rows (bf16 [B, Hkv, D] on the device) enter the cache (hc_append_kv)."""
+        hc.hc_append_kv(self.ctx.handle, self.handle, k_new, v_new, self.arena, self.tier, stream)
+
+    def context(self, b: int) -> int:
+        return hc.hc_layer_context(self.handle, b)
 
     def gather(self, stream=None, wait_event=None, done_event=None) -> None:
         hc.hc_gather_retrieve(self.ctx.handle, self.handle, self.tier, self.topk_idx, self.flag, self.arena,

@@ -54,12 +54,13 @@ def check_set_valid(T_gpu: np.ndarray, T_ref: np.ndarray, s_ref: np.ndarray, rel
 class Pair:
     """One layer on the GPU and its oracle twin, fed the same inputs."""
 
-    def __init__(self, spec, data, device="cuda:0", ctx=None, host_tier=True, wg_per_cu=None, delta_gather=True):
+    def __init__(self, spec, data, device="cuda:0", ctx=None, host_tier=True, wg_per_cu=None, delta_gather=True, growth=0):
         self.spec, self.data = spec, data
+        self.ctx0 = list(spec.ctx)
         retrieved, base = I.initial_lists(spec)
         self.own_ctx = ctx is None
-        self.ctx = ctx or R.Context(R.make_config(spec), device, workgroups_per_cu=wg_per_cu)
-        self.gpu = R.LayerRuntime(self.ctx, spec, data, retrieved, base, host_tier=host_tier, delta_gather=delta_gather)
+        self.ctx = ctx or R.Context(R.make_config(spec, growth=growth), device, workgroups_per_cu=wg_per_cu)
+        self.gpu = R.LayerRuntime(self.ctx, spec, data, retrieved, base, host_tier=host_tier, delta_gather=delta_gather, growth=growth)
         cpu = I.LayerData({k: v.cpu() for k, v in data.K.items()}, {k: v.cpu() for k, v in data.V.items()}, {})
         self.ref = ref.RefLayer(spec, cpu, retrieved, base)
 
@@ -69,6 +70,7 @@ class Pair:
         and every slot must hold the rows of the position the map names."""
         arena = self.gpu.arena.cpu().view(torch.int16).numpy().view(np.uint16)
         slot_pos = self.gpu.slot_pos.cpu().numpy() if self.gpu.slot_pos is not None else None
+        ctx0 = getattr(self, "ctx0", self.spec.ctx)
         for b in range(self.spec.B):
             for h in range(self.spec.Hkv):
                 hs = self.spec.heads[b][h]
@@ -80,6 +82,12 @@ class Pair:
                 Vg = arena[d.v_off:d.v_off + d.len * 128].reshape(-1, 128)
                 fixed = hs.sink + hs.recent
                 r = d.len - fixed
+                if hs.recent and self.ref.ctx[b] != ctx0[b]:
+                    # after appends the recent slots are a ring: slot sink + (position - initial ctx) mod recent
+                    pos = self.ref.resident(b, h)[hs.sink:fixed]
+                    ring = np.argsort((pos - ctx0[b]) % hs.recent)           # oracle rows in GPU slot order
+                    Kr = np.concatenate([Kr[:hs.sink], Kr[hs.sink:fixed][ring], Kr[fixed:]])
+                    Vr = np.concatenate([Vr[:hs.sink], Vr[hs.sink:fixed][ring], Vr[fixed:]])
                 if slot_pos is not None and hs.role == I.ROLE_SATELLITE and r > 0:
                     sp = slot_pos[b * self.spec.Hkv + h, :r]
                     order = np.argsort(sp, kind="stable")

@@ -87,7 +87,7 @@ def mutate(descs, i, **kw):
     (1, dict(sink=600), "sink + recent"),
     (1, dict(k_off=3), "multiples of 8"),
     (1, dict(role=7), "bad role"),
-    (1, dict(reserved=1), "reserved"),
+    (1, dict(cap=5), "cap"),
     (1, dict(ctx=2048), "ctx"),
     (1, dict(k_off=0), "overlap"),
     (0, dict(k_mon=5000), "k_mon"),

@@ -514,12 +514,20 @@ def test_gather_with_slot_map_moves_only_the_difference():
 # ------------------------------------------------------------------------------------------
 # Multi-step integration (Algorithm 1, stage 3 loop)
 # ------------------------------------------------------------------------------------------
-def run_steps(p, sched, steps, side=None, rel_band=1e-4, tag="", stepper=None):
-    """stepper(q): runs one decode step of p.gpu (default: LayerRuntime.step)."""
+def run_steps(p, sched, steps, side=None, rel_band=1e-4, tag="", stepper=None, append_seed=None, token_gain=None):
+    """stepper(q): runs one decode step of p.gpu (default: LayerRuntime.step).  With append_seed every step first
+    appends a generated token's K/V to both sides (token_gain(t): how strongly its key is planted toward q)."""
     sp = p.spec
     resyncs = triggers = 0
     for t in range(steps):
         q = sched.next()
+        if append_seed is not None:
+            gain = token_gain(t) if token_gain else 0.0
+            kn, vn = I.draw_token(sp, append_seed + t, toward=q if gain else None, gain=gain)
+            if p.gpu._side_pending:                 # the tables the append updates are read by the side work
+                torch.cuda.current_stream().wait_event(p.gpu.ev_done)
+            p.gpu.append(kn.to(DEV), vn.to(DEV))
+            p.ref.append(kn, vn)
         if stepper is None:
             p.gpu.step(q.to(DEV), side=side)
         else:
@@ -530,7 +538,7 @@ def run_steps(p, sched, steps, side=None, rel_band=1e-4, tag="", stepper=None):
         topk = p.gpu.topk_idx.cpu().numpy()
         same = True
         for (b, pv), s_ref in rec["scores"].items():
-            lo, hi = sp.cand_range(b, pv)
+            lo, hi = p.ref.cand_range(b, pv)
             U.check_scores(p.gpu.scores[p.gpu.rep_slot(b, pv)].cpu().numpy(), s_ref, lo, hi, f"{tag} step {t}")
             for h in [pv] + sp.satellites(b, pv):
                 T = rec["topk"][(b, h)]
@@ -660,6 +668,67 @@ def test_window_3_multi_step(mode):
     assert triggers >= 1
     if mode == 1:
         assert p.ref.n_tests == 4           # steps 3, 6, 9, 12 only
+    p.close()
+
+
+# ------------------------------------------------------------------------------------------
+# Growing context: hc_append_kv before every step
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("use_side", [False, True])
+def test_growing_context_multi_step(use_side):
+    """70 decode steps that each append the generated token first: the recent ring of the compressed heads
+    wraps twice (recent = 32), the split-K plan is rebalanced once (after 64 tokens), the candidate range
+    grows, and every 9th token is planted heavy so that it is retrieved after it has left the window."""
+    say("growing context, 70 steps", "side stream" if use_side else "one stream")
+    spec = I.spec_tiny(4096, budget=512, sink=16, recent=32)
+    q0 = I.draw_q(spec, 71)
+    data = I.draw_layer(spec, q0, 72, heavy_count=40)
+    sched = I.QuerySchedule(q0, 73, step_deg=5.0)
+    p = U.Pair(spec, data, DEV, growth=96)
+    n0 = spec.ctx[0]
+    side = torch.cuda.Stream() if use_side else None
+    resyncs, triggers = run_steps(p, sched, 70, side=side, tag="grow", append_seed=7000,
+                                  token_gain=lambda t: 40.0 if t % 9 == 4 else 0.0)
+    say("  resyncs", resyncs, "triggers", triggers)
+    assert p.gpu.context(0) == n0 + 70 == p.ref.ctx[0]
+    assert triggers >= 3 and resyncs <= 2
+    planted = [n0 + t for t in range(70) if t % 9 == 4 and t < 70 - 34]
+    got = set(p.ref.retrieved[(0, 1)].tolist())
+    assert all(pos in got for pos in planted), "planted tokens that left the window are retrieved"
+    p.close()
+
+
+def test_growing_context_batched_ragged_with_decode_step():
+    """hc_decode_step with k_new / v_new on a ragged batch (pivots, satellites, anchors, several sequences),
+    40 steps, against the oracle."""
+    say("growing context, decode step, ragged batch")
+    spec = I.spec_ragged(61, B=3, lo=1200, hi=5000, budgets=(96, 160, 352))
+    for b in range(spec.B):
+        spec.heads[b] = [h if h.role == I.ROLE_FULL else I.HeadSpec(h.role, rep=h.rep, sink=16, recent=24, budget=h.budget)
+                         for h in spec.heads[b]]
+    q0 = I.draw_q(spec, 62)
+    data = I.draw_layer(spec, q0, 63, heavy_frac=0.01)
+    p = U.Pair(spec, data, DEV, growth=64)
+    sched = I.QuerySchedule(q0, 64, step_deg=5.0)
+    q_cur = torch.zeros((1, spec.B, spec.Hq, 128), dtype=torch.bfloat16, device=DEV)
+    k_cur = torch.zeros((spec.B, spec.Hkv, 128), dtype=torch.bfloat16, device=DEV)
+    v_cur = torch.zeros_like(k_cur)
+    io = R.make_step_io([p.gpu], q_cur)
+    io[0].k_new, io[0].v_new = k_cur.data_ptr(), v_cur.data_ptr()
+    side = torch.cuda.Stream()
+
+    def stepper(q):
+        q_cur[0].copy_(q)
+        hc.hc_decode_step(p.ctx.handle, io, 1, None, side, 1)
+
+    for t in range(40):
+        kn, vn = I.draw_token(spec, 8000 + t)
+        torch.cuda.synchronize()
+        k_cur.copy_(kn)
+        v_cur.copy_(vn)
+        p.ref.append(kn, vn)
+        run_steps(p, sched, 1, tag=f"grow-batch {t}", stepper=stepper)
+    assert [p.gpu.context(b) for b in range(spec.B)] == p.ref.ctx
     p.close()
 
 
