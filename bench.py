@@ -44,6 +44,7 @@ def main():
                     help="step: hc_decode_step (native launch loop, two streams); graph: captured HIP graph; eager: Python loop")
     ap.add_argument("--dense", action="store_true", help="uncompressed comparison: all 8 KV heads full")
     ap.add_argument("--no-tier", action="store_true", help="no host tier / gather (attention + monitor only)")
+    ap.add_argument("--append", action="store_true", help="every step appends the generated token's K/V first (growing context)")
     ap.add_argument("--full-gather", action="store_true", help="refills fetch whole lists (no slot map: nothing is kept)")
     ap.add_argument("--wg-per-cu", type=int, default=0)
     ap.add_argument("--share-weights", default="", help="16 comma-separated share weights [die*2+slot] (tuning)")
@@ -91,12 +92,12 @@ def main():
         if args.dense:
             spec = I.spec_dense(spec.ctx[0])
         if ctx is None:
-            ctx = R.Context(R.make_config(spec), dev, workgroups_per_cu=args.wg_per_cu or None)
+            ctx = R.Context(R.make_config(spec, growth=T_total if args.append else 0), dev, workgroups_per_cu=args.wg_per_cu or None)
             if args.share_weights:
                 hc.hc_set_share_weights(ctx.handle, [float(x) for x in args.share_weights.split(",")])
         retrieved, base = I.initial_lists(spec)
         layers.append(R.LayerRuntime(ctx, spec, w.data, retrieved, base, host_tier=not args.no_tier, own_scratch=True,
-                                     delta_gather=not args.full_gather))
+                                     delta_gather=not args.full_gather, growth=T_total if args.append else 0))
         scheds.append(w.schedule)
         if l < 2 and not args.no_oracle:
             keep[l] = (spec, I.LayerData({k: v.cpu() for k, v in w.data.K.items()},
@@ -107,6 +108,12 @@ def main():
     kv_bytes = spec0.kv_bytes()
     Q_all = torch.stack([torch.stack([s.next() for s in scheds]) for _ in range(T_total)]).contiguous()   # [T,L,B,Hq,D]
     q_cur = Q_all[0].clone()
+    KV_new = None
+    if args.append:       # the generated tokens' K/V rows: [T, 2, L, B, Hkv, D]
+        gk = torch.Generator(device=dev)
+        gk.manual_seed(4242)
+        KV_new = torch.randn((T_total, 2, L, spec0.B, spec0.Hkv, 128), generator=gk, device=dev).to(torch.bfloat16)
+        kv_cur = KV_new[0].clone()
     t_dev = torch.zeros((1,), dtype=torch.long, device=dev)
     side = torch.cuda.Stream()
     torch.cuda.synchronize()
@@ -114,11 +121,17 @@ def main():
 
     def load_q():
         q_cur.copy_(Q_all.index_select(0, t_dev)[0])
+        if KV_new is not None:
+            kv_cur.copy_(KV_new.index_select(0, t_dev)[0])
         t_dev.add_(1)
 
     def step_eager():
         load_q()
         for l, lay in enumerate(layers):
+            if KV_new is not None:
+                if lay._side_pending:
+                    torch.cuda.current_stream().wait_event(lay.ev_done)
+                lay.append(kv_cur[0, l], kv_cur[1, l])
             if args.attn_only:
                 lay.attn(q_cur[l], monitor=False)
             else:
@@ -160,6 +173,9 @@ def main():
     graph = None
     if args.mode == "step":
         io = R.make_step_io(layers, q_cur, monitor=not args.attn_only)
+        if KV_new is not None:
+            for l in range(L):
+                io[l].k_new, io[l].v_new = kv_cur[0, l].data_ptr(), kv_cur[1, l].data_ptr()
         main_s = torch.cuda.current_stream()
 
         def run():
@@ -236,6 +252,8 @@ def main():
                 if n_steps_or == 0:
                     oracles[l] = ref.RefLayer(sp, data, retrieved, base)
                 ts = time.perf_counter()
+                if KV_new is not None:
+                    oracles[l].append(KV_new[n_steps_or, 0, l].cpu(), KV_new[n_steps_or, 1, l].cpu())
                 rec = oracles[l].step(Q_all[n_steps_or, l].cpu())
                 sample_t.append(time.perf_counter() - ts)
                 n_ls += 1
@@ -257,7 +275,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"config{args.config}{' dense' if args.dense else ''}: {spec0.ctx[0]} ctx, {L} layers, "
                                f"B={spec0.B}, {spec0.Hq}q/{spec0.Hkv}kv heads, D=128",
-                   "layers": L, "context": spec0.ctx[0], "mode": args.mode, "host_tier": not args.no_tier, "gather": "none" if args.no_tier else ("whole lists" if args.full_gather else "difference only"), "overlap_monitor": not args.serial, "layers_per_group": args.group,
+                   "layers": L, "context": spec0.ctx[0], "mode": args.mode, "host_tier": not args.no_tier, "gather": "none" if args.no_tier else ("whole lists" if args.full_gather else "difference only"), "overlap_monitor": not args.serial, "layers_per_group": args.group, "growing_context": args.append,
                    "kv_bytes_per_layer_step": kv_bytes,
                    "split_workgroups": hc.hc_layer_num_workgroups(layers[0].handle),
                    "split_partials": hc.hc_layer_num_partials(layers[0].handle)},
