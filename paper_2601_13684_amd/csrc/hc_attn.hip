@@ -20,11 +20,10 @@
 #include <hip/hip_ext.h>
 
 #include "hc_internal.h"
-#ifdef HC_TUNE
-#include <stdio.h>
-#include <stdlib.h>
-#endif
-
+// Optional instrumentation (build with -DHC_TUNE; the shipped library has none of it): every workgroup of the
+// split pass leaves timestamps of its phases (entry, descriptor read, rows done, end) and the die / compute
+// unit it ran on in hc_dbg, which hc_debug_read copies out.  That is how the phase times, the spread between
+// workgroups and the die patterns quoted in the comments of this file were measured.
 #ifdef HC_TUNE
 __device__ unsigned long long hc_dbg[4096 * 8];
 extern "C" int hc_debug_read(unsigned long long* host, int n)
