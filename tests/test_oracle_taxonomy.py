@@ -60,26 +60,52 @@ def test_budget_closed_forms():
     # equal stability: every compressed head gets L_base = (rho N - N_full) L / N_comp (Eq. 7)
     role = [T.ROLE_FULL, T.ROLE_FULL] + [T.ROLE_SATELLITE] * 5 + [T.ROLE_ANCHOR]
     L, rho = 12000, Fraction(1, 2)
-    out = T.budgets(role, [0.5] * 8, rho, L)
+    out = T.budgets(role, [0.5] * 8, 1, 2, L)
     assert out[:2] == [L, L]
     assert out[2:] == [(rho * 8 - 2) * L // 6] * 6 == [4000] * 6
     # inverse-stability weights: budgets in the ratio 1/S, summing to the total of Eq. 7
     s = [1.0, 1.0, 0.25, 0.5, 0.5, 1.0, 1.0, 1.0]
-    out = T.budgets(role, s, rho, L)
+    out = T.budgets(role, s, 1, 2, L)
     total = (rho * 8 - 2) * L
     assert sum(out[2:]) == total
     w = [1 / Fraction(x) for x in s[2:]]
     for o, wi in zip(out[2:], w):
         assert abs(o - total * wi / sum(w)) < 1
     # weights 4 : 2 : 2 : 1 : 1 : 1 of a total of 2 L = 22000: exact
-    assert T.budgets(role, s, rho, 11000)[2:] == [8000, 4000, 4000, 2000, 2000, 2000]
+    assert T.budgets(role, s, 1, 2, 11000)[2:] == [8000, 4000, 4000, 2000, 2000, 2000]
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_budgets_stay_within_one_slot_of_the_exact_shares(seed):
+    """The double-precision evaluation against exact rational arithmetic of Eq. 8 on the same inputs."""
+    rng = random.Random(500 + seed)
+    n = rng.randint(2, 48)
+    role = [rng.choice([T.ROLE_FULL, T.ROLE_SATELLITE, T.ROLE_SATELLITE, T.ROLE_ANCHOR]) for _ in range(n)]
+    if all(r == T.ROLE_FULL for r in role):
+        role[0] = T.ROLE_ANCHOR
+    s = [rng.uniform(0.3, 1.0) for _ in range(n)]
+    n_full = sum(r == T.ROLE_FULL for r in role)
+    num = rng.randint(1, 9)
+    L = rng.choice([4096, 229376])
+    total = Fraction(num * n - n_full * 10, 10) * L
+    if total <= 0:
+        return
+    out = T.budgets(role, s, num, 10, L)
+    comp = [i for i in range(n) if role[i] != T.ROLE_FULL]
+    tot = min(int(total), len(comp) * L)
+    assert sum(out[i] for i in comp) == tot and all(out[i] == L for i in range(n) if role[i] == T.ROLE_FULL)
+    if max(out[i] for i in comp) < L:           # nobody was cut to L: plain proportional shares
+        w = {i: 1 / Fraction(s[i]) for i in comp}
+        sw = sum(w.values())
+        for i in comp:
+            assert abs(out[i] - tot * w[i] / sw) <= 1
 
 
 def test_budget_rounding_and_clamping():
     role = [T.ROLE_FULL] + [T.ROLE_ANCHOR] * 3
-    out = T.budgets(role, [1.0, 1.0, 1.0, 1.0], Fraction(1, 2), 100)         # total (2 - 1) * 100 = 100 over 3 heads
+    out = T.budgets(role, [1.0, 1.0, 1.0, 1.0], 1, 2, 100)         # total (2 - 1) * 100 = 100 over 3 heads
     assert out == [100, 34, 33, 33]                                           # the spare slot goes to the lowest index
-    out = T.budgets(role, [1.0, 0.01, 1.0, 1.0], Fraction(3, 4), 100)        # total 200; head 1 would get 196 > L
+    out = T.budgets(role, [1.0, 0.01, 1.0, 1.0], 3, 4, 100)        # total 200; head 1 would get 196 > L
     assert out == [100, 100, 50, 50]
     with pytest.raises(ValueError):
-        T.budgets(role, [1.0] * 4, Fraction(1, 4), 100)                       # rho N = N_full: nothing left
+        T.budgets(role, [1.0] * 4, 1, 4, 100)                       # rho N = N_full: nothing left
