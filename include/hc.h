@@ -162,6 +162,28 @@ typedef struct {
 hc_status hc_plan_describe(const hc_config* cfg, const hc_head_desc* heads_host, int32_t compute_units,
                            int32_t workgroups_per_cu, hc_plan_info* info, char* err, int32_t err_len);
 
+/* ---- offline stages of Algorithm 1 (host only; no GPU, no context) ------------------------- */
+/* Head taxonomy of one layer (Sec. 4.1, Eq. 4-6; App. C.2; Algorithm 1 stage 1) from the calibration results:
+ * adjacency [n][n] (uint8, symmetric; non-zero: the two heads' active sets overlap by more than tau_sim)
+ * and the stability scores.  Greedy star clustering: the unassigned head with the most unassigned
+ * neighbours (lowest index on a tie) becomes a pivot and all its unassigned neighbours its satellites, until
+ * no unassigned head has an unassigned neighbour; what is left is an anchor if s_stable >= tau_stable and a
+ * volatile head otherwise.  role_out: HC_ROLE_FULL for pivots and volatile heads (both keep their full
+ * cache), HC_ROLE_SATELLITE, HC_ROLE_ANCHOR; rep_out: a satellite's pivot, else -1; is_pivot_out (may be
+ * NULL): 1 for pivots.  (Sec. 4.1 words it as a split by the similarity score first; App. C.2's procedure is
+ * the one implemented.) */
+hc_status hc_taxonomy(int32_t n_heads, const uint8_t* adjacency, const double* s_stable, double tau_stable,
+                      int32_t* role_out, int32_t* rep_out, int32_t* is_pivot_out);
+/* Stability-based budget allocation (Sec. 4.2, Eq. 7-8; Algorithm 1 stage 2): the total (rho N - N_full) L,
+ * rho = rho_num / rho_den, is shared among the compressed heads (satellites and anchors) in proportion to
+ * 1 / s_stable; full heads get L.  Shares are evaluated in double precision (w = 1.0 / s, sums in head
+ * order, share = (total * w) / sum w), rounded down, the slots left over given to the largest fractional
+ * parts (lowest index first), so that the budgets add up to the total rounded down; a share above L is cut
+ * to L and the rest shared in the same proportion (the paper leaves rounding and that case open).
+ * HC_EINVAL if rho N <= N_full (nothing is left for compressed heads). */
+hc_status hc_budgets(int32_t n_heads, const int32_t* role, const double* s_stable, int32_t rho_num, int32_t rho_den,
+                     int32_t L, int32_t* len_out);
+
 /* ---- hot path ---------------------------------------------------------------------------- */
 
 /* Attention of the decode token over the heterogeneous cache (Algorithm 1, ModelForward over

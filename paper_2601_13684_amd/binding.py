@@ -20,7 +20,7 @@ HC_MAX_WINDOW, HC_MAX_K_PER_REP, HC_MAX_GROUP = 64, 8, 8
 
 EXPORTS = ["hc_create", "hc_destroy", "hc_strerror", "hc_last_error", "hc_layer_create", "hc_layer_destroy",
            "hc_layer_num_reps", "hc_layer_rep_slot", "hc_layer_num_workgroups", "hc_layer_num_partials",
-           "hc_set_split", "hc_set_share_weights", "hc_set_monitor_span", "hc_set_timing_events", "hc_plan_describe", "hc_decode_attn", "hc_rep_topk_drift", "hc_gather_retrieve", "hc_append_kv", "hc_layer_context", "hc_decode_step"]
+           "hc_set_split", "hc_set_share_weights", "hc_set_monitor_span", "hc_set_timing_events", "hc_plan_describe", "hc_decode_attn", "hc_rep_topk_drift", "hc_gather_retrieve", "hc_append_kv", "hc_layer_context", "hc_decode_step", "hc_taxonomy", "hc_budgets"]
 
 
 class hc_config(C.Structure):
@@ -86,6 +86,8 @@ def lib():
         L.hc_rep_topk_drift.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
         L.hc_gather_retrieve.argtypes = [vp] * 10
         L.hc_append_kv.argtypes = [vp] * 7
+        L.hc_taxonomy.argtypes = [i32, vp, vp, C.c_double, vp, vp, vp]
+        L.hc_budgets.argtypes = [i32, vp, vp, i32, i32, i32, vp]
         L.hc_layer_context.argtypes = [vp, i32]
         L.hc_layer_context.restype = i32
         L.hc_decode_step.argtypes = [vp, C.POINTER(hc_layer_io), i32, i32, vp, vp]
