@@ -698,6 +698,28 @@ def test_growing_context_multi_step(use_side):
     p.close()
 
 
+def test_append_without_room_is_refused_on_the_host():
+    say("append without room")
+    spec = I.spec_tiny(2048, budget=256, sink=16, recent=32)
+    q0 = I.draw_q(spec, 81)
+    data = I.draw_layer(spec, q0, 82)
+    p = U.Pair(spec, data, DEV, growth=2)
+    for t in range(2):
+        kn, vn = I.draw_token(spec, 9000 + t)
+        p.gpu.append(kn.to(DEV), vn.to(DEV))
+        p.ref.append(kn, vn)
+    kn, vn = I.draw_token(spec, 9002)
+    with pytest.raises(hc.HcError) as e:
+        p.gpu.append(kn.to(DEV), vn.to(DEV))
+    assert e.value.status == hc.HC_ESHAPE and "no room" in str(e.value)
+    assert p.gpu.context(0) == 2050
+    q = q0.to(torch.bfloat16)
+    p.gpu.attn(q.to(DEV))                       # the refused call changed nothing
+    torch.cuda.synchronize()
+    U.check_attention(p.gpu.out, p.gpu.lse, p.ref.step(q, monitor=False), "after refused append")
+    p.close()
+
+
 def test_growing_context_batched_ragged_with_decode_step():
     """hc_decode_step with k_new / v_new on a ragged batch (pivots, satellites, anchors, several sequences),
     40 steps, against the oracle."""
