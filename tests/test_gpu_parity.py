@@ -783,6 +783,69 @@ def test_config4_full_size_single_layer():
     p.close()
 
 
+def test_config4_full_size_in_the_benchmark_launch_configuration():
+    """Two full-size layers through hc_decode_step as bench.py launches it (groups of 8, monitor and gather
+    batched on a side stream, 7 chunks per monitor workgroup as a batch of 8 layers gets at this size),
+    2 steps, every output of both layers against the oracle."""
+    say("config 4 full size, decode step, 2 layers, 2 steps")
+    ws = [I.make_workload(4, layer=l, device=DEV) for l in range(2)]
+    ctx = R.Context(R.make_config(ws[0].spec), DEV)
+    hc.hc_set_monitor_span(ctx.handle, 7)
+    pairs = [U.Pair(w.spec, w.data, DEV, ctx=ctx) for w in ws]
+    for p in pairs:
+        p.gpu.rep_logits = torch.zeros_like(p.gpu.rep_logits)        # own buffers: the layers' monitors run together
+        p.gpu.scores = torch.zeros_like(p.gpu.scores)
+    q_cur = torch.zeros((2, 1, 32, 128), dtype=torch.bfloat16, device=DEV)
+    io = R.make_step_io([p.gpu for p in pairs], q_cur)
+    side = torch.cuda.Stream()
+    for t in range(2):
+        qs = [w.schedule.next() for w in ws]
+        q_cur.copy_(torch.stack([q.to(DEV) for q in qs]))
+        hc.hc_decode_step(ctx.handle, io, 2, None, side, 8)
+        torch.cuda.synchronize()
+        for l, (p, w) in enumerate(zip(pairs, ws)):
+            rec = p.ref.step(qs[l].cpu())
+            worst, lerr = U.check_attention(p.gpu.out, p.gpu.lse, rec, f"cfg4 L{l} step {t}")
+            topk = p.gpu.topk_idx.cpu().numpy()
+            nd = 0
+            for (b, pv), s_ref in rec["scores"].items():
+                lo, hi = w.spec.cand_range(b, pv)
+                U.check_scores(p.gpu.scores[p.gpu.rep_slot(b, pv)].cpu().numpy(), s_ref, lo, hi, "cfg4")
+                for h in [pv] + w.spec.satellites(b, pv):
+                    T = rec["topk"][(b, h)]
+                    nd += U.check_set_valid(topk[b * 8 + h, :T.size], T, s_ref, 1e-4, f"cfg4 head {h}")
+                assert int(p.gpu.flag[pv]) == rec["flag"][(b, pv)] or nd
+            say(f"  layer {l} step {t}: err/rms {worst:.2e} lse {lerr:.1e} set differences {nd} flags {rec['flag']}")
+            if nd:
+                resync(p, rec)
+            assert p.slots_equal_oracle()
+    for p in pairs:
+        p.close()
+    ctx.close()
+
+
+def test_decode_step_degenerate_stacks():
+    """No layers at all; a layer without pivots (its monitor and gather are skipped even though buffers are given)."""
+    say("decode step, degenerate stacks")
+    spec = ragged_spec([100, 33], 4, ctx=1500)
+    q0 = I.draw_q(spec, 91)
+    data = I.draw_layer(spec, q0, 92)
+    retrieved = {(0, h + 1): torch.arange(2, l, dtype=torch.int32) for h, l in enumerate([100, 33])}
+    ctx = R.Context(R.make_config(spec), DEV)
+    gpu = R.LayerRuntime(ctx, spec, data, retrieved, {}, host_tier=False)
+    oracle = ref.RefLayer(spec, data, retrieved, {})
+    q = q0.to(torch.bfloat16)
+    q_cur = q.to(DEV)[None].contiguous()
+    io = R.make_step_io([gpu], q_cur)
+    hc.hc_decode_step(ctx.handle, io, 0, None, None, 4)          # nothing to do
+    hc.hc_decode_step(ctx.handle, io, 1, None, torch.cuda.Stream(), 4)
+    torch.cuda.synchronize()
+    U.check_attention(gpu.out, gpu.lse, oracle.step(q, monitor=False), "no pivots")
+    assert hc.hc_layer_num_reps(gpu.handle) == 0
+    gpu.close()
+    ctx.close()
+
+
 # ------------------------------------------------------------------------------------------
 # hc_decode_step: the native launch loop over a stack of layers, monitor and gather on a side stream
 # ------------------------------------------------------------------------------------------
