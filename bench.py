@@ -47,6 +47,7 @@ def main():
     ap.add_argument("--append", action="store_true", help="every step appends the generated token's K/V first (growing context)")
     ap.add_argument("--full-gather", action="store_true", help="refills fetch whole lists (no slot map: nothing is kept)")
     ap.add_argument("--wg-per-cu", type=int, default=0)
+    ap.add_argument("--tune-rounds", type=int, default=0, help="rounds of on-device measurement of the share weights on the first layer (0: built-in weights, as the parity tests use)")
     ap.add_argument("--share-weights", default="", help="16 comma-separated share weights [die*2+slot] (tuning)")
     ap.add_argument("--group", type=int, default=8, help="layers per cross-stream sync group in step mode")
     ap.add_argument("--serial", action="store_true", help="monitor and gather on the main stream (no overlap)")
@@ -98,6 +99,9 @@ def main():
         retrieved, base = I.initial_lists(spec)
         layers.append(R.LayerRuntime(ctx, spec, w.data, retrieved, base, host_tier=not args.no_tier, own_scratch=True,
                                      delta_gather=not args.full_gather, growth=T_total if args.append else 0))
+        if l == 0 and args.tune_rounds and not args.share_weights:
+            layers[0].tune(w.schedule.q.to(torch.bfloat16).to(dev), args.tune_rounds)       # untimed set-up
+            print("[bench] share weights " + " ".join(f"{x:.3f}" for x in hc.hc_get_share_weights(ctx.handle)), file=sys.stderr, flush=True)
         scheds.append(w.schedule)
         if l < 2 and not args.no_oracle:
             keep[l] = (spec, I.LayerData({k: v.cpu() for k, v in w.data.K.items()},

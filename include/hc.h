@@ -131,6 +131,18 @@ hc_status hc_set_split(hc_ctx* ctx, int32_t workgroups_per_cu, int32_t compute_u
  * defaults (measured on MI355X: the second workgroup on a compute unit and the workgroups on odd
  * dies stream a few per cent slower).  Used when the number of workgroups is a multiple of 16. */
 hc_status hc_set_share_weights(hc_ctx* ctx, const float* weights16);
+/* Copies the 16 weights in use (built-in, set, or measured by hc_layer_tune) to host memory weights16. */
+hc_status hc_get_share_weights(const hc_ctx* ctx, float* weights16);
+
+/* Measures the share weights (see hc_set_share_weights) on the device at hand: runs the layer's split pass
+ * 18 times per round with per-workgroup timestamps (out, lse and rep_logits are overwritten with the
+ * results of attention for q, as hc_decode_attn would), equalises the mean finish times of the 16 (die,
+ * dispatch slot) classes, replans the layer, and leaves the weights in the context for layers created
+ * later.  Which dies stream slower differs between devices; the built-in weights are one device's.
+ * Set-up time only: allocates, synchronises the stream.  A plan whose shares are not weighted (short
+ * passes) is left alone.  rounds: 1..16; 4 is enough. */
+hc_status hc_layer_tune(hc_ctx* ctx, hc_layer* layer, const void* kv_arena, const void* q, float* out, float* lse,
+                        float* rep_logits, int32_t rounds, void* stream);
 
 /* Tuning knob: how many 1024-candidate chunks a workgroup of the monitor's selection passes takes
  * (1..64); 0 (default) lets every call choose: 1 for a single layer (many small workgroups, lowest

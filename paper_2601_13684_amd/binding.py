@@ -20,7 +20,7 @@ HC_MAX_WINDOW, HC_MAX_K_PER_REP, HC_MAX_GROUP = 64, 8, 8
 
 EXPORTS = ["hc_create", "hc_destroy", "hc_strerror", "hc_last_error", "hc_layer_create", "hc_layer_destroy",
            "hc_layer_num_reps", "hc_layer_rep_slot", "hc_layer_num_workgroups", "hc_layer_num_partials",
-           "hc_set_split", "hc_set_share_weights", "hc_set_monitor_span", "hc_set_timing_events", "hc_plan_describe", "hc_decode_attn", "hc_rep_topk_drift", "hc_gather_retrieve", "hc_append_kv", "hc_layer_context", "hc_decode_step", "hc_taxonomy", "hc_budgets"]
+           "hc_set_split", "hc_set_share_weights", "hc_get_share_weights", "hc_layer_tune", "hc_set_monitor_span", "hc_set_timing_events", "hc_plan_describe", "hc_decode_attn", "hc_rep_topk_drift", "hc_gather_retrieve", "hc_append_kv", "hc_layer_context", "hc_decode_step", "hc_taxonomy", "hc_budgets"]
 
 
 class hc_config(C.Structure):
@@ -79,6 +79,8 @@ def lib():
         L.hc_set_split.argtypes = [vp, i32, i32]
         L.hc_set_share_weights.argtypes = [vp, C.POINTER(C.c_float)]
         L.hc_set_monitor_span.argtypes = [vp, i32]
+        L.hc_get_share_weights.argtypes = [vp, C.POINTER(C.c_float)]
+        L.hc_layer_tune.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp]
         L.hc_set_timing_events.argtypes = [vp, vp, vp, i32]
         L.hc_plan_describe.argtypes = [C.POINTER(hc_config), C.POINTER(hc_head_desc), i32, i32,
                                        C.POINTER(hc_plan_info), C.c_char_p, i32]
@@ -165,6 +167,18 @@ def hc_set_share_weights(ctx: int, weights=None) -> None:
             raise ValueError("hc_set_share_weights: 16 weights")
         arr = (C.c_float * 16)(*[float(w) for w in weights])
     _check(lib().hc_set_share_weights(ctx, arr), "hc_set_share_weights", ctx)
+
+
+def hc_get_share_weights(ctx: int) -> list:
+    w = (C.c_float * 16)()
+    _check(lib().hc_get_share_weights(ctx, w), "hc_get_share_weights", ctx)
+    return [float(x) for x in w]
+
+
+def hc_layer_tune(ctx: int, layer: int, kv_arena: Ptr, q: Ptr, out: Ptr, lse: Ptr, rep_logits: Ptr = None, rounds: int = 4,
+                  stream=None) -> None:
+    _check(lib().hc_layer_tune(ctx, layer, _p(kv_arena), _p(q), _p(out), _p(lse), _p(rep_logits), rounds, _stream(stream)),
+           "hc_layer_tune", ctx)
 
 
 def hc_set_monitor_span(ctx: int, span: int = 0) -> None:

@@ -336,7 +336,8 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
                                                                     const SegDev* __restrict__ segs,
                                                                     float* __restrict__ part_acc,
                                                                     float* __restrict__ part_ml,
-                                                                    float* __restrict__ rep_logits, int max_ctx)
+                                                                    float* __restrict__ rep_logits, int max_ctx,
+                                                                    unsigned long long* __restrict__ stamps)
 {
     __shared__ float sm_m[4][G];
     __shared__ float sm_Z[16][G];
@@ -349,6 +350,8 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
     const int r = lane >> 3;     // row inside a row step
     const int c = lane & 7;      // column lane
 
+    // tuning runs only: when the workgroup started and (below) when it was through its last rows
+    if (stamps && threadIdx.x == 0) stamps[2 * blockIdx.x] = __builtin_amdgcn_s_memrealtime();
     HC_STAMP(0);
 #ifdef HC_TUNE
     if (threadIdx.x == 0 && blockIdx.x < 4096) {
@@ -388,6 +391,8 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
 #ifdef HC_TUNE
         if (st.Z[0] >= 0.f) HC_STAMP(2);
 #endif
+        if (stamps && threadIdx.x == 0 && next_extra >= blk.extra_end && st.Z[0] >= 0.f)      // (the condition on Z orders the stamp after the rows)
+            stamps[2 * blockIdx.x + 1] = __builtin_amdgcn_s_memrealtime();
 
         // ---- merge the 4 waves x 8 row lanes into one partial ----
         // Inside a wave the 16 G accumulators of a lane are summed over the wave's 8 row lanes in registers:
@@ -547,7 +552,8 @@ hc_status launch(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* 
 #define HC_LAUNCH(KERNEL)                                                                                         \
     hipExtLaunchKernelGGL(KERNEL, dim3(L->n_blocks), dim3(256), 0, st, ev_begin, ev_end, 0,                      \
                           (const uint16_t*)arena, (const uint16_t*)q, (const BlkDev*)L->blks,                    \
-                          (const SegDev*)L->segs, ctx->part_acc, ctx->part_ml, rep_logits, ctx->cfg.max_ctx)
+                          (const SegDev*)L->segs, ctx->part_acc, ctx->part_ml, rep_logits, ctx->cfg.max_ctx,       \
+                          ctx->tune_stamps)
     HC_LAUNCH((attn_split_kernel<G, Tune<G>::WG>));
 #undef HC_LAUNCH
     HC_HIP(ctx, hipGetLastError());

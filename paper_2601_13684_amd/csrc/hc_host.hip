@@ -175,6 +175,13 @@ extern "C" hc_status hc_set_split(hc_ctx* ctx, int32_t workgroups_per_cu, int32_
     return HC_OK;
 }
 
+extern "C" hc_status hc_get_share_weights(const hc_ctx* ctx, float* weights16)
+{
+    if (!ctx_ok(ctx) || !weights16) return HC_ESTATE;
+    for (int i = 0; i < 16; ++i) weights16[i] = ctx->share_weights[i];
+    return HC_OK;
+}
+
 extern "C" hc_status hc_set_share_weights(hc_ctx* ctx, const float* weights16)
 {
     if (!ctx_ok(ctx)) return HC_ESTATE;
@@ -742,6 +749,90 @@ extern "C" hc_status hc_append_kv(hc_ctx* ctx, hc_layer* layer, const void* k_ne
     L->max_nchunk = max_nchunk;
     if (++L->appended_since_plan >= 64) return replan(ctx, L, st);
     return HC_OK;
+}
+
+// Share weights measured on the device at hand.  Which dies stream slower differs from one MI355X to the
+// next (and the built-in weights come from one of them), so the layer's own split pass is run a few times
+// with per-workgroup timestamps, the 16 (die, dispatch slot) classes' mean finish times are equalised
+// (work_c proportional to rate_c * (T - entry_c)), and the layer is replanned; the weights stay in the
+// context for the layers created afterwards.  Launches are timed back to back, as in a decode step: a
+// launch into an idle GPU reaches the dies up to 2 us apart, which steady state does not see.
+extern "C" hc_status hc_layer_tune(hc_ctx* ctx, hc_layer* layer, const void* kv_arena, const void* q, float* out, float* lse,
+                                   float* rep_logits, int32_t rounds, void* stream)
+{
+    if (!ctx_ok(ctx)) return HC_ESTATE;
+    if (!layer_ok(layer) || layer->ctx != ctx) return hc_fail(ctx, HC_ESTATE, "hc_layer_tune: layer does not belong to this context");
+    if (rounds < 1 || rounds > 16) return hc_fail(ctx, HC_EINVAL, "hc_layer_tune: rounds 1..16");
+    hc_layer* L = layer;
+    const int nb = L->n_blocks;
+    int64_t total_units = 0;
+    for (const hc_head_desc& h : L->hd_host) total_units += (h.len + HC_UNIT_ROWS - 1) / HC_UNIT_ROWS;
+    if (nb % 16 != 0 || total_units < 16 * (int64_t)nb) return HC_OK;        // shares of this plan are not weighted
+    hipStream_t st = (hipStream_t)stream;
+    unsigned long long* dev = nullptr;
+    HC_HIP(ctx, hipMalloc((void**)&dev, (size_t)nb * 2 * sizeof(unsigned long long)));
+    std::vector<unsigned long long> host((size_t)nb * 2);
+    hc_status result = HC_OK;
+    constexpr int SAMPLES = 6;
+    for (int round = 0; round < rounds && result == HC_OK; ++round) {
+        double ent[16] = {}, fin[16] = {};
+        bool give_up = false;
+        for (int s = 0; s < SAMPLES && result == HC_OK; ++s) {
+            for (int k = 0; k < 3 && result == HC_OK; ++k) {                  // the third of three back-to-back launches is read
+                ctx->tune_stamps = k == 2 ? dev : nullptr;
+                if (k == 2 && hipMemsetAsync(dev, 0, host.size() * sizeof(unsigned long long), st) != hipSuccess) result = HC_EHIP;
+                if (result == HC_OK) result = hc_decode_attn(ctx, L, kv_arena, q, out, lse, rep_logits, st);
+            }
+            ctx->tune_stamps = nullptr;
+            if (result != HC_OK) break;
+            hipError_t e = hipStreamSynchronize(st);
+            if (e == hipSuccess) e = hipMemcpy(host.data(), dev, host.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost);
+            if (e != hipSuccess) {
+                result = hc_hip_fail(ctx, e, "hc_layer_tune");
+                break;
+            }
+            unsigned long long t0 = ~0ull;
+            bool stamped = true;
+            for (int b = 0; b < nb; ++b) {
+                t0 = std::min(t0, host[2 * b]);
+                stamped &= host[2 * b] != 0 && host[2 * b + 1] > host[2 * b];
+            }
+            if (!stamped) {                                                    // a workgroup left no time: keep what we have
+                give_up = true;
+                break;
+            }
+            for (int b = 0; b < nb; ++b) {
+                const int cls = (b % 8) * 2 + (b >= nb / 2);
+                ent[cls] += (double)(host[2 * b] - t0) / (nb / 16) / SAMPLES;
+                fin[cls] += (double)(host[2 * b + 1] - t0) / (nb / 16) / SAMPLES;
+            }
+        }
+        if (result != HC_OK || give_up) break;
+        double rate[16], sum_w = 0, sum_rate = 0, sum_re = 0;
+        bool ok = true;
+        for (int c = 0; c < 16; ++c) {
+            ok &= fin[c] > ent[c];
+            rate[c] = ctx->share_weights[c] / std::max(1.0, fin[c] - ent[c]);
+            sum_w += ctx->share_weights[c];
+            sum_rate += rate[c];
+            sum_re += rate[c] * ent[c];
+        }
+        if (!ok) break;                                                        // timestamps make no sense: keep what we have
+        const double T = (sum_w + sum_re) / sum_rate;
+        double neww[16], sum_new = 0;
+        for (int c = 0; c < 16; ++c) {
+            neww[c] = rate[c] * (T - ent[c]);
+            sum_new += neww[c];
+        }
+        for (int c = 0; c < 16; ++c) {
+            const double w = 0.5 * ctx->share_weights[c] + 0.5 * neww[c] * 16.0 / sum_new;      // damped
+            ctx->share_weights[c] = (float)std::min(1.25, std::max(0.8, w));
+        }
+        result = replan(ctx, L, st);
+    }
+    ctx->tune_stamps = nullptr;
+    (void)hipFree(dev);
+    return result;
 }
 
 // One decode step over a stack of layers, launched from native code so that the host keeps ahead of the

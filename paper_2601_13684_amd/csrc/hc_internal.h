@@ -81,6 +81,7 @@ struct hc_ctx {
     int G;
     int n_cu;
     int wg_per_cu;
+    unsigned long long* tune_stamps = nullptr;   // non-null only inside hc_layer_tune: per-workgroup start / rows-done times
     float share_weights[16];     // by die and dispatch slot, see hc_set_share_weights
     int device;
     char err[512];

@@ -166,6 +166,11 @@ class LayerRuntime:
         hc.hc_rep_topk_drift(self.ctx.handle, self.handle, self.rep_logits, self.lse, self.scores, scores_given,
                              self.topk_idx, self.base_idx, self.ring, self.inter, self.flag, stream)
 
+    def tune(self, q: torch.Tensor, rounds: int = 4) -> None:
+        """Measure the split pass's share weights on this device with this layer (hc_layer_tune)."""
+        hc.hc_layer_tune(self.ctx.handle, self.handle, self.arena, q, self.out, self.lse,
+                         self.rep_logits if self.n_reps else None, rounds)
+
     def append(self, k_new: torch.Tensor, v_new: torch.Tensor, stream=None) -> None:
         """The decode token's K/V rows (bf16 [B, Hkv, D] on the device) enter the cache (hc_append_kv)."""
         hc.hc_append_kv(self.ctx.handle, self.handle, k_new, v_new, self.arena, self.tier, stream)

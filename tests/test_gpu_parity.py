@@ -783,6 +783,43 @@ def test_config4_full_size_single_layer():
     p.close()
 
 
+def test_config4_full_size_after_measuring_the_share_weights():
+    """hc_layer_tune replans the split pass with weights measured on this device; the attention of the
+    replanned layer is checked like any other, and a short layer (unweighted plan) is left as it was."""
+    say("config 4 full size: share weights measured on the device, then 1 step")
+    w = I.make_workload(4, device=DEV)
+    p = U.Pair(w.spec, w.data, DEV)
+    q = w.schedule.next()
+    before = hc.hc_get_share_weights(p.gpu.ctx.handle)
+    p.gpu.tune(q.to(DEV), rounds=3)
+    torch.cuda.synchronize()
+    after = hc.hc_get_share_weights(p.gpu.ctx.handle)
+    say("  weights " + " ".join(f"{x:.3f}" for x in after))
+    assert after != before and all(0.8 <= x <= 1.25 for x in after) and abs(sum(after) / 16 - 1) < 0.02
+    assert hc.hc_layer_num_workgroups(p.gpu.handle) == 512
+    p.gpu.step(q.to(DEV), side=torch.cuda.Stream())
+    torch.cuda.synchronize()
+    rec = p.ref.step(q.cpu())
+    worst, lerr = U.check_attention(p.gpu.out, p.gpu.lse, rec, "cfg4 tuned")
+    for (b, pv), s_ref in rec["scores"].items():
+        lo, hi = w.spec.cand_range(b, pv)
+        U.check_scores(p.gpu.scores[p.gpu.rep_slot(b, pv)].cpu().numpy(), s_ref, lo, hi, "cfg4 tuned")
+    say(f"  err/rms {worst:.2e} lse {lerr:.1e}")
+    p.close()
+
+    say("  short layer: tune is a no-op")
+    w = I.make_workload(1, device=DEV)
+    p = U.Pair(w.spec, w.data, DEV)
+    q = w.schedule.next()
+    before = hc.hc_get_share_weights(p.gpu.ctx.handle)
+    p.gpu.tune(q.to(DEV), rounds=2)
+    assert hc.hc_get_share_weights(p.gpu.ctx.handle) == before
+    p.gpu.step(q.to(DEV))
+    torch.cuda.synchronize()
+    U.check_attention(p.gpu.out, p.gpu.lse, p.ref.step(q.cpu()), "cfg1 after tune")
+    p.close()
+
+
 def test_config4_full_size_in_the_benchmark_launch_configuration():
     """Two full-size layers through hc_decode_step as bench.py launches it (groups of 8, monitor and gather
     batched on a side stream, 7 chunks per monitor workgroup as a batch of 8 layers gets at this size),
