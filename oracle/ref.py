@@ -148,6 +148,13 @@ class RefLayer:
     attend over all of it; a compressed head sees the token through its window of the last `recent`
     positions, and the position that thereby leaves the window becomes an ordinary candidate of the
     pivot's top-k, retrievable like any other.
+
+    window_mode 2 is Algorithm 1's test as printed: the pivot's queries of the window are buffered, and at
+    the step that fills the window every buffered query is scored again against the pivot's cache AS IT IS
+    THEN (Attention(q_k, C_GPU) with the current C_GPU), its top-k taken over the current candidate range
+    and compared with the baseline; the median of those W overlaps decides.  While the cache does not
+    change inside a window this equals window_mode 1 (same query, same cache); with a growing context it
+    does not (tokens appended since step k are in the softmax, and the candidate range has moved).
     """
 
     def __init__(self, spec: LayerSpec, data: LayerData,
@@ -159,6 +166,7 @@ class RefLayer:
         self.retrieved = {k: np.asarray(v, dtype=np.int32).copy() for k, v in retrieved.items()}
         self.base = {k: np.asarray(v, dtype=np.int32).copy() for k, v in base.items()}
         self.ring: Dict[Tuple[int, int], List[int]] = {k: [] for k in self.base}
+        self.qbuf: Dict[Tuple[int, int], List[np.ndarray]] = {k: [] for k in self.base}    # Q_buffer of Algorithm 1
         self.n_tests = 0
         self.n_triggers = 0
 
@@ -206,7 +214,7 @@ class RefLayer:
         res = attn_many(jobs)
         out = np.empty((sp.B, sp.Hq, D), np.float64)
         lse = np.empty((sp.B, sp.Hq), np.float64)
-        rec = {"out": out, "lse": lse, "scores": {}, "topk": {}, "inter": {}, "flag": {}, "logits": {}}
+        rec = {"out": out, "lse": lse, "scores": {}, "topk": {}, "inter": {}, "flag": {}, "logits": {}, "rescored": {}}
         for (b, h), (o, l, lg) in zip(where, res):
             out[b, h * G:(h + 1) * G] = o
             lse[b, h * G:(h + 1) * G] = l
@@ -234,6 +242,21 @@ class RefLayer:
                     ring.pop(0)
                 flag = 0
                 tested = len(ring) == sp.window
+                if sp.window_mode == 2:
+                    qbuf = self.qbuf[(b, p)]
+                    qbuf.append(np.ascontiguousarray(qb[b, p * G:(p + 1) * G]))
+                    if tested:
+                        # every buffered query but the current one (whose overlap was just computed against
+                        # this same cache) is scored again over the pivot's whole current cache
+                        again = []
+                        for j, qk in enumerate(qbuf[:-1]):
+                            _, lse_k, lg_k = attn(qk, self.Kb[(b, p)], self.Vb[(b, p)], None, True)
+                            s_k = scores(lg_k, lse_k, sp.agg)
+                            T_k = topk(s_k.astype(np.float32), lo, hi, kmon)
+                            ring[j] = intersect(T_k, self.base[(b, p)])
+                            again.append((s_k, T_k, ring[j]))
+                        rec["rescored"][(b, p)] = again
+                        qbuf.clear()
                 if tested:
                     self.n_tests += 1
                     flag = trigger(ring, kmon, sp.metric, sp.tau_num, sp.tau_den)
@@ -244,7 +267,7 @@ class RefLayer:
                         self.retrieved[(b, sat)] = rec["topk"][(b, sat)].copy()
                     self.base[(b, p)] = T.copy()
                     ring.clear()
-                elif tested and sp.window_mode == 1:
+                elif tested and sp.window_mode in (1, 2):
                     # Algorithm 1: the buffer of the window is emptied after every test (t mod W = 0),
                     # whether or not it led to a retrieval
                     ring.clear()

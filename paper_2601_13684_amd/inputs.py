@@ -56,7 +56,8 @@ class LayerSpec:
     tau_num: int = 4                   # drift threshold tau = tau_num / tau_den
     tau_den: int = 5
     agg: int = AGG_PROB
-    window_mode: int = 0               # 0: sliding window (Eq. 10), 1: tumbling window (Algorithm 1)
+    window_mode: int = 0               # 0: sliding window (Eq. 10), 1: tumbling window (Algorithm 1), 2: tumbling with the
+                                       # window's buffered queries scored again at the test step (Algorithm 1 as printed)
 
     @property
     def G(self) -> int:
