@@ -47,6 +47,9 @@ def main():
     ap.add_argument("--append", action="store_true", help="every step appends the generated token's K/V first (growing context)")
     ap.add_argument("--full-gather", action="store_true", help="refills fetch whole lists (no slot map: nothing is kept)")
     ap.add_argument("--wg-per-cu", type=int, default=0)
+    ap.add_argument("--window", type=int, default=0, help="W of the drift test (0: the config's, which is 1)")
+    ap.add_argument("--window-mode", type=int, default=-1, help="0 sliding (Eq. 10), 1 tumbling, 2 tumbling with the window's "
+                    "queries scored again at the test step (Algorithm 1); -1: the config's (sliding)")
     ap.add_argument("--tune-rounds", type=int, default=0, help="rounds of on-device measurement of the share weights on the first layer (0: built-in weights, as the parity tests use)")
     ap.add_argument("--share-weights", default="", help="16 comma-separated share weights [die*2+slot] (tuning)")
     ap.add_argument("--group", type=int, default=8, help="layers per cross-stream sync group in step mode")
@@ -92,6 +95,10 @@ def main():
         spec = w.spec
         if args.dense:
             spec = I.spec_dense(spec.ctx[0])
+        if args.window:
+            spec.window = args.window
+        if args.window_mode >= 0:
+            spec.window_mode = args.window_mode
         if ctx is None:
             ctx = R.Context(R.make_config(spec, growth=T_total if args.append else 0), dev, workgroups_per_cu=args.wg_per_cu or None)
             if args.share_weights:

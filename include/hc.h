@@ -55,7 +55,7 @@ typedef enum {
 enum { HC_ROLE_FULL = 0, HC_ROLE_SATELLITE = 1, HC_ROLE_ANCHOR = 2 };
 enum { HC_METRIC_OVERLAP = 0, HC_METRIC_JACCARD = 1 };
 enum { HC_AGG_PROB = 0, HC_AGG_LOGIT = 1 };
-enum { HC_WINDOW_SLIDING = 0, HC_WINDOW_TUMBLING = 1 };
+enum { HC_WINDOW_SLIDING = 0, HC_WINDOW_TUMBLING = 1, HC_WINDOW_RESCORED = 2 };
 enum { HC_MAX_WINDOW = 64, HC_MAX_K_PER_REP = 8, HC_MAX_GROUP = 8 };
 
 typedef struct {
@@ -78,7 +78,11 @@ typedef struct {
                           emptied after every test.  (Algorithm 1 re-scores the W buffered queries at
                           that point; as long as the pivot's cache has not changed in between, that
                           gives the overlaps already computed at those steps, which are what is
-                          stored.)                                                               */
+                          stored.)  HC_WINDOW_RESCORED: the same loop with that re-scoring done:
+                          hc_rescore_window, called before the monitor at every step, buffers the
+                          queries and at the test step replaces the stored overlaps of the window's
+                          earlier queries by those of their top-k over the pivot's cache as it is
+                          then (they differ once the context grows inside a window).             */
 } hc_config;
 
 /* One KV head of one sequence; table of B*Hkv entries, row (b*Hkv + h), HOST memory. */
@@ -277,6 +281,38 @@ hc_status hc_append_kv(hc_ctx* ctx, hc_layer* layer, const void* k_new, const vo
 /* Current context length of sequence b of the layer (grows with hc_append_kv); -1 on a bad argument. */
 int32_t hc_layer_context(const hc_layer* layer, int32_t b);
 
+/* ---- Algorithm 1, the loop over the window's buffered queries at t mod W = 0 (HC_WINDOW_RESCORED) ------
+ * Call once per decode step and layer, after hc_decode_attn and BEFORE hc_rep_topk_drift, on the stream
+ * of the monitor (hc_decode_step does).  The layer counts the steps of the window: slot = monitored
+ * steps since the window was last emptied, 0 when the layer is created (the ring is emptied after every
+ * test, so for a ring that started empty slot = steps so far mod W); every call advances it, and
+ * hc_layer_set_window_slot sets it for a caller that starts from a ring that is not empty.  The call
+ *   - copies the current queries q (dev bf16 [B][Hq][D]) into row `slot` of q_window (dev bf16
+ *     [W][B][Hq][D], 16-byte aligned, the caller's: Q_buffer of Algorithm 1);
+ *   - at slot == W - 1 (the following hc_rep_topk_drift is the one that tests), for every pivot and every
+ *     buffered query k = 0 .. W-2: logits of q_k's group against all of the pivot's K rows as they are now
+ *     (a [G (W-1)] x [ctx] x [D] contraction on the matrix cores), their log-sum-exp over the whole
+ *     context, the aggregated scores, T_{k_mon} over the current candidate range and |T ∩ K_base|, which
+ *     replaces value k of ring[p].  The monitor call then pushes the current step's overlap and decides on
+ *     the median of the W re-computed values.  The ring is only touched if it holds exactly W - 1 values.
+ * work: device buffer of at least hc_rescore_work_bytes(ctx, layer) bytes, 256-byte aligned, the caller's;
+ * contents are scratch (logits, scores and lists of the re-scored queries, laid out as
+ * hc_rescore_work_layout reports: place i holds the last query k with k mod items_per_pass == i, which
+ * is what the tests read).  Uses the context's
+ * selection workspaces like a batched monitor call: stream-order it with other monitor calls.
+ * Enqueue-only, no allocation.  W == 1 or a layer without pivots: only the copy happens. */
+size_t hc_rescore_work_bytes(const hc_ctx* ctx, const hc_layer* layer);
+/* Byte offsets of the passes' results inside `work` and how many queries a pass holds
+ * (min(8, 32 / G)): logits [items][num_reps][max_ctx][G] f32, scores [items][num_reps][max_ctx] f32,
+ * lse [items][B*Hq] f32, lists [items][B*Hkv][max_k] int32.  Any pointer may be NULL. */
+hc_status hc_rescore_work_layout(const hc_ctx* ctx, const hc_layer* layer, int32_t* items_per_pass, size_t* logits_off,
+                                 size_t* scores_off, size_t* lse_off, size_t* topk_off);
+hc_status hc_rescore_window(hc_ctx* ctx, hc_layer* layer, const void* kv_arena, const void* q, void* q_window,
+                            const int32_t* base_idx, int32_t* ring, void* work, size_t work_bytes, void* stream);
+/* The layer's count of steps inside the current window (-1: bad layer), and its setter (0 .. W-1). */
+int32_t hc_layer_window_slot(const hc_layer* layer);
+hc_status hc_layer_set_window_slot(hc_layer* layer, int32_t slot);
+
 /* One decode step over a stack of layers (Algorithm 1, the body of the loop over t, for every layer):
  * for each layer in order, hc_decode_attn on main_stream, then hc_rep_topk_drift and hc_gather_retrieve
  * on side_stream (NULL = on main_stream, no overlap).  Layers are handled in groups of layers_per_group
@@ -308,6 +344,9 @@ typedef struct {
     int32_t* slot_pos;        /* dev [B*Hkv][max_k] in/out, or NULL: see hc_gather_retrieve */
     const void* k_new;        /* dev bf16 [B][Hkv][D]: with v_new, the token to append before attention  */
     const void* v_new;        /*   (hc_append_kv); both NULL: the context does not grow                  */
+    void* q_window;           /* HC_WINDOW_RESCORED: dev bf16 [W][B][Hq][D] and the work buffer of               */
+    void* rescore_work;       /*   hc_rescore_window;                                                            */
+    size_t rescore_work_bytes;/*   ignored in the other window modes                                              */
 } hc_layer_io;
 hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* layers, int32_t n_layers, int32_t layers_per_group,
                          void* main_stream, void* side_stream);

@@ -214,7 +214,7 @@ class RefLayer:
         res = attn_many(jobs)
         out = np.empty((sp.B, sp.Hq, D), np.float64)
         lse = np.empty((sp.B, sp.Hq), np.float64)
-        rec = {"out": out, "lse": lse, "scores": {}, "topk": {}, "inter": {}, "flag": {}, "logits": {}, "rescored": {}}
+        rec = {"out": out, "lse": lse, "scores": {}, "topk": {}, "inter": {}, "flag": {}, "logits": {}, "rescored": {}, "window": {}}
         for (b, h), (o, l, lg) in zip(where, res):
             out[b, h * G:(h + 1) * G] = o
             lse[b, h * G:(h + 1) * G] = l
@@ -259,6 +259,7 @@ class RefLayer:
                         qbuf.clear()
                 if tested:
                     self.n_tests += 1
+                    rec["window"][(b, p)] = list(ring)          # the W overlaps the decision is taken on
                     flag = trigger(ring, kmon, sp.metric, sp.tau_num, sp.tau_den)
                 rec["flag"][(b, p)] = flag
                 if flag:

@@ -20,7 +20,14 @@ HC_MAX_WINDOW, HC_MAX_K_PER_REP, HC_MAX_GROUP = 64, 8, 8
 
 EXPORTS = ["hc_create", "hc_destroy", "hc_strerror", "hc_last_error", "hc_layer_create", "hc_layer_destroy",
            "hc_layer_num_reps", "hc_layer_rep_slot", "hc_layer_num_workgroups", "hc_layer_num_partials",
-           "hc_set_split", "hc_set_share_weights", "hc_get_share_weights", "hc_layer_tune", "hc_set_monitor_span", "hc_set_timing_events", "hc_plan_describe", "hc_decode_attn", "hc_rep_topk_drift", "hc_gather_retrieve", "hc_append_kv", "hc_layer_context", "hc_decode_step", "hc_taxonomy", "hc_budgets"]
+           "hc_set_split", "hc_set_share_weights", "hc_get_share_weights", "hc_layer_tune", "hc_set_monitor_span",
+           "hc_set_timing_events", "hc_plan_describe", "hc_decode_attn", "hc_rep_topk_drift", "hc_gather_retrieve",
+           "hc_append_kv", "hc_rescore_work_bytes", "hc_rescore_work_layout", "hc_rescore_window", "hc_layer_window_slot",
+           "hc_layer_set_window_slot", "hc_layer_context",
+           "hc_decode_step", "hc_taxonomy", "hc_budgets"]
+
+
+HC_WINDOW_SLIDING, HC_WINDOW_TUMBLING, HC_WINDOW_RESCORED = 0, 1, 2
 
 
 class hc_config(C.Structure):
@@ -42,7 +49,8 @@ class hc_plan_info(C.Structure):
 
 class hc_layer_io(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("layer", "kv_arena", "host_tier", "q", "out", "lse", "rep_logits", "scores",
-                                          "topk_idx", "base_idx", "ring", "inter", "flag", "slot_pos", "k_new", "v_new")]
+                                          "topk_idx", "base_idx", "ring", "inter", "flag", "slot_pos", "k_new", "v_new",
+                                          "q_window", "rescore_work")] + [("rescore_work_bytes", C.c_size_t)]
 
 
 class HcError(RuntimeError):
@@ -80,6 +88,13 @@ def lib():
         L.hc_set_share_weights.argtypes = [vp, C.POINTER(C.c_float)]
         L.hc_set_monitor_span.argtypes = [vp, i32]
         L.hc_get_share_weights.argtypes = [vp, C.POINTER(C.c_float)]
+        L.hc_rescore_work_bytes.argtypes = [vp, vp]
+        L.hc_rescore_work_bytes.restype = C.c_size_t
+        L.hc_rescore_work_layout.argtypes = [vp, vp, C.POINTER(i32)] + [C.POINTER(C.c_size_t)] * 4
+        L.hc_rescore_window.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.hc_layer_window_slot.argtypes = [vp]
+        L.hc_layer_window_slot.restype = i32
+        L.hc_layer_set_window_slot.argtypes = [vp, i32]
         L.hc_layer_tune.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp]
         L.hc_set_timing_events.argtypes = [vp, vp, vp, i32]
         L.hc_plan_describe.argtypes = [C.POINTER(hc_config), C.POINTER(hc_head_desc), i32, i32,
@@ -95,7 +110,8 @@ def lib():
         L.hc_decode_step.argtypes = [vp, C.POINTER(hc_layer_io), i32, i32, vp, vp]
         for n in EXPORTS:
             if n not in ("hc_strerror", "hc_last_error", "hc_layer_num_reps", "hc_layer_rep_slot",
-                         "hc_layer_num_workgroups", "hc_layer_num_partials"):
+                         "hc_layer_num_workgroups", "hc_layer_num_partials", "hc_rescore_work_bytes",
+                         "hc_layer_window_slot"):
                 getattr(L, n).restype = C.c_int
         _lib = L
     return _lib
@@ -256,6 +272,32 @@ def hc_gather_retrieve(ctx: int, layer: int, host_tier: Ptr, topk_idx: Ptr, flag
 def hc_append_kv(ctx: int, layer: int, k_new: Ptr, v_new: Ptr, kv_arena: Ptr, host_tier: Ptr = None, stream=None) -> None:
     _check(lib().hc_append_kv(ctx, layer, _p(k_new), _p(v_new), _p(kv_arena), _p(host_tier), _stream(stream)),
            "hc_append_kv", ctx)
+
+
+def hc_rescore_work_bytes(ctx: int, layer: int) -> int:
+    return int(lib().hc_rescore_work_bytes(ctx, layer))
+
+
+def hc_rescore_work_layout(ctx: int, layer: int) -> dict:
+    """Where the first pass's results lie inside the work buffer (byte offsets) and how many queries a pass holds."""
+    n = C.c_int32(0)
+    off = [C.c_size_t(0) for _ in range(4)]
+    _check(lib().hc_rescore_work_layout(ctx, layer, C.byref(n), *[C.byref(o) for o in off]), "hc_rescore_work_layout", ctx)
+    return dict(items_per_pass=n.value, logits=off[0].value, scores=off[1].value, lse=off[2].value, topk=off[3].value)
+
+
+def hc_rescore_window(ctx: int, layer: int, kv_arena: Ptr, q: Ptr, q_window: Ptr, base_idx: Ptr, ring: Ptr,
+                      work: Ptr, work_bytes: int, stream=None) -> None:
+    _check(lib().hc_rescore_window(ctx, layer, _p(kv_arena), _p(q), _p(q_window), _p(base_idx), _p(ring), _p(work),
+                                   work_bytes, _stream(stream)), "hc_rescore_window", ctx)
+
+
+def hc_layer_window_slot(layer: int) -> int:
+    return lib().hc_layer_window_slot(layer)
+
+
+def hc_layer_set_window_slot(layer: int, slot: int) -> None:
+    _check(lib().hc_layer_set_window_slot(layer, slot), "hc_layer_set_window_slot")
 
 
 def hc_layer_context(layer: int, b: int) -> int:

@@ -77,7 +77,7 @@ static hc_status check_config(const hc_config* cfg)
     if (cfg->window < 1 || cfg->window > HC_MAX_WINDOW) return HC_EINVAL;
     if (cfg->metric != HC_METRIC_OVERLAP && cfg->metric != HC_METRIC_JACCARD) return HC_EINVAL;
     if (cfg->agg != HC_AGG_PROB && cfg->agg != HC_AGG_LOGIT) return HC_EINVAL;
-    if (cfg->window_mode != HC_WINDOW_SLIDING && cfg->window_mode != HC_WINDOW_TUMBLING) return HC_EINVAL;
+    if (cfg->window_mode < HC_WINDOW_SLIDING || cfg->window_mode > HC_WINDOW_RESCORED) return HC_EINVAL;
     if (cfg->tau_den < 1 || cfg->tau_num < 0) return HC_EINVAL;
     if ((int64_t)cfg->B * cfg->Hkv > (1 << 20)) return HC_ESHAPE;
     return HC_OK;
@@ -835,6 +835,125 @@ extern "C" hc_status hc_layer_tune(hc_ctx* ctx, hc_layer* layer, const void* kv_
     return result;
 }
 
+// ---- re-scoring of the window's buffered queries (Algorithm 1, t mod W = 0) ----
+extern "C" size_t hc_rescore_work_bytes(const hc_ctx* ctx, const hc_layer* layer)
+{
+    if (!ctx_ok(ctx) || !layer_ok(layer) || layer->ctx != ctx) return 0;
+    return hc_rescore_plan(ctx, layer).bytes;
+}
+
+extern "C" hc_status hc_rescore_work_layout(const hc_ctx* ctx, const hc_layer* layer, int32_t* items_per_pass, size_t* logits_off,
+                                            size_t* scores_off, size_t* lse_off, size_t* topk_off)
+{
+    if (!ctx_ok(ctx) || !layer_ok(layer) || layer->ctx != ctx) return HC_ESTATE;
+    const hc_rescore_layout lay = hc_rescore_plan(ctx, layer);
+    if (items_per_pass) *items_per_pass = hc_rescore_items_per_pass(ctx);
+    if (logits_off) *logits_off = lay.logits_off;
+    if (scores_off) *scores_off = lay.scores_off;
+    if (lse_off) *lse_off = lay.lse_off;
+    if (topk_off) *topk_off = lay.topk_off;
+    return HC_OK;
+}
+
+static hc_status rescore_check(hc_ctx* ctx, const hc_layer* layer, const void* kv_arena, const void* q, const void* q_window,
+                               const int32_t* base_idx, const int32_t* ring, const void* work, size_t work_bytes)
+{
+    if (!layer_ok(layer) || layer->ctx != ctx) return hc_fail(ctx, HC_ESTATE, "hc_rescore_window: layer does not belong to this context");
+    if (ctx->cfg.window_mode != HC_WINDOW_RESCORED) return hc_fail(ctx, HC_ESTATE, "hc_rescore_window: the context's window_mode is not HC_WINDOW_RESCORED");
+    if (!kv_arena || !q || !q_window || !base_idx || !ring || !work) return hc_fail(ctx, HC_EINVAL, "hc_rescore_window: null pointer");
+    if (((uintptr_t)q | (uintptr_t)q_window) & 15) return hc_fail(ctx, HC_EINVAL, "hc_rescore_window: q and q_window must be 16-byte aligned");
+    if ((uintptr_t)work & 255) return hc_fail(ctx, HC_EINVAL, "hc_rescore_window: work must be 256-byte aligned");
+    if (work_bytes < hc_rescore_plan(ctx, layer).bytes)
+        return hc_fail(ctx, HC_EINVAL, "hc_rescore_window: work buffer of %zu bytes, %zu needed", work_bytes, hc_rescore_plan(ctx, layer).bytes);
+    return HC_OK;
+}
+
+// The passes of a test step for one or more layers (the layers of a hc_decode_step group reach the end of
+// their windows together): logits and lse of up to items_per_pass buffered queries of every layer, then
+// the selection passes over all (layer, query) pairs, HC_MAX_GROUP pairs to a batched call, whose last
+// kernel stores each pair's overlap into its layer's ring.
+struct RescoreJob {
+    const hc_layer* L;
+    const void* kv_arena;
+    const void* q_window;
+    const int32_t* base_idx;
+    int32_t* ring;
+    void* work;
+};
+static hc_status rescore_passes(hc_ctx* ctx, int n_jobs, const RescoreJob* jobs, hipStream_t st)
+{
+    const int W = ctx->cfg.window;
+    if (W < 2) return HC_OK;
+    const int per = hc_rescore_items_per_pass(ctx);
+    for (int first = 0; first < W - 1; first += per) {
+        const int n = std::min(per, W - 1 - first);
+        for (int j = 0; j < n_jobs; ++j) {
+            if (jobs[j].L->n_reps == 0) continue;
+            const hc_status s = hc_launch_rescore_logits(ctx, jobs[j].L, jobs[j].kv_arena, jobs[j].q_window, first, n, jobs[j].work, st);
+            if (s != HC_OK) return s;
+        }
+        hc_monitor_call calls[HC_MAX_GROUP];
+        int n_calls = 0;
+        for (int j = 0; j < n_jobs; ++j) {
+            const hc_layer* L = jobs[j].L;
+            if (L->n_reps == 0) continue;
+            const hc_rescore_layout lay = hc_rescore_plan(ctx, L);
+            char* wb = (char*)jobs[j].work;
+            int32_t* scratch = (int32_t*)(wb + lay.scratch_off);
+            for (int i = 0; i < n; ++i) {
+                calls[n_calls++] = hc_monitor_call{L,
+                                                   (const float*)(wb + lay.logits_off) + (size_t)i * lay.logits_item,
+                                                   (const float*)(wb + lay.lse_off) + (size_t)i * lay.lse_item,
+                                                   (float*)(wb + lay.scores_off) + (size_t)i * lay.scores_item,
+                                                   (int32_t*)(wb + lay.topk_off) + (size_t)i * lay.topk_item,
+                                                   const_cast<int32_t*>(jobs[j].base_idx),
+                                                   jobs[j].ring,
+                                                   scratch,
+                                                   scratch + (size_t)ctx->cfg.B * ctx->cfg.Hkv,
+                                                   first + i};
+                if (n_calls == HC_MAX_GROUP || (j == n_jobs - 1 && i == n - 1)) {
+                    const hc_status s = hc_launch_monitor(ctx, n_calls, calls, 0, st);
+                    if (s != HC_OK) return s;
+                    n_calls = 0;
+                }
+            }
+        }
+        if (n_calls > 0) {
+            const hc_status s = hc_launch_monitor(ctx, n_calls, calls, 0, st);
+            if (s != HC_OK) return s;
+        }
+    }
+    return HC_OK;
+}
+
+extern "C" int32_t hc_layer_window_slot(const hc_layer* layer) { return layer_ok(layer) ? layer->window_slot : -1; }
+
+extern "C" hc_status hc_layer_set_window_slot(hc_layer* layer, int32_t slot)
+{
+    if (!layer_ok(layer)) return HC_ESTATE;
+    if (slot < 0 || slot >= layer->ctx->cfg.window) return hc_fail(layer->ctx, HC_EINVAL, "hc_layer_set_window_slot: slot %d outside 0..W-1", (int)slot);
+    layer->window_slot = slot;
+    return HC_OK;
+}
+
+extern "C" hc_status hc_rescore_window(hc_ctx* ctx, hc_layer* layer, const void* kv_arena, const void* q, void* q_window,
+                                       const int32_t* base_idx, int32_t* ring, void* work, size_t work_bytes, void* stream)
+{
+    if (!ctx_ok(ctx)) return HC_ESTATE;
+    hc_status s = rescore_check(ctx, layer, kv_arena, q, q_window, base_idx, ring, work, work_bytes);
+    if (s != HC_OK) return s;
+    const int slot = layer->window_slot;
+    layer->window_slot = (slot + 1) % ctx->cfg.window;
+    hipStream_t st = (hipStream_t)stream;
+    const size_t q_bytes = (size_t)ctx->cfg.B * ctx->cfg.Hq * HC_D * 2;
+    const void* src = q;
+    void* dst = (char*)q_window + (size_t)slot * q_bytes;
+    s = hc_launch_rescore_push(ctx, 1, &src, &dst, st);
+    if (s != HC_OK || slot != ctx->cfg.window - 1) return s;
+    const RescoreJob job{layer, kv_arena, q_window, base_idx, ring, work};
+    return rescore_passes(ctx, 1, &job, st);
+}
+
 // One decode step over a stack of layers, launched from native code so that the host keeps ahead of the
 // GPU.  Layers are taken in groups: the attention of a group's layers on the main stream; then, on the
 // side stream, ONE batched monitor and ONE batched gather for the whole group (seven launches per group
@@ -860,6 +979,11 @@ extern "C" hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* io, int32_t 
         hc_monitor_call mon[HC_MAX_GROUP];
         hc_gather_call gat[HC_MAX_GROUP];
         int n_mon = 0, n_gat = 0;
+        const bool rescored = ctx->cfg.window_mode == HC_WINDOW_RESCORED;
+        const void* push_src[HC_MAX_GROUP];
+        void* push_dst[HC_MAX_GROUP];
+        RescoreJob test_job[HC_MAX_GROUP];
+        int n_push = 0, n_test = 0;
         for (int l = g0; l < g1; ++l) {
             const hc_layer_io& x = io[l];
             hc_layer* L = x.layer;
@@ -873,6 +997,15 @@ extern "C" hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* io, int32_t 
                 hc_status st = monitor_check(ctx, L, x.rep_logits, x.lse, x.scores, 0, x.topk_idx, x.base_idx, x.ring, x.inter, x.flag);
                 if (st != HC_OK) return st;
                 mon[n_mon++] = hc_monitor_call{L, x.rep_logits, x.lse, x.scores, x.topk_idx, x.base_idx, x.ring, x.inter, x.flag};
+                if (rescored) {
+                    st = rescore_check(ctx, L, x.kv_arena, x.q, x.q_window, x.base_idx, x.ring, x.rescore_work, x.rescore_work_bytes);
+                    if (st != HC_OK) return st;
+                    push_src[n_push] = x.q;
+                    push_dst[n_push++] = (char*)x.q_window + (size_t)L->window_slot * ctx->cfg.B * ctx->cfg.Hq * HC_D * 2;
+                    if (L->window_slot == ctx->cfg.window - 1)
+                        test_job[n_test++] = RescoreJob{L, x.kv_arena, x.q_window, x.base_idx, x.ring, x.rescore_work};
+                    L->window_slot = (L->window_slot + 1) % ctx->cfg.window;
+                }
                 if (x.host_tier && L->n_sats > 0) {
                     st = gather_check(ctx, L, x.host_tier, x.topk_idx, x.flag, x.kv_arena);
                     if (st != HC_OK) return st;
@@ -888,13 +1021,21 @@ extern "C" hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* io, int32_t 
             if (st != HC_OK) return st;
         }
         if (n_mon == 0) continue;
+        // The queries go into the window buffers on the main stream: the caller may overwrite q as soon
+        // as this call returns, in main-stream order, while the side stream may still be behind.
+        if (n_push > 0) {
+            const hc_status sp = hc_launch_rescore_push(ctx, n_push, push_src, push_dst, ms);
+            if (sp != HC_OK) return sp;
+        }
         hc_layer* Lg = io[g1 - 1].layer;          // the group's events live in its last layer
         hipStream_t run = ss ? ss : ms;
         if (ss) {
             HC_HIP(ctx, hipEventRecord(Lg->ev_attn, ms));
             HC_HIP(ctx, hipStreamWaitEvent(ss, Lg->ev_attn, 0));
         }
-        hc_status st = hc_launch_monitor(ctx, n_mon, mon, 0, run);
+        hc_status st = HC_OK;
+        if (n_test > 0) st = rescore_passes(ctx, n_test, test_job, run);       // test step of a re-scored window: the earlier queries first
+        if (st == HC_OK) st = hc_launch_monitor(ctx, n_mon, mon, 0, run);
         if (st == HC_OK && n_gat > 0) st = hc_launch_gather(ctx, n_gat, gat, run);
         if (ss) {
             // recorded even after a failed launch, so that no later call waits on a stale event

@@ -117,6 +117,7 @@ struct hc_layer {
     std::vector<int32_t> ctx0_host;     // [B*Hkv] context lengths at creation
     std::vector<int32_t> rep_lo_host, rep_recent_host;   // per pivot: first candidate, recent slots of its satellites
     int appended_since_plan = 0;
+    int window_slot = 0;                // hc_decode_step with a re-scored window: monitored steps since the window was emptied
     int seg_capacity = 0;               // device room in segs (a rebalanced plan may have a few more segments)
     HeadDev* heads = nullptr;
     SegDev* segs = nullptr;
@@ -149,6 +150,8 @@ struct hc_monitor_call {
     const float* lse;
     float* scores;
     int32_t *topk_idx, *base_idx, *ring, *inter, *flag;
+    int store_slot = -1;   // >= 0: a re-scored query of the window: only its overlap is kept, as value store_slot of the
+                           // ring (if the ring is one short of full), and baseline, inter, flag are left alone
 };
 struct hc_gather_call {
     const hc_layer* L;
@@ -163,5 +166,16 @@ hc_status hc_launch_attn(hc_ctx* ctx, const hc_layer* L, const void* arena, cons
 hc_status hc_launch_monitor(hc_ctx* ctx, int n, const hc_monitor_call* calls, int scores_given, hipStream_t st);
 hc_status hc_launch_gather(hc_ctx* ctx, int n, const hc_gather_call* calls, hipStream_t st);
 hc_status hc_gather_set_lds_limit();     // once per process, at context creation
+// Work buffer of the window re-scoring pass (offsets in bytes, item sizes in elements).
+constexpr int HC_RESCORE_MAX_BLOCKS = 512;
+struct hc_rescore_layout {
+    size_t logits_off, scores_off, lse_off, topk_off, part_off, scratch_off, bytes;
+    size_t logits_item, scores_item, lse_item, topk_item;
+};
+int hc_rescore_items_per_pass(const hc_ctx* ctx);
+hc_rescore_layout hc_rescore_plan(const hc_ctx* ctx, const hc_layer* L);
+hc_status hc_launch_rescore_push(hc_ctx* ctx, int n, const void* const* q, void* const* dst, hipStream_t st);
+hc_status hc_launch_rescore_logits(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* q_window, int first,
+                                   int n_items, void* work, hipStream_t st);
 hc_status hc_launch_append(hc_ctx* ctx, const hc_layer* L, const void* k_new, const void* v_new, void* arena, void* tier,
                            hipStream_t st);

@@ -88,6 +88,7 @@ struct MonItem {
     int32_t* inter;
     int32_t* flag;
     int n_reps, n_outs;
+    int store_slot;
 };
 struct MonBatch {
     MonItem it[HC_MAX_GROUP];
@@ -550,6 +551,17 @@ __global__ __launch_bounds__(BLK) void mon_decide(MonBatch B, DriftCfg cfg)
         __syncthreads();
     }
     const int32_t inter = (int32_t)(sm_hits[0] + sm_hits[1] + sm_hits[2] + sm_hits[3]);
+    if (it.store_slot >= 0) {
+        // A buffered query of the window scored again at the test step (Algorithm 1): its overlap replaces the
+        // one stored when the query was current.  Only while the ring is one short of full, i.e. the
+        // monitor call that follows is the one that tests.
+        if (threadIdx.x == 0 && n == cfg.window - 1 && it.store_slot < n) rg[1 + it.store_slot] = inter;
+        const RepWs w = ws.rep(blockIdx.x);
+        uint4* h4 = reinterpret_cast<uint4*>(w.h1);
+        for (int i = threadIdx.x; i < (1 + 2 * HC_MAX_K_PER_REP) * HC_RADIX_BINS / 4; i += BLK) h4[i] = make_uint4(0u, 0u, 0u, 0u);
+        for (int i = threadIdx.x; i < (rd.hi + 31) / 32; i += BLK) w.bitmap[i] = 0u;
+        return;
+    }
     const int m = n - drop + 1;                      // values in the window after the push
     if ((int)threadIdx.x < m) sm_ring[threadIdx.x] = (int)threadIdx.x == m - 1 ? inter : rg[1 + drop + threadIdx.x];
     __syncthreads();
@@ -615,6 +627,7 @@ hc_status hc_launch_monitor(hc_ctx* ctx, int n, const hc_monitor_call* calls, in
         it.flag = x.flag;
         it.n_reps = x.L->n_reps;
         it.n_outs = x.L->n_outs;
+        it.store_slot = x.store_slot;
         max_reps = std::max(max_reps, x.L->n_reps);
         max_nchunk = std::max(max_nchunk, x.L->max_nchunk);
         max_nk = std::max(max_nk, x.L->max_nk);
@@ -644,7 +657,7 @@ hc_status hc_launch_monitor(hc_ctx* ctx, int n, const hc_monitor_call* calls, in
     HC_HIP(ctx, hipGetLastError());
     mon_count<<<gk, dim3(BLK), 0, st>>>(B, span);
     HC_HIP(ctx, hipGetLastError());
-    DriftCfg dc{c.window, c.metric, c.tau_num, c.tau_den, c.max_k, c.window_mode == HC_WINDOW_TUMBLING};
+    DriftCfg dc{c.window, c.metric, c.tau_num, c.tau_den, c.max_k, c.window_mode != HC_WINDOW_SLIDING};
     // the write pass has no per-workgroup set-up to amortise: one chunk per wave
     const int span_w = NWAVE;
     mon_write<<<dim3((max_nchunk + 1 + span_w - 1) / span_w, max_reps, n), dim3(BLK), 0, st>>>(B, dc, span_w);

@@ -146,6 +146,11 @@ class LayerRuntime:
             self.scores = torch.zeros((n, cfg.max_ctx), dtype=torch.float32, device=dev)
         else:
             self.rep_logits, self.scores = ctx.scratch(self.n_reps)
+        # Algorithm 1's re-scored window: the buffer of the window's queries and the pass's work buffer
+        self.q_window = self.rescore_work = None
+        if cfg.window_mode == hc.HC_WINDOW_RESCORED:
+            self.q_window = torch.zeros((cfg.window, B, spec.Hq, D), dtype=torch.bfloat16, device=dev)
+            self.rescore_work = torch.zeros((hc.hc_rescore_work_bytes(ctx.handle, self.handle),), dtype=torch.uint8, device=dev)
         # torch creates the HIP event lazily at the first record: do it now, the C ABI needs the handle
         self.ev_topk = torch.cuda.Event()
         self.ev_done = torch.cuda.Event()
@@ -165,6 +170,27 @@ class LayerRuntime:
     def monitor(self, scores_given: bool = False, stream=None) -> None:
         hc.hc_rep_topk_drift(self.ctx.handle, self.handle, self.rep_logits, self.lse, self.scores, scores_given,
                              self.topk_idx, self.base_idx, self.ring, self.inter, self.flag, stream)
+
+    def rescore(self, q: torch.Tensor, stream=None) -> None:
+        """Buffer this step's queries; at the window's last step score the earlier ones again (hc_rescore_window).
+        Call between attn and monitor, once per monitored step: the layer counts the steps of the window."""
+        hc.hc_rescore_window(self.ctx.handle, self.handle, self.arena, q, self.q_window, self.base_idx,
+                             self.ring, self.rescore_work, self.rescore_work.numel(), stream)
+
+    def rescored(self, item: int) -> dict:
+        """Views of what the last test step's first pass left in the work buffer for buffered query `item`."""
+        lay = hc.hc_rescore_work_layout(self.ctx.handle, self.handle)
+        cfg, n, w = self.ctx.cfg, max(1, self.n_reps), self.rescore_work
+        assert 0 <= item < lay["items_per_pass"]
+
+        def view(off, count, dtype, shape):
+            size = count * 4
+            return w[off + item * size:off + (item + 1) * size].view(dtype).view(shape)
+        nr = self.n_reps
+        return dict(logits=view(lay["logits"], nr * cfg.max_ctx * self.ctx.G, torch.float32, (nr, cfg.max_ctx, self.ctx.G)),
+                    scores=view(lay["scores"], nr * cfg.max_ctx, torch.float32, (nr, cfg.max_ctx)),
+                    lse=view(lay["lse"], cfg.B * cfg.Hq, torch.float32, (cfg.B, cfg.Hq)),
+                    topk=view(lay["topk"], cfg.B * cfg.Hkv * cfg.max_k, torch.int32, (cfg.B * cfg.Hkv, cfg.max_k)))
 
     def tune(self, q: torch.Tensor, rounds: int = 4) -> None:
         """Measure the split pass's share weights on this device with this layer (hc_layer_tune)."""
@@ -196,12 +222,16 @@ class LayerRuntime:
         if not self.n_reps:
             return
         if side is None:
+            if self.q_window is not None:
+                self.rescore(q)
             self.monitor()
             if self.tier is not None:
                 self.gather()
             return
         self.ev_topk.record(main)                   # attention of this layer is enqueued
         side.wait_event(self.ev_topk)
+        if self.q_window is not None:
+            self.rescore(q, stream=side)            # q must stay untouched until the side stream is through (ev_done)
         self.monitor(stream=side)
         if self.tier is not None:
             self.gather(stream=side, done_event=self.ev_done)
@@ -227,5 +257,8 @@ def make_step_io(layers: List[LayerRuntime], q_per_layer: torch.Tensor, monitor:
                                 scores=lay.scores.data_ptr() if monitor else None,
                                 topk_idx=lay.topk_idx.data_ptr(), base_idx=lay.base_idx.data_ptr(),
                                 ring=lay.ring.data_ptr(), inter=lay.inter.data_ptr(), flag=lay.flag.data_ptr(),
-                                slot_pos=lay.slot_pos.data_ptr() if lay.slot_pos is not None else None)
+                                slot_pos=lay.slot_pos.data_ptr() if lay.slot_pos is not None else None,
+                                q_window=lay.q_window.data_ptr() if lay.q_window is not None else None,
+                                rescore_work=lay.rescore_work.data_ptr() if lay.rescore_work is not None else None,
+                                rescore_work_bytes=lay.rescore_work.numel() if lay.rescore_work is not None else 0)
     return arr

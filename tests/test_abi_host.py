@@ -50,7 +50,7 @@ def cfg_for(spec, **kw):
     ("D", 64, hc.HC_ESHAPE), ("Hq", 7, hc.HC_EINVAL), ("Hq", 32, hc.HC_ESHAPE),   # G = 16
     ("max_ctx", 100, hc.HC_ESHAPE), ("window", 0, hc.HC_EINVAL), ("window", 65, hc.HC_EINVAL),
     ("metric", 2, hc.HC_EINVAL), ("tau_den", 0, hc.HC_EINVAL), ("agg", 3, hc.HC_EINVAL), ("max_k", 0, hc.HC_EINVAL),
-    ("window_mode", 2, hc.HC_EINVAL),
+    ("window_mode", 3, hc.HC_EINVAL),
 ])
 def test_bad_config_is_rejected_before_any_gpu_call(field, value, status):
     spec = I.spec_tiny(1024, budget=160, sink=16, recent=32)
@@ -70,6 +70,9 @@ def test_null_arguments():
     assert hc.lib().hc_decode_attn(None, None, None, None, None, None, None, None) == hc.HC_ESTATE
     assert hc.lib().hc_rep_topk_drift(None, None, None, None, None, 0, None, None, None, None, None, None) == hc.HC_ESTATE
     assert hc.lib().hc_gather_retrieve(None, None, None, None, None, None, None, None, None, None) == hc.HC_ESTATE
+    assert hc.lib().hc_rescore_window(None, None, None, None, None, None, None, None, 0, None) == hc.HC_ESTATE
+    assert hc.lib().hc_rescore_work_bytes(None, None) == 0
+    assert hc.lib().hc_layer_window_slot(None) == -1 and hc.lib().hc_layer_set_window_slot(None, 0) == hc.HC_ESTATE
     assert hc.lib().hc_layer_num_reps(None) == -1
 
 

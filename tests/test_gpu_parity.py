@@ -544,6 +544,8 @@ def run_steps(p, sched, steps, side=None, rel_band=1e-4, tag="", stepper=None, a
                 T = rec["topk"][(b, h)]
                 if U.check_set_valid(topk[b * sp.Hkv + h, :T.size], T, s_ref, rel_band, f"{tag} step {t} head {h}"):
                     same = False
+            if (b, pv) in rec["rescored"] and not check_rescored(p, rec, b, pv, rel_band, f"{tag} step {t}"):
+                same = False
             gi, gf = int(p.gpu.inter[b * sp.Hkv + pv]), int(p.gpu.flag[b * sp.Hkv + pv])
             if gi != rec["inter"][(b, pv)] or gf != rec["flag"][(b, pv)]:
                 assert not same, (tag, t, "same sets but different inter/flag", gi, rec["inter"][(b, pv)], gf)
@@ -555,6 +557,31 @@ def run_steps(p, sched, steps, side=None, rel_band=1e-4, tag="", stepper=None, a
         assert p.slots_equal_oracle(), f"{tag}: slots differ after step {t}"
         say(f"  {tag} step {t}: err/rms {worst:.2e} lse {lerr:.1e} flags {list(rec['flag'].values())} inter {list(rec['inter'].values())}")
     return resyncs, triggers
+
+
+def check_rescored(p, rec, b, pv, rel_band, tag):
+    """Test step of a re-scored window: what the pass left for every buffered query that is still in its work
+    buffer (scores, lse, list) and the W overlaps in the ring, against the oracle's.  False: a near-tie
+    went the other way in some list (then the overlaps may differ too)."""
+    sp, g = p.spec, p.gpu
+    again = rec["rescored"][(b, pv)]
+    per = hc.hc_rescore_work_layout(p.ctx.handle, g.handle)["items_per_pass"]
+    lo, hi = p.ref.cand_range(b, pv)
+    slot = g.rep_slot(b, pv)
+    row = b * sp.Hkv + pv
+    same = True
+    for k, (s_k, T_k, inter_k) in enumerate(again):
+        if k + per < len(again):
+            continue                                  # a later pass reused this item's place in the buffer
+        got = g.rescored(k % per)
+        U.check_scores(got["scores"][slot].cpu().numpy(), s_k, lo, hi, f"{tag} re-scored query {k}")
+        if U.check_set_valid(got["topk"][row, :T_k.size].cpu().numpy(), T_k, s_k, rel_band, f"{tag} re-scored query {k}"):
+            same = False
+    ring = g.ring[row].cpu().numpy()
+    want = rec["window"][(b, pv)]
+    if ring[1:len(want)].tolist() != want[:-1]:           # the last value is the current step's: checked with inter
+        assert not same, (tag, "same lists but different overlaps", ring.tolist(), want)
+    return same
 
 
 def resync(p, rec):
@@ -922,4 +949,172 @@ def test_decode_step_stack_of_layers_matches_oracle(n_layers, n_side, group):
     assert triggers >= 2 * n_layers
     for gpu, _, _ in pairs:
         gpu.close()
+    ctx.close()
+
+
+# ------------------------------------------------------------------------------------------
+# Algorithm 1's window with the buffered queries scored again at the test step
+# ------------------------------------------------------------------------------------------
+def test_rescored_window_hand_worked_growing_cache():
+    """The oracle's hand-worked case on the GPU: k = 2, W = 3, one recent slot, mean-of-logits scores, a
+    dominant token appended before every step.  Overlaps as first computed 2, 1, 0 (median 1: not below
+    tau = 1/2); scored again at step 3 they are 0, 0, 0: only the re-scored window fires."""
+    say("re-scored window, hand-worked")
+    N = 400
+    for mode in (1, 2):
+        heads = [I.HeadSpec(I.ROLE_FULL), I.HeadSpec(I.ROLE_SATELLITE, rep=0, sink=4, recent=1, budget=4 + 1 + 2)]
+        spec = I.LayerSpec(B=1, Hq=8, Hkv=2, D=128, ctx=[N], heads=[heads], tau_num=1, tau_den=2, metric=I.METRIC_OVERLAP,
+                           agg=I.AGG_LOGIT)
+        spec.window, spec.window_mode = 3, mode
+        q0 = I.draw_q(spec, 21)
+        data = I.draw_layer(spec, q0, 22)
+        q = q0.to(torch.bfloat16)
+        p = U.Pair(spec, data, DEV, growth=8)
+        best2 = ref.RefLayer(spec, data, *I.initial_lists(spec)).step(q)["topk"][(0, 0)]
+        p.ref.base[(0, 0)] = best2.copy()
+        p.gpu.base_idx[0, :2] = torch.from_numpy(best2).to(DEV)
+        inters, flags = [], []
+        for t in range(3):
+            kn, vn = I.draw_token(spec, 30 + t, toward=q, gain=20.0 + 5 * t)
+            p.gpu.append(kn.to(DEV), vn.to(DEV))
+            p.ref.append(kn, vn)
+            p.gpu.step(q.to(DEV))
+            torch.cuda.synchronize()
+            rec = p.ref.step(q)
+            inters.append(int(p.gpu.inter[0]))
+            flags.append(int(p.gpu.flag[0]))
+            assert inters[-1] == rec["inter"][(0, 0)] and flags[-1] == rec["flag"][(0, 0)]
+        assert inters == [2, 1, 0]
+        assert flags == ([0, 0, 1] if mode == 2 else [0, 0, 0])
+        ring = p.gpu.ring[0].cpu().tolist()
+        assert ring[0] == 0 and ring[1:4] == ([0, 0, 0] if mode == 2 else [2, 1, 0])
+        if mode == 2:
+            assert p.gpu.base_idx[0, :2].cpu().tolist() == [N, N + 1]
+            assert p.slots_equal_oracle()
+        p.close()
+
+
+@pytest.mark.parametrize("use_side", [False, True])
+def test_rescored_window_growing_context_multi_step(use_side):
+    """W = 4 over 24 steps with a token appended before every step, every third one planted heavy: at the six
+    test steps the three buffered queries' scores, lse, lists and overlaps against the oracle's, and the
+    decisions taken on them."""
+    say("re-scored window, growing context, 24 steps", "side stream" if use_side else "one stream")
+    spec = I.spec_tiny(4096, budget=512, sink=16, recent=8)
+    spec.window, spec.window_mode = 4, 2
+    q0 = I.draw_q(spec, 91)
+    data = I.draw_layer(spec, q0, 92, heavy_count=40)
+    sched = I.QuerySchedule(q0, 93, step_deg=4.0)
+    p = U.Pair(spec, data, DEV, growth=32)
+    side = torch.cuda.Stream() if use_side else None
+    recs, oracle_step = [], p.ref.step
+    p.ref.step = lambda q, **kw: recs.append(oracle_step(q, **kw)) or recs[-1]
+    resyncs, triggers = run_steps(p, sched, 24, side=side, tag="rescored", append_seed=9100,
+                                  token_gain=lambda t: 30.0 if t % 3 == 0 else 0.0)
+    say("  resyncs", resyncs, "triggers", triggers)
+    assert p.ref.n_tests == 6 and triggers >= 1 and resyncs <= 2
+    # the case is worth its name only if scoring again changes some overlap
+    changed = 0
+    for t in range(3, 24, 4):
+        first = [recs[u]["inter"][(0, 0)] for u in range(t - 3, t)]
+        again = recs[t]["window"][(0, 0)][:3]
+        say(f"  test at step {t}: overlaps as first computed {first}, scored again {again}")
+        changed += first != again
+    assert changed >= 2
+    p.close()
+
+
+@pytest.mark.parametrize("G,W", [(1, 3), (2, 5), (8, 6), (4, 12)])
+def test_rescored_window_group_sizes_and_several_passes(G, W):
+    """Group sizes 1, 2, 8 (32 / G queries per pass, at most 8) and a window whose earlier queries need two
+    passes (W - 1 = 11 > 8)."""
+    say(f"re-scored window, G {G} W {W}")
+    N = 3000 + 17 * G
+    heads = [I.HeadSpec(I.ROLE_FULL), I.HeadSpec(I.ROLE_SATELLITE, rep=0, sink=8, recent=4, budget=8 + 4 + 96),
+             I.HeadSpec(I.ROLE_FULL), I.HeadSpec(I.ROLE_SATELLITE, rep=2, sink=8, recent=4, budget=8 + 4 + 40)]
+    spec = I.LayerSpec(B=1, Hq=4 * G, Hkv=4, D=128, ctx=[N], heads=[heads])
+    spec.window, spec.window_mode = W, 2
+    q0 = I.draw_q(spec, 95 + G)
+    data = I.draw_layer(spec, q0, 96 + G, heavy_count=30)
+    sched = I.QuerySchedule(q0, 97 + G, step_deg=6.0)
+    p = U.Pair(spec, data, DEV, growth=2 * W + 2)
+    resyncs, triggers = run_steps(p, sched, 2 * W, tag=f"rescored G{G}", append_seed=9300 + G,
+                                  token_gain=lambda t: 25.0 if t % 2 == 0 else 0.0)
+    assert p.ref.n_tests == 4 and resyncs <= 2          # two pivots, two test steps each
+    p.close()
+
+
+@pytest.mark.parametrize("W", [3, 6])
+def test_rescored_window_in_the_decode_step(W):
+    """hc_decode_step pushes the queries on the main stream and runs the selection passes of all (layer,
+    buffered query) pairs of a group in batches of 8 (W = 6: 10 pairs, two batches): two layers on a
+    ragged batch, 3 W steps with appended tokens, groups of 2 with a side stream."""
+    say(f"re-scored window, decode step, ragged batch, 2 layers, W {W}")
+    specs, pairs = [], []
+    ctx = None
+    for l in range(2):
+        spec = I.spec_ragged(161 + l, B=3, lo=1200, hi=5000, budgets=(96, 160, 352))
+        if l:
+            spec.ctx = list(specs[0].ctx)
+        for b in range(spec.B):
+            spec.heads[b] = [h if h.role == I.ROLE_FULL else I.HeadSpec(h.role, rep=h.rep, sink=16, recent=6, budget=h.budget)
+                             for h in spec.heads[b]]
+        spec.window, spec.window_mode = W, 2
+        specs.append(spec)
+    growth = 3 * W + 2
+    cfg = R.make_config(specs[0], growth=growth, max_k=max(R.make_config(s, growth=growth).max_k for s in specs))
+    ctx = R.Context(cfg, DEV)
+    scheds = []
+    for l, spec in enumerate(specs):
+        q0 = I.draw_q(spec, 170 + l)
+        data = I.draw_layer(spec, q0, 180 + l, heavy_frac=0.01)
+        pr = U.Pair(spec, data, DEV, ctx=ctx, growth=growth)
+        pr.gpu.rep_logits = torch.zeros_like(pr.gpu.rep_logits)
+        pr.gpu.scores = torch.zeros_like(pr.gpu.scores)
+        pairs.append(pr)
+        scheds.append(I.QuerySchedule(q0, 190 + l, step_deg=8.0))
+    B, Hq, Hkv = specs[0].B, specs[0].Hq, specs[0].Hkv
+    q_cur = torch.zeros((2, B, Hq, 128), dtype=torch.bfloat16, device=DEV)
+    k_cur = torch.zeros((2, B, Hkv, 128), dtype=torch.bfloat16, device=DEV)
+    v_cur = torch.zeros_like(k_cur)
+    io = R.make_step_io([pr.gpu for pr in pairs], q_cur)
+    for l in range(2):
+        io[l].k_new, io[l].v_new = k_cur[l].data_ptr(), v_cur[l].data_ptr()
+    side = torch.cuda.Stream()
+    tests = 0
+    for t in range(3 * W):
+        qs = [s.next() for s in scheds]
+        toks = [I.draw_token(specs[l], 9500 + 10 * t + l, toward=qs[l], gain=25.0 if t % 2 else 0.0) for l in range(2)]
+        torch.cuda.synchronize()
+        for l in range(2):
+            q_cur[l].copy_(qs[l])
+            k_cur[l].copy_(toks[l][0])
+            v_cur[l].copy_(toks[l][1])
+            pairs[l].ref.append(*toks[l])
+        hc.hc_decode_step(ctx.handle, io, 2, None, side, 2)
+        q_cur.zero_()                       # the caller may reuse q at once: the window buffer has its own copy
+        torch.cuda.synchronize()
+        for l, pr in enumerate(pairs):
+            rec = pr.ref.step(qs[l])
+            U.check_attention(pr.gpu.out, pr.gpu.lse, rec, f"rescored decode step L{l} t{t}")
+            same = True
+            topk = pr.gpu.topk_idx.cpu().numpy()
+            for (b, pv), s_ref in rec["scores"].items():
+                for h in [pv] + specs[l].satellites(b, pv):
+                    T = rec["topk"][(b, h)]
+                    if U.check_set_valid(topk[b * Hkv + h, :T.size], T, s_ref, 1e-4, f"L{l} t{t} head {h}"):
+                        same = False
+                if (b, pv) in rec["rescored"]:
+                    tests += 1
+                    same &= check_rescored(pr, rec, b, pv, 1e-4, f"decode step L{l} t{t}")
+                gi, gf = int(pr.gpu.inter[b * Hkv + pv]), int(pr.gpu.flag[b * Hkv + pv])
+                if gi != rec["inter"][(b, pv)] or gf != rec["flag"][(b, pv)]:
+                    assert not same
+                    same = False
+            if not same:
+                resync(pr, rec)
+            assert pr.slots_equal_oracle()
+    assert tests >= 6
+    for pr in pairs:
+        pr.close()
     ctx.close()
