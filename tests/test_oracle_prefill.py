@@ -1,0 +1,115 @@
+"""Pins of the prefill-time initialisation oracle (oracle/prefill.py): Sec. 4.3's split storage at the end
+of the prefill stage and Algorithm 1's initial K_base, with App. C.1's group mean and average pooling."""
+import numpy as np
+import torch
+import torch.nn.functional as F
+
+from oracle import prefill, ref
+from paper_2601_13684_amd import inputs as I
+
+
+def test_pooling_is_the_library_average_pooling_with_zero_padding():
+    rng = np.random.default_rng(3)
+    for n, P in [(1, 1), (1, 3), (2, 5), (17, 3), (64, 7), (301, 13), (50, 1)]:
+        s = rng.random(n)
+        want = F.avg_pool1d(torch.from_numpy(s)[None, None], kernel_size=P, stride=1, padding=P // 2)[0, 0].numpy()
+        np.testing.assert_allclose(prefill.avg_pool(s, P), want, rtol=1e-13, atol=1e-15)
+        np.testing.assert_allclose(prefill.avg_pool_fast(s, P), want, rtol=1e-12, atol=1e-14)
+
+
+def test_pooling_by_hand():
+    np.testing.assert_allclose(prefill.avg_pool(np.array([1.0, 2, 3, 4, 5]), 3), [1.0, 2, 3, 4, 3])     # (0+1+2)/3 ... (4+5+0)/3
+    np.testing.assert_allclose(prefill.avg_pool(np.array([3.0, 0, 0, 6]), 5), [0.6, 1.8, 1.8, 1.2])
+    s = np.array([0.25, 0.5, 0.125])
+    assert prefill.avg_pool(s, 1).tolist() == s.tolist()
+
+
+def tiny(N=300, sink=3, recent=5, r=20, seed=1, **kw):
+    heads = [I.HeadSpec(I.ROLE_FULL), I.HeadSpec(I.ROLE_SATELLITE, rep=0, sink=sink, recent=recent, budget=sink + recent + r),
+             I.HeadSpec(I.ROLE_ANCHOR, sink=sink, recent=recent, budget=sink + recent + r // 2), I.HeadSpec(I.ROLE_FULL)]
+    spec = I.LayerSpec(B=1, Hq=16, Hkv=4, D=128, ctx=[N], heads=[heads], **kw)
+    q0 = I.draw_q(spec, seed)
+    data = I.draw_layer(spec, q0, seed + 1, heavy_count=8, heavy_gain=3.0 * np.sqrt(128.0))
+    return spec, q0.to(torch.bfloat16), data
+
+
+def test_who_selects_what():
+    """Compressed heads select by their own scores over their own candidates; the pivot gets a baseline of
+    k_mon over its satellites' candidates; a full head without satellites selects nothing."""
+    spec, q, data = tiny()
+    retrieved, base, scores = prefill.prefill_init(spec, data, q)
+    assert sorted(retrieved) == [(0, 1), (0, 2)] and sorted(base) == [(0, 0)] and sorted(scores) == [(0, 0), (0, 1), (0, 2)]
+    assert retrieved[(0, 1)].size == 20 and retrieved[(0, 2)].size == 10 and base[(0, 0)].size == 20
+    for lst in list(retrieved.values()) + list(base.values()):
+        assert np.all(np.diff(lst) > 0) and lst.min() >= 3 and lst.max() < 300 - 5
+
+
+def test_brute_force_selection_with_numpy():
+    for P in (1, 5):
+        spec, q, data = tiny(N=90, r=12, seed=4)
+        retrieved, base, _ = prefill.prefill_init(spec, data, q, pool=P, exact_pool=True)
+        for (b, h), got in list(retrieved.items()) + list(base.items()):
+            K = data.K[(b, h)].float().double().numpy()
+            qq = q[b, 4 * h:4 * h + 4].float().double().numpy()
+            lg = qq @ K.T / np.sqrt(128.0)
+            p = np.exp(lg - lg.max(1, keepdims=True))
+            p /= p.sum(1, keepdims=True)
+            s = p.mean(0)
+            pad = np.concatenate([np.zeros(P // 2), s, np.zeros(P // 2)])
+            sm = np.array([pad[j:j + P].sum() / P for j in range(s.size)]).astype(np.float32)
+            order = sorted(range(3, 90 - 5), key=lambda j: (-sm[j], j))[:got.size]
+            assert sorted(order) == got.tolist(), (P, b, h)
+
+
+def test_planted_heavy_tokens_are_kept():
+    spec, q, data = tiny(N=2000, r=40, seed=7)
+    retrieved, base, _ = prefill.prefill_init(spec, data, q)
+    for (b, h), lst in list(retrieved.items()) + list(base.items()):
+        heavy = [int(p) for p in data.heavy[(b, h)].tolist() if 3 <= p < 2000 - 5]
+        assert len(heavy) >= 6 and set(heavy) <= set(lst.tolist()), (b, h)
+
+
+def test_budget_of_the_whole_context_keeps_everything_and_decoding_is_dense_attention():
+    N = 128
+    heads = [I.HeadSpec(I.ROLE_FULL), I.HeadSpec(I.ROLE_SATELLITE, rep=0, sink=0, recent=0, budget=N)]
+    spec = I.LayerSpec(B=1, Hq=8, Hkv=2, D=128, ctx=[N], heads=[heads])
+    q0 = I.draw_q(spec, 9)
+    data = I.draw_layer(spec, q0, 10)
+    q = q0.to(torch.bfloat16)
+    retrieved, base, _ = prefill.prefill_init(spec, data, q, pool=3)
+    assert retrieved[(0, 1)].tolist() == list(range(N)) == base[(0, 0)].tolist()
+    rec = ref.RefLayer(spec, data, retrieved, base).step(q)
+    o = F.scaled_dot_product_attention(q[0, 4:8].double()[None, :, None, :], data.K[(0, 1)].double()[None, None].expand(1, 4, -1, -1),
+                                       data.V[(0, 1)].double()[None, None].expand(1, 4, -1, -1))[0, :, 0]
+    np.testing.assert_allclose(rec["out"][0, 4:8], o.numpy(), rtol=1e-12, atol=1e-13)
+
+
+def test_first_decode_step_with_the_same_query_finds_the_baseline_again():
+    """Without pooling the pivot's baseline is the top-k of exactly the scores the first decode step
+    computes for the same query: full overlap, no retrieval.  A satellite whose keys and queries equal its
+    pivot's selects what the pivot would retrieve for it."""
+    spec, q, data = tiny(N=500, r=24, seed=11)
+    data.K[(0, 1)] = data.K[(0, 0)].clone()
+    q = q.clone()
+    q[0, 4:8] = q[0, 0:4]
+    retrieved, base, _ = prefill.prefill_init(spec, data, q, pool=1)
+    layer = ref.RefLayer(spec, data, retrieved, base)
+    rec = layer.step(q)
+    assert rec["inter"][(0, 0)] == spec.k_mon(0, 0) and rec["flag"][(0, 0)] == 0
+    assert rec["topk"][(0, 1)].tolist() == retrieved[(0, 1)].tolist()
+    # with pooling the baseline is taken on smoothed scores: it still overlaps the raw top-k mostly, not fully
+    _, base5, _ = prefill.prefill_init(spec, data, q, pool=5)
+    inter = ref.intersect(rec["topk"][(0, 0)], base5[(0, 0)])
+    assert 0 < inter < spec.k_mon(0, 0)
+
+
+def test_pooling_prefers_a_run_of_good_positions_over_an_isolated_better_one():
+    """Scores by hand: an isolated spike of 0.30 and a run of five 0.20s.  Raw top-1 is the spike; with a
+    window of 5 the middle of the run (mean 0.20) beats the spike's neighbourhood (0.30 / 5 = 0.06)."""
+    s = np.zeros(40)
+    s[8] = 0.30
+    s[20:25] = 0.20
+    assert int(np.argmax(s)) == 8
+    sm = prefill.avg_pool(s, 5)
+    assert int(np.argmax(sm)) == 22 and abs(sm[22] - 0.20) < 1e-15 and abs(sm[8] - 0.06) < 1e-15
+    assert ref.topk(sm.astype(np.float32), 0, 40, 3).tolist() == [21, 22, 23]
