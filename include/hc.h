@@ -281,6 +281,35 @@ hc_status hc_append_kv(hc_ctx* ctx, hc_layer* layer, const void* k_new, const vo
 /* Current context length of sequence b of the layer (grows with hc_append_kv); -1 on a bad argument. */
 int32_t hc_layer_context(const hc_layer* layer, int32_t b);
 
+/* ---- Prefill-time initialisation (Sec. 4.3, first paragraphs; Algorithm 1, stage 3 before the loop) --------
+ * Builds the state decoding starts from, out of the prefill stage's K/V and the last prompt token's
+ * queries:
+ *   C_GPU: the full heads' K/V rows copied whole; for every compressed head, slots [0, sink) = the first
+ *          positions, the next `recent` slots = the last positions, and the other r slots = the r positions
+ *          of [sink, ctx - recent) with the head's OWN best scores, in ascending order;
+ *   C_CPU: every satellite's whole K/V into its [ctx][2][D] block of host_tier (skipped if NULL);
+ *   K_base of every pivot = T_{k_mon} of the pivot's own scores over its satellites' candidate positions;
+ *   topk_idx rows of the selecting heads = their lists; slot_pos rows of the satellites (if not NULL) =
+ *   their lists; ring rows emptied.
+ * Scores: last token's softmax weights over the head's whole context, mean over the query group (or mean of
+ * the logits with HC_AGG_LOGIT), then a centred average pooling over positions of odd width `pool` with
+ * zero padding and divisor `pool` (App. C.1; 1 = none); decisions in fp32, (score descending, index
+ * ascending).
+ * kv_prefill: dev bf16; head (b, h)'s K rows [ctx][D] at element offset k_src_off[b*Hkv+h], V rows at
+ * v_src_off[..] (HOST arrays of B*Hkv, multiples of 8).  q_last: dev bf16 [B][Hq][D].  work: dev, at least
+ * hc_prefill_work_bytes bytes, 256-byte aligned, scratch (hc_prefill_work_layout says where the selecting
+ * heads' logits [n][max_ctx][G], scores [n][max_ctx] and the lse [B*Hq] are left, and which table row
+ * each selecting head is; head_of needs room for B*Hkv entries).
+ * Set-up call: synchronises the stream once (a small table goes to the device), then enqueues.  Must
+ * precede any hc_append_kv on the layer. */
+size_t hc_prefill_work_bytes(const hc_ctx* ctx, const hc_layer* layer);
+hc_status hc_prefill_work_layout(const hc_ctx* ctx, const hc_layer* layer, int32_t* n_selecting, int32_t* head_of,
+                                 size_t* logits_off, size_t* scores_off, size_t* lse_off);
+hc_status hc_prefill_init(hc_ctx* ctx, hc_layer* layer, const void* kv_prefill, const int64_t* k_src_off,
+                          const int64_t* v_src_off, const void* q_last, int32_t pool, void* kv_arena, void* host_tier,
+                          int32_t* topk_idx, int32_t* base_idx, int32_t* slot_pos, int32_t* ring, void* work,
+                          size_t work_bytes, void* stream);
+
 /* ---- Algorithm 1, the loop over the window's buffered queries at t mod W = 0 (HC_WINDOW_RESCORED) ------
  * Call once per decode step and layer, after hc_decode_attn and BEFORE hc_rep_topk_drift, on the stream
  * of the monitor (hc_decode_step does).  The layer counts the steps of the window: slot = monitored

@@ -22,7 +22,8 @@ EXPORTS = ["hc_create", "hc_destroy", "hc_strerror", "hc_last_error", "hc_layer_
            "hc_layer_num_reps", "hc_layer_rep_slot", "hc_layer_num_workgroups", "hc_layer_num_partials",
            "hc_set_split", "hc_set_share_weights", "hc_get_share_weights", "hc_layer_tune", "hc_set_monitor_span",
            "hc_set_timing_events", "hc_plan_describe", "hc_decode_attn", "hc_rep_topk_drift", "hc_gather_retrieve",
-           "hc_append_kv", "hc_rescore_work_bytes", "hc_rescore_work_layout", "hc_rescore_window", "hc_layer_window_slot",
+           "hc_append_kv", "hc_rescore_work_bytes", "hc_rescore_work_layout", "hc_rescore_window", "hc_prefill_work_bytes", "hc_prefill_work_layout", "hc_prefill_init",
+           "hc_layer_window_slot",
            "hc_layer_set_window_slot", "hc_layer_context",
            "hc_decode_step", "hc_taxonomy", "hc_budgets"]
 
@@ -92,6 +93,11 @@ def lib():
         L.hc_rescore_work_bytes.restype = C.c_size_t
         L.hc_rescore_work_layout.argtypes = [vp, vp, C.POINTER(i32)] + [C.POINTER(C.c_size_t)] * 4
         L.hc_rescore_window.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.hc_prefill_work_bytes.argtypes = [vp, vp]
+        L.hc_prefill_work_bytes.restype = C.c_size_t
+        L.hc_prefill_work_layout.argtypes = [vp, vp, C.POINTER(i32), C.POINTER(i32)] + [C.POINTER(C.c_size_t)] * 3
+        L.hc_prefill_init.argtypes = [vp, vp, vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64), vp, i32, vp, vp, vp, vp, vp, vp, vp,
+                                      C.c_size_t, vp]
         L.hc_layer_window_slot.argtypes = [vp]
         L.hc_layer_window_slot.restype = i32
         L.hc_layer_set_window_slot.argtypes = [vp, i32]
@@ -110,7 +116,7 @@ def lib():
         L.hc_decode_step.argtypes = [vp, C.POINTER(hc_layer_io), i32, i32, vp, vp]
         for n in EXPORTS:
             if n not in ("hc_strerror", "hc_last_error", "hc_layer_num_reps", "hc_layer_rep_slot",
-                         "hc_layer_num_workgroups", "hc_layer_num_partials", "hc_rescore_work_bytes",
+                         "hc_layer_num_workgroups", "hc_layer_num_partials", "hc_rescore_work_bytes", "hc_prefill_work_bytes",
                          "hc_layer_window_slot"):
                 getattr(L, n).restype = C.c_int
         _lib = L
@@ -290,6 +296,28 @@ def hc_rescore_window(ctx: int, layer: int, kv_arena: Ptr, q: Ptr, q_window: Ptr
                       work: Ptr, work_bytes: int, stream=None) -> None:
     _check(lib().hc_rescore_window(ctx, layer, _p(kv_arena), _p(q), _p(q_window), _p(base_idx), _p(ring), _p(work),
                                    work_bytes, _stream(stream)), "hc_rescore_window", ctx)
+
+
+def hc_prefill_work_bytes(ctx: int, layer: int) -> int:
+    return int(lib().hc_prefill_work_bytes(ctx, layer))
+
+
+def hc_prefill_work_layout(ctx: int, layer: int, n_heads: int) -> dict:
+    n = C.c_int32(0)
+    head_of = (C.c_int32 * n_heads)()
+    off = [C.c_size_t(0) for _ in range(3)]
+    _check(lib().hc_prefill_work_layout(ctx, layer, C.byref(n), head_of, *[C.byref(o) for o in off]), "hc_prefill_work_layout", ctx)
+    return dict(heads=[int(head_of[i]) for i in range(n.value)], logits=off[0].value, scores=off[1].value, lse=off[2].value)
+
+
+def hc_prefill_init(ctx: int, layer: int, kv_prefill: Ptr, k_src_off, v_src_off, q_last: Ptr, pool: int, kv_arena: Ptr,
+                    host_tier: Ptr, topk_idx: Ptr, base_idx: Ptr, slot_pos: Ptr, ring: Ptr, work: Ptr, work_bytes: int,
+                    stream=None) -> None:
+    n = len(k_src_off)
+    ko = (C.c_int64 * n)(*[int(x) for x in k_src_off])
+    vo = (C.c_int64 * n)(*[int(x) for x in v_src_off])
+    _check(lib().hc_prefill_init(ctx, layer, _p(kv_prefill), ko, vo, _p(q_last), pool, _p(kv_arena), _p(host_tier), _p(topk_idx),
+                                 _p(base_idx), _p(slot_pos), _p(ring), _p(work), work_bytes, _stream(stream)), "hc_prefill_init", ctx)
 
 
 def hc_layer_window_slot(layer: int) -> int:

@@ -108,7 +108,8 @@ extern "C" hc_status hc_create(const hc_config* cfg, hc_ctx** out)
     }
     c->n_cu = prop.multiProcessorCount;
 
-    c->max_reps = std::max(1, cfg->B * cfg->Hkv / 2);
+    // pivots are at most half of the heads; the prefill-time selection runs over up to all of them
+    c->max_reps = std::max(1, cfg->B * cfg->Hkv);
     c->max_chunks = (cfg->max_ctx + HC_SEL_CHUNK - 1) / HC_SEL_CHUNK;
     const size_t hist_w = (size_t)c->max_reps * rep_hist_words();
     const size_t sel_w = (size_t)c->max_reps * HC_MAX_K_PER_REP * 4;
@@ -247,6 +248,10 @@ static void layer_free(hc_layer* L)
     (void)hipFree(L->reps);
     (void)hipFree(L->outs);
     (void)hipFree(L->sats);
+    (void)hipFree(L->sel_reps);
+    (void)hipFree(L->sel_outs);
+    (void)hipFree(L->pre_src);
+    (void)hipFree(L->rep_slot_dev);
     if (L->ev_attn) (void)hipEventDestroy(L->ev_attn);
     if (L->ev_side) (void)hipEventDestroy(L->ev_side);
     L->magic = 0;
@@ -588,6 +593,48 @@ extern "C" hc_status hc_layer_create(hc_ctx* ctx, const hc_head_desc* hd, hc_lay
     if (st == HC_OK) st = upload(ctx, P.reps, &L->reps);
     if (st == HC_OK) st = upload(ctx, P.outs, &L->outs);
     if (st == HC_OK) st = upload(ctx, P.sats, &L->sats);
+    if (st == HC_OK) {
+        // prefill-time selection (hc_prefill_init): every compressed head with refillable slots selects r
+        // positions of its own candidates; every pivot selects its baseline set
+        std::vector<RepDev> sel;
+        std::vector<OutDev> outs;
+        for (int i = 0; i < L->n_heads; ++i) {
+            const hc_head_desc& h = hd[i];
+            RepDev r;
+            memset(&r, 0, sizeof r);
+            r.bh = i;
+            if (h.role == HC_ROLE_FULL) {
+                if (P.rep_slot_of[i] < 0) continue;
+                const RepDev& pv = P.reps[P.rep_slot_of[i]];
+                r.lo = pv.lo;
+                r.hi = pv.hi;
+                r.k[0] = pv.k[0];
+            } else {
+                r.lo = h.sink;
+                r.hi = h.ctx - h.recent;
+                r.k[0] = h.len - h.sink - h.recent;
+                if (r.k[0] == 0) continue;
+                if (r.k[0] > ctx->cfg.max_k || r.k[0] > r.hi - r.lo) {
+                    st = hc_fail(ctx, HC_EINVAL, "head %d: %d refillable slots exceed max_k or its candidate positions", i, r.k[0]);
+                    break;
+                }
+            }
+            r.nk = 1;
+            r.nchunk = (r.hi - r.lo + HC_SEL_CHUNK - 1) / HC_SEL_CHUNK;
+            r.out_begin = (int32_t)outs.size();
+            r.out_count = 1;
+            outs.push_back(OutDev{(int32_t)sel.size(), 0, i, 0});
+            sel.push_back(r);
+            L->sel_head_host.push_back(i);
+            L->sel_max_nchunk = std::max(L->sel_max_nchunk, r.nchunk);
+            L->sel_max_len = std::max(L->sel_max_len, (int)h.ctx);
+        }
+        L->n_sel = (int)sel.size();
+        if (st == HC_OK) st = upload(ctx, sel, &L->sel_reps);
+        if (st == HC_OK) st = upload(ctx, outs, &L->sel_outs);
+        if (st == HC_OK) st = upload(ctx, std::vector<PreSrc>(), &L->pre_src, (size_t)L->n_heads);
+        if (st == HC_OK) st = upload(ctx, P.rep_slot_of, &L->rep_slot_dev);
+    }
     if (st == HC_OK && hipEventCreateWithFlags(&L->ev_attn, hipEventDisableTiming) != hipSuccess) st = hc_fail(ctx, HC_EHIP, "hipEventCreate failed");
     if (st == HC_OK && hipEventCreateWithFlags(&L->ev_side, hipEventDisableTiming) != hipSuccess) st = hc_fail(ctx, HC_EHIP, "hipEventCreate failed");
     if (st != HC_OK) {
@@ -747,6 +794,7 @@ extern "C" hc_status hc_append_kv(hc_ctx* ctx, hc_layer* layer, const void* k_ne
             max_nchunk = std::max(max_nchunk, (hi - lo + HC_SEL_CHUNK - 1) / HC_SEL_CHUNK);
         }
     L->max_nchunk = max_nchunk;
+    ++L->total_appended;
     if (++L->appended_since_plan >= 64) return replan(ctx, L, st);
     return HC_OK;
 }
@@ -833,6 +881,76 @@ extern "C" hc_status hc_layer_tune(hc_ctx* ctx, hc_layer* layer, const void* kv_
     ctx->tune_stamps = nullptr;
     (void)hipFree(dev);
     return result;
+}
+
+// ---- prefill-time initialisation (Sec. 4.3; Algorithm 1, stage 3 before the loop) ----
+extern "C" size_t hc_prefill_work_bytes(const hc_ctx* ctx, const hc_layer* layer)
+{
+    if (!ctx_ok(ctx) || !layer_ok(layer) || layer->ctx != ctx) return 0;
+    return hc_prefill_plan(ctx, layer).bytes;
+}
+
+extern "C" hc_status hc_prefill_work_layout(const hc_ctx* ctx, const hc_layer* layer, int32_t* n_selecting, int32_t* head_of,
+                                            size_t* logits_off, size_t* scores_off, size_t* lse_off)
+{
+    if (!ctx_ok(ctx) || !layer_ok(layer) || layer->ctx != ctx) return HC_ESTATE;
+    const hc_prefill_layout lay = hc_prefill_plan(ctx, layer);
+    if (n_selecting) *n_selecting = layer->n_sel;
+    if (head_of)
+        for (int i = 0; i < layer->n_sel; ++i) head_of[i] = layer->sel_head_host[(size_t)i];
+    if (logits_off) *logits_off = lay.logits_off;
+    if (scores_off) *scores_off = lay.scores_off;
+    if (lse_off) *lse_off = lay.lse_off;
+    return HC_OK;
+}
+
+extern "C" hc_status hc_prefill_init(hc_ctx* ctx, hc_layer* layer, const void* kv_prefill, const int64_t* k_src_off,
+                                     const int64_t* v_src_off, const void* q_last, int32_t pool, void* kv_arena, void* host_tier,
+                                     int32_t* topk_idx, int32_t* base_idx, int32_t* slot_pos, int32_t* ring, void* work,
+                                     size_t work_bytes, void* stream)
+{
+    if (!ctx_ok(ctx)) return HC_ESTATE;
+    if (!layer_ok(layer) || layer->ctx != ctx) return hc_fail(ctx, HC_ESTATE, "hc_prefill_init: layer does not belong to this context");
+    hc_layer* L = layer;
+    if (!kv_prefill || !k_src_off || !v_src_off || !q_last || !kv_arena || !topk_idx || !base_idx || !ring || !work)
+        return hc_fail(ctx, HC_EINVAL, "hc_prefill_init: null pointer");
+    if (pool < 1 || pool > HC_MAX_POOL || pool % 2 == 0) return hc_fail(ctx, HC_EINVAL, "hc_prefill_init: pool %d must be odd, 1..%d", (int)pool, HC_MAX_POOL);
+    if (((uintptr_t)kv_prefill | (uintptr_t)kv_arena | (uintptr_t)host_tier | (uintptr_t)q_last) & 15)
+        return hc_fail(ctx, HC_EINVAL, "hc_prefill_init: buffers must be 16-byte aligned");
+    if ((uintptr_t)work & 255) return hc_fail(ctx, HC_EINVAL, "hc_prefill_init: work must be 256-byte aligned");
+    const hc_prefill_layout lay = hc_prefill_plan(ctx, L);
+    if (work_bytes < lay.bytes) return hc_fail(ctx, HC_EINVAL, "hc_prefill_init: work buffer of %zu bytes, %zu needed", work_bytes, lay.bytes);
+    if (L->total_appended != 0) return hc_fail(ctx, HC_ESTATE, "hc_prefill_init: tokens have been appended to this layer already");
+    std::vector<PreSrc> src((size_t)L->n_heads);
+    for (int i = 0; i < L->n_heads; ++i) {
+        if (k_src_off[i] < 0 || v_src_off[i] < 0 || (k_src_off[i] & 7) || (v_src_off[i] & 7))
+            return hc_fail(ctx, HC_EINVAL, "hc_prefill_init: head %d: source offsets must be non-negative multiples of 8 elements", i);
+        src[(size_t)i] = PreSrc{k_src_off[i], v_src_off[i]};
+    }
+    hipStream_t st = (hipStream_t)stream;
+    // (pageable source: the copy has left the host buffer when the call returns)
+    HC_HIP(ctx, hipMemcpyAsync(L->pre_src, src.data(), src.size() * sizeof(PreSrc), hipMemcpyHostToDevice, st));
+    HC_HIP(ctx, hipStreamSynchronize(st));
+    char* wb = (char*)work;
+    if (L->n_sel > 0) {
+        float* logits = (float*)(wb + lay.logits_off);
+        float* scores = (float*)(wb + lay.scores_off);
+        float* lse = (float*)(wb + lay.lse_off);
+        hc_status s = hc_launch_logits_lse(ctx, L, L->sel_reps, L->n_sel, L->sel_max_len, kv_prefill, L->pre_src, q_last, 1, logits, 0,
+                                           lse, 0, (float*)(wb + lay.part_off), st);
+        if (s == HC_OK) s = hc_launch_prefill_scores(ctx, L, logits, lse, scores, pool, st);
+        if (s != HC_OK) return s;
+        int32_t* scratch = (int32_t*)(wb + lay.scratch_off);
+        hc_monitor_call call{L, nullptr, lse, scores, topk_idx, base_idx, ring, scratch, scratch + (size_t)ctx->cfg.B * ctx->cfg.Hkv, -2};
+        call.reps = L->sel_reps;
+        call.outs = L->sel_outs;
+        call.n_reps = call.n_outs = L->n_sel;
+        call.max_nchunk = L->sel_max_nchunk;
+        call.max_nk = 1;
+        s = hc_launch_monitor(ctx, 1, &call, 1, st);
+        if (s != HC_OK) return s;
+    }
+    return hc_launch_prefill_place(ctx, L, kv_prefill, kv_arena, host_tier, topk_idx, base_idx, slot_pos, ring, st);
 }
 
 // ---- re-scoring of the window's buffered queries (Algorithm 1, t mod W = 0) ----

@@ -60,6 +60,11 @@ struct OutDev {
     int32_t rep, kslot, row, is_mon;
 };
 
+// Where a head's K and V rows of the prefill stage are (element offsets in the caller's prefill buffer).
+struct PreSrc {
+    int64_t k_off, v_off;
+};
+
 // One satellite to refill.
 struct SatDev {
     int32_t bh, rep_bh, r, first_slot;   // first_slot = sink + recent
@@ -117,6 +122,15 @@ struct hc_layer {
     std::vector<int32_t> ctx0_host;     // [B*Hkv] context lengths at creation
     std::vector<int32_t> rep_lo_host, rep_recent_host;   // per pivot: first candidate, recent slots of its satellites
     int appended_since_plan = 0;
+    long long total_appended = 0;       // tokens appended since creation
+    // prefill-time initialisation: the heads that select (compressed heads by their own scores, pivots for their
+    // baseline sets), one list each
+    int n_sel = 0, sel_max_nchunk = 1, sel_max_len = 1;
+    RepDev* sel_reps = nullptr;
+    OutDev* sel_outs = nullptr;
+    PreSrc* pre_src = nullptr;          // [n_heads]
+    int32_t* rep_slot_dev = nullptr;    // [n_heads]: device copy of rep_slot_of
+    std::vector<int32_t> sel_head_host; // table rows of the selecting heads, in the order of sel_reps
     int window_slot = 0;                // hc_decode_step with a re-scored window: monitored steps since the window was emptied
     int seg_capacity = 0;               // device room in segs (a rebalanced plan may have a few more segments)
     HeadDev* heads = nullptr;
@@ -151,7 +165,12 @@ struct hc_monitor_call {
     float* scores;
     int32_t *topk_idx, *base_idx, *ring, *inter, *flag;
     int store_slot = -1;   // >= 0: a re-scored query of the window: only its overlap is kept, as value store_slot of the
-                           // ring (if the ring is one short of full), and baseline, inter, flag are left alone
+                           // ring (if the ring is one short of full), and baseline, inter, flag are left alone;
+                           // -2: lists only (prefill-time selection): no overlap, no decision, tables untouched
+    // prefill-time selection runs over its own list of heads instead of the layer's pivots
+    const RepDev* reps = nullptr;
+    const OutDev* outs = nullptr;
+    int n_reps = 0, n_outs = 0, max_nchunk = 0, max_nk = 0;
 };
 struct hc_gather_call {
     const hc_layer* L;
@@ -175,6 +194,19 @@ struct hc_rescore_layout {
 int hc_rescore_items_per_pass(const hc_ctx* ctx);
 hc_rescore_layout hc_rescore_plan(const hc_ctx* ctx, const hc_layer* L);
 hc_status hc_launch_rescore_push(hc_ctx* ctx, int n, const void* const* q, void* const* dst, hipStream_t st);
+hc_status hc_launch_logits_lse(hc_ctx* ctx, const hc_layer* L, const RepDev* reps, int n_heads, int max_len, const void* arena,
+                               const PreSrc* src, const void* q, int n_items, float* logits, size_t logits_item, float* lse,
+                               size_t lse_item, float* part, hipStream_t st);
+// prefill-time initialisation
+constexpr int HC_MAX_POOL = 63;
+struct hc_prefill_layout {
+    size_t logits_off, scores_off, lse_off, part_off, scratch_off, bytes;
+};
+hc_prefill_layout hc_prefill_plan(const hc_ctx* ctx, const hc_layer* L);
+hc_status hc_launch_prefill_scores(hc_ctx* ctx, const hc_layer* L, const float* logits, const float* lse, float* scores, int pool,
+                                   hipStream_t st);
+hc_status hc_launch_prefill_place(hc_ctx* ctx, const hc_layer* L, const void* kv_prefill, void* arena, void* tier,
+                                  const int32_t* topk_idx, int32_t* base_idx, int32_t* slot_pos, int32_t* ring, hipStream_t st);
 hc_status hc_launch_rescore_logits(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* q_window, int first,
                                    int n_items, void* work, hipStream_t st);
 hc_status hc_launch_append(hc_ctx* ctx, const hc_layer* L, const void* k_new, const void* v_new, void* arena, void* tier,

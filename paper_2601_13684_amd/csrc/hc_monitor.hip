@@ -551,11 +551,11 @@ __global__ __launch_bounds__(BLK) void mon_decide(MonBatch B, DriftCfg cfg)
         __syncthreads();
     }
     const int32_t inter = (int32_t)(sm_hits[0] + sm_hits[1] + sm_hits[2] + sm_hits[3]);
-    if (it.store_slot >= 0) {
-        // A buffered query of the window scored again at the test step (Algorithm 1): its overlap replaces the
-        // one stored when the query was current.  Only while the ring is one short of full, i.e. the
-        // monitor call that follows is the one that tests.
-        if (threadIdx.x == 0 && n == cfg.window - 1 && it.store_slot < n) rg[1 + it.store_slot] = inter;
+    if (it.store_slot != -1) {
+        // >= 0: a buffered query of the window scored again at the test step (Algorithm 1): its overlap replaces
+        // the one stored when the query was current.  Only while the ring is one short of full, i.e. the
+        // monitor call that follows is the one that tests.  -2: the lists were all that was wanted.
+        if (threadIdx.x == 0 && it.store_slot >= 0 && n == cfg.window - 1 && it.store_slot < n) rg[1 + it.store_slot] = inter;
         const RepWs w = ws.rep(blockIdx.x);
         uint4* h4 = reinterpret_cast<uint4*>(w.h1);
         for (int i = threadIdx.x; i < (1 + 2 * HC_MAX_K_PER_REP) * HC_RADIX_BINS / 4; i += BLK) h4[i] = make_uint4(0u, 0u, 0u, 0u);
@@ -615,8 +615,8 @@ hc_status hc_launch_monitor(hc_ctx* ctx, int n, const hc_monitor_call* calls, in
         hc_monitor_ws& m = ctx->ws[i];
         MonItem& it = B.it[i];
         it.ws = Ws{m.hist, m.sel, m.misc, m.cnt, m.bitmap, m.hits, ctx->max_chunks, c.max_ctx};
-        it.reps = x.L->reps;
-        it.outs = x.L->outs;
+        it.reps = x.reps ? x.reps : x.L->reps;
+        it.outs = x.reps ? x.outs : x.L->outs;
         it.rep_logits = x.rep_logits;
         it.lse = x.lse;
         it.scores = x.scores;
@@ -625,12 +625,12 @@ hc_status hc_launch_monitor(hc_ctx* ctx, int n, const hc_monitor_call* calls, in
         it.ring = x.ring;
         it.inter = x.inter;
         it.flag = x.flag;
-        it.n_reps = x.L->n_reps;
-        it.n_outs = x.L->n_outs;
+        it.n_reps = x.reps ? x.n_reps : x.L->n_reps;
+        it.n_outs = x.reps ? x.n_outs : x.L->n_outs;
         it.store_slot = x.store_slot;
-        max_reps = std::max(max_reps, x.L->n_reps);
-        max_nchunk = std::max(max_nchunk, x.L->max_nchunk);
-        max_nk = std::max(max_nk, x.L->max_nk);
+        max_reps = std::max(max_reps, it.n_reps);
+        max_nchunk = std::max(max_nchunk, x.reps ? x.max_nchunk : x.L->max_nchunk);
+        max_nk = std::max(max_nk, x.reps ? x.max_nk : x.L->max_nk);
         if (m.dirty) {     // a previous call that used this workspace copy did not run to its last kernel
             mon_prep<<<dim3(16, ctx->max_reps), dim3(256), 0, st>>>(it.ws, c.max_ctx);
             HC_HIP(ctx, hipGetLastError());

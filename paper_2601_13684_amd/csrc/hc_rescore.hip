@@ -50,6 +50,7 @@ struct RescoreArgs {
     float* lse;                     // [n_items][B*Hq]
     size_t lse_item_stride;
     float* part;                    // [n_reps][nblk][RS_ROWS][2]: running maximum (base-2 exponent), sum
+    const PreSrc* src;              // prefill-time use: the K rows of head bh are at arena + src[bh].k_off, all ctx of them
     int n_items, n_reps, max_ctx, nblk;
 };
 
@@ -71,7 +72,9 @@ __global__ __launch_bounds__(RS_BLK) void rescore_logits_kernel(RescoreArgs a)
     const int rep = blockIdx.y;
     const RepDev rd = a.reps[rep];
     const HeadDev hd = a.heads[rd.bh];
-    const int ctx = hd.len;                                     // a pivot is a full head: all of its context
+    // a pivot is a full head: all of its context, in the arena; at prefill time any head's full K, in the caller's buffer
+    const int ctx = a.src ? hd.ctx : hd.len;
+    const int64_t k_off = a.src ? a.src[rd.bh].k_off : hd.k_off;
     const int tiles = (ctx + RS_WG_TILE - 1) / RS_WG_TILE;
     const int per = (tiles + a.nblk - 1) / a.nblk;
     const int t0 = blockIdx.x * per, t1 = min(tiles, t0 + per);
@@ -100,7 +103,7 @@ __global__ __launch_bounds__(RS_BLK) void rescore_logits_kernel(RescoreArgs a)
         z[v] = 0.f;
     }
 
-    const unsigned char* Kb = reinterpret_cast<const unsigned char*>(a.arena + hd.k_off);
+    const unsigned char* Kb = reinterpret_cast<const unsigned char*>(a.arena + k_off);
     unsigned char* mine = sm_k[w];
     // coalesced load of a tile: instruction s, lane l -> row 4 s + l / 16, 16-byte piece l % 16
     const int lrow = lane >> 4, lpiece = lane & 15;
@@ -315,36 +318,37 @@ hc_status hc_launch_rescore_push(hc_ctx* ctx, int n, const void* const* q, void*
     return HC_OK;
 }
 
-// Logits and lse of buffered queries [first, first + n_items) of the window against the layer's pivots.
-hc_status hc_launch_rescore_logits(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* q_window, int first,
-                                   int n_items, void* work, hipStream_t st)
+// Logits [n_items][n_heads][max_ctx][G] and lse [n_items][B*Hq] of n_items queries (q, item stride B*Hq*D)
+// against the K rows of the heads listed in `reps`: in the arena (src == nullptr: pivots, hd.k_off, hd.len
+// rows) or in a prefill buffer (`arena` is that buffer, src[bh].k_off, hd.ctx rows).
+hc_status hc_launch_logits_lse(hc_ctx* ctx, const hc_layer* L, const RepDev* reps, int n_heads, int max_len, const void* arena,
+                               const PreSrc* src, const void* q, int n_items, float* logits, size_t logits_item, float* lse,
+                               size_t lse_item, float* part, hipStream_t st)
 {
-    if (n_items < 1 || n_items > hc_rescore_items_per_pass(ctx)) return hc_fail(ctx, HC_EINVAL, "re-scoring pass of %d queries", n_items);
-    const hc_rescore_layout lay = hc_rescore_plan(ctx, L);
-    int max_len = 1;
-    for (size_t i = 0; i < L->hd_host.size(); ++i)
-        if (L->rep_slot_of[i] >= 0) max_len = std::max(max_len, (int)L->hd_host[i].len);
-    const int tiles = (max_len + RS_WG_TILE - 1) / RS_WG_TILE;
-    // two workgroups per compute unit over all pivots (measured at 224K: 31 us, against 35 us with four and
-    // 33 us with one), each with at least two iterations
-    const int want = std::max(1, 2 * ctx->n_cu / std::max(1, L->n_reps));
+    if (n_items < 1 || n_items > hc_rescore_items_per_pass(ctx)) return hc_fail(ctx, HC_EINVAL, "scoring pass of %d queries", n_items);
+    if (n_heads < 1) return HC_OK;
+    const int tiles = (std::max(1, max_len) + RS_WG_TILE - 1) / RS_WG_TILE;
+    // two workgroups per compute unit over all heads (measured at 224K, two pivots: 31 us, against 35 us with
+    // four and 33 us with one), each with at least two iterations
+    const int want = std::max(1, 2 * ctx->n_cu / n_heads);
     const int nblk = std::max(1, std::min({(int)HC_RESCORE_MAX_BLOCKS, want, (tiles + 1) / 2}));
     RescoreArgs a{};
     a.heads = L->heads;
-    a.reps = L->reps;
+    a.reps = reps;
     a.arena = (const uint16_t*)arena;
     a.q_item_stride = (size_t)ctx->cfg.B * ctx->cfg.Hq * HC_D;
-    a.q_first = (const uint16_t*)q_window + (size_t)first * a.q_item_stride;
-    a.logits = (float*)((char*)work + lay.logits_off);
-    a.logits_item_stride = lay.logits_item;
-    a.lse = (float*)((char*)work + lay.lse_off);
-    a.lse_item_stride = lay.lse_item;
-    a.part = (float*)((char*)work + lay.part_off);
+    a.q_first = (const uint16_t*)q;
+    a.logits = logits;
+    a.logits_item_stride = logits_item;
+    a.lse = lse;
+    a.lse_item_stride = lse_item;
+    a.part = part;
+    a.src = src;
     a.n_items = n_items;
-    a.n_reps = L->n_reps;
+    a.n_reps = n_heads;
     a.max_ctx = ctx->cfg.max_ctx;
     a.nblk = nblk;
-    const dim3 grid(nblk, L->n_reps);
+    const dim3 grid(nblk, n_heads);
     switch (ctx->G) {
     case 1: rescore_logits_kernel<1><<<grid, dim3(RS_BLK), 0, st>>>(a); break;
     case 2: rescore_logits_kernel<2><<<grid, dim3(RS_BLK), 0, st>>>(a); break;
@@ -353,11 +357,25 @@ hc_status hc_launch_rescore_logits(hc_ctx* ctx, const hc_layer* L, const void* a
     }
     HC_HIP(ctx, hipGetLastError());
     switch (ctx->G) {
-    case 1: rescore_lse_kernel<1><<<dim3(L->n_reps), dim3(RS_LSE_BLK), 0, st>>>(a); break;
-    case 2: rescore_lse_kernel<2><<<dim3(L->n_reps), dim3(RS_LSE_BLK), 0, st>>>(a); break;
-    case 4: rescore_lse_kernel<4><<<dim3(L->n_reps), dim3(RS_LSE_BLK), 0, st>>>(a); break;
-    default: rescore_lse_kernel<8><<<dim3(L->n_reps), dim3(RS_LSE_BLK), 0, st>>>(a); break;
+    case 1: rescore_lse_kernel<1><<<dim3(n_heads), dim3(RS_LSE_BLK), 0, st>>>(a); break;
+    case 2: rescore_lse_kernel<2><<<dim3(n_heads), dim3(RS_LSE_BLK), 0, st>>>(a); break;
+    case 4: rescore_lse_kernel<4><<<dim3(n_heads), dim3(RS_LSE_BLK), 0, st>>>(a); break;
+    default: rescore_lse_kernel<8><<<dim3(n_heads), dim3(RS_LSE_BLK), 0, st>>>(a); break;
     }
     HC_HIP(ctx, hipGetLastError());
     return HC_OK;
+}
+
+// Logits and lse of buffered queries [first, first + n_items) of the window against the layer's pivots.
+hc_status hc_launch_rescore_logits(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* q_window, int first,
+                                   int n_items, void* work, hipStream_t st)
+{
+    const hc_rescore_layout lay = hc_rescore_plan(ctx, L);
+    int max_len = 1;
+    for (size_t i = 0; i < L->hd_host.size(); ++i)
+        if (L->rep_slot_of[i] >= 0) max_len = std::max(max_len, (int)L->hd_host[i].len);
+    const size_t q_item = (size_t)ctx->cfg.B * ctx->cfg.Hq * HC_D;
+    return hc_launch_logits_lse(ctx, L, L->reps, L->n_reps, max_len, arena, nullptr, (const uint16_t*)q_window + (size_t)first * q_item,
+                                n_items, (float*)((char*)work + lay.logits_off), lay.logits_item, (float*)((char*)work + lay.lse_off),
+                                lay.lse_item, (float*)((char*)work + lay.part_off), st);
 }

@@ -87,7 +87,10 @@ class Context:
 class LayerRuntime:
     def __init__(self, ctx: Context, spec: LayerSpec, data: LayerData,
                  retrieved: Dict[Tuple[int, int], torch.Tensor], base: Dict[Tuple[int, int], torch.Tensor],
-                 host_tier: bool = True, own_scratch: bool = False, delta_gather: bool = True, growth: int = 0):
+                 host_tier: bool = True, own_scratch: bool = False, delta_gather: bool = True, growth: int = 0,
+                 prefill: Optional[Tuple[torch.Tensor, int]] = None):
+        """``prefill = (q_last, pool)``: ``retrieved`` and ``base`` are ignored (may be None) and the library builds
+        the initial state itself from ``data`` and the last prompt token's queries (hc_prefill_init)."""
         self.ctx, self.spec = ctx, spec
         cfg, dev = ctx.cfg, ctx.device
         B, Hkv = spec.B, spec.Hkv
@@ -95,7 +98,7 @@ class LayerRuntime:
         self.descs = descs
         # ---- arena ----
         self.arena = torch.zeros((off,), dtype=torch.bfloat16, device=dev)
-        for b in range(B):
+        for b in range(B if prefill is None else 0):
             for h in range(Hkv):
                 d = descs[b * Hkv + h]
                 hs = spec.heads[b][h]
@@ -113,7 +116,9 @@ class LayerRuntime:
         self.tier = None
         if host_tier and tier_off > 0:
             self.tier = torch.empty((tier_off,), dtype=torch.bfloat16, pin_memory=True)
-            for b in range(B):
+            if prefill is not None:
+                self.tier.zero_()
+            for b in range(B if prefill is None else 0):
                 for h in range(Hkv):
                     if spec.heads[b][h].role == ROLE_SATELLITE:
                         d = descs[b * Hkv + h]
@@ -123,13 +128,13 @@ class LayerRuntime:
         nh = B * Hkv
         self.topk_idx = torch.full((nh, cfg.max_k), -1, dtype=torch.int32, device=dev)
         self.base_idx = torch.full((nh, cfg.max_k), -1, dtype=torch.int32, device=dev)
-        for (b, p), lst in base.items():
+        for (b, p), lst in (base.items() if prefill is None else ()):
             self.base_idx[b * Hkv + p, :lst.numel()] = lst.to(dev, torch.int32)
         # which position every retrieved slot of a satellite holds (None: refills replace whole lists)
         self.slot_pos = None
         if delta_gather:
             self.slot_pos = torch.full((nh, cfg.max_k), -1, dtype=torch.int32, device=dev)
-            for (b, h), lst in retrieved.items():
+            for (b, h), lst in (retrieved.items() if prefill is None else ()):
                 if spec.heads[b][h].role == ROLE_SATELLITE:
                     self.slot_pos[b * Hkv + h, :lst.numel()] = lst.to(dev, torch.int32)
         self.ring = torch.zeros((nh, cfg.window + 1), dtype=torch.int32, device=dev)
@@ -151,6 +156,8 @@ class LayerRuntime:
         if cfg.window_mode == hc.HC_WINDOW_RESCORED:
             self.q_window = torch.zeros((cfg.window, B, spec.Hq, D), dtype=torch.bfloat16, device=dev)
             self.rescore_work = torch.zeros((hc.hc_rescore_work_bytes(ctx.handle, self.handle),), dtype=torch.uint8, device=dev)
+        if prefill is not None:
+            self.prefill_init(data, prefill[0], prefill[1])
         # torch creates the HIP event lazily at the first record: do it now, the C ABI needs the handle
         self.ev_topk = torch.cuda.Event()
         self.ev_done = torch.cuda.Event()
@@ -170,6 +177,30 @@ class LayerRuntime:
     def monitor(self, scores_given: bool = False, stream=None) -> None:
         hc.hc_rep_topk_drift(self.ctx.handle, self.handle, self.rep_logits, self.lse, self.scores, scores_given,
                              self.topk_idx, self.base_idx, self.ring, self.inter, self.flag, stream)
+
+    def prefill_init(self, data: LayerData, q_last: torch.Tensor, pool: int = 1, stream=None) -> None:
+        """The state decoding starts from, built by the library from the prefill stage's K/V (``data``, copied into
+        one device buffer here) and the last prompt token's queries (hc_prefill_init)."""
+        spec, dev = self.spec, self.ctx.device
+        k_off, v_off, parts, off = [], [], [], 0
+        for b in range(spec.B):
+            for h in range(spec.Hkv):
+                for lst, t in ((k_off, data.K[(b, h)]), (v_off, data.V[(b, h)])):
+                    lst.append(off)
+                    parts.append(t.reshape(-1))
+                    off += t.numel()
+        self.kv_prefill = torch.cat([p.to(dev) for p in parts])
+        self.prefill_work = torch.zeros((hc.hc_prefill_work_bytes(self.ctx.handle, self.handle),), dtype=torch.uint8, device=dev)
+        hc.hc_prefill_init(self.ctx.handle, self.handle, self.kv_prefill, k_off, v_off, q_last.to(dev), pool, self.arena, self.tier,
+                           self.topk_idx, self.base_idx, self.slot_pos, self.ring, self.prefill_work, self.prefill_work.numel(), stream)
+
+    def prefill_scores(self) -> dict:
+        """{table row of a selecting head: view of the fp32 scores its selection was taken on}."""
+        lay = hc.hc_prefill_work_layout(self.ctx.handle, self.handle, self.spec.B * self.spec.Hkv)
+        mc = self.ctx.cfg.max_ctx
+        n = len(lay["heads"])
+        sc = self.prefill_work[lay["scores"]:lay["scores"] + n * mc * 4].view(torch.float32).view(n, mc)
+        return {bh: sc[i] for i, bh in enumerate(lay["heads"])}
 
     def rescore(self, q: torch.Tensor, stream=None) -> None:
         """Buffer this step's queries; at the window's last step score the earlier ones again (hc_rescore_window).

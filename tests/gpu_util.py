@@ -2,6 +2,7 @@
 import numpy as np
 import torch
 
+from oracle import prefill as oracle_prefill
 from oracle import ref
 from paper_2601_13684_amd import inputs as I
 from paper_2601_13684_amd import runtime as R
@@ -63,6 +64,56 @@ class Pair:
         self.gpu = R.LayerRuntime(self.ctx, spec, data, retrieved, base, host_tier=host_tier, delta_gather=delta_gather, growth=growth)
         cpu = I.LayerData({k: v.cpu() for k, v in data.K.items()}, {k: v.cpu() for k, v in data.V.items()}, {})
         self.ref = ref.RefLayer(spec, cpu, retrieved, base)
+
+    @classmethod
+    def from_prefill(cls, spec, data, q_last, pool, device="cuda:0", growth=0, rel_band=1e-4, where="prefill"):
+        """The GPU side builds its initial state with hc_prefill_init, the oracle twin with oracle/prefill.py.  Scores
+        and lists are compared here (a list may differ from the oracle's inside the near-tie band: the twin
+        then starts from the GPU's list, so that everything downstream compares like with like).
+        Returns (pair, number of lists that differed)."""
+        self = cls.__new__(cls)
+        self.spec, self.data = spec, data
+        self.ctx0 = list(spec.ctx)
+        self.own_ctx = True
+        self.ctx = R.Context(R.make_config(spec, growth=growth), device)
+        self.gpu = R.LayerRuntime(self.ctx, spec, data, None, None, growth=growth, prefill=(q_last, pool))
+        torch.cuda.synchronize()
+        cpu = I.LayerData({k: v.cpu() for k, v in data.K.items()}, {k: v.cpu() for k, v in data.V.items()}, {})
+        retrieved, base, scores = oracle_prefill.prefill_init(spec, cpu, q_last.cpu(), pool)
+        got_scores = self.gpu.prefill_scores()
+        assert sorted(got_scores) == sorted(b * spec.Hkv + h for (b, h) in scores)
+        topk = self.gpu.topk_idx.cpu().numpy()
+        basei = self.gpu.base_idx.cpu().numpy()
+        differed = 0
+        for (b, h), s_ref in scores.items():
+            row = b * spec.Hkv + h
+            check_scores(got_scores[row].cpu().numpy(), s_ref, 0, spec.ctx[b], f"{where} head {(b, h)}")
+            want = base[(b, h)] if (b, h) in base else retrieved[(b, h)]
+            got = topk[row, :want.size].copy()
+            if check_set_valid(got, want, s_ref, rel_band, f"{where} head {(b, h)}"):
+                differed += 1
+            if (b, h) in base:
+                assert np.array_equal(basei[row, :want.size], got), (where, "baseline row is not the pivot's list")
+                base[(b, h)] = got
+            else:
+                retrieved[(b, h)] = got
+        self.ref = ref.RefLayer(spec, cpu, {k: torch.from_numpy(v) for k, v in retrieved.items()},
+                                {k: torch.from_numpy(v) for k, v in base.items()})
+        return self, differed
+
+    def tier_equals_masters(self):
+        """Every satellite's block of the host tier holds its whole K and V, K row then V row per position."""
+        tier = self.gpu.tier.view(torch.int16).numpy().view(np.uint16)
+        for b in range(self.spec.B):
+            for h in range(self.spec.Hkv):
+                if self.spec.heads[b][h].role != I.ROLE_SATELLITE:
+                    continue
+                d = self.gpu.descs[b * self.spec.Hkv + h]
+                N = self.spec.ctx[b]
+                want = np.stack([ref._bits(self.data.K[(b, h)].cpu()), ref._bits(self.data.V[(b, h)].cpu())], axis=1).reshape(-1)
+                if not np.array_equal(tier[d.tier_off:d.tier_off + N * 256], want):
+                    return False
+        return True
 
     def slots_equal_oracle(self):
         """Byte-exact comparison of every compressed head's K/V slots with the oracle's rows.  With a slot

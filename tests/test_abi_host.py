@@ -71,7 +71,8 @@ def test_null_arguments():
     assert hc.lib().hc_rep_topk_drift(None, None, None, None, None, 0, None, None, None, None, None, None) == hc.HC_ESTATE
     assert hc.lib().hc_gather_retrieve(None, None, None, None, None, None, None, None, None, None) == hc.HC_ESTATE
     assert hc.lib().hc_rescore_window(None, None, None, None, None, None, None, None, 0, None) == hc.HC_ESTATE
-    assert hc.lib().hc_rescore_work_bytes(None, None) == 0
+    assert hc.lib().hc_rescore_work_bytes(None, None) == 0 and hc.lib().hc_prefill_work_bytes(None, None) == 0
+    assert hc.lib().hc_prefill_init(*([None] * 6 + [1] + [None] * 7 + [0, None])) == hc.HC_ESTATE
     assert hc.lib().hc_layer_window_slot(None) == -1 and hc.lib().hc_layer_set_window_slot(None, 0) == hc.HC_ESTATE
     assert hc.lib().hc_layer_num_reps(None) == -1
 

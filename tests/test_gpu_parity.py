@@ -1118,3 +1118,93 @@ def test_rescored_window_in_the_decode_step(W):
     for pr in pairs:
         pr.close()
     ctx.close()
+
+
+# ------------------------------------------------------------------------------------------
+# Prefill-time initialisation: the state decoding starts from
+# ------------------------------------------------------------------------------------------
+def prefill_spec(N, B=1, G=4):
+    rows = []
+    for b in range(B):
+        rows.append([I.HeadSpec(I.ROLE_FULL), I.HeadSpec(I.ROLE_SATELLITE, rep=0, sink=16, recent=24, budget=16 + 24 + 300),
+                     I.HeadSpec(I.ROLE_ANCHOR, sink=8, recent=8, budget=8 + 8 + 120), I.HeadSpec(I.ROLE_FULL),
+                     I.HeadSpec(I.ROLE_SATELLITE, rep=0, sink=16, recent=24, budget=16 + 24 + 77),
+                     I.HeadSpec(I.ROLE_SATELLITE, rep=5 if b % 2 else 0, sink=16 if b % 2 == 0 else 4, recent=24 if b % 2 == 0 else 0,
+                                budget=(40 if b % 2 == 0 else 4) + 200)] +
+                    ([I.HeadSpec(I.ROLE_FULL)] if True else []))
+        if b % 2:
+            rows[-1][5], rows[-1][6] = rows[-1][6], rows[-1][5]          # head 5 full (pivot of head 6), head 6 its satellite
+            rows[-1][6] = I.HeadSpec(I.ROLE_SATELLITE, rep=5, sink=4, recent=0, budget=4 + 200)
+    ctx = [N - 613 * b for b in range(B)]
+    return I.LayerSpec(B=B, Hq=7 * G, Hkv=7, D=128, ctx=ctx, heads=rows)
+
+
+@pytest.mark.parametrize("pool,G,B", [(1, 4, 1), (7, 4, 2), (13, 8, 1), (3, 1, 2), (63, 2, 1)])
+def test_prefill_init_matches_oracle_and_decoding_continues_from_it(pool, G, B):
+    """Scores, lists, baseline sets, slot contents, slot maps and the host tier after hc_prefill_init against the
+    prefill oracle (pivots, satellites, an anchor, volatile heads; ragged batch; pooling widths 1..63); then 5
+    decode steps from that state against the decode oracle started from the same lists."""
+    say(f"prefill init, pool {pool}, G {G}, B {B}")
+    spec = prefill_spec(5000 + 37 * pool, B=B, G=G)
+    q0 = I.draw_q(spec, 300 + pool)
+    data = I.draw_layer(spec, q0, 301 + pool, heavy_count=60)
+    q = q0.to(torch.bfloat16)
+    p, differed = U.Pair.from_prefill(spec, data, q, pool, DEV)
+    say("  lists that differ inside the near-tie band:", differed)
+    assert differed <= 1
+    assert p.slots_equal_oracle(), "slots after prefill"
+    assert p.tier_equals_masters(), "host tier after prefill"
+    assert int(p.gpu.ring.abs().sum()) == 0
+    sched = I.QuerySchedule(q0, 302 + pool, step_deg=6.0)
+    resyncs, triggers = run_steps(p, sched, 5, side=torch.cuda.Stream(), tag=f"after prefill pool {pool}")
+    assert resyncs <= 1
+    p.close()
+
+
+def test_prefill_init_without_pooling_is_found_again_by_the_first_decode_step():
+    """The pivot's baseline is the top-k of exactly the scores the first decode step computes for the same
+    query: its overlap is k_mon of k_mon and nothing is refilled."""
+    say("prefill init, first decode step")
+    spec = prefill_spec(4100)
+    q0 = I.draw_q(spec, 320)
+    data = I.draw_layer(spec, q0, 321, heavy_count=60)
+    q = q0.to(torch.bfloat16)
+    p, _ = U.Pair.from_prefill(spec, data, q, 1, DEV)
+    p.gpu.step(q.to(DEV))
+    torch.cuda.synchronize()
+    rec = p.ref.step(q)
+    for pv in spec.reps(0):
+        assert int(p.gpu.inter[pv]) == spec.k_mon(0, pv) == rec["inter"][(0, pv)]
+        assert int(p.gpu.flag[pv]) == 0 == rec["flag"][(0, pv)]
+    U.check_attention(p.gpu.out, p.gpu.lse, rec, "first step after prefill")
+    p.close()
+
+
+def test_prefill_init_then_growing_context():
+    """hc_prefill_init must come before any append; after it the layer appends and decodes as usual."""
+    say("prefill init, then appends")
+    spec = prefill_spec(3000)
+    q0 = I.draw_q(spec, 330)
+    data = I.draw_layer(spec, q0, 331, heavy_count=40)
+    q = q0.to(torch.bfloat16)
+    p, _ = U.Pair.from_prefill(spec, data, q, 5, DEV, growth=16)
+    sched = I.QuerySchedule(q0, 332, step_deg=6.0)
+    run_steps(p, sched, 10, tag="prefill + grow", append_seed=9700, token_gain=lambda t: 30.0 if t % 3 == 0 else 0.0)
+    with pytest.raises(hc.HcError) as e:
+        p.gpu.prefill_init(data, q, 5)
+    assert e.value.status == hc.HC_ESTATE and "appended" in str(e.value)
+    p.close()
+
+
+def test_prefill_init_config4_full_size():
+    """One full-size layer of the 224K workload: lists, baseline sets, slots and host tier."""
+    say("prefill init, config 4 full size")
+    w = I.make_workload(4, device=DEV)
+    q = w.schedule.next()
+    p, differed = U.Pair.from_prefill(w.spec, w.data, q.to(DEV), 7, DEV)
+    say("  lists that differ inside the near-tie band:", differed)
+    assert p.slots_equal_oracle() and p.tier_equals_masters()
+    p.gpu.step(q.to(DEV), side=torch.cuda.Stream())
+    torch.cuda.synchronize()
+    U.check_attention(p.gpu.out, p.gpu.lse, p.ref.step(q.cpu()), "cfg4 after prefill")
+    p.close()
