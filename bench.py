@@ -47,6 +47,9 @@ def main():
     ap.add_argument("--append", action="store_true", help="every step appends the generated token's K/V first (growing context)")
     ap.add_argument("--full-gather", action="store_true", help="refills fetch whole lists (no slot map: nothing is kept)")
     ap.add_argument("--wg-per-cu", type=int, default=0)
+    ap.add_argument("--prefill-init", type=int, default=0, help="odd P >= 1: every layer's initial state is built by the library from "
+                    "the full K/V and the last prompt token's queries (hc_prefill_init, pooling width P) instead of the positional "
+                    "fill, and the call is timed (prefill_init_ms_per_layer)")
     ap.add_argument("--window", type=int, default=0, help="W of the drift test (0: the config's, which is 1)")
     ap.add_argument("--window-mode", type=int, default=-1, help="0 sliding (Eq. 10), 1 tumbling, 2 tumbling with the window's "
                     "queries scored again at the test step (Algorithm 1); -1: the config's (sliding)")
@@ -89,6 +92,7 @@ def main():
 
     # ---- build the stack, layer by layer (masters are dropped once packed) ----
     layers, scheds, keep = [], [], {}
+    prefill_ms = []
     ctx = None
     for l in range(L):
         w = I.make_workload(args.config, layer=l, device=dev, N=args.ctx or None)
@@ -104,8 +108,27 @@ def main():
             if args.share_weights:
                 hc.hc_set_share_weights(ctx.handle, [float(x) for x in args.share_weights.split(",")])
         retrieved, base = I.initial_lists(spec)
+        pre = None
+        if args.prefill_init:
+            pre = (w.schedule.q.to(torch.bfloat16).to(dev), args.prefill_init)
         layers.append(R.LayerRuntime(ctx, spec, w.data, retrieved, base, host_tier=not args.no_tier, own_scratch=True,
-                                     delta_gather=not args.full_gather, growth=T_total if args.append else 0))
+                                     delta_gather=not args.full_gather, growth=T_total if args.append else 0, prefill=pre))
+        if pre is not None:
+            # timed a second time (the first call paid the first-touch costs); the state comes out the same
+            ev = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+            torch.cuda.synchronize()
+            ev[0].record()
+            layers[-1].prefill_init(None, pre[0], pre[1])
+            ev[1].record()
+            torch.cuda.synchronize()
+            prefill_ms.append(ev[0].elapsed_time(ev[1]))
+            del layers[-1].kv_prefill, layers[-1].prefill_work
+            if l < 2 and not args.no_oracle:
+                from oracle import prefill as oracle_prefill
+                cpu_data = I.LayerData({k: v.cpu() for k, v in w.data.K.items()}, {k: v.cpu() for k, v in w.data.V.items()}, {})
+                r_np, b_np, _ = oracle_prefill.prefill_init(spec, cpu_data, pre[0].cpu(), pre[1])
+                retrieved = {k: torch.from_numpy(v) for k, v in r_np.items()}
+                base = {k: torch.from_numpy(v) for k, v in b_np.items()}
         if l == 0 and args.tune_rounds and not args.share_weights:
             layers[0].tune(w.schedule.q.to(torch.bfloat16).to(dev), args.tune_rounds)       # untimed set-up
             print("[bench] share weights " + " ".join(f"{x:.3f}" for x in hc.hc_get_share_weights(ctx.handle)), file=sys.stderr, flush=True)
@@ -291,6 +314,7 @@ def main():
                    "split_workgroups": hc.hc_layer_num_workgroups(layers[0].handle),
                    "split_partials": hc.hc_layer_num_partials(layers[0].handle)},
         "host_enqueue_ms_per_step": host_enqueue_ms,
+        "prefill_init_ms_per_layer": float(np.mean(prefill_ms)) if prefill_ms else None,
         "tokens_per_s": spec0.B / (ms_per_step * 1e-3),
         "step_GBps": kv_bytes * L / (ms_per_step * 1e-3) / 1e9,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",

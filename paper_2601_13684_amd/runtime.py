@@ -178,21 +178,27 @@ class LayerRuntime:
         hc.hc_rep_topk_drift(self.ctx.handle, self.handle, self.rep_logits, self.lse, self.scores, scores_given,
                              self.topk_idx, self.base_idx, self.ring, self.inter, self.flag, stream)
 
-    def prefill_init(self, data: LayerData, q_last: torch.Tensor, pool: int = 1, stream=None) -> None:
-        """The state decoding starts from, built by the library from the prefill stage's K/V (``data``, copied into
-        one device buffer here) and the last prompt token's queries (hc_prefill_init)."""
+    def stage_prefill(self, data: LayerData) -> None:
+        """The prefill stage's K/V of every head in one device buffer (the caller's side of hc_prefill_init)."""
         spec, dev = self.spec, self.ctx.device
-        k_off, v_off, parts, off = [], [], [], 0
+        self._k_src, self._v_src, parts, off = [], [], [], 0
         for b in range(spec.B):
             for h in range(spec.Hkv):
-                for lst, t in ((k_off, data.K[(b, h)]), (v_off, data.V[(b, h)])):
+                for lst, t in ((self._k_src, data.K[(b, h)]), (self._v_src, data.V[(b, h)])):
                     lst.append(off)
                     parts.append(t.reshape(-1))
                     off += t.numel()
         self.kv_prefill = torch.cat([p.to(dev) for p in parts])
         self.prefill_work = torch.zeros((hc.hc_prefill_work_bytes(self.ctx.handle, self.handle),), dtype=torch.uint8, device=dev)
-        hc.hc_prefill_init(self.ctx.handle, self.handle, self.kv_prefill, k_off, v_off, q_last.to(dev), pool, self.arena, self.tier,
-                           self.topk_idx, self.base_idx, self.slot_pos, self.ring, self.prefill_work, self.prefill_work.numel(), stream)
+
+    def prefill_init(self, data: Optional[LayerData], q_last: torch.Tensor, pool: int = 1, stream=None) -> None:
+        """The state decoding starts from, built by the library from the prefill stage's K/V (``data``; None: what
+        stage_prefill left) and the last prompt token's queries (hc_prefill_init)."""
+        if data is not None:
+            self.stage_prefill(data)
+        hc.hc_prefill_init(self.ctx.handle, self.handle, self.kv_prefill, self._k_src, self._v_src, q_last.to(self.ctx.device), pool,
+                           self.arena, self.tier, self.topk_idx, self.base_idx, self.slot_pos, self.ring, self.prefill_work,
+                           self.prefill_work.numel(), stream)
 
     def prefill_scores(self) -> dict:
         """{table row of a selecting head: view of the fp32 scores its selection was taken on}."""
