@@ -615,8 +615,9 @@ extern "C" hc_status hc_layer_create(hc_ctx* ctx, const hc_head_desc* hd, hc_lay
                 r.k[0] = h.len - h.sink - h.recent;
                 if (r.k[0] == 0) continue;
                 if (r.k[0] > ctx->cfg.max_k || r.k[0] > r.hi - r.lo) {
-                    st = hc_fail(ctx, HC_EINVAL, "head %d: %d refillable slots exceed max_k or its candidate positions", i, r.k[0]);
-                    break;
+                    // fine for decoding (an anchor's slots are never selected again), but hc_prefill_init cannot fill them
+                    L->prefill_unfit_head = i;
+                    continue;
                 }
             }
             r.nk = 1;
@@ -921,6 +922,9 @@ extern "C" hc_status hc_prefill_init(hc_ctx* ctx, hc_layer* layer, const void* k
     const hc_prefill_layout lay = hc_prefill_plan(ctx, L);
     if (work_bytes < lay.bytes) return hc_fail(ctx, HC_EINVAL, "hc_prefill_init: work buffer of %zu bytes, %zu needed", work_bytes, lay.bytes);
     if (L->total_appended != 0) return hc_fail(ctx, HC_ESTATE, "hc_prefill_init: tokens have been appended to this layer already");
+    if (L->prefill_unfit_head >= 0)
+        return hc_fail(ctx, HC_ESHAPE, "hc_prefill_init: head %d has more refillable slots than max_k or than candidate positions",
+                       L->prefill_unfit_head);
     std::vector<PreSrc> src((size_t)L->n_heads);
     for (int i = 0; i < L->n_heads; ++i) {
         if (k_src_off[i] < 0 || v_src_off[i] < 0 || (k_src_off[i] & 7) || (v_src_off[i] & 7))

@@ -126,6 +126,7 @@ struct hc_layer {
     // prefill-time initialisation: the heads that select (compressed heads by their own scores, pivots for their
     // baseline sets), one list each
     int n_sel = 0, sel_max_nchunk = 1, sel_max_len = 1;
+    int prefill_unfit_head = -1;        // a compressed head whose slots the selection cannot fill (list longer than max_k)
     RepDev* sel_reps = nullptr;
     OutDev* sel_outs = nullptr;
     PreSrc* pre_src = nullptr;          // [n_heads]

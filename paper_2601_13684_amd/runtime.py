@@ -26,6 +26,7 @@ def make_config(spec: LayerSpec, max_ctx: Optional[int] = None, max_k: Optional[
     mc = (mc + 63) // 64 * 64
     ks = [1]
     for b in range(spec.B):
+        ks += [spec.r(b, h) for h in range(spec.Hkv) if spec.heads[b][h].role == ROLE_ANCHOR]     # selected once, at prefill
         for p in spec.reps(b):
             ks.append(spec.k_mon(b, p))
             ks += [spec.r(b, s) for s in spec.satellites(b, p)]
