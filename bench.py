@@ -47,6 +47,7 @@ def main():
     ap.add_argument("--append", action="store_true", help="every step appends the generated token's K/V first (growing context)")
     ap.add_argument("--full-gather", action="store_true", help="refills fetch whole lists (no slot map: nothing is kept)")
     ap.add_argument("--wg-per-cu", type=int, default=0)
+    ap.add_argument("--dump-kernel-times", default="", help="write the split kernel's per-launch durations (us, launch order) to this file")
     ap.add_argument("--prefill-init", type=int, default=0, help="odd P >= 1: every layer's initial state is built by the library from "
                     "the full K/V and the last prompt token's queries (hc_prefill_init, pooling width P) instead of the positional "
                     "fill, and the call is timed (prefill_init_ms_per_layer)")
@@ -257,6 +258,8 @@ def main():
     torch.cuda.synchronize()
     kern_ms = np.array([a.elapsed_time(b) for a, b in evs]) if n_pairs else np.array([float("nan")])
     kern_us = float(kern_ms.mean() * 1e3)
+    if args.dump_kernel_times and n_pairs:
+        np.savetxt(args.dump_kernel_times, kern_ms.reshape(K, L) * 1e3, fmt="%.2f")
     achieved = kv_bytes / (kern_us * 1e-6) / 1e9
 
     # ---- for comparison: the same kernel with nothing else on the GPU (monitor and gather on the same stream,

@@ -3,7 +3,7 @@
 // The host tier is pinned host memory that the kernels read directly over the host link, 512
 // contiguous bytes per retrieved position (its K row followed by its V row), so no host thread has
 // to learn which pivots fired: the predicate (flag of the satellite's pivot) is read on the device
-// and workgroups of untriggered satellites leave at once.  32 lanes move one position: lanes 0-15
+// and an untriggered call finds no rows to move.  32 lanes move one position: lanes 0-15
 // the K row, lanes 16-31 the V row, 16 bytes each.
 //
 // The host link is the bound (about 55 GB/s against a refill of 10 MB per pivot), so with a slot map
@@ -20,8 +20,9 @@ namespace {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int ROWS_PER_PASS = 64;    // positions a workgroup has in flight: 8 per sub-pass, 8 sub-passes
-constexpr int BLOCKS_PER_SAT = 16;   // workgroups per satellite: 1024 positions (512 KB) in flight per satellite;
-                                     // few enough that an untriggered call costs next to nothing
+constexpr int GATHER_WORKGROUPS = 96; // workgroups of a gather launch, whatever the batch (measured at the 224K shape, batches
+                                      // of 8 layers: 48 and fewer make the refill itself the bottleneck of the step, 128 and
+                                      // more slow the attention pass that runs beside it; an untriggered call costs ~2 us)
 constexpr int PLAN_THREADS = 1024;
 
 // One layer of a batched call (blockIdx.z picks the layer).
@@ -145,45 +146,87 @@ __global__ __launch_bounds__(PLAN_THREADS) void gather_plan_kernel(GatherBatch B
     if (tid == 0) it.npairs[sd.bh] = (int32_t)tot_free;
 }
 
-__global__ __launch_bounds__(256) void gather_kernel(GatherBatch B, int max_k)
+// The rows to move, over all satellites of all layers of the batch, are numbered consecutively (satellite
+// after satellite) and dealt to the workgroups in equal contiguous runs, so that the time does not depend on
+// how unequal the satellites' lists are and a launch has as many workgroups as the host link needs, no more.
+// Every workgroup makes the prefix sums of the satellites' row counts itself (a few hundred numbers).
+// 32 lanes move one position (lanes 0-15 its K row, 16-31 its V row, 16 bytes each); a workgroup has
+// ROWS_PER_PASS positions in flight.
+constexpr int MAX_GATHER_SATS = 1024;     // satellites of a batch (layers x satellites per layer)
+__global__ __launch_bounds__(256) void gather_kernel(GatherBatch B, int n_items, int max_sats, int max_k)
 {
-    const GatherItem& it = B.it[blockIdx.z];
-    if ((int)blockIdx.y >= it.n_sats) return;
-    const HeadDev* __restrict__ heads = it.heads;
-    const uint16_t* __restrict__ tier = it.tier;
-    uint16_t* __restrict__ arena = it.arena;
-    const SatDev sd = it.sats[blockIdx.y];
-    if (it.flag[sd.rep_bh] == 0) return;
-    const HeadDev hd = heads[sd.bh];
-    const bool delta = it.slot_pos != nullptr;
-    const int32_t* pos_list = (delta ? it.pair_pos : it.topk_idx) + (size_t)sd.bh * max_k;
-    const int32_t* slot_list = delta ? it.pair_slot + (size_t)sd.bh * max_k : nullptr;
-    const int count = delta ? min(it.npairs[sd.bh], sd.r) : sd.r;
+    __shared__ int sm_start[MAX_GATHER_SATS + 1];
+    __shared__ int sm_wsum[4];
+    const int n_ent = n_items * max_sats;
+    // counts -> exclusive prefix sums (entry e = item e / max_sats, satellite e % max_sats)
+    int carry = 0;
+    for (int base = 0; base < n_ent; base += 256) {
+        const int e = base + threadIdx.x;
+        int c = 0;
+        if (e < n_ent) {
+            const GatherItem& it = B.it[e / max_sats];
+            const int sidx = e % max_sats;
+            if (sidx < it.n_sats) {
+                const SatDev sd = it.sats[sidx];
+                if (it.flag[sd.rep_bh] != 0) c = it.slot_pos ? min(max(it.npairs[sd.bh], 0), sd.r) : sd.r;
+            }
+        }
+        int inc = c;
+        const int lane = threadIdx.x & 63;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(inc, o);
+            if (lane >= o) inc += t;
+        }
+        if (lane == 63) sm_wsum[threadIdx.x >> 6] = inc;
+        __syncthreads();
+        int before = carry;
+        for (int k = 0; k < (int)(threadIdx.x >> 6); ++k) before += sm_wsum[k];
+        if (e < n_ent) sm_start[e] = before + inc - c;
+        carry += sm_wsum[0] + sm_wsum[1] + sm_wsum[2] + sm_wsum[3];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) sm_start[n_ent] = carry;
+    __syncthreads();
+    const int total = carry;
+    if (total == 0) return;
+    const int per = ((total + (int)gridDim.x - 1) / (int)gridDim.x + 7) & ~7;
+    const int g_begin = blockIdx.x * per, g_end = min(total, g_begin + per);
     const int sub = threadIdx.x >> 5;          // which of the 8 positions of a sub-pass
     const int l32 = threadIdx.x & 31;
     const int is_v = l32 >> 4;                 // lanes 16..31 move the V row
     const int chunk = l32 & 15;                // 16-byte chunk of the 256-byte row
-    const u32x4* src_base = reinterpret_cast<const u32x4*>(tier + hd.tier_off);
-    u32x4* dst_base = reinterpret_cast<u32x4*>(arena + (is_v ? hd.v_off : hd.k_off));
-    for (int row_first = blockIdx.x * ROWS_PER_PASS; row_first < count; row_first += gridDim.x * ROWS_PER_PASS) {
+    for (int row_first = g_begin; row_first < g_end; row_first += ROWS_PER_PASS) {
         u32x4 buf[ROWS_PER_PASS / 8];
-        int slot[ROWS_PER_PASS / 8];
+        u32x4* dst[ROWS_PER_PASS / 8];
 #pragma unroll
         for (int p = 0; p < ROWS_PER_PASS / 8; ++p) {      // issue every host read first: they are latency-bound
-            const int i = row_first + p * 8 + sub;
-            slot[p] = -1;
-            if (i < count) {
-                const int j = pos_list[i];
-                const int s = slot_list ? slot_list[i] : i;
-                if (j >= 0 && j < hd.ctx && s >= 0 && s < sd.r) {     // a corrupt entry must not leave the tier block or the head's slots
-                    buf[p] = __builtin_nontemporal_load(src_base + (size_t)j * 32 + is_v * 16 + chunk);
-                    slot[p] = sd.first_slot + s;
+            const int g = row_first + p * 8 + sub;
+            dst[p] = nullptr;
+            if (g < g_end) {
+                int lo = 0, hi = n_ent;                    // the entry whose run holds row g
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) >> 1;
+                    if (sm_start[mid] <= g) lo = mid;
+                    else hi = mid;
+                }
+                const GatherItem& it = B.it[lo / max_sats];
+                const SatDev sd = it.sats[lo % max_sats];
+                const HeadDev hd = it.heads[sd.bh];
+                const int i = g - sm_start[lo];
+                const bool delta = it.slot_pos != nullptr;
+                const int j = (delta ? it.pair_pos : it.topk_idx)[(size_t)sd.bh * max_k + i];
+                const int sl = delta ? it.pair_slot[(size_t)sd.bh * max_k + i] : i;
+                if (j >= 0 && j < hd.ctx && sl >= 0 && sl < sd.r) {     // a corrupt entry must not leave the tier block or the head's slots
+                    const u32x4* src = reinterpret_cast<const u32x4*>(it.tier + hd.tier_off);
+                    buf[p] = __builtin_nontemporal_load(src + (size_t)j * 32 + is_v * 16 + chunk);
+                    dst[p] = reinterpret_cast<u32x4*>(it.arena + (is_v ? hd.v_off : hd.k_off)) + (size_t)(sd.first_slot + sl) * 16 + chunk;
                 }
             }
         }
 #pragma unroll
         for (int p = 0; p < ROWS_PER_PASS / 8; ++p)
-            if (slot[p] >= 0) dst_base[(size_t)slot[p] * 16 + chunk] = buf[p];
+            if (dst[p]) *dst[p] = buf[p];
     }
 }
 
@@ -216,8 +259,15 @@ hc_status hc_launch_gather(hc_ctx* ctx, int n, const hc_gather_call* calls, hipS
         gather_plan_kernel<<<dim3(1, max_sats, n), dim3(PLAN_THREADS), lds, st>>>(B, max_k);
         HC_HIP(ctx, hipGetLastError());
     }
-    const dim3 grid(std::min(BLOCKS_PER_SAT, (max_r + ROWS_PER_PASS - 1) / ROWS_PER_PASS), max_sats, n);
-    gather_kernel<<<grid, dim3(256), 0, st>>>(B, max_k);
+    // A few dozen workgroups keep the host link busy.  More do not make the refill faster, and every compute unit
+    // that hosts gather waves has its memory pipeline filled with reads that take microseconds, behind which the
+    // attention waves on the same unit queue (measured at the 224K shape with 16 workgroups per satellite in a
+    // batch of 8 layers: the attention launch that ran beside a refill took 400 us instead of 45).
+    if (n * max_sats > MAX_GATHER_SATS) return hc_fail(ctx, HC_ESHAPE, "hc_gather: more than %d satellites in a batch", MAX_GATHER_SATS);
+    long long rows_max = 0;
+    for (int i = 0; i < n; ++i) rows_max += (long long)calls[i].L->n_sats * calls[i].L->max_r;
+    const int nwg = (int)std::max<long long>(1, std::min<long long>(GATHER_WORKGROUPS, (rows_max + ROWS_PER_PASS - 1) / ROWS_PER_PASS));
+    gather_kernel<<<dim3(nwg), dim3(256), 0, st>>>(B, n, max_sats, max_k);
     HC_HIP(ctx, hipGetLastError());
     return HC_OK;
 }
