@@ -1024,6 +1024,22 @@ def test_rescored_window_growing_context_multi_step(use_side):
     p.close()
 
 
+@pytest.mark.parametrize("W", [1, 2])
+def test_rescored_window_of_one_and_two_steps(W):
+    """W = 1: there is no earlier query to score again (the call only buffers the query); W = 2: one."""
+    say(f"re-scored window, W {W}")
+    spec = I.spec_tiny(3000, budget=300, sink=16, recent=8)
+    spec.window, spec.window_mode = W, 2
+    q0 = I.draw_q(spec, 191)
+    data = I.draw_layer(spec, q0, 192, heavy_count=30)
+    p = U.Pair(spec, data, DEV, growth=16)
+    resyncs, triggers = run_steps(p, I.QuerySchedule(q0, 193, step_deg=6.0), 8, tag=f"rescored W{W}", append_seed=9800,
+                                  token_gain=lambda t: 30.0 if t % 2 else 0.0)
+    assert p.ref.n_tests == 8 // W and triggers >= 1 and resyncs <= 1
+    assert hc.hc_layer_window_slot(p.gpu.handle) == 8 % W
+    p.close()
+
+
 @pytest.mark.parametrize("G,W", [(1, 3), (2, 5), (8, 6), (4, 12)])
 def test_rescored_window_group_sizes_and_several_passes(G, W):
     """Group sizes 1, 2, 8 (32 / G queries per pass, at most 8) and a window whose earlier queries need two
