@@ -11,7 +11,7 @@
 //   * up to 32 query rows (32 / G buffered queries) form the A operand of v_mfma_f32_32x32x16_bf16 and stay
 //     in registers for the whole pass; a wave takes 32 positions at a time as the B operand;
 //   * a wave reads its 32 K rows (8 KB) with fully coalesced 16-byte loads (each instruction covers four
-//     whole rows), double-buffered in registers, and turns them into operand layout (lane = position,
+//     whole rows), two tiles in flight in registers, and turns them into operand layout (lane = position,
 //     8 consecutive dimensions per lane and instruction) through a private, padded LDS tile: no block
 //     barriers in the loop;
 //   * the accumulator layout puts G = 4 consecutive rows, i.e. the G heads of one query, into four
@@ -116,14 +116,13 @@ __global__ __launch_bounds__(RS_BLK) void rescore_logits_kernel(RescoreArgs a)
         }
     };
 
-    u32x4 nxt[8];
-    if (t0 < t1) load_tile(nxt, t0);
-#pragma unroll 1
-    for (int t = t0; t < t1; ++t) {
+    // Two tiles are in flight per wave (register buffers A and B): tile t is staged and consumed while t + 1 is
+    // on its way and t + 2 is requested.
+    auto consume = [&](u32x4 (&buf)[8], int t) {
 #pragma unroll
         for (int s = 0; s < 8; ++s)
-            *reinterpret_cast<u32x4*>(mine + (4 * s + lrow) * RS_LDS_ROW + lpiece * 16) = nxt[s];
-        if (t + 1 < t1) load_tile(nxt, t + 1);
+            *reinterpret_cast<u32x4*>(mine + (4 * s + lrow) * RS_LDS_ROW + lpiece * 16) = buf[s];
+        if (t + 2 < t1) load_tile(buf, t + 2);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
 
@@ -186,16 +185,28 @@ __global__ __launch_bounds__(RS_BLK) void rescore_logits_kernel(RescoreArgs a)
                 }
             }
         }
+    };
+    u32x4 bufA[8], bufB[8];
+    if (t0 < t1) load_tile(bufA, t0);
+    if (t0 + 1 < t1) load_tile(bufB, t0 + 1);
+#pragma unroll 1
+    for (int t = t0; t < t1; t += 2) {
+        consume(bufA, t);
+        if (t + 1 < t1) consume(bufB, t + 1);
     }
 
-    // merge over the 32 positions a half-wave holds, then over the waves
+    // merge over the 32 positions a half-wave holds (the common reference first, then one rescaling per lane
+    // and plain sums), then over the waves
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
+        float mm = m[v];
 #pragma unroll
-        for (int o = 1; o < 32; o <<= 1) {
-            const float mo = __shfl_xor(m[v], o), zo = __shfl_xor(z[v], o);
-            merge_ml(m[v], z[v], mo, zo);
-        }
+        for (int o = 1; o < 32; o <<= 1) mm = fmaxf(mm, __shfl_xor(mm, o));
+        float zz = z[v] * __builtin_amdgcn_exp2f(m[v] - mm);
+#pragma unroll
+        for (int o = 1; o < 32; o <<= 1) zz += __shfl_xor(zz, o);
+        m[v] = mm;
+        z[v] = zz;
     }
     if (col == 0) {
 #pragma unroll
@@ -328,8 +339,8 @@ hc_status hc_launch_logits_lse(hc_ctx* ctx, const hc_layer* L, const RepDev* rep
     if (n_items < 1 || n_items > hc_rescore_items_per_pass(ctx)) return hc_fail(ctx, HC_EINVAL, "scoring pass of %d queries", n_items);
     if (n_heads < 1) return HC_OK;
     const int tiles = (std::max(1, max_len) + RS_WG_TILE - 1) / RS_WG_TILE;
-    // two workgroups per compute unit over all heads (measured at 224K, two pivots: 31 us, against 35 us with
-    // four and 33 us with one), each with at least two iterations
+    // two workgroups per compute unit over all heads (measured at 224K, two pivots: 29.5 us, against 33-35 us with
+    // three or four and 31 us with one), each with at least two iterations
     const int want = std::max(1, 2 * ctx->n_cu / n_heads);
     const int nblk = std::max(1, std::min({(int)HC_RESCORE_MAX_BLOCKS, want, (tiles + 1) / 2}));
     RescoreArgs a{};
