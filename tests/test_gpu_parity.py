@@ -1024,6 +1024,19 @@ def test_rescored_window_growing_context_multi_step(use_side):
     p.close()
 
 
+def test_rescored_window_config4_full_size():
+    """The 224K layer with a window of 4 and a token appended before every step: the test step's three re-scored
+    queries (1792 workgroup tiles per pivot, 256 workgroups each) and the decision against the oracle."""
+    say("re-scored window, config 4 full size, 4 steps")
+    w = I.make_workload(4, device=DEV)
+    w.spec.window, w.spec.window_mode = 4, 2
+    p = U.Pair(w.spec, w.data, DEV, growth=8)
+    resyncs, triggers = run_steps(p, w.schedule, 4, side=torch.cuda.Stream(), tag="cfg4 rescored", append_seed=9900,
+                                  token_gain=lambda t: 30.0 if t == 1 else 0.0)
+    assert p.ref.n_tests == 2 and resyncs <= 1          # two pivots, one test step
+    p.close()
+
+
 @pytest.mark.parametrize("W", [1, 2])
 def test_rescored_window_of_one_and_two_steps(W):
     """W = 1: there is no earlier query to score again (the call only buffers the query); W = 2: one."""
