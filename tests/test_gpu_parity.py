@@ -1237,3 +1237,22 @@ def test_prefill_init_config4_full_size():
     torch.cuda.synchronize()
     U.check_attention(p.gpu.out, p.gpu.lse, p.ref.step(q.cpu()), "cfg4 after prefill")
     p.close()
+
+
+def test_prefill_and_rescored_window_on_a_very_short_context():
+    """70 positions (less than one 128-position tile of the contraction, one selection chunk), lists of 5 and 3,
+    pooling wider than the candidate range's margin, W = 3 with appended tokens: every kernel's ragged path."""
+    say("prefill + re-scored window, 70 positions")
+    heads = [I.HeadSpec(I.ROLE_FULL), I.HeadSpec(I.ROLE_SATELLITE, rep=0, sink=2, recent=3, budget=2 + 3 + 5),
+             I.HeadSpec(I.ROLE_ANCHOR, sink=1, recent=0, budget=1 + 3), I.HeadSpec(I.ROLE_SATELLITE, rep=0, sink=2, recent=3, budget=2 + 3 + 1)]
+    spec = I.LayerSpec(B=2, Hq=16, Hkv=4, D=128, ctx=[70, 33], heads=[heads, heads])
+    spec.window, spec.window_mode = 3, 2
+    q0 = I.draw_q(spec, 400)
+    data = I.draw_layer(spec, q0, 401, heavy_count=4)
+    q = q0.to(torch.bfloat16)
+    p, differed = U.Pair.from_prefill(spec, data, q, 9, DEV, growth=8)
+    assert differed == 0 and p.slots_equal_oracle() and p.tier_equals_masters()
+    resyncs, triggers = run_steps(p, I.QuerySchedule(q0, 402, step_deg=20.0), 6, tag="short", append_seed=9950,
+                                  token_gain=lambda t: 20.0 if t % 2 else 0.0)
+    assert p.ref.n_tests == 4 and resyncs == 0
+    p.close()
