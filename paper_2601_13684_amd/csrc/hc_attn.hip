@@ -484,6 +484,17 @@ __global__ __launch_bounds__(1024) void attn_combine_kernel(const HeadDev* __res
     const float2* ml = reinterpret_cast<const float2*>(part_ml);
     const float4* pa = reinterpret_cast<const float4*>(part_acc);
 
+    // The first 128 partials' loads do not depend on the common maximum: they are issued before it is known,
+    // so that the pass costs two memory round trips (descriptor, then everything) instead of three.
+    float2 mz[4];
+    float4 a[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int s = pl + 32 * u;
+        const size_t slot = (size_t)(hd.part_begin + (s < n ? s : 0));
+        mz[u] = ml[slot * G + g];
+        a[u] = pa[(slot * G + g) * (HC_D / 4) + dq];
+    }
     float mx = M_INIT;
     for (int s = tid; s < n; s += 1024) mx = fmaxf(mx, ml[(size_t)(hd.part_begin + s) * G + g].x);
     for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
@@ -496,14 +507,14 @@ __global__ __launch_bounds__(1024) void attn_combine_kernel(const HeadDev* __res
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     float z = 0.f;
     for (int s0 = pl; s0 < n; s0 += 128) {
-        float2 mz[4];
-        float4 a[4];
+        if (s0 != pl) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int s = s0 + 32 * u;
-            const size_t slot = (size_t)(hd.part_begin + (s < n ? s : pl));
-            mz[u] = ml[slot * G + g];
-            a[u] = pa[(slot * G + g) * (HC_D / 4) + dq];
+            for (int u = 0; u < 4; ++u) {
+                const int s = s0 + 32 * u;
+                const size_t slot = (size_t)(hd.part_begin + (s < n ? s : 0));
+                mz[u] = ml[slot * G + g];
+                a[u] = pa[(slot * G + g) * (HC_D / 4) + dq];
+            }
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
