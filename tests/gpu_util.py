@@ -103,6 +103,8 @@ class Pair:
 
     def tier_equals_masters(self):
         """Every satellite's block of the host tier holds its whole K and V, K row then V row per position."""
+        if self.gpu.tier is None:               # a layer without satellites has no host tier
+            return all(h.role != I.ROLE_SATELLITE for row in self.spec.heads for h in row)
         tier = self.gpu.tier.view(torch.int16).numpy().view(np.uint16)
         for b in range(self.spec.B):
             for h in range(self.spec.Hkv):
