@@ -329,7 +329,9 @@ hc_status hc_prefill_init(hc_ctx* ctx, hc_layer* layer, const void* kv_prefill, 
  * hc_rescore_work_layout reports: place i holds the last query k with k mod items_per_pass == i, which
  * is what the tests read).  Uses the context's
  * selection workspaces like a batched monitor call: stream-order it with other monitor calls.
- * Enqueue-only, no allocation.  W == 1 or a layer without pivots: only the copy happens. */
+ * Enqueue-only, no allocation.  W == 1 or a layer without pivots: only the copy happens.  Which row the
+ * queries go to and whether the passes run is decided on the host when the call is made, so a captured
+ * graph of this call would repeat one step of the window: capture whole windows (W calls) or none. */
 size_t hc_rescore_work_bytes(const hc_ctx* ctx, const hc_layer* layer);
 /* Byte offsets of the passes' results inside `work` and how many queries a pass holds
  * (min(8, 32 / G)): logits [items][num_reps][max_ctx][G] f32, scores [items][num_reps][max_ctx] f32,
