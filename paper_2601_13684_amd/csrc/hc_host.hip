@@ -583,13 +583,15 @@ extern "C" hc_status hc_layer_create(hc_ctx* ctx, const hc_head_desc* hd, hc_lay
         L->rep_lo_host.push_back(r.lo);
         L->rep_recent_host.push_back(hd[r.bh].ctx - r.hi);
     }
-    // a plan has at most one segment per workgroup plus one per head boundary: room for any later plan
-    L->seg_capacity = P.n_blocks + L->n_heads;
+    // a plan has at most one segment per workgroup plus one per head boundary, and a short layer gets more
+    // workgroups as it grows: room for any later plan
+    L->blk_capacity = ctx->wg_per_cu * ctx->n_cu;
+    L->seg_capacity = L->blk_capacity + L->n_heads;
 
     st = ensure_partials(ctx, (size_t)L->seg_capacity);
     if (st == HC_OK) st = upload(ctx, P.heads, &L->heads);
     if (st == HC_OK) st = upload(ctx, P.segs, &L->segs, (size_t)L->seg_capacity);
-    if (st == HC_OK) st = upload(ctx, P.blks, &L->blks);
+    if (st == HC_OK) st = upload(ctx, P.blks, &L->blks, (size_t)L->blk_capacity);
     if (st == HC_OK) st = upload(ctx, P.reps, &L->reps);
     if (st == HC_OK) st = upload(ctx, P.outs, &L->outs);
     if (st == HC_OK) st = upload(ctx, P.sats, &L->sats);
@@ -747,7 +749,7 @@ static hc_status replan(hc_ctx* ctx, hc_layer* L, hipStream_t st)
     hc_status s = make_plan(ctx->cfg, L->hd_host.data(), ctx->n_cu, ctx->wg_per_cu, ctx->share_weights, P,
                             ErrBuf{ctx->err, sizeof ctx->err});
     if (s != HC_OK) return s;
-    if (P.n_blocks != L->n_blocks || (int)P.segs.size() > L->seg_capacity || (int)P.reps.size() != L->n_reps)
+    if (P.n_blocks > L->blk_capacity || (int)P.segs.size() > L->seg_capacity || (int)P.reps.size() != L->n_reps)
         return hc_fail(ctx, HC_ESTATE, "internal: a rebalanced plan does not fit the layer");
     for (int i = 0; i < L->n_heads; ++i) P.heads[i].ctx0 = L->ctx0_host[i];        // the ring of recent slots keeps its origin
     HC_HIP(ctx, hipMemcpyAsync(L->heads, P.heads.data(), P.heads.size() * sizeof(HeadDev), hipMemcpyHostToDevice, st));
@@ -755,6 +757,7 @@ static hc_status replan(hc_ctx* ctx, hc_layer* L, hipStream_t st)
     HC_HIP(ctx, hipMemcpyAsync(L->blks, P.blks.data(), P.blks.size() * sizeof(BlkDev), hipMemcpyHostToDevice, st));
     HC_HIP(ctx, hipMemcpyAsync(L->reps, P.reps.data(), P.reps.size() * sizeof(RepDev), hipMemcpyHostToDevice, st));
     HC_HIP(ctx, hipStreamSynchronize(st));        // the host vectors go away; rare (every 64 tokens)
+    L->n_blocks = P.n_blocks;
     L->n_segs = L->n_partials = (int)P.segs.size();
     L->max_nchunk = P.max_nchunk;
     L->appended_since_plan = 0;

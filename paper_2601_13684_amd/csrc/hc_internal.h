@@ -134,6 +134,7 @@ struct hc_layer {
     std::vector<int32_t> sel_head_host; // table rows of the selecting heads, in the order of sel_reps
     int window_slot = 0;                // hc_decode_step with a re-scored window: monitored steps since the window was emptied
     int seg_capacity = 0;               // device room in segs (a rebalanced plan may have a few more segments)
+    int blk_capacity = 0;               // device room in blks (a short layer gets more workgroups as it grows)
     HeadDev* heads = nullptr;
     SegDev* segs = nullptr;
     BlkDev* blks = nullptr;        // [n_blocks]

@@ -1053,6 +1053,21 @@ def test_rescored_window_of_one_and_two_steps(W):
     p.close()
 
 
+def test_rescored_window_of_the_maximum_width():
+    """W = 64, the largest window the library takes: 63 buffered queries, eight passes of the contraction."""
+    say("re-scored window, W 64")
+    spec = I.spec_tiny(1500, budget=200, sink=8, recent=4)
+    spec.window, spec.window_mode = 64, 2
+    q0 = I.draw_q(spec, 195)
+    data = I.draw_layer(spec, q0, 196, heavy_count=20)
+    p = U.Pair(spec, data, DEV, growth=72)
+    resyncs, triggers = run_steps(p, I.QuerySchedule(q0, 197, step_deg=3.0), 66, tag="rescored W64", append_seed=9850,
+                                  token_gain=lambda t: 30.0 if t % 7 == 0 else 0.0)
+    assert p.ref.n_tests == 1 and resyncs <= 1
+    assert hc.hc_layer_window_slot(p.gpu.handle) == 2
+    p.close()
+
+
 @pytest.mark.parametrize("G,W", [(1, 3), (2, 5), (8, 6), (4, 12)])
 def test_rescored_window_group_sizes_and_several_passes(G, W):
     """Group sizes 1, 2, 8 (32 / G queries per pass, at most 8) and a window whose earlier queries need two
