@@ -15,10 +15,10 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def random_spec(rng: random.Random):
-    B = rng.choice([1, 1, 2, 3])
-    G = rng.choice([1, 2, 4, 4, 8])
-    Hkv = rng.randint(2, 6)
+def random_spec(rng: random.Random, B=None, G=None, Hkv=None, common=None):
+    B = B or rng.choice([1, 1, 2, 3])
+    G = G or rng.choice([1, 2, 4, 4, 8])
+    Hkv = Hkv or rng.randint(2, 6)
     rows, ctx = [], []
     for b in range(B):
         N = rng.choice([rng.randint(150, 700), rng.randint(700, 6000)])
@@ -42,12 +42,10 @@ def random_spec(rng: random.Random):
                 row.append(I.HeadSpec(I.ROLE_SATELLITE, rep=p, sink=sink, recent=recent,
                                       budget=sink + recent + rng.randint(1, min(300, room))))
         rows.append(row)
-    spec = I.LayerSpec(B=B, Hq=Hkv * G, Hkv=Hkv, D=128, ctx=ctx, heads=rows,
-                       metric=rng.choice([I.METRIC_OVERLAP, I.METRIC_JACCARD]), tau_num=rng.choice([1, 3, 4]), tau_den=5,
-                       agg=rng.choice([I.AGG_PROB, I.AGG_PROB, I.AGG_LOGIT]))
-    spec.window = rng.choice([1, 1, 2, 3, 4])
-    spec.window_mode = rng.choice([0, 1, 2])
-    return spec
+    common = common or dict(metric=rng.choice([I.METRIC_OVERLAP, I.METRIC_JACCARD]), tau_num=rng.choice([1, 3, 4]), tau_den=5,
+                            agg=rng.choice([I.AGG_PROB, I.AGG_PROB, I.AGG_LOGIT]), window=rng.choice([1, 1, 2, 3, 4]),
+                            window_mode=rng.choice([0, 1, 2]))
+    return I.LayerSpec(B=B, Hq=Hkv * G, Hkv=Hkv, D=128, ctx=ctx, heads=rows, **common)
 
 
 @pytest.mark.parametrize("seed", list(range(int(os.environ.get("HC_RANDOM_CASES", "16")))))      # more cases on request
@@ -86,3 +84,92 @@ def test_random_layer(seed):
     if grow:
         assert [p.gpu.context(b) for b in range(spec.B)] == p.ref.ctx
     p.close()
+
+
+@pytest.mark.parametrize("seed", list(range(int(os.environ.get("HC_RANDOM_STACKS", "6")))))
+def test_random_stack_through_the_decode_step(seed):
+    """2-9 layers that differ in everything a layer may differ in (roles, budgets, windows of recent positions) through
+    hc_decode_step: batched monitor, gather and window re-scoring over unlike layers, appended tokens, random group size."""
+    import gpu_util as U
+    import test_gpu_parity as T
+    rng = random.Random(3000 + seed)
+    first = random_spec(rng)
+    common = dict(metric=first.metric, tau_num=first.tau_num, tau_den=first.tau_den, agg=first.agg, window=first.window,
+                  window_mode=first.window_mode)
+    n_layers = rng.randint(2, 9)
+    specs = [first] + [random_spec(rng, first.B, first.G, first.Hkv, common) for _ in range(n_layers - 1)]
+    for sp in specs[1:]:
+        sp.ctx = list(first.ctx)                # one batch: the sequences have the same lengths in every layer
+        for b in range(sp.B):                   # ... so budgets drawn for another length are cut to fit
+            sp.heads[b] = [h if h.role == I.ROLE_FULL else
+                           I.HeadSpec(h.role, rep=h.rep, sink=min(h.sink, 4), recent=min(h.recent, 8),
+                                      budget=min(h.sink, 4) + min(h.recent, 8) + max(1, min(h.budget - h.sink - h.recent, sp.ctx[b] - 64)))
+                           for h in sp.heads[b]]
+            for p in sp.reps(b):                # satellites of one pivot share sink and recent
+                sats = sp.satellites(b, p)
+                s0 = sp.heads[b][sats[0]]
+                for si in sats[1:]:
+                    h = sp.heads[b][si]
+                    sp.heads[b][si] = I.HeadSpec(h.role, rep=h.rep, sink=s0.sink, recent=s0.recent,
+                                                 budget=s0.sink + s0.recent + (h.budget - h.sink - h.recent))
+    steps = rng.randint(5, 8)
+    grow = rng.random() < 0.6
+    growth = steps + 1 if grow else 0
+    group = rng.choice([1, 2, 4, 8])
+    side = torch.cuda.Stream() if rng.random() < 0.7 else None
+    T.say(f"random stack {seed}: {n_layers} layers, B {first.B} G {first.G} Hkv {first.Hkv} ctx {first.ctx} W {first.window} "
+          f"mode {first.window_mode} grow {grow} group {group} side {side is not None}")
+    cfg = R.make_config(first, growth=growth, max_k=max(R.make_config(sp, growth=growth).max_k for sp in specs))
+    ctx = R.Context(cfg, DEV)
+    pairs, scheds = [], []
+    for l, sp in enumerate(specs):
+        q0 = I.draw_q(sp, 3100 + 10 * seed + l)
+        data = I.draw_layer(sp, q0, 3200 + 10 * seed + l, heavy_count=10)
+        pr = U.Pair(sp, data, DEV, ctx=ctx, growth=growth)
+        pr.gpu.rep_logits = torch.zeros_like(pr.gpu.rep_logits)      # own buffers: the layers' monitors run together
+        pr.gpu.scores = torch.zeros_like(pr.gpu.scores)
+        pairs.append(pr)
+        scheds.append(I.QuerySchedule(q0, 3300 + 10 * seed + l, step_deg=rng.choice([5.0, 20.0])))
+    B, Hq, Hkv = first.B, first.Hq, first.Hkv
+    q_cur = torch.zeros((n_layers, B, Hq, 128), dtype=torch.bfloat16, device=DEV)
+    k_cur = torch.zeros((n_layers, B, Hkv, 128), dtype=torch.bfloat16, device=DEV)
+    v_cur = torch.zeros_like(k_cur)
+    io = R.make_step_io([pr.gpu for pr in pairs], q_cur)
+    if grow:
+        for l in range(n_layers):
+            io[l].k_new, io[l].v_new = k_cur[l].data_ptr(), v_cur[l].data_ptr()
+    for t in range(steps):
+        qs = [s.next() for s in scheds]
+        torch.cuda.synchronize()
+        for l in range(n_layers):
+            q_cur[l].copy_(qs[l])
+            if grow:
+                kn, vn = I.draw_token(specs[l], 3400 + 100 * seed + 10 * t + l, toward=qs[l], gain=25.0 if t % 3 == 1 else 0.0)
+                k_cur[l].copy_(kn)
+                v_cur[l].copy_(vn)
+                pairs[l].ref.append(kn, vn)
+        hc.hc_decode_step(ctx.handle, io, n_layers, None, side, group)
+        torch.cuda.synchronize()
+        for l, pr in enumerate(pairs):
+            sp = specs[l]
+            rec = pr.ref.step(qs[l])
+            U.check_attention(pr.gpu.out, pr.gpu.lse, rec, f"stack {seed} L{l} t{t}")
+            same = True
+            topk = pr.gpu.topk_idx.cpu().numpy()
+            for (b, pv), s_ref in rec["scores"].items():
+                for h in [pv] + sp.satellites(b, pv):
+                    Tl = rec["topk"][(b, h)]
+                    if U.check_set_valid(topk[b * Hkv + h, :Tl.size], Tl, s_ref, 1e-4, f"stack {seed} L{l} t{t} head {h}"):
+                        same = False
+                if (b, pv) in rec["rescored"]:
+                    same &= T.check_rescored(pr, rec, b, pv, 1e-4, f"stack {seed} L{l} t{t}")
+                gi, gf = int(pr.gpu.inter[b * Hkv + pv]), int(pr.gpu.flag[b * Hkv + pv])
+                if gi != rec["inter"][(b, pv)] or gf != rec["flag"][(b, pv)]:
+                    assert not same, (seed, l, t, "same sets but different inter / flag")
+                    same = False
+            if not same:
+                T.resync(pr, rec)
+            assert pr.slots_equal_oracle(), f"stack {seed}: slots differ, layer {l} step {t}"
+    for pr in pairs:
+        pr.close()
+    ctx.close()
