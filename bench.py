@@ -154,6 +154,12 @@ def main():
     torch.cuda.synchronize()
     setup_s = time.time() - t_setup
 
+    # Every step's queries (and generated tokens) are resident in HBM before the timed region.  A captured graph has
+    # to pick the step's rows on the device (a gather into fixed buffers, part of the replayed work); the other modes
+    # simply hand the library the step's rows.
+    dev_index = args.mode == "graph"
+    t_pos = [0]
+
     def load_q():
         q_cur.copy_(Q_all.index_select(0, t_dev)[0])
         if KV_new is not None:
@@ -161,16 +167,21 @@ def main():
         t_dev.add_(1)
 
     def step_eager():
-        load_q()
+        if dev_index:
+            load_q()
+            q_t, kv_t = q_cur, (kv_cur if KV_new is not None else None)
+        else:
+            q_t, kv_t = Q_all[t_pos[0]], (KV_new[t_pos[0]] if KV_new is not None else None)
+        t_pos[0] += 1
         for l, lay in enumerate(layers):
-            if KV_new is not None:
+            if kv_t is not None:
                 if lay._side_pending:
                     torch.cuda.current_stream().wait_event(lay.ev_done)
-                lay.append(kv_cur[0, l], kv_cur[1, l])
+                lay.append(kv_t[0, l], kv_t[1, l])
             if args.attn_only:
-                lay.attn(q_cur[l], monitor=False)
+                lay.attn(q_t[l], monitor=False)
             else:
-                lay.step(q_cur[l], side=None if args.serial else side)
+                lay.step(q_t[l], side=None if args.serial else side)
 
     def step_for_capture():
         # the same calls; every layer's side-stream work (monitor, gather) is joined back before the step
@@ -208,13 +219,19 @@ def main():
     graph = None
     if args.mode == "step":
         io = R.make_step_io(layers, q_cur, monitor=not args.attn_only)
-        if KV_new is not None:
-            for l in range(L):
-                io[l].k_new, io[l].v_new = kv_cur[0, l].data_ptr(), kv_cur[1, l].data_ptr()
         main_s = torch.cuda.current_stream()
+        q_base, q_step, q_layer = Q_all.data_ptr(), Q_all.stride(0) * 2, Q_all.stride(1) * 2
+        if KV_new is not None:
+            kv_base, kv_step, kv_which, kv_layer = KV_new.data_ptr(), KV_new.stride(0) * 2, KV_new.stride(1) * 2, KV_new.stride(2) * 2
 
         def run():
-            load_q()
+            t = t_pos[0]
+            t_pos[0] += 1
+            for l in range(L):
+                io[l].q = q_base + t * q_step + l * q_layer
+                if KV_new is not None:
+                    io[l].k_new = kv_base + t * kv_step + l * kv_layer
+                    io[l].v_new = kv_base + t * kv_step + kv_which + l * kv_layer
             hc.hc_decode_step(ctx.handle, io, L, main_s, None if (args.serial or args.attn_only) else side, args.group)
     elif args.mode == "graph":
         cap = torch.cuda.Stream()
@@ -269,7 +286,13 @@ def main():
         n_iso = min(K, 8)
         hc.hc_set_timing_events(ctx.handle, [a for a, _ in evs[:n_iso * L]], [b for _, b in evs[:n_iso * L]])
         for _ in range(n_iso):
-            load_q()
+            t = t_pos[0]
+            t_pos[0] += 1
+            for l in range(L):
+                io[l].q = q_base + t * q_step + l * q_layer
+                if KV_new is not None:
+                    io[l].k_new = kv_base + t * kv_step + l * kv_layer
+                    io[l].v_new = kv_base + t * kv_step + kv_which + l * kv_layer
             hc.hc_decode_step(ctx.handle, io, L, main_s, None, args.group)
         hc.hc_set_timing_events(ctx.handle)
         torch.cuda.synchronize()
