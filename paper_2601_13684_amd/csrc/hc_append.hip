@@ -8,15 +8,41 @@
 // device tables on (the head's context length; a full head's resident length and the end of its last
 // split-K segment, in the segment table and in the workgroup descriptor that carries a copy of it; a pivot's
 // candidate range), so that no host copy is needed per token.
+#include <algorithm>
+
 #include "hc_internal.h"
 
 namespace {
 
-__global__ __launch_bounds__(64) void append_kernel(HeadDev* __restrict__ heads, SegDev* __restrict__ segs,
-                                                    BlkDev* __restrict__ blks, RepDev* __restrict__ reps,
-                                                    const uint32_t* __restrict__ k_new, const uint32_t* __restrict__ v_new,
-                                                    uint32_t* __restrict__ arena, uint32_t* __restrict__ tier)
+// One layer of a batched call (blockIdx.y picks the layer): the layers of a hc_decode_step group take their
+// tokens with one launch.
+struct AppendItem {
+    HeadDev* heads;
+    SegDev* segs;
+    BlkDev* blks;
+    RepDev* reps;
+    const uint32_t* k_new;
+    const uint32_t* v_new;
+    uint32_t* arena;
+    uint32_t* tier;
+    int n_heads, pad;
+};
+struct AppendBatch {
+    AppendItem it[HC_MAX_GROUP];
+};
+
+__global__ __launch_bounds__(64) void append_kernel(AppendBatch B)
 {
+    const AppendItem& it = B.it[blockIdx.y];
+    if ((int)blockIdx.x >= it.n_heads) return;
+    HeadDev* __restrict__ heads = it.heads;
+    SegDev* __restrict__ segs = it.segs;
+    BlkDev* __restrict__ blks = it.blks;
+    RepDev* __restrict__ reps = it.reps;
+    const uint32_t* __restrict__ k_new = it.k_new;
+    const uint32_t* __restrict__ v_new = it.v_new;
+    uint32_t* __restrict__ arena = it.arena;
+    uint32_t* __restrict__ tier = it.tier;
     const int bh = blockIdx.x, t = threadIdx.x;
     const HeadDev hd = heads[bh];
     const int pos = hd.ctx;                                      // the new position
@@ -55,11 +81,18 @@ __global__ __launch_bounds__(64) void append_kernel(HeadDev* __restrict__ heads,
 
 }   // namespace
 
-hc_status hc_launch_append(hc_ctx* ctx, const hc_layer* L, const void* k_new, const void* v_new, void* arena, void* tier,
-                           hipStream_t st)
+hc_status hc_launch_append(hc_ctx* ctx, int n, const hc_append_call* calls, hipStream_t st)
 {
-    append_kernel<<<dim3(L->n_heads), dim3(64), 0, st>>>(L->heads, L->segs, L->blks, L->reps, (const uint32_t*)k_new,
-                                                         (const uint32_t*)v_new, (uint32_t*)arena, (uint32_t*)tier);
+    if (n < 1 || n > HC_MAX_GROUP) return hc_fail(ctx, HC_EINVAL, "append batch of %d layers", n);
+    AppendBatch B{};
+    int max_heads = 0;
+    for (int i = 0; i < n; ++i) {
+        const hc_append_call& x = calls[i];
+        B.it[i] = AppendItem{x.L->heads, x.L->segs, x.L->blks, x.L->reps, (const uint32_t*)x.k_new, (const uint32_t*)x.v_new,
+                             (uint32_t*)x.arena, (uint32_t*)x.tier, x.L->n_heads, 0};
+        max_heads = std::max(max_heads, x.L->n_heads);
+    }
+    append_kernel<<<dim3(max_heads, n), dim3(64), 0, st>>>(B);
     HC_HIP(ctx, hipGetLastError());
     return HC_OK;
 }

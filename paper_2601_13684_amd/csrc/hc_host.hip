@@ -764,27 +764,28 @@ static hc_status replan(hc_ctx* ctx, hc_layer* L, hipStream_t st)
     return HC_OK;
 }
 
-extern "C" hc_status hc_append_kv(hc_ctx* ctx, hc_layer* layer, const void* k_new, const void* v_new, void* kv_arena,
-                                  void* host_tier, void* stream)
+static hc_status append_check(hc_ctx* ctx, const hc_layer* layer, const void* k_new, const void* v_new, const void* kv_arena,
+                              const void* host_tier)
 {
-    if (!ctx_ok(ctx)) return HC_ESTATE;
     if (!layer_ok(layer) || layer->ctx != ctx) return hc_fail(ctx, HC_ESTATE, "hc_append_kv: layer does not belong to this context");
     if (!k_new || !v_new || !kv_arena) return hc_fail(ctx, HC_EINVAL, "hc_append_kv: null pointer");
     if (((uintptr_t)k_new | (uintptr_t)v_new | (uintptr_t)kv_arena | (uintptr_t)host_tier) & 3)
         return hc_fail(ctx, HC_EINVAL, "hc_append_kv: pointers must be 4-byte aligned");
-    hc_layer* L = layer;
-    for (int i = 0; i < L->n_heads; ++i) {
-        const hc_head_desc& h = L->hd_host[i];
+    for (int i = 0; i < layer->n_heads; ++i) {
+        const hc_head_desc& h = layer->hd_host[i];
         const bool grows = h.role == HC_ROLE_FULL || h.role == HC_ROLE_SATELLITE;
         if (h.ctx + 1 > ctx->cfg.max_ctx || (grows && h.ctx + 1 > (h.cap ? h.cap : h.ctx)))
             return hc_fail(ctx, HC_ESHAPE, "hc_append_kv: head %d has no room for position %d (cap %d, max_ctx %d)", i, h.ctx,
                            h.cap, ctx->cfg.max_ctx);
         if (h.role == HC_ROLE_SATELLITE && !host_tier) return hc_fail(ctx, HC_EINVAL, "hc_append_kv: host_tier is needed for satellites");
     }
-    hipStream_t st = (hipStream_t)stream;
-    const hc_status s = hc_launch_append(ctx, L, k_new, v_new, kv_arena, host_tier, st);
-    if (s != HC_OK) return s;
-    // the host's copy of the lengths follows what the kernel does to the device tables
+    return HC_OK;
+}
+
+// The host's copy of the lengths follows what the kernel does to the device tables; every 64 tokens the
+// split-K plan is rebalanced.
+static hc_status append_done(hc_ctx* ctx, hc_layer* L, hipStream_t st)
+{
     for (int i = 0; i < L->n_heads; ++i) {
         hc_head_desc& h = L->hd_host[i];
         h.ctx += 1;
@@ -801,6 +802,19 @@ extern "C" hc_status hc_append_kv(hc_ctx* ctx, hc_layer* layer, const void* k_ne
     ++L->total_appended;
     if (++L->appended_since_plan >= 64) return replan(ctx, L, st);
     return HC_OK;
+}
+
+extern "C" hc_status hc_append_kv(hc_ctx* ctx, hc_layer* layer, const void* k_new, const void* v_new, void* kv_arena,
+                                  void* host_tier, void* stream)
+{
+    if (!ctx_ok(ctx)) return HC_ESTATE;
+    hc_status s = append_check(ctx, layer, k_new, v_new, kv_arena, host_tier);
+    if (s != HC_OK) return s;
+    hipStream_t st = (hipStream_t)stream;
+    const hc_append_call call{layer, k_new, v_new, kv_arena, host_tier};
+    s = hc_launch_append(ctx, 1, &call, st);
+    if (s != HC_OK) return s;
+    return append_done(ctx, layer, st);
 }
 
 // Share weights measured on the device at hand.  Which dies stream slower differs from one MI355X to the
@@ -1109,6 +1123,9 @@ extern "C" hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* io, int32_t 
         void* push_dst[HC_MAX_GROUP];
         RescoreJob test_job[HC_MAX_GROUP];
         int n_push = 0, n_test = 0;
+        // the tokens of the group's layers enter their caches with one launch, ahead of the group's attention
+        hc_append_call app[HC_MAX_GROUP];
+        int n_app = 0;
         for (int l = g0; l < g1; ++l) {
             const hc_layer_io& x = io[l];
             hc_layer* L = x.layer;
@@ -1117,6 +1134,20 @@ extern "C" hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* io, int32_t 
                 last_waited = L->pending_ev;
                 L->pending_ev = nullptr;
             }
+            if (x.k_new || x.v_new) {
+                const hc_status sa = append_check(ctx, L, x.k_new, x.v_new, x.kv_arena, x.host_tier);
+                if (sa != HC_OK) return sa;
+                app[n_app++] = hc_append_call{L, x.k_new, x.v_new, const_cast<void*>(x.kv_arena), const_cast<void*>(x.host_tier)};
+            }
+        }
+        if (n_app > 0) {
+            hc_status sa = hc_launch_append(ctx, n_app, app, ms);
+            for (int i = 0; i < n_app && sa == HC_OK; ++i) sa = append_done(ctx, const_cast<hc_layer*>(app[i].L), ms);
+            if (sa != HC_OK) return sa;
+        }
+        for (int l = g0; l < g1; ++l) {
+            const hc_layer_io& x = io[l];
+            hc_layer* L = x.layer;
             const bool side = L->n_reps > 0 && x.scores != nullptr;
             if (side) {
                 hc_status st = monitor_check(ctx, L, x.rep_logits, x.lse, x.scores, 0, x.topk_idx, x.base_idx, x.ring, x.inter, x.flag);
@@ -1136,11 +1167,6 @@ extern "C" hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* io, int32_t 
                     if (st != HC_OK) return st;
                     gat[n_gat++] = hc_gather_call{L, x.host_tier, x.topk_idx, x.flag, const_cast<void*>(x.kv_arena), x.slot_pos};
                 }
-            }
-            if (x.k_new || x.v_new) {
-                const hc_status sa = hc_append_kv(ctx, L, x.k_new, x.v_new, const_cast<void*>(x.kv_arena),
-                                                  const_cast<void*>(x.host_tier), ms);
-                if (sa != HC_OK) return sa;
             }
             const hc_status st = hc_decode_attn(ctx, L, x.kv_arena, x.q, x.out, x.lse, side ? x.rep_logits : nullptr, ms);
             if (st != HC_OK) return st;

@@ -211,5 +211,11 @@ hc_status hc_launch_prefill_place(hc_ctx* ctx, const hc_layer* L, const void* kv
                                   const int32_t* topk_idx, int32_t* base_idx, int32_t* slot_pos, int32_t* ring, hipStream_t st);
 hc_status hc_launch_rescore_logits(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* q_window, int first,
                                    int n_items, void* work, hipStream_t st);
-hc_status hc_launch_append(hc_ctx* ctx, const hc_layer* L, const void* k_new, const void* v_new, void* arena, void* tier,
-                           hipStream_t st);
+struct hc_append_call {
+    const hc_layer* L;
+    const void* k_new;
+    const void* v_new;
+    void* arena;
+    void* tier;            // or nullptr (a layer without satellites)
+};
+hc_status hc_launch_append(hc_ctx* ctx, int n, const hc_append_call* calls, hipStream_t st);
