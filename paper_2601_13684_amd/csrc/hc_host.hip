@@ -957,8 +957,9 @@ extern "C" hc_status hc_prefill_init(hc_ctx* ctx, hc_layer* layer, const void* k
         float* logits = (float*)(wb + lay.logits_off);
         float* scores = (float*)(wb + lay.scores_off);
         float* lse = (float*)(wb + lay.lse_off);
-        hc_status s = hc_launch_logits_lse(ctx, L, L->sel_reps, L->n_sel, L->sel_max_len, kv_prefill, L->pre_src, q_last, 1, logits, 0,
-                                           lse, 0, (float*)(wb + lay.part_off), st);
+        const hc_logits_job job{L, L->sel_reps, L->n_sel, L->sel_max_len, kv_prefill, L->pre_src, q_last, logits, 0, lse, 0,
+                                (float*)(wb + lay.part_off)};
+        hc_status s = hc_launch_logits_lse(ctx, 1, &job, 1, st);
         if (s == HC_OK) s = hc_launch_prefill_scores(ctx, L, logits, lse, scores, pool, st);
         if (s != HC_OK) return s;
         int32_t* scratch = (int32_t*)(wb + lay.scratch_off);
@@ -1026,10 +1027,15 @@ static hc_status rescore_passes(hc_ctx* ctx, int n_jobs, const RescoreJob* jobs,
     const int per = hc_rescore_items_per_pass(ctx);
     for (int first = 0; first < W - 1; first += per) {
         const int n = std::min(per, W - 1 - first);
-        for (int j = 0; j < n_jobs; ++j) {
-            if (jobs[j].L->n_reps == 0) continue;
-            const hc_status s = hc_launch_rescore_logits(ctx, jobs[j].L, jobs[j].kv_arena, jobs[j].q_window, first, n, jobs[j].work, st);
-            if (s != HC_OK) return s;
+        {
+            hc_logits_job lj[HC_MAX_GROUP];
+            int n_lj = 0;
+            for (int j = 0; j < n_jobs; ++j)
+                if (jobs[j].L->n_reps > 0) lj[n_lj++] = hc_rescore_job(ctx, jobs[j].L, jobs[j].kv_arena, jobs[j].q_window, first, jobs[j].work);
+            if (n_lj > 0) {
+                const hc_status s = hc_launch_logits_lse(ctx, n_lj, lj, n, st);
+                if (s != HC_OK) return s;
+            }
         }
         hc_monitor_call calls[HC_MAX_GROUP];
         int n_calls = 0;

@@ -196,9 +196,21 @@ struct hc_rescore_layout {
 int hc_rescore_items_per_pass(const hc_ctx* ctx);
 hc_rescore_layout hc_rescore_plan(const hc_ctx* ctx, const hc_layer* L);
 hc_status hc_launch_rescore_push(hc_ctx* ctx, int n, const void* const* q, void* const* dst, hipStream_t st);
-hc_status hc_launch_logits_lse(hc_ctx* ctx, const hc_layer* L, const RepDev* reps, int n_heads, int max_len, const void* arena,
-                               const PreSrc* src, const void* q, int n_items, float* logits, size_t logits_item, float* lse,
-                               size_t lse_item, float* part, hipStream_t st);
+struct hc_logits_job {
+    const hc_layer* L;
+    const RepDev* reps;        // the heads to score against, n_heads of them; max_len: the longest
+    int n_heads, max_len;
+    const void* arena;         // where their K rows are (see src)
+    const PreSrc* src;
+    const void* q;             // first query
+    float* logits;
+    size_t logits_item;
+    float* lse;
+    size_t lse_item;
+    float* part;
+};
+hc_status hc_launch_logits_lse(hc_ctx* ctx, int n_jobs, const hc_logits_job* jobs, int n_items, hipStream_t st);
+hc_logits_job hc_rescore_job(const hc_ctx* ctx, const hc_layer* L, const void* arena, const void* q_window, int first, void* work);
 // prefill-time initialisation
 constexpr int HC_MAX_POOL = 63;
 struct hc_prefill_layout {
@@ -209,8 +221,6 @@ hc_status hc_launch_prefill_scores(hc_ctx* ctx, const hc_layer* L, const float* 
                                    hipStream_t st);
 hc_status hc_launch_prefill_place(hc_ctx* ctx, const hc_layer* L, const void* kv_prefill, void* arena, void* tier,
                                   const int32_t* topk_idx, int32_t* base_idx, int32_t* slot_pos, int32_t* ring, hipStream_t st);
-hc_status hc_launch_rescore_logits(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* q_window, int first,
-                                   int n_items, void* work, hipStream_t st);
 struct hc_append_call {
     const hc_layer* L;
     const void* k_new;

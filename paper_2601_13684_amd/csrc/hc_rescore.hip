@@ -39,6 +39,8 @@ constexpr float RS_INV_SQRT_D = 0.08838834764831845f;   // 1/sqrt(128), the fact
 constexpr float RS_SLACK = 16.0f;               // a term of the running sum is at most 2^16 times the reference's
 constexpr float RS_M_INIT = -1.0e30f;           // finite: (old - new) never is inf - inf
 
+// One layer of a batched launch (blockIdx.z picks the layer): the layers of a hc_decode_step group reach the
+// end of their windows together, and one launch over all their pivots amortises what a launch costs.
 struct RescoreArgs {
     const HeadDev* heads;
     const RepDev* reps;
@@ -53,6 +55,9 @@ struct RescoreArgs {
     const PreSrc* src;              // prefill-time use: the K rows of head bh are at arena + src[bh].k_off, all ctx of them
     int n_items, n_reps, max_ctx, nblk;
 };
+struct RescoreBatch {
+    RescoreArgs it[HC_MAX_GROUP];
+};
 
 __device__ __forceinline__ void merge_ml(float& m, float& z, float mo, float zo)
 {
@@ -62,8 +67,10 @@ __device__ __forceinline__ void merge_ml(float& m, float& z, float mo, float zo)
 }
 
 template <int G>
-__global__ __launch_bounds__(RS_BLK) void rescore_logits_kernel(RescoreArgs a)
+__global__ __launch_bounds__(RS_BLK) void rescore_logits_kernel(RescoreBatch batch)
 {
+    const RescoreArgs& a = batch.it[blockIdx.z];
+    if ((int)blockIdx.y >= a.n_reps) return;
     __shared__ __attribute__((aligned(16))) unsigned char sm_k[RS_NWAVE][RS_TILE * RS_LDS_ROW];
     __shared__ float sm_m[RS_NWAVE][RS_ROWS], sm_z[RS_NWAVE][RS_ROWS];
 
@@ -234,8 +241,10 @@ constexpr int RS_LSE_BLK = 1024;
 constexpr int RS_LSE_SLICES = RS_LSE_BLK / RS_ROWS;                        // 32
 constexpr int RS_LSE_PER = HC_RESCORE_MAX_BLOCKS / RS_LSE_SLICES;          // partials per thread: 16
 template <int G>
-__global__ __launch_bounds__(RS_LSE_BLK) void rescore_lse_kernel(RescoreArgs a)
+__global__ __launch_bounds__(RS_LSE_BLK) void rescore_lse_kernel(RescoreBatch batch)
 {
+    const RescoreArgs& a = batch.it[blockIdx.y];
+    if ((int)blockIdx.x >= a.n_reps) return;
     __shared__ float sm_m[RS_LSE_SLICES][RS_ROWS], sm_z[RS_LSE_SLICES][RS_ROWS];
     const int rep = blockIdx.x;
     const RepDev rd = a.reps[rep];
@@ -331,62 +340,71 @@ hc_status hc_launch_rescore_push(hc_ctx* ctx, int n, const void* const* q, void*
 
 // Logits [n_items][n_heads][max_ctx][G] and lse [n_items][B*Hq] of n_items queries (q, item stride B*Hq*D)
 // against the K rows of the heads listed in `reps`: in the arena (src == nullptr: pivots, hd.k_off, hd.len
-// rows) or in a prefill buffer (`arena` is that buffer, src[bh].k_off, hd.ctx rows).
-hc_status hc_launch_logits_lse(hc_ctx* ctx, const hc_layer* L, const RepDev* reps, int n_heads, int max_len, const void* arena,
-                               const PreSrc* src, const void* q, int n_items, float* logits, size_t logits_item, float* lse,
-                               size_t lse_item, float* part, hipStream_t st)
+// rows) or in a prefill buffer (`arena` is that buffer, src[bh].k_off, hd.ctx rows).  One launch for all jobs.
+hc_status hc_launch_logits_lse(hc_ctx* ctx, int n_jobs, const hc_logits_job* jobs, int n_items, hipStream_t st)
 {
     if (n_items < 1 || n_items > hc_rescore_items_per_pass(ctx)) return hc_fail(ctx, HC_EINVAL, "scoring pass of %d queries", n_items);
-    if (n_heads < 1) return HC_OK;
-    const int tiles = (std::max(1, max_len) + RS_WG_TILE - 1) / RS_WG_TILE;
+    if (n_jobs < 1 || n_jobs > HC_MAX_GROUP) return hc_fail(ctx, HC_EINVAL, "scoring pass over %d layers", n_jobs);
+    int total_heads = 0, max_heads = 0, max_len = 1;
+    for (int j = 0; j < n_jobs; ++j) {
+        total_heads += jobs[j].n_heads;
+        max_heads = std::max(max_heads, jobs[j].n_heads);
+        max_len = std::max(max_len, jobs[j].max_len);
+    }
+    if (total_heads == 0) return HC_OK;
+    const int tiles = (max_len + RS_WG_TILE - 1) / RS_WG_TILE;
     // two workgroups per compute unit over all heads (measured at 224K, two pivots: 29.5 us, against 33-35 us with
     // three or four and 31 us with one), each with at least two iterations
-    const int want = std::max(1, 2 * ctx->n_cu / n_heads);
+    const int want = std::max(1, 2 * ctx->n_cu / total_heads);
     const int nblk = std::max(1, std::min({(int)HC_RESCORE_MAX_BLOCKS, want, (tiles + 1) / 2}));
-    RescoreArgs a{};
-    a.heads = L->heads;
-    a.reps = reps;
-    a.arena = (const uint16_t*)arena;
-    a.q_item_stride = (size_t)ctx->cfg.B * ctx->cfg.Hq * HC_D;
-    a.q_first = (const uint16_t*)q;
-    a.logits = logits;
-    a.logits_item_stride = logits_item;
-    a.lse = lse;
-    a.lse_item_stride = lse_item;
-    a.part = part;
-    a.src = src;
-    a.n_items = n_items;
-    a.n_reps = n_heads;
-    a.max_ctx = ctx->cfg.max_ctx;
-    a.nblk = nblk;
-    const dim3 grid(nblk, n_heads);
+    RescoreBatch B{};
+    for (int j = 0; j < n_jobs; ++j) {
+        RescoreArgs& a = B.it[j];
+        const hc_logits_job& x = jobs[j];
+        a.heads = x.L->heads;
+        a.reps = x.reps;
+        a.arena = (const uint16_t*)x.arena;
+        a.q_item_stride = (size_t)ctx->cfg.B * ctx->cfg.Hq * HC_D;
+        a.q_first = (const uint16_t*)x.q;
+        a.logits = x.logits;
+        a.logits_item_stride = x.logits_item;
+        a.lse = x.lse;
+        a.lse_item_stride = x.lse_item;
+        a.part = x.part;
+        a.src = x.src;
+        a.n_items = n_items;
+        a.n_reps = x.n_heads;
+        a.max_ctx = ctx->cfg.max_ctx;
+        a.nblk = nblk;
+    }
+    const dim3 grid(nblk, max_heads, n_jobs);
     switch (ctx->G) {
-    case 1: rescore_logits_kernel<1><<<grid, dim3(RS_BLK), 0, st>>>(a); break;
-    case 2: rescore_logits_kernel<2><<<grid, dim3(RS_BLK), 0, st>>>(a); break;
-    case 4: rescore_logits_kernel<4><<<grid, dim3(RS_BLK), 0, st>>>(a); break;
-    default: rescore_logits_kernel<8><<<grid, dim3(RS_BLK), 0, st>>>(a); break;
+    case 1: rescore_logits_kernel<1><<<grid, dim3(RS_BLK), 0, st>>>(B); break;
+    case 2: rescore_logits_kernel<2><<<grid, dim3(RS_BLK), 0, st>>>(B); break;
+    case 4: rescore_logits_kernel<4><<<grid, dim3(RS_BLK), 0, st>>>(B); break;
+    default: rescore_logits_kernel<8><<<grid, dim3(RS_BLK), 0, st>>>(B); break;
     }
     HC_HIP(ctx, hipGetLastError());
+    const dim3 grid2(max_heads, n_jobs);
     switch (ctx->G) {
-    case 1: rescore_lse_kernel<1><<<dim3(n_heads), dim3(RS_LSE_BLK), 0, st>>>(a); break;
-    case 2: rescore_lse_kernel<2><<<dim3(n_heads), dim3(RS_LSE_BLK), 0, st>>>(a); break;
-    case 4: rescore_lse_kernel<4><<<dim3(n_heads), dim3(RS_LSE_BLK), 0, st>>>(a); break;
-    default: rescore_lse_kernel<8><<<dim3(n_heads), dim3(RS_LSE_BLK), 0, st>>>(a); break;
+    case 1: rescore_lse_kernel<1><<<grid2, dim3(RS_LSE_BLK), 0, st>>>(B); break;
+    case 2: rescore_lse_kernel<2><<<grid2, dim3(RS_LSE_BLK), 0, st>>>(B); break;
+    case 4: rescore_lse_kernel<4><<<grid2, dim3(RS_LSE_BLK), 0, st>>>(B); break;
+    default: rescore_lse_kernel<8><<<grid2, dim3(RS_LSE_BLK), 0, st>>>(B); break;
     }
     HC_HIP(ctx, hipGetLastError());
     return HC_OK;
 }
 
-// Logits and lse of buffered queries [first, first + n_items) of the window against the layer's pivots.
-hc_status hc_launch_rescore_logits(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* q_window, int first,
-                                   int n_items, void* work, hipStream_t st)
+// The job of a layer's pivots against buffered queries [first, ...) of its window.
+hc_logits_job hc_rescore_job(const hc_ctx* ctx, const hc_layer* L, const void* arena, const void* q_window, int first, void* work)
 {
     const hc_rescore_layout lay = hc_rescore_plan(ctx, L);
     int max_len = 1;
     for (size_t i = 0; i < L->hd_host.size(); ++i)
         if (L->rep_slot_of[i] >= 0) max_len = std::max(max_len, (int)L->hd_host[i].len);
     const size_t q_item = (size_t)ctx->cfg.B * ctx->cfg.Hq * HC_D;
-    return hc_launch_logits_lse(ctx, L, L->reps, L->n_reps, max_len, arena, nullptr, (const uint16_t*)q_window + (size_t)first * q_item,
-                                n_items, (float*)((char*)work + lay.logits_off), lay.logits_item, (float*)((char*)work + lay.lse_off),
-                                lay.lse_item, (float*)((char*)work + lay.part_off), st);
+    return hc_logits_job{L, L->reps, L->n_reps, max_len, arena, nullptr, (const uint16_t*)q_window + (size_t)first * q_item,
+                         (float*)((char*)work + lay.logits_off), lay.logits_item, (float*)((char*)work + lay.lse_off), lay.lse_item,
+                         (float*)((char*)work + lay.part_off)};
 }
