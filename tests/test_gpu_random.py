@@ -68,7 +68,14 @@ def test_random_layer(seed):
         p, _ = U.Pair.from_prefill(spec, data, q0.to(torch.bfloat16), rng.choice([1, 3, 7]), DEV, growth=growth)
         assert p.slots_equal_oracle() and p.tier_equals_masters()
     else:
-        p = U.Pair(spec, data, DEV, growth=growth)
+        # a third of these run on "8 or 16 compute units": few, long shares per workgroup, i.e. the weighted and
+        # cost-charged split of the long passes, and rebalanced plans, at sizes the oracle still likes
+        ctx = None
+        if rng.random() < 0.35:
+            ctx = R.Context(R.make_config(spec, growth=growth), DEV)
+            hc.hc_set_split(ctx.handle, 2, rng.choice([8, 16]))
+        p = U.Pair(spec, data, DEV, ctx=ctx, growth=growth)
+        p.own_ctx = True
     sched = I.QuerySchedule(q0, 7000 + seed, step_deg=rng.choice([3.0, 10.0, 30.0]))
     stepper = None
     if step_api:
