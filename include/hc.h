@@ -327,8 +327,8 @@ hc_status hc_prefill_init(hc_ctx* ctx, hc_layer* layer, const void* kv_prefill, 
  * work: device buffer of at least hc_rescore_work_bytes(ctx, layer) bytes, 256-byte aligned, the caller's;
  * contents are scratch (logits, scores and lists of the re-scored queries, laid out as
  * hc_rescore_work_layout reports: place i holds the last query k with k mod items_per_pass == i, which
- * is what the tests read).  Uses the context's
- * selection workspaces like a batched monitor call: stream-order it with other monitor calls.
+ * is what the tests read).  Uses the context's selection workspaces like a batched monitor call:
+ * stream-order it with other monitor calls.
  * Enqueue-only, no allocation.  W == 1 or a layer without pivots: only the copy happens.  Which row the
  * queries go to and whether the passes run is decided on the host when the call is made, so a captured
  * graph of this call would repeat one step of the window: capture whole windows (W calls) or none. */
@@ -347,10 +347,12 @@ hc_status hc_layer_set_window_slot(hc_layer* layer, int32_t slot);
 /* One decode step over a stack of layers (Algorithm 1, the body of the loop over t, for every layer):
  * for each layer in order, hc_decode_attn on main_stream, then hc_rep_topk_drift and hc_gather_retrieve
  * on side_stream (NULL = on main_stream, no overlap).  Layers are handled in groups of layers_per_group
- * (1..HC_MAX_GROUP; 4 is a good value): a group's attentions, then one cross-stream event, then ONE
- * batched monitor and ONE batched gather for the whole group (the launches, and nearly the GPU time, of
- * a single layer: those kernels are latency-bound), which overlap the attention of the following
- * groups.  The attention of a layer at the next call waits for that layer's side work of this call, so
+ * (1..HC_MAX_GROUP; 8 measured best at 32 layers of 224K): the group's appended tokens (k_new / v_new) in
+ * one launch, the group's attentions, then one cross-stream event, then ONE batched monitor and ONE
+ * batched gather for the whole group, which overlap the attention of the following groups; with
+ * HC_WINDOW_RESCORED also one launch that buffers the group's queries (on main_stream: q may be
+ * overwritten as soon as the call returns) and, at the window's last step, the re-scoring passes of the
+ * whole group ahead of its monitor.  The attention of a layer at the next call waits for that layer's side work of this call, so
  * a refill decided at step t is used from step t+1.  Launching from native code keeps the host ahead
  * of the GPU.  All buffers are the caller's, as in the three calls; scores == NULL (or a layer without
  * pivots) skips monitor and gather for that layer; host_tier == NULL skips the gather.  Layers whose
