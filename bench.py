@@ -37,7 +37,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=48)
     ap.add_argument("--warmup", type=int, default=4)
-    ap.add_argument("--config", type=int, default=4, choices=[2, 3, 4])
+    ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--layers", type=int, default=0, help="0 = the config's own layer count")
     ap.add_argument("--ctx", type=int, default=0, help="override the context length (testing)")
     ap.add_argument("--mode", default="step", choices=["step", "graph", "eager"],
@@ -96,7 +96,10 @@ def main():
     prefill_ms = []
     ctx = None
     for l in range(L):
-        w = I.make_workload(args.config, layer=l, device=dev, N=args.ctx or None)
+        extra = {}
+        if args.config == 5 and layers:
+            extra["ctx"] = layers[0].spec.ctx        # one batch: every layer sees the same sequences; roles are drawn per layer
+        w = I.make_workload(args.config, layer=l, device=dev, N=args.ctx or None, **extra)
         spec = w.spec
         if args.dense:
             spec = I.spec_dense(spec.ctx[0])
@@ -105,7 +108,10 @@ def main():
         if args.window_mode >= 0:
             spec.window_mode = args.window_mode
         if ctx is None:
-            ctx = R.Context(R.make_config(spec, growth=T_total if args.append else 0), dev, workgroups_per_cu=args.wg_per_cu or None)
+            cfg = R.make_config(spec, growth=T_total if args.append else 0)
+            if args.config == 5:
+                cfg.max_k = 4096 - 64 - 256          # the largest list any layer of this config can draw
+            ctx = R.Context(cfg, dev, workgroups_per_cu=args.wg_per_cu or None)
             if args.share_weights:
                 hc.hc_set_share_weights(ctx.handle, [float(x) for x in args.share_weights.split(",")])
         retrieved, base = I.initial_lists(spec)
@@ -140,7 +146,7 @@ def main():
         del w
         print(f"[bench] layer {l + 1}/{L} packed ({time.time() - t_setup:.0f}s)", file=sys.stderr, flush=True)
     spec0 = layers[0].spec
-    kv_bytes = spec0.kv_bytes()
+    kv_bytes = int(sum(lay.spec.kv_bytes() for lay in layers) // len(layers))      # (config 5 draws the roles per layer)
     Q_all = torch.stack([torch.stack([s.next() for s in scheds]) for _ in range(T_total)]).contiguous()   # [T,L,B,Hq,D]
     q_cur = Q_all[0].clone()
     KV_new = None
@@ -333,7 +339,8 @@ def main():
         "metric": METRIC, "value": us_per_layer, "unit": "us per decode step per layer",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step, "higher_is_better": False,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"config{args.config}{' dense' if args.dense else ''}: {spec0.ctx[0]} ctx, {L} layers, "
+        "config": {"workload": f"config{args.config}{' dense' if args.dense else ''}: "
+                               f"{spec0.ctx[0] if spec0.B == 1 else '%d..%d (sum %d)' % (min(spec0.ctx), max(spec0.ctx), sum(spec0.ctx))} ctx, {L} layers, "
                                f"B={spec0.B}, {spec0.Hq}q/{spec0.Hkv}kv heads, D=128",
                    "layers": L, "context": spec0.ctx[0], "mode": args.mode, "host_tier": not args.no_tier, "gather": "none" if args.no_tier else ("whole lists" if args.full_gather else "difference only"), "overlap_monitor": not args.serial, "layers_per_group": args.group, "growing_context": args.append,
                    "kv_bytes_per_layer_step": kv_bytes,

@@ -284,13 +284,16 @@ CONFIG_STEPS = {1: 8, 2: 64, 3: 128, 4: 64, 5: 64}
 
 def spec_ragged(seed: int, B: int = 16, lo: int = 8192, hi: int = 131072,
                 budgets: Sequence[int] = (512, 1024, 2048, 4096), n_full: int = 2,
-                Hq: int = 32, Hkv: int = 8, sink: int = 64, recent: int = 256) -> LayerSpec:
+                Hq: int = 32, Hkv: int = 8, sink: int = 64, recent: int = 256, ctx: Optional[Sequence[int]] = None) -> LayerSpec:
     """Batched ragged workload: contexts log-uniform in [lo, hi]; per sequence ``n_full`` of the
     KV heads are full (drawn uniformly), every compressed head follows a uniformly drawn full
-    head and gets a budget drawn uniformly from ``budgets``."""
+    head and gets a budget drawn uniformly from ``budgets``.  ``ctx``: the sequences' lengths are these instead
+    (the layers of one stack see the same batch; the roles are still drawn from ``seed``)."""
     g = _gen(seed, "cpu")
     u = torch.rand((B,), generator=g, dtype=torch.float64)
-    ctx = [int(round(math.exp(math.log(lo) + float(x) * (math.log(hi) - math.log(lo))))) for x in u]
+    if ctx is None:
+        ctx = [int(round(math.exp(math.log(lo) + float(x) * (math.log(hi) - math.log(lo))))) for x in u]
+    ctx = list(ctx)
     heads = []
     for b in range(B):
         full = sorted(torch.randperm(Hkv, generator=g)[:n_full].tolist())
@@ -342,7 +345,7 @@ def make_workload(config: int, layer: int = 0, device: str = "cpu", N: Optional[
         data = draw_layer(spec, q0, seed + 1, device, heavy_frac=0.005, segments=16)
         sched = QuerySchedule(q0, seed + 2, jump_every=16, jump_deg=kw.get("jump_deg", 15.0))
     elif config == 5:
-        spec = spec_ragged(seed, B=kw.get("B", 16), lo=kw.get("lo", 8192), hi=kw.get("hi", 131072))
+        spec = spec_ragged(seed, B=kw.get("B", 16), lo=kw.get("lo", 8192), hi=kw.get("hi", 131072), ctx=kw.get("ctx"))
         q0 = draw_q(spec, seed, device)
         data = draw_layer(spec, q0, seed + 1, device, heavy_frac=0.01)
         sched = QuerySchedule(q0, seed + 2, jump_deg=15.0, jump_prob=1.0 / 16.0)
