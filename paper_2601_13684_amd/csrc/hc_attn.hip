@@ -466,20 +466,23 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
 }
 
 // Second pass: out = sum_s 2^(m_s - M) acc_s / sum_s 2^(m_s - M) Z_s over the partials of one head.
-// One workgroup of 1024 threads per (b, query head): 32 partial lanes x 32 column quads; every
-// thread's loads are independent and issued together.
+// One workgroup per (b, query head, quarter of the columns): 32 partial lanes x CQ column quads; every thread's
+// loads are independent and issued together.  (Four small workgroups per query head instead of one of 1024
+// threads: they find room beside the monitor's kernels sooner.)
+constexpr int CQ = 8;                       // column quads (of 32) per workgroup
+constexpr int COMBINE_BLK = 32 * CQ;
 template <int G>
-__global__ __launch_bounds__(1024) void attn_combine_kernel(const HeadDev* __restrict__ heads,
-                                                            const float* __restrict__ part_acc,
-                                                            const float* __restrict__ part_ml,
-                                                            float* __restrict__ out, float* __restrict__ lse)
+__global__ __launch_bounds__(COMBINE_BLK) void attn_combine_kernel(const HeadDev* __restrict__ heads,
+                                                                   const float* __restrict__ part_acc,
+                                                                   const float* __restrict__ part_ml,
+                                                                   float* __restrict__ out, float* __restrict__ lse)
 {
-    __shared__ float sm_max[16];
-    __shared__ float4 sm_acc[32][32];
+    __shared__ float sm_max[COMBINE_BLK / 64];
+    __shared__ float4 sm_acc[32][CQ];
     __shared__ float sm_z[32];
     const int bh = blockIdx.x / G, g = blockIdx.x % G;
     const HeadDev hd = heads[bh];
-    const int tid = threadIdx.x, dq = tid & 31, pl = tid >> 5;
+    const int tid = threadIdx.x, dq = (tid % CQ) + CQ * blockIdx.y, pl = tid / CQ;
     const int n = hd.part_count;
     const float2* ml = reinterpret_cast<const float2*>(part_ml);
     const float4* pa = reinterpret_cast<const float4*>(part_acc);
@@ -496,13 +499,13 @@ __global__ __launch_bounds__(1024) void attn_combine_kernel(const HeadDev* __res
         a[u] = pa[(slot * G + g) * (HC_D / 4) + dq];
     }
     float mx = M_INIT;
-    for (int s = tid; s < n; s += 1024) mx = fmaxf(mx, ml[(size_t)(hd.part_begin + s) * G + g].x);
+    for (int s = tid; s < n; s += COMBINE_BLK) mx = fmaxf(mx, ml[(size_t)(hd.part_begin + s) * G + g].x);
     for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
     if ((tid & 63) == 0) sm_max[tid >> 6] = mx;
     __syncthreads();
     float M = sm_max[0];
 #pragma unroll
-    for (int i = 1; i < 16; ++i) M = fmaxf(M, sm_max[i]);
+    for (int i = 1; i < COMBINE_BLK / 64; ++i) M = fmaxf(M, sm_max[i]);
 
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     float z = 0.f;
@@ -526,19 +529,19 @@ __global__ __launch_bounds__(1024) void attn_combine_kernel(const HeadDev* __res
             acc.w += wgt * a[u].w;
         }
     }
-    sm_acc[pl][dq] = acc;
-    if (dq == 0) sm_z[pl] = z;
+    sm_acc[pl][tid % CQ] = acc;
+    if (tid % CQ == 0) sm_z[pl] = z;
     __syncthreads();
-    if (tid < HC_D) {     // column tid: quad tid/4, component tid%4
+    if (tid < 4 * CQ) {     // column tid of this workgroup's 4 CQ: quad tid / 4, component tid % 4
         const float* col = reinterpret_cast<const float*>(&sm_acc[0][0]) + tid;
         float a = 0.f, zz = 0.f;
 #pragma unroll
         for (int i = 0; i < 32; ++i) {
-            a += col[i * HC_D];
+            a += col[i * 4 * CQ];
             zz += sm_z[i];
         }
-        out[(size_t)blockIdx.x * HC_D + tid] = a / zz;
-        if (tid == 0) lse[blockIdx.x] = (M + __builtin_amdgcn_logf(zz)) * LN2;
+        out[(size_t)blockIdx.x * HC_D + 4 * CQ * blockIdx.y + tid] = a / zz;
+        if (tid == 0 && blockIdx.y == 0) lse[blockIdx.x] = (M + __builtin_amdgcn_logf(zz)) * LN2;
     }
 }
 
@@ -568,7 +571,7 @@ hc_status launch(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* 
     HC_LAUNCH((attn_split_kernel<G, Tune<G>::WG>));
 #undef HC_LAUNCH
     HC_HIP(ctx, hipGetLastError());
-    attn_combine_kernel<G><<<dim3(L->n_heads * G), dim3(1024), 0, st>>>(L->heads, ctx->part_acc, ctx->part_ml, out, lse);
+    attn_combine_kernel<G><<<dim3(L->n_heads * G, 32 / CQ), dim3(COMBINE_BLK), 0, st>>>(L->heads, ctx->part_acc, ctx->part_ml, out, lse);
     HC_HIP(ctx, hipGetLastError());
     return HC_OK;
 }
