@@ -54,6 +54,7 @@ def main():
     ap.add_argument("--window", type=int, default=0, help="W of the drift test (0: the config's, which is 1)")
     ap.add_argument("--window-mode", type=int, default=-1, help="0 sliding (Eq. 10), 1 tumbling, 2 tumbling with the window's "
                     "queries scored again at the test step (Algorithm 1); -1: the config's (sliding)")
+    ap.add_argument("--monitor-span", type=int, default=0, help="1024-candidate chunks per workgroup of the selection passes (0: chosen per launch)")
     ap.add_argument("--tune-rounds", type=int, default=0, help="rounds of on-device measurement of the share weights on the first layer (0: built-in weights, as the parity tests use)")
     ap.add_argument("--share-weights", default="", help="16 comma-separated share weights [die*2+slot] (tuning)")
     ap.add_argument("--group", type=int, default=8, help="layers per cross-stream sync group in step mode")
@@ -114,6 +115,8 @@ def main():
             ctx = R.Context(cfg, dev, workgroups_per_cu=args.wg_per_cu or None)
             if args.share_weights:
                 hc.hc_set_share_weights(ctx.handle, [float(x) for x in args.share_weights.split(",")])
+            if args.monitor_span:
+                hc.hc_set_monitor_span(ctx.handle, args.monitor_span)
         retrieved, base = I.initial_lists(spec)
         pre = None
         if args.prefill_init:
