@@ -148,3 +148,11 @@ def test_single_row_heads():
     descs, _, _ = R.make_descs(spec)
     info = hc.hc_plan_describe(R.make_config(spec, max_ctx=64), descs)
     assert info.n_workgroups == 1 and info.n_partials == 2 and info.rows_covered == 2
+
+
+def test_benchmark_refuses_more_than_one_gpu():
+    """The build runs on one GPU; asking the benchmark for more ends with a message, before anything touches a GPU."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
