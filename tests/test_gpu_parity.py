@@ -1053,6 +1053,31 @@ def test_rescored_window_of_one_and_two_steps(W):
     p.close()
 
 
+def test_window_slot_can_be_set_back():
+    """hc_layer_set_window_slot: after two steps of a window of three, both sides are put back to "one step
+    taken" (ring count, buffered queries, the layer's slot) and the second step is taken again with another
+    query; the test step that follows must score the buffered queries of the repeated history."""
+    say("re-scored window, slot set back")
+    spec = I.spec_tiny(2500, budget=260, sink=8, recent=4)
+    spec.window, spec.window_mode = 3, 2
+    q0 = I.draw_q(spec, 181)
+    data = I.draw_layer(spec, q0, 182, heavy_count=25)
+    p = U.Pair(spec, data, DEV)
+    sched = I.QuerySchedule(q0, 183, step_deg=15.0)
+    run_steps(p, sched, 2, tag="slot")
+    assert hc.hc_layer_window_slot(p.gpu.handle) == 2
+    hc.hc_layer_set_window_slot(p.gpu.handle, 1)
+    p.gpu.ring[:, 0] = 1
+    for key in p.ref.ring:
+        del p.ref.ring[key][1:]
+        del p.ref.qbuf[key][1:]
+    with pytest.raises(hc.HcError):
+        hc.hc_layer_set_window_slot(p.gpu.handle, 3)
+    resyncs, _ = run_steps(p, sched, 5, tag="slot, again")           # steps 2', 3 (test), 4, 5, 6 (test)
+    assert p.ref.n_tests == 2 and resyncs == 0 and hc.hc_layer_window_slot(p.gpu.handle) == 0
+    p.close()
+
+
 def test_rescored_window_of_the_maximum_width():
     """W = 64, the largest window the library takes: 63 buffered queries, eight passes of the contraction."""
     say("re-scored window, W 64")
