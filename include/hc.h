@@ -274,8 +274,10 @@ hc_status hc_gather_retrieve(hc_ctx* ctx, const hc_layer* layer, const void* hos
  *                     left the window.
  * Call it before the hc_decode_attn that attends over the token, on the same stream, and after the layer's
  * monitor and gather of the previous step have completed (they read the tables this call updates;
- * hc_decode_step orders it so).  Every 64 appended tokens the split-K plan is rebalanced (a small
- * host-to-device copy on the stream).  Fails with HC_ESHAPE when a head has no room left. */
+ * hc_decode_step orders it so).  Enqueue-only: every 64 appended tokens the split-K plan is rebalanced on the
+ * host and copied to the device in stream order from pinned staging memory that the layer owns; the host does
+ * not wait for the stream.  (Not for graph capture: the host's copy of the lengths moves with every call.)
+ * Fails with HC_ESHAPE when a head has no room left, before anything is launched. */
 hc_status hc_append_kv(hc_ctx* ctx, hc_layer* layer, const void* k_new, const void* v_new, void* kv_arena,
                        void* host_tier, void* stream);
 /* Current context length of sequence b of the layer (grows with hc_append_kv); -1 on a bad argument. */
@@ -358,7 +360,8 @@ hc_status hc_layer_set_window_slot(hc_layer* layer, int32_t slot);
  * pivots) skips monitor and gather for that layer; host_tier == NULL skips the gather.  Layers whose
  * monitors overlap other layers' attention need their own rep_logits, scores, lse, out.  The context
  * holds one selection workspace per position in a group; hc_rep_topk_drift uses the first, so a direct
- * call must be stream-ordered with this call's side work.  Enqueue-only; not meant for graph capture
+ * call must be stream-ordered with this call's side work.  Every layer's arguments are checked before the first
+ * launch, so a refused call leaves every layer as it was.  Enqueue-only; not meant for graph capture
  * (it uses per-layer events). */
 typedef struct {
     hc_layer* layer;

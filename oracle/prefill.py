@@ -26,11 +26,12 @@ import numpy as np
 import torch
 
 from oracle import ref
-from paper_2601_13684_amd.inputs import ROLE_FULL, LayerData, LayerSpec
+from oracle.layer import ROLE_FULL, RefSpec
 
 
-def avg_pool(s: np.ndarray, P: int) -> np.ndarray:
-    """out[j] = (1/P) * sum of s[j - P//2 .. j + P//2], positions outside the array counting as zero."""
+def avg_pool_loops(s: np.ndarray, P: int) -> np.ndarray:
+    """out[j] = (1/P) * sum of s[j - P//2 .. j + P//2], positions outside the array counting as zero: the
+    definition, one position and one term at a time (short arrays)."""
     assert P >= 1 and P % 2 == 1
     s = np.asarray(s, np.float64)
     out = np.zeros_like(s)
@@ -44,29 +45,32 @@ def avg_pool(s: np.ndarray, P: int) -> np.ndarray:
     return out
 
 
-def avg_pool_fast(s: np.ndarray, P: int) -> np.ndarray:
-    """The same sums taken as one difference of prefix sums per position (long arrays)."""
+def avg_pool(s: np.ndarray, P: int) -> np.ndarray:
+    """The same sums, term by term in the same order (offset -P//2 first), each term added for all positions at
+    once; no rearrangement of the arithmetic, so the result equals avg_pool_loops bit for bit."""
     assert P >= 1 and P % 2 == 1
     s = np.asarray(s, np.float64)
-    h = P // 2
-    c = np.concatenate([[0.0], np.cumsum(s)])
-    j = np.arange(s.size)
-    return (c[np.minimum(j + h + 1, s.size)] - c[np.maximum(j - h, 0)]) / P
+    n, h = s.size, P // 2
+    acc = np.zeros_like(s)
+    for d in range(-h, h + 1):
+        lo, hi = max(0, -d), min(n, n - d)          # positions j with 0 <= j + d < n
+        if lo < hi:
+            acc[lo:hi] += s[lo + d:hi + d]
+    return acc / P
 
 
-def head_scores(q_bits: np.ndarray, K_bits: np.ndarray, agg: int, pool: int, exact: bool = False) -> np.ndarray:
+def head_scores(q_bits: np.ndarray, K_bits: np.ndarray, agg: int, pool: int) -> np.ndarray:
     """Smoothed last-token score of every position of one KV head, fp64 [N]."""
     _, lse, lg = ref.attn(q_bits, K_bits, K_bits, None, True)        # the value rows do not matter here
     s = ref.scores(lg, lse, agg)
-    if pool == 1:
-        return s
-    return avg_pool(s, pool) if exact else avg_pool_fast(s, pool)
+    return s if pool == 1 else avg_pool(s, pool)
 
 
-def prefill_init(spec: LayerSpec, data: LayerData, q_last: torch.Tensor, pool: int = 1, exact_pool: bool = False):
+def prefill_init(spec, data, q_last: torch.Tensor, pool: int = 1):
     """Returns (retrieved, base, scores): retrieved[(b, h)] = ascending int32 positions in the r refillable
     slots of compressed head h; base[(b, p)] = ascending int32 baseline set of pivot p; scores[(b, h)] =
     the fp64 smoothed scores the selection of head h was taken on."""
+    spec = RefSpec.of(spec)
     G, D = spec.G, spec.D
     qb = ref._bits(q_last).reshape(spec.B, spec.Hq, D)
     retrieved: Dict[Tuple[int, int], np.ndarray] = {}
@@ -79,11 +83,11 @@ def prefill_init(spec: LayerSpec, data: LayerData, q_last: torch.Tensor, pool: i
             hs = spec.heads[b][h]
             if hs.role == ROLE_FULL and h not in pivots:
                 continue                                   # a volatile head keeps everything and selects nothing
-            s = head_scores(np.ascontiguousarray(qb[b, h * G:(h + 1) * G]), ref._bits(data.K[(b, h)]), spec.agg, pool, exact_pool)
+            s = head_scores(np.ascontiguousarray(qb[b, h * G:(h + 1) * G]), ref._bits(data.K[(b, h)]), spec.agg, pool)
             scores[(b, h)] = s
             s32 = s.astype(np.float32)
             if hs.role == ROLE_FULL:
-                lo, hi = spec.cand_range(b, h)
+                lo, hi = spec.cand_range(b, h, N)
                 base[(b, h)] = ref.topk(s32, lo, hi, spec.k_mon(b, h))
             else:
                 retrieved[(b, h)] = ref.topk(s32, hs.sink, N - hs.recent, spec.r(b, h))

@@ -14,7 +14,7 @@ from typing import Dict, List, Optional, Tuple
 import numpy as np
 import torch
 
-from paper_2601_13684_amd.inputs import ROLE_FULL, LayerData, LayerSpec
+from oracle.layer import ROLE_FULL, RefSpec
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libhc_oracle.so")
@@ -157,9 +157,11 @@ class RefLayer:
     does not (tokens appended since step k are in the softmax, and the candidate range has moved).
     """
 
-    def __init__(self, spec: LayerSpec, data: LayerData,
+    def __init__(self, spec, data,
                  retrieved: Dict[Tuple[int, int], torch.Tensor], base: Dict[Tuple[int, int], torch.Tensor]):
-        self.spec = spec
+        """spec: a RefSpec or anything RefSpec.of accepts; data: the master K and V of every KV head
+        (data.K[(b, h)], data.V[(b, h)]: bf16 [N_b, D])."""
+        self.spec = spec = RefSpec.of(spec)
         self.ctx = list(spec.ctx)              # current context length per sequence (grows with append)
         self.Kb = {k: _bits(v) for k, v in data.K.items()}
         self.Vb = {k: _bits(v) for k, v in data.V.items()}
@@ -181,8 +183,7 @@ class RefLayer:
 
     def cand_range(self, b: int, p: int) -> Tuple[int, int]:
         """Candidate positions [lo, hi) of pivot p's top-k at the current context length."""
-        s0 = self.spec.heads[b][self.spec.satellites(b, p)[0]]
-        return s0.sink, self.ctx[b] - s0.recent
+        return self.spec.cand_range(b, p, self.ctx[b])
 
     def append(self, k_new: torch.Tensor, v_new: torch.Tensor) -> None:
         """k_new, v_new: bf16 [B, Hkv, D], the decode token's rows; they become position ctx_b of every

@@ -10,9 +10,11 @@ Readings where the paper leaves a choice (the same ones the library documents):
   * budgets are real numbers in Eq. 8; they are rounded down and the remaining slots go to the largest
     fractional parts (lowest index first), so that the sum is exactly the total of Eq. 7 rounded down;
     a budget above the sequence length is cut to it and the excess shared among the others in the same
-    proportion.  The shares are evaluated in IEEE double precision in a fixed order (see budgets), the
-    precision in which both sides take the integer decision.
+    proportion.  Eq. 8 is real-valued: the shares here are exact rationals of the given floats.  (The library
+    evaluates them in double precision; a test allows it the one-slot differences that double rounding can
+    cause at exact near-ties, and nothing else.)
 """
+from fractions import Fraction
 from typing import List, Sequence, Tuple
 
 ROLE_FULL, ROLE_SATELLITE, ROLE_ANCHOR = 0, 1, 2
@@ -48,24 +50,23 @@ def taxonomy(adj: Sequence[Sequence[int]], s_stable: Sequence[float], tau_stable
 
 def budgets(role: Sequence[int], s_stable: Sequence[float], rho_num: int, rho_den: int, L: int) -> List[int]:
     """Eq. 7-8: the total (rho N - N_full) L, rho = rho_num / rho_den, shared among the compressed heads in
-    proportion to w_i = 1 / S_stable_i; full heads get L.  The total is exact integer arithmetic; the shares
-    are evaluated in IEEE double precision, w = 1.0 / S, sums in head order, share = (total * w) / sum(w),
-    which is the precision in which the integer budgets are decided on both sides."""
+    proportion to w_i = 1 / S_stable_i; full heads get L.  Exact rational arithmetic on the given floats
+    (every float is a rational number; nothing is rounded before the final floor)."""
     n = len(role)
     comp = [i for i in range(n) if role[i] != ROLE_FULL]
     n_full = n - len(comp)
-    total = ((rho_num * n - n_full * rho_den) * L) // rho_den if rho_num * n > n_full * rho_den else 0
+    total = (Fraction(rho_num, rho_den) * n - n_full) * L
     if total <= 0 or not comp:
         raise ValueError("no budget for compressed heads")
-    total = min(total, len(comp) * L)
-    w = {i: 1.0 / float(s_stable[i]) for i in comp}
+    total = min(total.__floor__(), len(comp) * L)
+    if total <= 0:
+        raise ValueError("no budget for compressed heads")
+    w = {i: 1 / Fraction(s_stable[i]) for i in comp}
     out = {i: L for i in range(n)}
     free, left = list(comp), total
     while True:       # heads whose share exceeds L are cut to L; the rest share what is left
-        sw = 0.0
-        for i in free:
-            sw += w[i]
-        over = [i for i in free if (float(left) * w[i]) / sw > float(L)]
+        sw = sum(w[i] for i in free)
+        over = [i for i in free if left * w[i] / sw > L]
         if not over:
             break
         for i in over:
@@ -74,11 +75,31 @@ def budgets(role: Sequence[int], s_stable: Sequence[float], rho_num: int, rho_de
             left -= L
         if not free:
             return [out[i] for i in range(n)]
-    share = {i: (float(left) * w[i]) / sw for i in free}
+    share = {i: left * w[i] / sw for i in free}
     for i in free:
-        out[i] = int(share[i] // 1.0)
-    rest = left - sum(out[i] for i in free)
-    order = sorted(free, key=lambda i: (-(share[i] - float(out[i])), i))
-    for k in range(max(0, rest)):           # rounding noise can leave a slot more than there are heads: go round again
-        out[order[k % len(order)]] += 1
+        out[i] = share[i].__floor__()
+    rest = left - sum(out[i] for i in free)            # 0 <= rest < len(free): the floors lose less than one slot each
+    order = sorted(free, key=lambda i: (-(share[i] - out[i]), i))
+    for i in order[:rest]:
+        out[i] += 1
     return [out[i] for i in range(n)]
+
+
+def exact_shares(role: Sequence[int], s_stable: Sequence[float], rho_num: int, rho_den: int, L: int):
+    """The real-valued shares of Eq. 8 before rounding, as exact fractions, for the heads that are not cut to L
+    ({head: share}); tests use them to tell a genuine difference from a double-rounding near-tie."""
+    n = len(role)
+    comp = [i for i in range(n) if role[i] != ROLE_FULL]
+    n_full = n - len(comp)
+    total = min(((Fraction(rho_num, rho_den) * n - n_full) * L).__floor__(), len(comp) * L)
+    w = {i: 1 / Fraction(s_stable[i]) for i in comp}
+    free, left = list(comp), total
+    while free:
+        sw = sum(w[i] for i in free)
+        over = [i for i in free if left * w[i] / sw > L]
+        if not over:
+            return {i: left * w[i] / sw for i in free}
+        for i in over:
+            free.remove(i)
+            left -= L
+    return {}

@@ -13,7 +13,7 @@ from typing import Optional, Sequence, Union
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("HC_LIB") or os.path.join(_HERE, "libhc.so")   # HC_LIB: load another build of the same ABI
+LIB_PATH = os.path.join(_HERE, "libhc.so")
 
 HC_OK, HC_EINVAL, HC_ESHAPE, HC_ENOMEM, HC_EHIP, HC_ESTATE = range(6)
 HC_MAX_WINDOW, HC_MAX_K_PER_REP, HC_MAX_GROUP = 64, 8, 8

@@ -20,20 +20,6 @@
 #include <hip/hip_ext.h>
 
 #include "hc_internal.h"
-// Optional instrumentation (build with -DHC_TUNE; the shipped library has none of it): every workgroup of the
-// split pass leaves timestamps of its phases (entry, descriptor read, rows done, end) and the die / compute
-// unit it ran on in hc_dbg, which hc_debug_read copies out.  That is how the phase times, the spread between
-// workgroups and the die patterns quoted in the comments of this file were measured.
-#ifdef HC_TUNE
-__device__ unsigned long long hc_dbg[4096 * 8];
-extern "C" int hc_debug_read(unsigned long long* host, int n)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(hc_dbg), sizeof(unsigned long long) * n);
-}
-#define HC_STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x < 4096) hc_dbg[blockIdx.x * 8 + (i)] = __builtin_amdgcn_s_memrealtime(); } while (0)
-#else
-#define HC_STAMP(i) do { } while (0)
-#endif
 
 namespace {
 
@@ -352,19 +338,9 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
 
     // tuning runs only: when the workgroup started and (below) when it was through its last rows
     if (stamps && threadIdx.x == 0) stamps[2 * blockIdx.x] = __builtin_amdgcn_s_memrealtime();
-    HC_STAMP(0);
-#ifdef HC_TUNE
-    if (threadIdx.x == 0 && blockIdx.x < 4096) {
-        hc_dbg[blockIdx.x * 8 + 5] = __builtin_amdgcn_s_getreg((3 << 11) | 20);     // XCC_ID
-        hc_dbg[blockIdx.x * 8 + 6] = __builtin_amdgcn_s_getreg((31 << 11) | 4);     // HW_ID
-    }
-#endif
     const BlkDev blk = blks[blockIdx.x];
     SegDev seg = blk.first;
     int next_extra = blk.extra_begin;
-#ifdef HC_TUNE
-    if (seg.row_end > 0) HC_STAMP(1);
-#endif
     for (;;) {
         const char* __restrict__ Kp = reinterpret_cast<const char*>(arena + seg.k_off);
         const char* __restrict__ Vp = reinterpret_cast<const char*>(arena + seg.v_off);
@@ -388,9 +364,6 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
         }
 
         process_rows<G>(st, qreg, Kp, Vp, rep_base, sm_stash, seg.row_begin, seg.row_end, w, r, c);
-#ifdef HC_TUNE
-        if (st.Z[0] >= 0.f) HC_STAMP(2);
-#endif
         if (stamps && threadIdx.x == 0 && next_extra >= blk.extra_end && st.Z[0] >= 0.f)      // (the condition on Z orders the stamp after the rows)
             stamps[2 * blockIdx.x + 1] = __builtin_amdgcn_s_memrealtime();
 
@@ -458,7 +431,6 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
             part_ml[((size_t)seg.slot * G + tid) * 2 + 0] = M;
             part_ml[((size_t)seg.slot * G + tid) * 2 + 1] = z;
         }
-        HC_STAMP(4);
         if (next_extra >= blk.extra_end) break;
         __syncthreads();
         seg = segs[next_extra++];
@@ -553,7 +525,7 @@ template <> struct Tune<8> { static constexpr int WG = 1; };
 
 template <int G>
 hc_status launch(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* q, float* out, float* lse,
-                 float* rep_logits, hipStream_t st)
+                 float* rep_logits, hipStream_t st, float* part_acc, float* part_ml)
 {
     // The optional timing events are attached to the kernel's own dispatch, so that their distance is the
     // kernel's execution time (what a profiler's kernel trace reports), not launch latency plus execution.
@@ -566,27 +538,33 @@ hc_status launch(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* 
 #define HC_LAUNCH(KERNEL)                                                                                         \
     hipExtLaunchKernelGGL(KERNEL, dim3(L->n_blocks), dim3(256), 0, st, ev_begin, ev_end, 0,                      \
                           (const uint16_t*)arena, (const uint16_t*)q, (const BlkDev*)L->blks,                    \
-                          (const SegDev*)L->segs, ctx->part_acc, ctx->part_ml, rep_logits, ctx->cfg.max_ctx,       \
+                          (const SegDev*)L->segs, part_acc, part_ml, rep_logits, ctx->cfg.max_ctx,                 \
                           ctx->tune_stamps)
     HC_LAUNCH((attn_split_kernel<G, Tune<G>::WG>));
 #undef HC_LAUNCH
     HC_HIP(ctx, hipGetLastError());
-    attn_combine_kernel<G><<<dim3(L->n_heads * G, 32 / CQ), dim3(COMBINE_BLK), 0, st>>>(L->heads, ctx->part_acc, ctx->part_ml, out, lse);
+    attn_combine_kernel<G><<<dim3(L->n_heads * G, 32 / CQ), dim3(COMBINE_BLK), 0, st>>>(L->heads, part_acc, part_ml, out, lse);
     HC_HIP(ctx, hipGetLastError());
     return HC_OK;
 }
 
 }   // namespace
 
+static hc_status launch_any(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* q, float* out, float* lse,
+                            float* rep_logits, hipStream_t st, float* part_acc, float* part_ml)
+{
+    switch (ctx->G) {
+    case 1: return launch<1>(ctx, L, arena, q, out, lse, rep_logits, st, part_acc, part_ml);
+    case 2: return launch<2>(ctx, L, arena, q, out, lse, rep_logits, st, part_acc, part_ml);
+    case 4: return launch<4>(ctx, L, arena, q, out, lse, rep_logits, st, part_acc, part_ml);
+    case 8: return launch<8>(ctx, L, arena, q, out, lse, rep_logits, st, part_acc, part_ml);
+    }
+    return hc_fail(ctx, HC_ESHAPE, "unsupported group size");
+}
+
 hc_status hc_launch_attn(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* q, float* out, float* lse,
                          float* rep_logits, hipStream_t st)
 {
     if ((size_t)L->n_partials > ctx->part_slots) return hc_fail(ctx, HC_ESTATE, "split-K workspace smaller than the plan");
-    switch (ctx->G) {
-    case 1: return launch<1>(ctx, L, arena, q, out, lse, rep_logits, st);
-    case 2: return launch<2>(ctx, L, arena, q, out, lse, rep_logits, st);
-    case 4: return launch<4>(ctx, L, arena, q, out, lse, rep_logits, st);
-    case 8: return launch<8>(ctx, L, arena, q, out, lse, rep_logits, st);
-    }
-    return hc_fail(ctx, HC_ESHAPE, "unsupported group size");
+    return launch_any(ctx, L, arena, q, out, lse, rep_logits, st, ctx->part_acc, ctx->part_ml);
 }

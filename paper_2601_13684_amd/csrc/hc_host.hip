@@ -139,6 +139,7 @@ extern "C" hc_status hc_create(const hc_config* cfg, hc_ctx** out)
         c->pair_pos = g + pair_w;
         c->npairs = g + 2 * pair_w;
         (void)hc_gather_set_lds_limit();
+        (void)hc_monitor_set_lds_limit();
     }
     for (int i = 0; i < HC_MAX_GROUP; ++i) {
         hc_monitor_ws& w = c->ws[i];
@@ -254,6 +255,10 @@ static void layer_free(hc_layer* L)
     (void)hipFree(L->rep_slot_dev);
     if (L->ev_attn) (void)hipEventDestroy(L->ev_attn);
     if (L->ev_side) (void)hipEventDestroy(L->ev_side);
+    for (int i = 0; i < 2; ++i) {
+        if (L->plan_stage[i]) (void)hipHostFree(L->plan_stage[i]);
+        if (L->plan_copied[i]) (void)hipEventDestroy(L->plan_copied[i]);
+    }
     L->magic = 0;
     delete L;
 }
@@ -638,6 +643,18 @@ extern "C" hc_status hc_layer_create(hc_ctx* ctx, const hc_head_desc* hd, hc_lay
         if (st == HC_OK) st = upload(ctx, std::vector<PreSrc>(), &L->pre_src, (size_t)L->n_heads);
         if (st == HC_OK) st = upload(ctx, P.rep_slot_of, &L->rep_slot_dev);
     }
+    if (st == HC_OK) {
+        // staging for rebalanced plans: heads, segments, workgroup descriptors, pivots, each 16-byte aligned
+        auto up16 = [](size_t x) { return (x + 15) & ~(size_t)15; };
+        L->plan_stage_bytes = up16((size_t)L->n_heads * sizeof(HeadDev)) + up16((size_t)L->seg_capacity * sizeof(SegDev)) +
+                              up16((size_t)L->blk_capacity * sizeof(BlkDev)) + up16((size_t)std::max(1, L->n_reps) * sizeof(RepDev));
+        for (int i = 0; i < 2 && st == HC_OK; ++i) {
+            if (hipHostMalloc((void**)&L->plan_stage[i], L->plan_stage_bytes, hipHostMallocDefault) != hipSuccess)
+                st = hc_fail(ctx, HC_ENOMEM, "pinned staging for the split-K plan");
+            else if (hipEventCreateWithFlags(&L->plan_copied[i], hipEventDisableTiming) != hipSuccess)
+                st = hc_fail(ctx, HC_EHIP, "hipEventCreate failed");
+        }
+    }
     if (st == HC_OK && hipEventCreateWithFlags(&L->ev_attn, hipEventDisableTiming) != hipSuccess) st = hc_fail(ctx, HC_EHIP, "hipEventCreate failed");
     if (st == HC_OK && hipEventCreateWithFlags(&L->ev_side, hipEventDisableTiming) != hipSuccess) st = hc_fail(ctx, HC_EHIP, "hipEventCreate failed");
     if (st != HC_OK) {
@@ -668,15 +685,15 @@ extern "C" int32_t hc_layer_rep_slot(const hc_layer* layer, int32_t b, int32_t h
 }
 
 // ---- hot path: validate, then enqueue ------------------------------------------------------
+static hc_status attn_check(hc_ctx* ctx, const hc_layer* layer, const void* kv_arena, const void* q, const float* out, const float* lse,
+                            const float* rep_logits);
 
 extern "C" hc_status hc_decode_attn(hc_ctx* ctx, const hc_layer* layer, const void* kv_arena, const void* q,
                                     float* out, float* lse, float* rep_logits, void* stream)
 {
     if (!ctx_ok(ctx)) return HC_ESTATE;
-    if (!layer_ok(layer) || layer->ctx != ctx) return hc_fail(ctx, HC_ESTATE, "hc_decode_attn: layer does not belong to this context");
-    if (!kv_arena || !q || !out || !lse) return hc_fail(ctx, HC_EINVAL, "hc_decode_attn: null pointer");
-    if (((uintptr_t)kv_arena | (uintptr_t)q) & 15) return hc_fail(ctx, HC_EINVAL, "hc_decode_attn: kv_arena and q must be 16-byte aligned");
-    if (((uintptr_t)out | (uintptr_t)lse | (uintptr_t)rep_logits) & 3) return hc_fail(ctx, HC_EINVAL, "hc_decode_attn: misaligned float pointer");
+    const hc_status chk = attn_check(ctx, layer, kv_arena, q, out, lse, rep_logits);
+    if (chk != HC_OK) return chk;
     return hc_launch_attn(ctx, layer, kv_arena, q, out, lse, rep_logits, (hipStream_t)stream);
 }
 
@@ -743,6 +760,9 @@ extern "C" int32_t hc_layer_context(const hc_layer* layer, int32_t b)
 
 // Rebuilds the split-K plan from the head table as it is now and copies it over the old one on `st`.
 // The workgroup count and the pivots do not change with the lengths; only shares, segments and slots do.
+// Enqueue-only: the new tables are written into one of the layer's two pinned staging buffers and copied
+// from there in stream order (behind the append kernel whose lengths they include, ahead of the attention
+// that uses them).  The host waits only if the buffer's previous copy, two rebalancings ago, has not run yet.
 static hc_status replan(hc_ctx* ctx, hc_layer* L, hipStream_t st)
 {
     Plan P;
@@ -752,11 +772,24 @@ static hc_status replan(hc_ctx* ctx, hc_layer* L, hipStream_t st)
     if (P.n_blocks > L->blk_capacity || (int)P.segs.size() > L->seg_capacity || (int)P.reps.size() != L->n_reps)
         return hc_fail(ctx, HC_ESTATE, "internal: a rebalanced plan does not fit the layer");
     for (int i = 0; i < L->n_heads; ++i) P.heads[i].ctx0 = L->ctx0_host[i];        // the ring of recent slots keeps its origin
-    HC_HIP(ctx, hipMemcpyAsync(L->heads, P.heads.data(), P.heads.size() * sizeof(HeadDev), hipMemcpyHostToDevice, st));
-    HC_HIP(ctx, hipMemcpyAsync(L->segs, P.segs.data(), P.segs.size() * sizeof(SegDev), hipMemcpyHostToDevice, st));
-    HC_HIP(ctx, hipMemcpyAsync(L->blks, P.blks.data(), P.blks.size() * sizeof(BlkDev), hipMemcpyHostToDevice, st));
-    HC_HIP(ctx, hipMemcpyAsync(L->reps, P.reps.data(), P.reps.size() * sizeof(RepDev), hipMemcpyHostToDevice, st));
-    HC_HIP(ctx, hipStreamSynchronize(st));        // the host vectors go away; rare (every 64 tokens)
+    auto up16 = [](size_t x) { return (x + 15) & ~(size_t)15; };
+    const size_t b_heads = P.heads.size() * sizeof(HeadDev), b_segs = P.segs.size() * sizeof(SegDev),
+                 b_blks = P.blks.size() * sizeof(BlkDev), b_reps = P.reps.size() * sizeof(RepDev);
+    const size_t o_segs = up16(b_heads), o_blks = o_segs + up16(b_segs), o_reps = o_blks + up16(b_blks);
+    if (o_reps + b_reps > L->plan_stage_bytes) return hc_fail(ctx, HC_ESTATE, "internal: plan staging too small");
+    const int which = L->plan_next;
+    L->plan_next ^= 1;
+    HC_HIP(ctx, hipEventSynchronize(L->plan_copied[which]));       // (an event never recorded counts as complete)
+    char* stage = L->plan_stage[which];
+    memcpy(stage, P.heads.data(), b_heads);
+    memcpy(stage + o_segs, P.segs.data(), b_segs);
+    memcpy(stage + o_blks, P.blks.data(), b_blks);
+    if (b_reps) memcpy(stage + o_reps, P.reps.data(), b_reps);
+    HC_HIP(ctx, hipMemcpyAsync(L->heads, stage, b_heads, hipMemcpyHostToDevice, st));
+    HC_HIP(ctx, hipMemcpyAsync(L->segs, stage + o_segs, b_segs, hipMemcpyHostToDevice, st));
+    HC_HIP(ctx, hipMemcpyAsync(L->blks, stage + o_blks, b_blks, hipMemcpyHostToDevice, st));
+    if (b_reps) HC_HIP(ctx, hipMemcpyAsync(L->reps, stage + o_reps, b_reps, hipMemcpyHostToDevice, st));
+    HC_HIP(ctx, hipEventRecord(L->plan_copied[which], st));
     L->n_blocks = P.n_blocks;
     L->n_segs = L->n_partials = (int)P.segs.size();
     L->max_nchunk = P.max_nchunk;
@@ -1107,6 +1140,16 @@ extern "C" hc_status hc_rescore_window(hc_ctx* ctx, hc_layer* layer, const void*
 // pair per group keeps the host cost of the cross-stream ordering small.  The attention of a layer
 // waits for that layer's side work of the previous step (a refill decided at step t is used from step
 // t+1; it also keeps rep_logits / lse from being overwritten while the monitor reads them).
+static hc_status attn_check(hc_ctx* ctx, const hc_layer* layer, const void* kv_arena, const void* q, const float* out, const float* lse,
+                            const float* rep_logits)
+{
+    if (!layer_ok(layer) || layer->ctx != ctx) return hc_fail(ctx, HC_ESTATE, "hc_decode_attn: layer does not belong to this context");
+    if (!kv_arena || !q || !out || !lse) return hc_fail(ctx, HC_EINVAL, "hc_decode_attn: null pointer");
+    if (((uintptr_t)kv_arena | (uintptr_t)q) & 15) return hc_fail(ctx, HC_EINVAL, "hc_decode_attn: kv_arena and q must be 16-byte aligned");
+    if (((uintptr_t)out | (uintptr_t)lse | (uintptr_t)rep_logits) & 3) return hc_fail(ctx, HC_EINVAL, "hc_decode_attn: misaligned float pointer");
+    return HC_OK;
+}
+
 extern "C" hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* io, int32_t n_layers, int32_t layers_per_group,
                                     void* main_stream, void* side_stream)
 {
@@ -1115,18 +1158,35 @@ extern "C" hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* io, int32_t 
         return hc_fail(ctx, HC_EINVAL, "hc_decode_step: bad argument (layers_per_group 1..%d)", (int)HC_MAX_GROUP);
     hipStream_t ms = (hipStream_t)main_stream, ss = (hipStream_t)side_stream;
     if (side_stream != nullptr && ss == ms) return hc_fail(ctx, HC_EINVAL, "hc_decode_step: side_stream must differ from main_stream");
-    for (int l = 0; l < n_layers; ++l)
-        if (!layer_ok(io[l].layer) || io[l].layer->ctx != ctx)
-            return hc_fail(ctx, HC_ESTATE, "hc_decode_step: layer %d does not belong to this context", l);
+    const bool rescored = ctx->cfg.window_mode == HC_WINDOW_RESCORED;
+    // Every layer's arguments are checked before anything is launched or any host-side state moves on, so that
+    // a refused call leaves the whole stack as it was.
+    for (int l = 0; l < n_layers; ++l) {
+        const hc_layer_io& x = io[l];
+        const hc_layer* L = x.layer;
+        if (!layer_ok(L) || L->ctx != ctx) return hc_fail(ctx, HC_ESTATE, "hc_decode_step: layer %d does not belong to this context", l);
+        for (int m = 0; m < l; ++m)
+            if (io[m].layer == L) return hc_fail(ctx, HC_EINVAL, "hc_decode_step: layer %d appears twice in the stack", l);
+        const bool side = L->n_reps > 0 && x.scores != nullptr;
+        hc_status st = attn_check(ctx, L, x.kv_arena, x.q, x.out, x.lse, side ? x.rep_logits : nullptr);
+        if (st == HC_OK && (x.k_new || x.v_new)) st = append_check(ctx, L, x.k_new, x.v_new, x.kv_arena, x.host_tier);
+        if (st == HC_OK && side) {
+            st = monitor_check(ctx, L, x.rep_logits, x.lse, x.scores, 0, x.topk_idx, x.base_idx, x.ring, x.inter, x.flag);
+            if (st == HC_OK && rescored)
+                st = rescore_check(ctx, L, x.kv_arena, x.q, x.q_window, x.base_idx, x.ring, x.rescore_work, x.rescore_work_bytes);
+            if (st == HC_OK && x.host_tier && L->n_sats > 0) st = gather_check(ctx, L, x.host_tier, x.topk_idx, x.flag, x.kv_arena);
+        }
+        if (st != HC_OK) return st;
+    }
     hipEvent_t last_waited = nullptr;
     for (int g0 = 0; g0 < n_layers; g0 += layers_per_group) {
         const int g1 = std::min(n_layers, g0 + layers_per_group);
         hc_monitor_call mon[HC_MAX_GROUP];
         hc_gather_call gat[HC_MAX_GROUP];
         int n_mon = 0, n_gat = 0;
-        const bool rescored = ctx->cfg.window_mode == HC_WINDOW_RESCORED;
         const void* push_src[HC_MAX_GROUP];
         void* push_dst[HC_MAX_GROUP];
+        hc_layer* push_layer[HC_MAX_GROUP];
         RescoreJob test_job[HC_MAX_GROUP];
         int n_push = 0, n_test = 0;
         // the tokens of the group's layers enter their caches with one launch, ahead of the group's attention
@@ -1140,11 +1200,8 @@ extern "C" hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* io, int32_t 
                 last_waited = L->pending_ev;
                 L->pending_ev = nullptr;
             }
-            if (x.k_new || x.v_new) {
-                const hc_status sa = append_check(ctx, L, x.k_new, x.v_new, x.kv_arena, x.host_tier);
-                if (sa != HC_OK) return sa;
+            if (x.k_new || x.v_new)
                 app[n_app++] = hc_append_call{L, x.k_new, x.v_new, const_cast<void*>(x.kv_arena), const_cast<void*>(x.host_tier)};
-            }
         }
         if (n_app > 0) {
             hc_status sa = hc_launch_append(ctx, n_app, app, ms);
@@ -1156,33 +1213,28 @@ extern "C" hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* io, int32_t 
             hc_layer* L = x.layer;
             const bool side = L->n_reps > 0 && x.scores != nullptr;
             if (side) {
-                hc_status st = monitor_check(ctx, L, x.rep_logits, x.lse, x.scores, 0, x.topk_idx, x.base_idx, x.ring, x.inter, x.flag);
-                if (st != HC_OK) return st;
                 mon[n_mon++] = hc_monitor_call{L, x.rep_logits, x.lse, x.scores, x.topk_idx, x.base_idx, x.ring, x.inter, x.flag};
                 if (rescored) {
-                    st = rescore_check(ctx, L, x.kv_arena, x.q, x.q_window, x.base_idx, x.ring, x.rescore_work, x.rescore_work_bytes);
-                    if (st != HC_OK) return st;
                     push_src[n_push] = x.q;
+                    push_layer[n_push] = L;
                     push_dst[n_push++] = (char*)x.q_window + (size_t)L->window_slot * ctx->cfg.B * ctx->cfg.Hq * HC_D * 2;
                     if (L->window_slot == ctx->cfg.window - 1)
                         test_job[n_test++] = RescoreJob{L, x.kv_arena, x.q_window, x.base_idx, x.ring, x.rescore_work};
-                    L->window_slot = (L->window_slot + 1) % ctx->cfg.window;
                 }
-                if (x.host_tier && L->n_sats > 0) {
-                    st = gather_check(ctx, L, x.host_tier, x.topk_idx, x.flag, x.kv_arena);
-                    if (st != HC_OK) return st;
+                if (x.host_tier && L->n_sats > 0)
                     gat[n_gat++] = hc_gather_call{L, x.host_tier, x.topk_idx, x.flag, const_cast<void*>(x.kv_arena), x.slot_pos};
-                }
             }
-            const hc_status st = hc_decode_attn(ctx, L, x.kv_arena, x.q, x.out, x.lse, side ? x.rep_logits : nullptr, ms);
+            const hc_status st = hc_launch_attn(ctx, L, x.kv_arena, x.q, x.out, x.lse, side ? x.rep_logits : nullptr, ms);
             if (st != HC_OK) return st;
         }
         if (n_mon == 0) continue;
         // The queries go into the window buffers on the main stream: the caller may overwrite q as soon
-        // as this call returns, in main-stream order, while the side stream may still be behind.
+        // as this call returns, in main-stream order, while the side stream may still be behind.  A layer's
+        // count of steps inside its window moves on once its query is in the buffer.
         if (n_push > 0) {
             const hc_status sp = hc_launch_rescore_push(ctx, n_push, push_src, push_dst, ms);
             if (sp != HC_OK) return sp;
+            for (int i = 0; i < n_push; ++i) push_layer[i]->window_slot = (push_layer[i]->window_slot + 1) % ctx->cfg.window;
         }
         hc_layer* Lg = io[g1 - 1].layer;          // the group's events live in its last layer
         hipStream_t run = ss ? ss : ms;

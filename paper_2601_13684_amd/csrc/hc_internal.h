@@ -133,6 +133,13 @@ struct hc_layer {
     int32_t* rep_slot_dev = nullptr;    // [n_heads]: device copy of rep_slot_of
     std::vector<int32_t> sel_head_host; // table rows of the selecting heads, in the order of sel_reps
     int window_slot = 0;                // hc_decode_step with a re-scored window: monitored steps since the window was emptied
+    // A rebalanced plan goes to the device from pinned staging memory the layer owns, so that the copy is
+    // asynchronous and the host need not wait for it: two staging buffers alternate, each guarded by an event
+    // recorded behind its copy (waited for only if that buffer comes round again before its copy has run).
+    char* plan_stage[2] = {nullptr, nullptr};
+    size_t plan_stage_bytes = 0;
+    hipEvent_t plan_copied[2] = {nullptr, nullptr};
+    int plan_next = 0;
     int seg_capacity = 0;               // device room in segs (a rebalanced plan may have a few more segments)
     int blk_capacity = 0;               // device room in blks (a short layer gets more workgroups as it grows)
     HeadDev* heads = nullptr;
@@ -187,6 +194,7 @@ hc_status hc_launch_attn(hc_ctx* ctx, const hc_layer* L, const void* arena, cons
 hc_status hc_launch_monitor(hc_ctx* ctx, int n, const hc_monitor_call* calls, int scores_given, hipStream_t st);
 hc_status hc_launch_gather(hc_ctx* ctx, int n, const hc_gather_call* calls, hipStream_t st);
 hc_status hc_gather_set_lds_limit();     // once per process, at context creation
+hc_status hc_monitor_set_lds_limit();    // likewise
 // Work buffer of the window re-scoring pass (offsets in bytes, item sizes in elements).
 constexpr int HC_RESCORE_MAX_BLOCKS = 512;
 struct hc_rescore_layout {

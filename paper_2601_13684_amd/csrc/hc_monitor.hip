@@ -664,7 +664,22 @@ hc_status hc_launch_monitor(hc_ctx* ctx, int n, const hc_monitor_call* calls, in
     HC_HIP(ctx, hipGetLastError());
     mon_decide<<<dim3(max_reps, n), dim3(BLK), 0, st>>>(B, dc);
     HC_HIP(ctx, hipGetLastError());
-    // everything enqueued: the workspace copies will be clear again when this call completes
-    for (int i = 0; i < n; ++i) ctx->ws[i].dirty = false;
+    // everything enqueued: the workspace copies will be clear again when this call completes.  (Not so under
+    // stream capture, where nothing has run yet and the graph may never be launched: they stay marked.)
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cap) != hipSuccess) cap = hipStreamCaptureStatusActive;
+    if (cap == hipStreamCaptureStatusNone)
+        for (int i = 0; i < n; ++i) ctx->ws[i].dirty = false;
     return HC_OK;
+}
+
+hc_status hc_monitor_set_lds_limit()
+{
+    // a pivot with HC_MAX_K_PER_REP distinct set sizes needs 64 KB of dynamic LDS for its histograms, on top of
+    // the kernels' static LDS: above the default limit of 64 KB per workgroup
+    const int bytes = HC_MAX_K_PER_REP * HC_RADIX_BINS * (int)sizeof(uint32_t);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(mon_hist<2>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(mon_hist<3>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    return e == hipSuccess ? HC_OK : HC_EHIP;
 }

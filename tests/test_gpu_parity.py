@@ -267,6 +267,26 @@ def test_monitor_extreme_set_sizes(N, sink, recent, span):
     ctx.close()
 
 
+@pytest.mark.parametrize("span", [0, 4])
+def test_monitor_eight_distinct_set_sizes_of_one_pivot(span):
+    """The most set sizes a pivot may have (k_mon of its own plus seven satellites with different budgets): the
+    histogram passes then need 64 KB of dynamic LDS per workgroup, above the default limit."""
+    say("monitor, 8 distinct set sizes, span", span)
+    N, sink, recent = 12000, 8, 24
+    rs = [700, 650, 333, 200, 150, 64, 1]
+    heads = [I.HeadSpec(I.ROLE_FULL, k_mon=900)] + \
+            [I.HeadSpec(I.ROLE_SATELLITE, rep=0, sink=sink, recent=recent, budget=sink + recent + r) for r in rs]
+    spec = I.LayerSpec(B=1, Hq=32, Hkv=8, D=128, ctx=[N], heads=[heads])
+    rng = np.random.default_rng(21)
+    s = (rng.integers(0, 3000, N) / 7.0).astype(np.float32)          # ties at every threshold
+    lo, hi = spec.cand_range(0, 0)
+    base = {(0, 0): torch.from_numpy(np.sort(rng.choice(np.arange(lo, hi), 900, replace=False)).astype(np.int32))}
+    ctx, gpu, base_all = monitor_case(spec, {(0, 0): s}, base, span=span)
+    compare_monitor(spec, gpu, {(0, 0): s}, base_all)
+    gpu.close()
+    ctx.close()
+
+
 @pytest.mark.parametrize("metric,num,den", [(0, 4, 5), (1, 4, 5), (0, 1, 2), (1, 1, 2)])
 def test_monitor_trigger_threshold_is_exact(metric, num, den):
     """Baselines built to overlap the true top-k in exactly t and t+1 entries around the integer
@@ -353,7 +373,7 @@ def test_scores_and_sets_from_logits_config2_shape():
         say("  pivot", pv, "score max abs err", dabs, "max rel err", drel)
         for h in [pv] + w.spec.satellites(b, pv):
             T = rec["topk"][(b, h)]
-            ndiff += U.check_set_valid(topk[b * w.spec.Hkv + h, :T.size], T, s_ref, 1e-4, f"head {h}")
+            ndiff += U.check_set_valid(topk[b * w.spec.Hkv + h, :T.size], T, s_ref, U.band_of(dabs), f"head {h}")
         # and bit-exactness of the selection against the oracle rule applied to fp32 scores that only
         # the CPU produced: covered by test_monitor_bit_exact_on_given_scores
     say("  symmetric difference over 8 lists:", ndiff)
@@ -514,11 +534,12 @@ def test_gather_with_slot_map_moves_only_the_difference():
 # ------------------------------------------------------------------------------------------
 # Multi-step integration (Algorithm 1, stage 3 loop)
 # ------------------------------------------------------------------------------------------
-def run_steps(p, sched, steps, side=None, rel_band=1e-4, tag="", stepper=None, append_seed=None, token_gain=None):
+def run_steps(p, sched, steps, side=None, tag="", stepper=None, append_seed=None, token_gain=None):
     """stepper(q): runs one decode step of p.gpu (default: LayerRuntime.step).  With append_seed every step first
     appends a generated token's K/V to both sides (token_gain(t): how strongly its key is planted toward q)."""
     sp = p.spec
     resyncs = triggers = 0
+    ties_before = len(U.NEAR_TIES)
     for t in range(steps):
         q = sched.next()
         if append_seed is not None:
@@ -539,12 +560,12 @@ def run_steps(p, sched, steps, side=None, rel_band=1e-4, tag="", stepper=None, a
         same = True
         for (b, pv), s_ref in rec["scores"].items():
             lo, hi = p.ref.cand_range(b, pv)
-            U.check_scores(p.gpu.scores[p.gpu.rep_slot(b, pv)].cpu().numpy(), s_ref, lo, hi, f"{tag} step {t}")
+            dabs, _ = U.check_scores(p.gpu.scores[p.gpu.rep_slot(b, pv)].cpu().numpy(), s_ref, lo, hi, f"{tag} step {t}")
             for h in [pv] + sp.satellites(b, pv):
                 T = rec["topk"][(b, h)]
-                if U.check_set_valid(topk[b * sp.Hkv + h, :T.size], T, s_ref, rel_band, f"{tag} step {t} head {h}"):
+                if U.check_set_valid(topk[b * sp.Hkv + h, :T.size], T, s_ref, U.band_of(dabs), f"{tag} step {t} head {h}"):
                     same = False
-            if (b, pv) in rec["rescored"] and not check_rescored(p, rec, b, pv, rel_band, f"{tag} step {t}"):
+            if (b, pv) in rec["rescored"] and not check_rescored(p, rec, b, pv, f"{tag} step {t}"):
                 same = False
             gi, gf = int(p.gpu.inter[b * sp.Hkv + pv]), int(p.gpu.flag[b * sp.Hkv + pv])
             if gi != rec["inter"][(b, pv)] or gf != rec["flag"][(b, pv)]:
@@ -556,10 +577,15 @@ def run_steps(p, sched, steps, side=None, rel_band=1e-4, tag="", stepper=None, a
             resync(p, rec)
         assert p.slots_equal_oracle(), f"{tag}: slots differ after step {t}"
         say(f"  {tag} step {t}: err/rms {worst:.2e} lse {lerr:.1e} flags {list(rec['flag'].values())} inter {list(rec['inter'].values())}")
+    # a re-synchronisation is only ever the consequence of a difference that was shown to lie inside the band
+    ties = U.NEAR_TIES[ties_before:]
+    assert resyncs <= len(ties), (tag, f"{resyncs} re-synchronisations but {len(ties)} near-ties logged")
+    if resyncs:
+        say(f"  {tag}: {resyncs} re-synchronisations after near-ties inside the band: {ties}")
     return resyncs, triggers
 
 
-def check_rescored(p, rec, b, pv, rel_band, tag):
+def check_rescored(p, rec, b, pv, tag):
     """Test step of a re-scored window: what the pass left for every buffered query that is still in its work
     buffer (scores, lse, list) and the W overlaps in the ring, against the oracle's.  False: a near-tie
     went the other way in some list (then the overlaps may differ too)."""
@@ -574,8 +600,8 @@ def check_rescored(p, rec, b, pv, rel_band, tag):
         if k + per < len(again):
             continue                                  # a later pass reused this item's place in the buffer
         got = g.rescored(k % per)
-        U.check_scores(got["scores"][slot].cpu().numpy(), s_k, lo, hi, f"{tag} re-scored query {k}")
-        if U.check_set_valid(got["topk"][row, :T_k.size].cpu().numpy(), T_k, s_k, rel_band, f"{tag} re-scored query {k}"):
+        dabs, _ = U.check_scores(got["scores"][slot].cpu().numpy(), s_k, lo, hi, f"{tag} re-scored query {k}")
+        if U.check_set_valid(got["topk"][row, :T_k.size].cpu().numpy(), T_k, s_k, U.band_of(dabs), f"{tag} re-scored query {k}"):
             same = False
     ring = g.ring[row].cpu().numpy()
     want = rec["window"][(b, pv)]
@@ -618,7 +644,7 @@ def test_config1_tiny_multi_step_with_side_stream():
     side = torch.cuda.Stream()
     resyncs, triggers = run_steps(p, w.schedule, 12, side=side, tag="cfg1")
     say("  resyncs", resyncs, "triggers", triggers)
-    assert triggers >= 2 and resyncs <= 1
+    assert triggers >= 2 and resyncs <= 1, (resyncs, U.NEAR_TIES[-4:])
     assert p.ref.n_tests == 12
     p.close()
 
@@ -660,7 +686,7 @@ def test_captured_graph_of_a_layer_step_replays_like_eager():
 
     resyncs, triggers = run_steps(p, w.schedule, 10, tag="graph", stepper=replay)
     say("  resyncs", resyncs, "triggers", triggers)
-    assert triggers >= 2 and resyncs <= 1
+    assert triggers >= 2 and resyncs <= 1, (resyncs, U.NEAR_TIES[-4:])
     p.close()
 
 
@@ -670,7 +696,7 @@ def test_config2_shape_multi_step():
     p = U.Pair(w.spec, w.data, DEV)
     resyncs, triggers = run_steps(p, w.schedule, 6, side=torch.cuda.Stream(), tag="cfg2")
     say("  resyncs", resyncs, "triggers", triggers)
-    assert triggers >= 2 and resyncs <= 2
+    assert triggers >= 2 and resyncs <= 2, (resyncs, U.NEAR_TIES[-4:])
     p.close()
 
 
@@ -680,7 +706,7 @@ def test_config5_shape_batched_multi_step():
     p = U.Pair(w.spec, w.data, DEV)
     resyncs, triggers = run_steps(p, w.schedule, 4, side=torch.cuda.Stream(), tag="cfg5")
     say("  resyncs", resyncs, "triggers", triggers)
-    assert resyncs <= 2
+    assert resyncs <= 2, (resyncs, U.NEAR_TIES[-4:])
     p.close()
 
 
@@ -718,7 +744,7 @@ def test_growing_context_multi_step(use_side):
                                   token_gain=lambda t: 40.0 if t % 9 == 4 else 0.0)
     say("  resyncs", resyncs, "triggers", triggers)
     assert p.gpu.context(0) == n0 + 70 == p.ref.ctx[0]
-    assert triggers >= 3 and resyncs <= 2
+    assert triggers >= 3 and resyncs <= 2, (resyncs, U.NEAR_TIES[-4:])
     planted = [n0 + t for t in range(70) if t % 9 == 4 and t < 70 - 34]
     got = set(p.ref.retrieved[(0, 1)].tolist())
     assert all(pos in got for pos in planted), "planted tokens that left the window are retrieved"
@@ -799,10 +825,10 @@ def test_config4_full_size_single_layer():
         nd = 0
         for (b, pv), s_ref in rec["scores"].items():
             lo, hi = w.spec.cand_range(b, pv)
-            U.check_scores(p.gpu.scores[p.gpu.rep_slot(b, pv)].cpu().numpy(), s_ref, lo, hi, "cfg4")
+            dabs, _ = U.check_scores(p.gpu.scores[p.gpu.rep_slot(b, pv)].cpu().numpy(), s_ref, lo, hi, "cfg4")
             for h in [pv] + w.spec.satellites(b, pv):
                 T = rec["topk"][(b, h)]
-                nd += U.check_set_valid(topk[b * 8 + h, :T.size], T, s_ref, 1e-4, f"cfg4 head {h}")
+                nd += U.check_set_valid(topk[b * 8 + h, :T.size], T, s_ref, U.band_of(dabs), f"cfg4 head {h}")
         say(f"  step {t}: err/rms {worst:.2e} lse {lerr:.1e} set differences {nd} flags {rec['flag']}")
         if nd:
             resync(p, rec)
@@ -874,10 +900,10 @@ def test_config4_full_size_in_the_benchmark_launch_configuration():
             nd = 0
             for (b, pv), s_ref in rec["scores"].items():
                 lo, hi = w.spec.cand_range(b, pv)
-                U.check_scores(p.gpu.scores[p.gpu.rep_slot(b, pv)].cpu().numpy(), s_ref, lo, hi, "cfg4")
+                dabs, _ = U.check_scores(p.gpu.scores[p.gpu.rep_slot(b, pv)].cpu().numpy(), s_ref, lo, hi, "cfg4")
                 for h in [pv] + w.spec.satellites(b, pv):
                     T = rec["topk"][(b, h)]
-                    nd += U.check_set_valid(topk[b * 8 + h, :T.size], T, s_ref, 1e-4, f"cfg4 head {h}")
+                    nd += U.check_set_valid(topk[b * 8 + h, :T.size], T, s_ref, U.band_of(dabs), f"cfg4 head {h}")
                 assert int(p.gpu.flag[pv]) == rec["flag"][(b, pv)] or nd
             say(f"  layer {l} step {t}: err/rms {worst:.2e} lse {lerr:.1e} set differences {nd} flags {rec['flag']}")
             if nd:
@@ -938,7 +964,7 @@ def test_decode_step_stack_of_layers_matches_oracle(n_layers, n_side, group):
             U.check_attention(gpu.out, gpu.lse, rec, f"step {t} layer {l}")
             topk = gpu.topk_idx.cpu().numpy()
             for (b, h), T in rec["topk"].items():
-                assert U.check_set_valid(topk[b * 8 + h, :T.size], T, rec["scores"][(b, h if h in w.spec.reps(b) else w.spec.heads[b][h].rep)], 1e-4) == 0
+                assert U.check_set_valid(topk[b * 8 + h, :T.size], T, rec["scores"][(b, h if h in w.spec.reps(b) else w.spec.heads[b][h].rep)], 0.0) == 0
             for (b, pv), f in rec["flag"].items():
                 assert int(gpu.flag[pv]) == f and int(gpu.inter[pv]) == rec["inter"][(b, pv)]
                 triggers += f
@@ -1012,7 +1038,7 @@ def test_rescored_window_growing_context_multi_step(use_side):
     resyncs, triggers = run_steps(p, sched, 24, side=side, tag="rescored", append_seed=9100,
                                   token_gain=lambda t: 30.0 if t % 3 == 0 else 0.0)
     say("  resyncs", resyncs, "triggers", triggers)
-    assert p.ref.n_tests == 6 and triggers >= 1 and resyncs <= 2
+    assert p.ref.n_tests == 6 and triggers >= 1 and resyncs <= 2, (resyncs, U.NEAR_TIES[-4:])
     # the case is worth its name only if scoring again changes some overlap
     changed = 0
     for t in range(3, 24, 4):
@@ -1033,7 +1059,7 @@ def test_rescored_window_config4_full_size():
     p = U.Pair(w.spec, w.data, DEV, growth=8)
     resyncs, triggers = run_steps(p, w.schedule, 4, side=torch.cuda.Stream(), tag="cfg4 rescored", append_seed=9900,
                                   token_gain=lambda t: 30.0 if t == 1 else 0.0)
-    assert p.ref.n_tests == 2 and resyncs <= 1          # two pivots, one test step
+    assert p.ref.n_tests == 2 and resyncs <= 1, (resyncs, U.NEAR_TIES[-4:])          # two pivots, one test step
     p.close()
 
 
@@ -1048,7 +1074,7 @@ def test_rescored_window_of_one_and_two_steps(W):
     p = U.Pair(spec, data, DEV, growth=16)
     resyncs, triggers = run_steps(p, I.QuerySchedule(q0, 193, step_deg=6.0), 8, tag=f"rescored W{W}", append_seed=9800,
                                   token_gain=lambda t: 30.0 if t % 2 else 0.0)
-    assert p.ref.n_tests == 8 // W and triggers >= 1 and resyncs <= 1
+    assert p.ref.n_tests == 8 // W and triggers >= 1 and resyncs <= 1, (resyncs, U.NEAR_TIES[-4:])
     assert hc.hc_layer_window_slot(p.gpu.handle) == 8 % W
     p.close()
 
@@ -1088,7 +1114,7 @@ def test_rescored_window_of_the_maximum_width():
     p = U.Pair(spec, data, DEV, growth=72)
     resyncs, triggers = run_steps(p, I.QuerySchedule(q0, 197, step_deg=3.0), 66, tag="rescored W64", append_seed=9850,
                                   token_gain=lambda t: 30.0 if t % 7 == 0 else 0.0)
-    assert p.ref.n_tests == 1 and resyncs <= 1
+    assert p.ref.n_tests == 1 and resyncs <= 1, (resyncs, U.NEAR_TIES[-4:])
     assert hc.hc_layer_window_slot(p.gpu.handle) == 2
     p.close()
 
@@ -1109,7 +1135,7 @@ def test_rescored_window_group_sizes_and_several_passes(G, W):
     p = U.Pair(spec, data, DEV, growth=2 * W + 2)
     resyncs, triggers = run_steps(p, sched, 2 * W, tag=f"rescored G{G}", append_seed=9300 + G,
                                   token_gain=lambda t: 25.0 if t % 2 == 0 else 0.0)
-    assert p.ref.n_tests == 4 and resyncs <= 2          # two pivots, two test steps each
+    assert p.ref.n_tests == 4 and resyncs <= 2, (resyncs, U.NEAR_TIES[-4:])          # two pivots, two test steps each
     p.close()
 
 
@@ -1169,13 +1195,15 @@ def test_rescored_window_in_the_decode_step(W):
             same = True
             topk = pr.gpu.topk_idx.cpu().numpy()
             for (b, pv), s_ref in rec["scores"].items():
+                lo, hi = pr.ref.cand_range(b, pv)
+                dabs, _ = U.check_scores(pr.gpu.scores[pr.gpu.rep_slot(b, pv)].cpu().numpy(), s_ref, lo, hi, f"L{l} t{t}")
                 for h in [pv] + specs[l].satellites(b, pv):
                     T = rec["topk"][(b, h)]
-                    if U.check_set_valid(topk[b * Hkv + h, :T.size], T, s_ref, 1e-4, f"L{l} t{t} head {h}"):
+                    if U.check_set_valid(topk[b * Hkv + h, :T.size], T, s_ref, U.band_of(dabs), f"L{l} t{t} head {h}"):
                         same = False
                 if (b, pv) in rec["rescored"]:
                     tests += 1
-                    same &= check_rescored(pr, rec, b, pv, 1e-4, f"decode step L{l} t{t}")
+                    same &= check_rescored(pr, rec, b, pv, f"decode step L{l} t{t}")
                 gi, gf = int(pr.gpu.inter[b * Hkv + pv]), int(pr.gpu.flag[b * Hkv + pv])
                 if gi != rec["inter"][(b, pv)] or gf != rec["flag"][(b, pv)]:
                     assert not same
@@ -1226,7 +1254,7 @@ def test_prefill_init_matches_oracle_and_decoding_continues_from_it(pool, G, B):
     assert int(p.gpu.ring.abs().sum()) == 0
     sched = I.QuerySchedule(q0, 302 + pool, step_deg=6.0)
     resyncs, triggers = run_steps(p, sched, 5, side=torch.cuda.Stream(), tag=f"after prefill pool {pool}")
-    assert resyncs <= 1
+    assert resyncs <= 1, (resyncs, U.NEAR_TIES[-4:])
     p.close()
 
 

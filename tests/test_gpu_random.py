@@ -87,7 +87,7 @@ def test_random_layer(seed):
             hc.hc_decode_step(p.ctx.handle, io, 1, None, side, rng.choice([1, 8]))
     resyncs, _ = T.run_steps(p, sched, steps, side=side, tag=f"random {seed}", append_seed=8000 + 100 * seed if grow else None,
                              token_gain=lambda t: 25.0 if t % 3 == 1 else 0.0, stepper=stepper)
-    assert resyncs <= 2
+    assert resyncs <= 2, (resyncs, U.NEAR_TIES[-4:])
     if grow:
         assert [p.gpu.context(b) for b in range(spec.B)] == p.ref.ctx
     p.close()
@@ -164,12 +164,14 @@ def test_random_stack_through_the_decode_step(seed):
             same = True
             topk = pr.gpu.topk_idx.cpu().numpy()
             for (b, pv), s_ref in rec["scores"].items():
+                lo, hi = pr.ref.cand_range(b, pv)
+                dabs, _ = U.check_scores(pr.gpu.scores[pr.gpu.rep_slot(b, pv)].cpu().numpy(), s_ref, lo, hi, f"stack {seed} L{l} t{t}")
                 for h in [pv] + sp.satellites(b, pv):
                     Tl = rec["topk"][(b, h)]
-                    if U.check_set_valid(topk[b * Hkv + h, :Tl.size], Tl, s_ref, 1e-4, f"stack {seed} L{l} t{t} head {h}"):
+                    if U.check_set_valid(topk[b * Hkv + h, :Tl.size], Tl, s_ref, U.band_of(dabs), f"stack {seed} L{l} t{t} head {h}"):
                         same = False
                 if (b, pv) in rec["rescored"]:
-                    same &= T.check_rescored(pr, rec, b, pv, 1e-4, f"stack {seed} L{l} t{t}")
+                    same &= T.check_rescored(pr, rec, b, pv, f"stack {seed} L{l} t{t}")
                 gi, gf = int(pr.gpu.inter[b * Hkv + pv]), int(pr.gpu.flag[b * Hkv + pv])
                 if gi != rec["inter"][(b, pv)] or gf != rec["flag"][(b, pv)]:
                     assert not same, (seed, l, t, "same sets but different inter / flag")

@@ -13,8 +13,18 @@ def test_pooling_is_the_library_average_pooling_with_zero_padding():
     for n, P in [(1, 1), (1, 3), (2, 5), (17, 3), (64, 7), (301, 13), (50, 1)]:
         s = rng.random(n)
         want = F.avg_pool1d(torch.from_numpy(s)[None, None], kernel_size=P, stride=1, padding=P // 2)[0, 0].numpy()
-        np.testing.assert_allclose(prefill.avg_pool(s, P), want, rtol=1e-13, atol=1e-15)
-        np.testing.assert_allclose(prefill.avg_pool_fast(s, P), want, rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(prefill.avg_pool_loops(s, P), want, rtol=1e-13, atol=1e-15)
+        # the form used on long arrays adds the same terms in the same order: bit for bit the same
+        assert prefill.avg_pool(s, P).tolist() == prefill.avg_pool_loops(s, P).tolist()
+
+
+def test_pooling_at_full_length_is_the_library_average_pooling():
+    """224K positions, the widths the GPU tests use: against the library routine in double precision."""
+    rng = np.random.default_rng(5)
+    s = rng.random(229376) ** 8                 # a few large values among many small ones, like attention weights
+    for P in (3, 7, 63):
+        want = F.avg_pool1d(torch.from_numpy(s)[None, None], kernel_size=P, stride=1, padding=P // 2)[0, 0].numpy()
+        np.testing.assert_allclose(prefill.avg_pool(s, P), want, rtol=1e-12, atol=1e-18)
 
 
 def test_pooling_by_hand():
@@ -47,7 +57,7 @@ def test_who_selects_what():
 def test_brute_force_selection_with_numpy():
     for P in (1, 5):
         spec, q, data = tiny(N=90, r=12, seed=4)
-        retrieved, base, _ = prefill.prefill_init(spec, data, q, pool=P, exact_pool=True)
+        retrieved, base, _ = prefill.prefill_init(spec, data, q, pool=P)
         for (b, h), got in list(retrieved.items()) + list(base.items()):
             K = data.K[(b, h)].float().double().numpy()
             qq = q[b, 4 * h:4 * h + 4].float().double().numpy()

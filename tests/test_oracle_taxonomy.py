@@ -77,7 +77,8 @@ def test_budget_closed_forms():
 
 @pytest.mark.parametrize("seed", range(20))
 def test_budgets_stay_within_one_slot_of_the_exact_shares(seed):
-    """The double-precision evaluation against exact rational arithmetic of Eq. 8 on the same inputs."""
+    """Every integer budget lies within one slot of the real-valued share of Eq. 8 (written out again here), and the
+    budgets add up to the total of Eq. 7."""
     rng = random.Random(500 + seed)
     n = rng.randint(2, 48)
     role = [rng.choice([T.ROLE_FULL, T.ROLE_SATELLITE, T.ROLE_SATELLITE, T.ROLE_ANCHOR]) for _ in range(n)]
