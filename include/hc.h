@@ -57,6 +57,7 @@ enum { HC_METRIC_OVERLAP = 0, HC_METRIC_JACCARD = 1 };
 enum { HC_AGG_PROB = 0, HC_AGG_LOGIT = 1 };
 enum { HC_WINDOW_SLIDING = 0, HC_WINDOW_TUMBLING = 1, HC_WINDOW_RESCORED = 2 };
 enum { HC_MAX_WINDOW = 64, HC_MAX_K_PER_REP = 8, HC_MAX_GROUP = 8 };
+enum { HC_STATIC_MAX_PARTIALS = 1024 };   /* largest split-K plan hc_decode_attn_static accepts */
 
 typedef struct {
     int32_t B;         /* sequences in the batch (>= 1)                                         */
@@ -216,6 +217,21 @@ hc_status hc_budgets(int32_t n_heads, const int32_t* role, const double* s_stabl
  * bf16 inputs, fp32 accumulation; split over the token axis with a second combine pass. */
 hc_status hc_decode_attn(hc_ctx* ctx, const hc_layer* layer, const void* kv_arena, const void* q,
                          float* out, float* lse, float* rep_logits, void* stream);
+
+/* hc_decode_attn for callers that cannot allocate device memory or let a library do it: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same results;
+ * the only difference is where the split-K partial results live between the two passes: not in the workspace
+ * that hc_layer_create sizes and allocates, but in a fixed array of device memory inside the library (4.3 MB per
+ * GPU, there from the moment the library is loaded until the process ends; its address on the context's device
+ * is looked up once, in hc_create).  The call allocates and frees nothing, on the host or the device.
+ * Limits: the layer's plan may have at most HC_STATIC_MAX_PARTIALS partial results (hc_layer_num_partials;
+ * 2 per compute unit plus one per KV head and sequence, i.e. any batch up to 512 head rows on a 256-unit GPU);
+ * a larger plan is refused with HC_ESHAPE and nothing is launched.  Every call on one GPU uses the same array,
+ * from whatever context: two calls that may overlap (different streams, no ordering between them) race, and the
+ * caller must order them; calls on one stream are safe, and nothing needs clearing between calls (the second
+ * pass reads only the slots the first pass of the same call wrote). */
+hc_status hc_decode_attn_static(hc_ctx* ctx, const hc_layer* layer, const void* kv_arena, const void* q,
+                                float* out, float* lse, float* rep_logits, void* stream);
 
 /* Pivot drift monitor (Sec. 4.3, Eq. 9-10; Algorithm 1, the block under "t mod W = 0" with the
  * window read as sliding and tested every step once it holds W values).  For every pivot p:

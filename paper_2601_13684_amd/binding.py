@@ -17,11 +17,12 @@ LIB_PATH = os.path.join(_HERE, "libhc.so")
 
 HC_OK, HC_EINVAL, HC_ESHAPE, HC_ENOMEM, HC_EHIP, HC_ESTATE = range(6)
 HC_MAX_WINDOW, HC_MAX_K_PER_REP, HC_MAX_GROUP = 64, 8, 8
+HC_STATIC_MAX_PARTIALS = 1024
 
 EXPORTS = ["hc_create", "hc_destroy", "hc_strerror", "hc_last_error", "hc_layer_create", "hc_layer_destroy",
            "hc_layer_num_reps", "hc_layer_rep_slot", "hc_layer_num_workgroups", "hc_layer_num_partials",
            "hc_set_split", "hc_set_share_weights", "hc_get_share_weights", "hc_layer_tune", "hc_set_monitor_span",
-           "hc_set_timing_events", "hc_plan_describe", "hc_decode_attn", "hc_rep_topk_drift", "hc_gather_retrieve",
+           "hc_set_timing_events", "hc_plan_describe", "hc_decode_attn", "hc_decode_attn_static", "hc_rep_topk_drift", "hc_gather_retrieve",
            "hc_append_kv", "hc_rescore_work_bytes", "hc_rescore_work_layout", "hc_rescore_window", "hc_prefill_work_bytes", "hc_prefill_work_layout", "hc_prefill_init",
            "hc_layer_window_slot",
            "hc_layer_set_window_slot", "hc_layer_context",
@@ -106,6 +107,7 @@ def lib():
         L.hc_plan_describe.argtypes = [C.POINTER(hc_config), C.POINTER(hc_head_desc), i32, i32,
                                        C.POINTER(hc_plan_info), C.c_char_p, i32]
         L.hc_decode_attn.argtypes = [vp] * 8
+        L.hc_decode_attn_static.argtypes = [vp] * 8
         L.hc_rep_topk_drift.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
         L.hc_gather_retrieve.argtypes = [vp] * 10
         L.hc_append_kv.argtypes = [vp] * 7
@@ -259,6 +261,12 @@ def hc_decode_attn(ctx: int, layer: int, kv_arena: Ptr, q: Ptr, out: Ptr, lse: P
                    stream=None) -> None:
     _check(lib().hc_decode_attn(ctx, layer, _p(kv_arena), _p(q), _p(out), _p(lse), _p(rep_logits), _stream(stream)),
            "hc_decode_attn", ctx)
+
+
+def hc_decode_attn_static(ctx: int, layer: int, kv_arena: Ptr, q: Ptr, out: Ptr, lse: Ptr, rep_logits: Ptr = None,
+                          stream=None) -> None:
+    _check(lib().hc_decode_attn_static(ctx, layer, _p(kv_arena), _p(q), _p(out), _p(lse), _p(rep_logits), _stream(stream)),
+           "hc_decode_attn_static", ctx)
 
 
 def hc_rep_topk_drift(ctx: int, layer: int, rep_logits: Ptr, lse: Ptr, scores: Ptr, scores_given: bool,

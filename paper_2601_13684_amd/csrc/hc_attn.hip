@@ -550,6 +550,24 @@ hc_status launch(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* 
 
 }   // namespace
 
+// Fixed scratch for callers that cannot allocate: room for the split-K partial results of the largest plan
+// hc_decode_attn_static accepts, HC_STATIC_MAX_PARTIALS slots of (accumulators [8][128], then (max, sum) [8][2]
+// behind all accumulators).  One copy per GPU, held until the process ends.  In host code the array's name is
+// only a handle for hipGetSymbolAddress: kernels get the address that call returns.
+constexpr size_t STATIC_ACC_FLOATS = (size_t)HC_STATIC_MAX_PARTIALS * 8 * HC_D;
+constexpr size_t STATIC_ML_FLOATS = (size_t)HC_STATIC_MAX_PARTIALS * 8 * 2;
+static __device__ __align__(256) float scratch[STATIC_ACC_FLOATS + STATIC_ML_FLOATS];
+
+hc_status hc_attn_static_scratch(hc_ctx* ctx, float** base)
+{
+    // once per context, with the context's device current (hc_create): every GPU holds its own copy of the array
+    // at its own address
+    void* ptr = nullptr;
+    HC_HIP(ctx, hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    *base = static_cast<float*>(ptr);
+    return HC_OK;
+}
+
 static hc_status launch_any(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* q, float* out, float* lse,
                             float* rep_logits, hipStream_t st, float* part_acc, float* part_ml)
 {
@@ -567,4 +585,14 @@ hc_status hc_launch_attn(hc_ctx* ctx, const hc_layer* L, const void* arena, cons
 {
     if ((size_t)L->n_partials > ctx->part_slots) return hc_fail(ctx, HC_ESTATE, "split-K workspace smaller than the plan");
     return launch_any(ctx, L, arena, q, out, lse, rep_logits, st, ctx->part_acc, ctx->part_ml);
+}
+
+hc_status hc_launch_attn_static(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* q, float* out, float* lse,
+                                float* rep_logits, hipStream_t st)
+{
+    if (!ctx->static_scratch) return hc_fail(ctx, HC_ESTATE, "hc_decode_attn_static: the fixed scratch array was not found on this device");
+    if (L->n_partials > HC_STATIC_MAX_PARTIALS)
+        return hc_fail(ctx, HC_ESHAPE, "hc_decode_attn_static: the layer's plan has %d partial results, the fixed scratch holds %d",
+                       L->n_partials, (int)HC_STATIC_MAX_PARTIALS);
+    return launch_any(ctx, L, arena, q, out, lse, rep_logits, st, ctx->static_scratch, ctx->static_scratch + STATIC_ACC_FLOATS);
 }

@@ -140,6 +140,9 @@ extern "C" hc_status hc_create(const hc_config* cfg, hc_ctx** out)
         c->npairs = g + 2 * pair_w;
         (void)hc_gather_set_lds_limit();
         (void)hc_monitor_set_lds_limit();
+        // the fixed scratch of hc_decode_attn_static: its address on this device (left null if the lookup fails;
+        // that entry point then refuses to run, the others do not need it)
+        if (hc_attn_static_scratch(c, &c->static_scratch) != HC_OK) c->static_scratch = nullptr;
     }
     for (int i = 0; i < HC_MAX_GROUP; ++i) {
         hc_monitor_ws& w = c->ws[i];
@@ -695,6 +698,15 @@ extern "C" hc_status hc_decode_attn(hc_ctx* ctx, const hc_layer* layer, const vo
     const hc_status chk = attn_check(ctx, layer, kv_arena, q, out, lse, rep_logits);
     if (chk != HC_OK) return chk;
     return hc_launch_attn(ctx, layer, kv_arena, q, out, lse, rep_logits, (hipStream_t)stream);
+}
+
+extern "C" hc_status hc_decode_attn_static(hc_ctx* ctx, const hc_layer* layer, const void* kv_arena, const void* q,
+                                           float* out, float* lse, float* rep_logits, void* stream)
+{
+    if (!ctx_ok(ctx)) return HC_ESTATE;
+    const hc_status chk = attn_check(ctx, layer, kv_arena, q, out, lse, rep_logits);
+    if (chk != HC_OK) return chk;
+    return hc_launch_attn_static(ctx, layer, kv_arena, q, out, lse, rep_logits, (hipStream_t)stream);
 }
 
 static hc_status monitor_check(hc_ctx* ctx, const hc_layer* layer, const float* rep_logits, const float* lse,

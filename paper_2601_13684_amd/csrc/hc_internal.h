@@ -96,6 +96,7 @@ struct hc_ctx {
     float* part_acc = nullptr;   // [slots][G][D]
     float* part_ml = nullptr;    // [slots][G][2]  (running max in log2 units, sum)
     size_t part_slots = 0;
+    float* static_scratch = nullptr;   // this device's address of the fixed scratch array of hc_decode_attn_static
     // selection workspace, sized for max_reps pivots; one copy per layer of a batched monitor call
     int max_reps = 0;
     uint32_t* ws_base = nullptr;   // the one allocation behind all lanes
@@ -191,6 +192,9 @@ struct hc_gather_call {
 };
 hc_status hc_launch_attn(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* q, float* out,
                          float* lse, float* rep_logits, hipStream_t st);
+hc_status hc_launch_attn_static(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* q, float* out,
+                                float* lse, float* rep_logits, hipStream_t st);
+hc_status hc_attn_static_scratch(hc_ctx* ctx, float** base);     // at context creation, with the context's device current
 hc_status hc_launch_monitor(hc_ctx* ctx, int n, const hc_monitor_call* calls, int scores_given, hipStream_t st);
 hc_status hc_launch_gather(hc_ctx* ctx, int n, const hc_gather_call* calls, hipStream_t st);
 hc_status hc_gather_set_lds_limit();     // once per process, at context creation
