@@ -62,6 +62,7 @@ def main():
     ap.add_argument("--attn-only", action="store_true", help="time hc_decode_attn alone (no monitor, no gather)")
     ap.add_argument("--oracle-seconds", type=float, default=12.0)
     ap.add_argument("--no-oracle", action="store_true")
+    ap.add_argument("--no-probes", action="store_true", help="skip the streaming-read / host-link probes and the gather-alone pass")
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the pass that times the split kernel")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="first run 8 plain streaming kernels (out = in + 1 over MiB of fp32 in, MiB out) so that a "
@@ -255,14 +256,19 @@ def main():
         run = graph.replay
     else:
         run = step_eager
-    trig_before = None
+    # one event between consecutive steps on the main stream: the distribution of the step time (GPU side)
+    step_ev = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+    first_timed_t = t_pos[0] if args.mode != "graph" else W
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(K):
+    step_ev[0].record()
+    for i in range(K):
         run()
+        step_ev[i + 1].record()
     t_host = time.perf_counter()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    step_ms = np.array([step_ev[i].elapsed_time(step_ev[i + 1]) for i in range(K)])
     host_enqueue_ms = (t_host - t0) * 1e3 / K
     ms_per_step = (t1 - t0) * 1e3 / K
     us_per_layer = ms_per_step * 1e3 / L
@@ -306,6 +312,150 @@ def main():
         hc.hc_set_timing_events(ctx.handle)
         torch.cuda.synchronize()
         iso_us = float(np.mean([a.elapsed_time(b) for a, b in evs[:n_iso * L]]) * 1e3)
+
+    # ---- step-time distribution (GPU side, events between steps of the timed region) ----
+    def dist(a):
+        a = np.asarray(a, dtype=np.float64)
+        return {"n": int(a.size), "median": float(np.median(a)), "p95": float(np.percentile(a, 95)), "max": float(a.max())} if a.size else None
+    jump_every = getattr(scheds[0], "jump_every", 0)
+    kinds = []
+    for i in range(K):
+        t = first_timed_t + i                                    # index of the step's query in the schedule
+        if jump_every and t > 0 and t % jump_every == 0:
+            kinds.append("jump")                                 # every pivot of every layer fires and refills
+        elif jump_every and t > 1 and (t - 1) % jump_every == 0:
+            kinds.append("after_jump")                           # its attention waits for the refills of the jump step
+        elif args.append and (t + 1) % 64 == 0:
+            kinds.append("replan")                               # the split-K plans are rebalanced on the host
+        else:
+            kinds.append("plain")
+    step_stats = {"unit": "ms per decode step (all layers)", "all": dist(step_ms)}
+    for kind in ("plain", "jump", "after_jump", "replan"):
+        sel = [step_ms[i] for i in range(K) if kinds[i] == kind]
+        if sel:
+            step_stats[kind] = dist(sel)
+    if "after_jump" in step_stats and "plain" in step_stats:
+        # what the step after a refill loses against an ordinary step: waiting for the refill (lag 1) shows here
+        step_stats["stall_ms_after_jump"] = max(0.0, step_stats["after_jump"]["median"] - step_stats["plain"]["median"])
+
+    # ---- what the machine gives: streaming-read rate of HBM, rates of the host link ----
+    probes = {}
+    if not args.no_probes:
+        ev_a, ev_b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        sink = torch.zeros((4,), dtype=torch.int32, device=dev)
+        # HBM: one streaming read of every layer's arena in turn (the stack is far larger than the last-level cache),
+        # for a few launch shapes and both kinds of load; the best is what a kernel can get out of this machine
+        arenas = [lay.arena for lay in layers]
+        reps = max(1, 32 // len(arenas))
+        nbytes = reps * sum(a.numel() * 2 for a in arenas)
+        sweep = {}
+        for nt in (True, False):
+            for wg in (1024, 2048, 8192):
+                for a in arenas[:2]:
+                    hc.hc_probe_stream_read(a, a.numel() * 2, sink, wg, nt)
+                torch.cuda.synchronize()
+                ev_a.record()
+                for _ in range(reps):
+                    for a in arenas:
+                        hc.hc_probe_stream_read(a, a.numel() * 2, sink, wg, nt)
+                ev_b.record()
+                torch.cuda.synchronize()
+                sweep[f"{'streaming' if nt else 'plain'}_loads_{wg}wg"] = nbytes / (ev_a.elapsed_time(ev_b) * 1e-3) / 1e9
+        probes["stream_read_sweep_GBps"] = sweep
+        probes["stream_read_GBps"] = max(sweep.values())
+        probes["stream_read_bytes_per_launch"] = int(arenas[0].numel() * 2)
+        probes["stream_read_us_per_launch"] = probes["stream_read_bytes_per_launch"] / probes["stream_read_GBps"] * 1e-3
+        tier0 = next((lay.tier for lay in layers if lay.tier is not None), None)
+        if tier0 is not None:
+            # host link: plain pinned host-to-device copies of growing size, and a kernel that reads pinned memory
+            n_max = min(tier0.numel(), 128 << 20)                # up to 256 MB of bf16
+            dst = torch.empty((n_max,), dtype=torch.bfloat16, device=dev)
+            sweep = {}
+            for mib in (1, 4, 16, 64, 256):
+                n = min(n_max, mib << 19)
+                dst[:n].copy_(tier0[:n], non_blocking=True)
+                torch.cuda.synchronize()
+                r = 4 if mib < 64 else 2
+                ev_a.record()
+                for _ in range(r):
+                    dst[:n].copy_(tier0[:n], non_blocking=True)
+                ev_b.record()
+                torch.cuda.synchronize()
+                sweep[f"{n * 2 >> 20}MiB"] = r * n * 2 / (ev_a.elapsed_time(ev_b) * 1e-3) / 1e9
+            probes["host_to_device_copy_GBps"] = sweep
+            ksweep = {}
+            for wg in (48, 96, 192, 512):
+                hc.hc_probe_host_copy(tier0, dst, n_max * 2, wg)
+                torch.cuda.synchronize()
+                ev_a.record()
+                hc.hc_probe_host_copy(tier0, dst, n_max * 2, wg)
+                ev_b.record()
+                torch.cuda.synchronize()
+                ksweep[f"{wg}wg"] = n_max * 2 / (ev_a.elapsed_time(ev_b) * 1e-3) / 1e9
+            probes["kernel_read_of_pinned_GBps"] = ksweep
+            probes["link_peak_GBps"] = max(max(sweep.values()), max(ksweep.values()))
+            del dst
+
+    # ---- the gather alone: a whole-list refill and a difference-only refill of known size, per layer ----
+    gather = None
+    sat_layers = [lay for lay in layers[:8] if lay.tier is not None and lay.n_reps]
+    if sat_layers and not args.no_probes and not args.attn_only:
+        ev_a, ev_b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        Hkv = spec0.Hkv
+
+        def sat_rows(lay):
+            return [(b * Hkv + h, lay.spec.r(b, h), lay.spec.ctx[b], lay.spec.heads[b][h]) for b in range(lay.spec.B)
+                    for h in range(Hkv) if lay.spec.heads[b][h].role == I.ROLE_SATELLITE and lay.spec.r(b, h) > 0]
+        torch.cuda.synchronize()
+        for lay in sat_layers:
+            lay.flag.fill_(1)
+        # (a) whole lists: every retrieved slot of every satellite is fetched again (no slot map)
+        rows_full = sum(r for lay in sat_layers for _, r, _, _ in sat_rows(lay))
+        torch.cuda.synchronize()
+        ev_a.record()
+        for lay in sat_layers:
+            hc.hc_gather_retrieve(ctx.handle, lay.handle, lay.tier, lay.topk_idx, lay.flag, lay.arena, None)
+        ev_b.record()
+        torch.cuda.synchronize()
+        us_full = ev_a.elapsed_time(ev_b) * 1e3
+        rows_delta = 0
+        us_delta = None
+        if all(lay.slot_pos is not None for lay in sat_layers):
+            # the slots now hold the lists in list order; (b) new lists that keep 75 % of every list and replace
+            # the rest by positions that are not resident: only those rows may cross the link
+            gd = torch.Generator(device=dev)
+            gd.manual_seed(99)
+            for lay in sat_layers:
+                for row, r, n_ctx, hs in sat_rows(lay):
+                    cur = lay.topk_idx[row, :r].long()
+                    lay.slot_pos[row, :r] = cur.int()
+                    n_new = r // 4
+                    resident = torch.zeros((n_ctx,), dtype=torch.bool, device=dev)
+                    resident[cur] = True
+                    resident[:hs.sink] = True
+                    resident[n_ctx - hs.recent:] = True
+                    free = (~resident).nonzero().flatten()
+                    fresh = free[torch.randperm(free.numel(), generator=gd, device=dev)[:n_new]]
+                    keep_ix = torch.randperm(r, generator=gd, device=dev)[:r - n_new]
+                    lay.topk_idx[row, :r] = torch.cat([cur[keep_ix], fresh]).sort().values.int()
+                    rows_delta += n_new
+            torch.cuda.synchronize()
+            ev_a.record()
+            for lay in sat_layers:
+                hc.hc_gather_retrieve(ctx.handle, lay.handle, lay.tier, lay.topk_idx, lay.flag, lay.arena, lay.slot_pos)
+            ev_b.record()
+            torch.cuda.synchronize()
+            us_delta = ev_a.elapsed_time(ev_b) * 1e3
+        for lay in sat_layers:
+            lay.flag.zero_()
+        gather = {"layers": len(sat_layers), "alone_on_the_gpu": True,
+                  "whole_lists": {"rows": rows_full, "bytes": rows_full * 512, "us": us_full, "GBps": rows_full * 512 / (us_full * 1e-6) / 1e9},
+                  "difference_only": None if us_delta is None else
+                  {"rows": rows_delta, "bytes": rows_delta * 512, "us": us_delta, "GBps": rows_delta * 512 / (us_delta * 1e-6) / 1e9,
+                   "rows_kept_resident": rows_full - rows_delta}}
+        if probes.get("link_peak_GBps"):
+            gather["link_peak_GBps"] = probes["link_peak_GBps"]
+            gather["frac_of_link_peak"] = gather["whole_lists"]["GBps"] / probes["link_peak_GBps"]
 
     # ---- CPU oracle on a bounded sample: layers 0..1, first steps (the same inputs as warm-up) ----
     cpu = None
@@ -360,7 +510,14 @@ def main():
                      "kernel_us_median": float(np.median(kern_ms) * 1e3), "kernel_us_p95": float(np.percentile(kern_ms, 95) * 1e3),
                      "launches_timed": n_pairs,
                      "kernel_us_mean_without_overlap": iso_us,
-                     "frac_without_overlap": (kv_bytes / (iso_us * 1e-6) / 1e9 / HBM_PEAK_GBPS) if iso_us else None},
+                     "frac_without_overlap": (kv_bytes / (iso_us * 1e-6) / 1e9 / HBM_PEAK_GBPS) if iso_us else None,
+                     "measured_stream_read_GBps": probes.get("stream_read_GBps"),
+                     "frac_of_measured_peak": (achieved / probes["stream_read_GBps"]) if probes.get("stream_read_GBps") else None},
+        "step_time": step_stats,
+        "gather_GBps": gather["whole_lists"]["GBps"] if gather else None,
+        "link_peak_GBps": probes.get("link_peak_GBps"),
+        "gather": gather,
+        "probes": probes,
         "cpu_baseline": cpu,
         "parity_max_err_over_rms": parity,
         "warmup_flags": flags_hist,

@@ -161,6 +161,18 @@ hc_status hc_set_monitor_span(hc_ctx* ctx, int32_t span);
  * are recorded.  The events are the caller's; they are only recorded, never waited on or destroyed. */
 hc_status hc_set_timing_events(hc_ctx* ctx, void* const* ev_begin, void* const* ev_end, int32_t n);
 
+/* Measurement helpers: two plain streaming kernels that compute nothing of the method and only show what the
+ * machine at hand gives the kernels they bound.  hc_probe_stream_read reads `bytes` (a multiple of 16 is read)
+ * of device memory once with coalesced 16-byte loads (streaming != 0: marked non-temporal, as the attention pass
+ * marks its K/V loads) from `workgroups` workgroups of 256 threads (2048 is a good choice) and stores nothing
+ * (dev_sink: 4 bytes of device memory or NULL): its rate is the read
+ * bandwidth of HBM that a kernel can reach, the bound of the attention pass.  hc_probe_host_copy copies `bytes`
+ * from pinned host memory to device memory with a kernel that reads the host memory over the host link, as the
+ * gather reads the host tier: its rate is the gather's bound.  Enqueue-only; the caller times them. */
+hc_status hc_probe_stream_read(const void* dev_buf, size_t bytes, void* dev_sink, int32_t workgroups, int32_t streaming,
+                               void* stream);
+hc_status hc_probe_host_copy(const void* pinned_src, void* dev_dst, size_t bytes, int32_t workgroups, void* stream);
+
 /* Host-only dry run of hc_layer_create: validates the head table exactly as hc_layer_create does
  * and reports the plan it would build for a device with the given number of compute units.  Touches
  * no GPU.  err (may be NULL) receives the text of a validation failure. */

@@ -26,7 +26,7 @@ EXPORTS = ["hc_create", "hc_destroy", "hc_strerror", "hc_last_error", "hc_layer_
            "hc_append_kv", "hc_rescore_work_bytes", "hc_rescore_work_layout", "hc_rescore_window", "hc_prefill_work_bytes", "hc_prefill_work_layout", "hc_prefill_init",
            "hc_layer_window_slot",
            "hc_layer_set_window_slot", "hc_layer_context",
-           "hc_decode_step", "hc_taxonomy", "hc_budgets"]
+           "hc_decode_step", "hc_taxonomy", "hc_budgets", "hc_probe_stream_read", "hc_probe_host_copy"]
 
 
 HC_WINDOW_SLIDING, HC_WINDOW_TUMBLING, HC_WINDOW_RESCORED = 0, 1, 2
@@ -113,6 +113,8 @@ def lib():
         L.hc_append_kv.argtypes = [vp] * 7
         L.hc_taxonomy.argtypes = [i32, vp, vp, C.c_double, vp, vp, vp]
         L.hc_budgets.argtypes = [i32, vp, vp, i32, i32, i32, vp]
+        L.hc_probe_stream_read.argtypes = [vp, C.c_size_t, vp, i32, i32, vp]
+        L.hc_probe_host_copy.argtypes = [vp, vp, C.c_size_t, i32, vp]
         L.hc_layer_context.argtypes = [vp, i32]
         L.hc_layer_context.restype = i32
         L.hc_decode_step.argtypes = [vp, C.POINTER(hc_layer_io), i32, i32, vp, vp]
@@ -338,6 +340,16 @@ def hc_layer_set_window_slot(layer: int, slot: int) -> None:
 
 def hc_layer_context(layer: int, b: int) -> int:
     return lib().hc_layer_context(layer, b)
+
+
+def hc_probe_stream_read(dev_buf: Ptr, nbytes: int, dev_sink: Ptr = None, workgroups: int = 2048, streaming: bool = True,
+                         stream=None) -> None:
+    _check(lib().hc_probe_stream_read(_p(dev_buf), nbytes, _p(dev_sink), workgroups, int(bool(streaming)), _stream(stream)),
+           "hc_probe_stream_read")
+
+
+def hc_probe_host_copy(pinned_src: Ptr, dev_dst: Ptr, nbytes: int, workgroups: int = 96, stream=None) -> None:
+    _check(lib().hc_probe_host_copy(_p(pinned_src), _p(dev_dst), nbytes, workgroups, _stream(stream)), "hc_probe_host_copy")
 
 
 def hc_decode_step(ctx: int, io, n_layers: int, main_stream=None, side_stream=None, layers_per_group: int = 4) -> None:

@@ -5,7 +5,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB = os.path.join(HERE, "libhc.so")
-SOURCES = ["hc_host.hip", "hc_attn.hip", "hc_monitor.hip", "hc_gather.hip", "hc_append.hip", "hc_rescore.hip", "hc_prefill.hip", "hc_taxonomy.hip"]
+SOURCES = ["hc_host.hip", "hc_attn.hip", "hc_monitor.hip", "hc_gather.hip", "hc_append.hip", "hc_rescore.hip", "hc_prefill.hip", "hc_taxonomy.hip", "hc_probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
