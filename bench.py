@@ -57,6 +57,8 @@ def main():
     ap.add_argument("--monitor-span", type=int, default=0, help="1024-candidate chunks per workgroup of the selection passes (0: chosen per launch)")
     ap.add_argument("--tune-rounds", type=int, default=0, help="rounds of on-device measurement of the share weights on the first layer (0: built-in weights, as the parity tests use)")
     ap.add_argument("--share-weights", default="", help="16 comma-separated share weights [die*2+slot] (tuning)")
+    ap.add_argument("--filter-margin", type=float, default=1.25, help="pivot-logit filter (hc_set_logit_filter): 0 = off, every "
+                    "logit of a pivot is stored and scored; >= 1: only the rows that can reach a list, checked on the device")
     ap.add_argument("--group", type=int, default=8, help="layers per cross-stream sync group in step mode")
     ap.add_argument("--serial", action="store_true", help="monitor and gather on the main stream (no overlap)")
     ap.add_argument("--attn-only", action="store_true", help="time hc_decode_attn alone (no monitor, no gather)")
@@ -113,7 +115,7 @@ def main():
             cfg = R.make_config(spec, growth=T_total if args.append else 0)
             if args.config == 5:
                 cfg.max_k = 4096 - 64 - 256          # the largest list any layer of this config can draw
-            ctx = R.Context(cfg, dev, workgroups_per_cu=args.wg_per_cu or None)
+            ctx = R.Context(cfg, dev, workgroups_per_cu=args.wg_per_cu or None, filter_margin=args.filter_margin)
             if args.share_weights:
                 hc.hc_set_share_weights(ctx.handle, [float(x) for x in args.share_weights.split(",")])
             if args.monitor_span:
@@ -457,6 +459,15 @@ def main():
             gather["link_peak_GBps"] = probes["link_peak_GBps"]
             gather["frac_of_link_peak"] = gather["whole_lists"]["GBps"] / probes["link_peak_GBps"]
 
+    # ---- the monitor's own counters (per pivot, since the layers were created) ----
+    mon = None
+    if not args.attn_only and any(lay.n_reps for lay in layers):
+        cs = [lay.monitor_counts(b, p) for lay in layers for b in range(lay.spec.B) for p in lay.spec.reps(b)]
+        kept = [c["kept"] for c in cs if c["kept"] is not None]
+        mon = {"pivots": len(cs), "decisions": sum(c["tests"] for c in cs), "retrievals": sum(c["triggers"] for c in cs),
+               "filter_margin": args.filter_margin, "filter_fallbacks": sum(c["fallbacks"] for c in cs),
+               "rows_kept_last_step_mean": float(np.mean(kept)) if kept else None}
+
     # ---- CPU oracle on a bounded sample: layers 0..1, first steps (the same inputs as warm-up) ----
     cpu = None
     parity = None
@@ -495,7 +506,7 @@ def main():
         "config": {"workload": f"config{args.config}{' dense' if args.dense else ''}: "
                                f"{spec0.ctx[0] if spec0.B == 1 else '%d..%d (sum %d)' % (min(spec0.ctx), max(spec0.ctx), sum(spec0.ctx))} ctx, {L} layers, "
                                f"B={spec0.B}, {spec0.Hq}q/{spec0.Hkv}kv heads, D=128",
-                   "layers": L, "context": spec0.ctx[0], "mode": args.mode, "host_tier": not args.no_tier, "gather": "none" if args.no_tier else ("whole lists" if args.full_gather else "difference only"), "overlap_monitor": not args.serial, "layers_per_group": args.group, "growing_context": args.append,
+                   "layers": L, "context": spec0.ctx[0], "mode": args.mode, "host_tier": not args.no_tier, "gather": "none" if args.no_tier else ("whole lists" if args.full_gather else "difference only"), "overlap_monitor": not args.serial, "logit_filter_margin": args.filter_margin, "layers_per_group": args.group, "growing_context": args.append,
                    "kv_bytes_per_layer_step": kv_bytes,
                    "split_workgroups": hc.hc_layer_num_workgroups(layers[0].handle),
                    "split_partials": hc.hc_layer_num_partials(layers[0].handle)},
@@ -514,6 +525,7 @@ def main():
                      "measured_stream_read_GBps": probes.get("stream_read_GBps"),
                      "frac_of_measured_peak": (achieved / probes["stream_read_GBps"]) if probes.get("stream_read_GBps") else None},
         "step_time": step_stats,
+        "monitor": mon,
         "gather_GBps": gather["whole_lists"]["GBps"] if gather else None,
         "link_peak_GBps": probes.get("link_peak_GBps"),
         "gather": gather,

@@ -154,6 +154,38 @@ hc_status hc_layer_tune(hc_ctx* ctx, hc_layer* layer, const void* kv_arena, cons
  * latency), up to 8 for a batch of layers (histograms cleared and flushed once per workgroup). */
 hc_status hc_set_monitor_span(hc_ctx* ctx, int32_t span);
 
+/* The pivot-logit filter (before hc_layer_create; layers created while it is on carry its buffers).  margin 0
+ * (default): off.  margin >= 1: hc_decode_attn / hc_decode_step store, of a pivot's scaled logits, only the rows
+ * that can matter to the monitor, and hc_rep_topk_drift works over those rows.  The 7 MB of logits per 224K pivot
+ * that the monitor otherwise writes and reads beside the attention pass shrink to a few hundred KB.
+ *   How: after every decision the monitor leaves, per pivot, this step's log-sum-exp and cut = (smallest score
+ *   that made it into any of the pivot's lists) / margin.  The next step's split pass keeps position j of the
+ *   candidate range only if (1/G) sum_g exp(logit_g[j] - lse_prev_g) >= cut.  The monitor then scores the kept
+ *   rows with the step's own log-sum-exp, selects among them, and CHECKS that the smallest list threshold it
+ *   found is at least cut * max_g exp(lse_prev_g - lse_g) (with room for rounding): every dropped row's true
+ *   score lies below that bound, so none can belong to any list, and the lists, the overlap and the decision
+ *   are exactly those of the unfiltered monitor.  If the check fails (or fewer rows were kept than the longest
+ *   list needs, or more than a few times that), all of the pivot's logits are computed again, with the same
+ *   arithmetic as the split pass, and the plain passes redo that pivot: the same results, a slower step.  All of
+ *   this is decided on the device; the calls stay enqueue-only.  The first step (no filter set yet) keeps every row.
+ *   margin trades kept rows against fallbacks: 1.25 keeps about 1.6 times the longest list at a 224K context and
+ *   has not fallen back on the synthetic workloads; a query whose attention changes abruptly needs more.
+ *   What changes for the caller: rep_logits and scores then hold the kept rows only (scores[p][0, n): the scores
+ *   of the n kept rows in position order; hc_layer_filter_view gives their positions), except for a pivot that
+ *   fell back, whose rows of both are dense as without the filter; the layer remembers the kv_arena of its last
+ *   attention call (the fallback reads K from it) and keeps its own copy of the pivots' queries.  Only with
+ *   HC_AGG_PROB; with HC_AGG_LOGIT, given scores, the window's re-scored queries and the prefill-time selection
+ *   the plain passes run. */
+hc_status hc_set_logit_filter(hc_ctx* ctx, float margin);
+/* Per-pivot counters of the monitor since the layer was created, copied to host memory (synchronous):
+ * counts4[0] decisions taken (windows tested), [1] retrievals triggered, [2] steps decided by the dense fallback of
+ * the filter, [3] rows the filter kept at the last step (0xffffffff: the last step was not filtered). */
+hc_status hc_layer_monitor_counts(const hc_layer* layer, int32_t b, int32_t h, uint32_t* counts4);
+/* Device pointers into a filtering layer's state, for inspection (NULL if the layer does not filter):
+ * kept_pos [num_reps][max_ctx] int32, the positions of the rows kept at the last step, ascending, the scores of
+ * which are scores[p][0, n); fell_back [num_reps] int32, != 0 where the last step's check failed. */
+hc_status hc_layer_filter_view(const hc_layer* layer, const int32_t** kept_pos, const int32_t** fell_back);
+
 /* Measurement hook: hands the library n pairs of hipEvent_t (host arrays of handles, copied).  The
  * next n launches of the split-pass kernel, from hc_decode_attn or hc_decode_step, attach pair i to
  * their i-th dispatch, so that hipEventElapsedTime(ev_begin[i], ev_end[i]) is that kernel's execution

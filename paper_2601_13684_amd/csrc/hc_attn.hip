@@ -19,6 +19,8 @@
 // row steps is in flight while the current one is being reduced.
 #include <hip/hip_ext.h>
 
+#include <algorithm>
+
 #include "hc_internal.h"
 
 namespace {
@@ -78,6 +80,21 @@ struct WaveState {
     float m[G];          // reference maximum, log2 units, identical in all lanes
     float Z[G];          // sum of exp2(t - m) over the rows this lane handled
     float acc[G][16];    // sum of exp2(t - m) * V[row][d] for the lane's 16 columns
+};
+
+// The pivot-logit filter of the segment being streamed (all fields wave-uniform).  A pivot's scaled logits are
+// what the drift monitor scores; with the filter on only the rows that can matter to it are kept: row j stays if
+// sum_g 2^(t_g[j] - ref_g) >= cutsum, where ref is the log-sum-exp the monitor saw at the step that set the filter
+// and cutsum a fraction of the smallest score that made it into a list then.  The monitor checks afterwards, with
+// this step's own log-sum-exp, that no dropped row could have reached a list, and otherwise has every logit
+// computed again; so the filter changes what is written, never what is selected.  (A cheaper test on the largest
+// of the four exponents alone keeps several times as many rows when the heads of a group attend differently.)
+template <int G>
+struct FilterCtx {
+    float cutsum;
+    float ref[G];
+    float cg[G];        // 2^(m_g - ref_g): turns the weights 2^(t - m) the softmax computes anyway into 2^(t - ref)
+    int lo, hi;         // the pivot's candidate positions
 };
 
 // One row step of a wave (its 8 rows): the lane's two 16-byte chunks of its K row and of its V row.
@@ -160,9 +177,9 @@ __device__ __forceinline__ uint64_t exponents(const WaveState<G>& st, const floa
 // Rare: raise the reference to the largest logit of this row step and recompute the exponents.
 // Returns, per head, the factor 2^(old reference - new reference) by which everything accumulated so
 // far has to be multiplied.
-template <int G>
+template <int G, bool FILT>
 __device__ __forceinline__ void move_reference(WaveState<G>& st, const float (&s)[G], float (&x)[G], float (&alpha)[G],
-                                               bool valid)
+                                               bool valid, FilterCtx<G>& fc)
 {
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -175,6 +192,7 @@ __device__ __forceinline__ void move_reference(WaveState<G>& st, const float (&s
         alpha[g] = __builtin_amdgcn_exp2f(st.m[g] - mn);
         st.m[g] = mn;
         x[g] = t - mn;
+        if (FILT) fc.cg[g] = __builtin_amdgcn_exp2f(mn - fc.ref[g]);
     }
 }
 
@@ -211,39 +229,72 @@ __device__ __forceinline__ void scale_if(uint64_t mask, float alpha, float& z, f
         : "scc");
 }
 
-// p.V: weights 2^x[g], accumulated into the lane's 16 columns.
-template <int G>
-__device__ __forceinline__ void pv(WaveState<G>& st, const float (&x)[G], const Tile& t)
+// p.V: weights 2^x[g], accumulated into the lane's 16 columns.  Returns sum_g 2^x[g] cg[g] (the filter's
+// statistic of the lane's row) when FILT, else 0.
+template <int G, bool FILT>
+__device__ __forceinline__ float pv(WaveState<G>& st, const float (&x)[G], const Tile& t, const FilterCtx<G>& fc)
 {
     float vf[16];
     vf[0] = bf_lo(t.v0.x); vf[1] = bf_hi(t.v0.x); vf[2] = bf_lo(t.v0.y); vf[3] = bf_hi(t.v0.y);
     vf[4] = bf_lo(t.v0.z); vf[5] = bf_hi(t.v0.z); vf[6] = bf_lo(t.v0.w); vf[7] = bf_hi(t.v0.w);
     vf[8] = bf_lo(t.v1.x); vf[9] = bf_hi(t.v1.x); vf[10] = bf_lo(t.v1.y); vf[11] = bf_hi(t.v1.y);
     vf[12] = bf_lo(t.v1.z); vf[13] = bf_hi(t.v1.z); vf[14] = bf_lo(t.v1.w); vf[15] = bf_hi(t.v1.w);
+    float est = 0.f;
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         const float p = __builtin_amdgcn_exp2f(x[g]);
         st.Z[g] += p;
+        if (FILT) est = fmaf(p, fc.cg[g], est);
 #pragma unroll
         for (int i = 0; i < 16; ++i) st.acc[g][i] = fmaf(p, vf[i], st.acc[g][i]);
     }
+    return est;
 }
 
-// One row step: logits, (pivot) logit stash, reference check, accumulate.
+// Filtered pivot logits: a wave appends the rows it keeps, in the order it meets them (ascending positions), to
+// a list of its own in LDS; the workgroup merges its four lists once, at the end of the segment.
 template <int G>
+struct KeepList {
+    float* logits;      // [CAPW][G] in LDS, or nullptr: this segment keeps nothing (not a pivot, or no logits wanted)
+    int32_t* pos;       // [CAPW]
+    int count;          // rows kept so far (wave-uniform); beyond the capacity the rows are only counted
+};
+constexpr int KEEP_WAVE_FLOATS = 2048;                                       // LDS floats of one wave's list
+template <int G> struct KeepCap { static constexpr int N = (KEEP_WAVE_FLOATS / (G + 1)) & ~3; };
+
+// One row step: logits, (pivot) logit stash, reference check, accumulate.  With the filter on (FILT) the rows that are
+// candidate positions and whose statistic reaches the filter's cut are appended to `kl` instead (`pos`: the position of
+// the lane's row).
+template <int G, bool FILT>
 __device__ __forceinline__ void row_step(WaveState<G>& st, const uint32_t (&qreg)[G][8], const Tile& t, float* stash,
-                                         int c, bool valid)
+                                         int c, bool valid, FilterCtx<G>& fc, KeepList<G>& kl, int pos)
 {
     float s[G], x[G], alpha[G];
     qk<G>(qreg, t, s);
-    if (stash) stash_rep<G>(stash, s, c, valid);
+    if (!FILT && stash) stash_rep<G>(stash, s, c, valid);
     const uint64_t over = exponents<G>(st, s, x, valid);
 #pragma unroll
     for (int g = 0; g < G; ++g) alpha[g] = 1.0f;
-    if (over) move_reference<G>(st, s, x, alpha, valid);
+    if (over) move_reference<G, FILT>(st, s, x, alpha, valid, fc);
 #pragma unroll
     for (int g = 0; g < G; ++g) scale_if(over, alpha[g], st.Z[g], st.acc[g]);
-    pv<G>(st, x, t);
+    const float est = pv<G, FILT>(st, x, t, fc);
+    if (FILT && kl.logits) {
+        // (not "est >= cutsum": a statistic that is not a number, 0 * inf after an extreme move of the reference,
+        // keeps its row)
+        uint64_t m = __builtin_amdgcn_ballot_w64(valid && c == 0 && !(est < fc.cutsum));     // bits 0, 8, ..., 56: the wave's 8 rows, ascending
+        if (m) {                                                           // most row steps keep nothing
+            const bool keep = valid && c == 0 && !(est < fc.cutsum) && pos >= fc.lo && pos < fc.hi;       // candidate positions only
+            m = __builtin_amdgcn_ballot_w64(keep);
+            const int n = __builtin_popcountll(m);
+            if (keep && kl.count + n <= KeepCap<G>::N) {
+                const int idx = kl.count + __builtin_popcountll(m & ((1ull << (threadIdx.x & 63)) - 1ull));
+                kl.pos[idx] = pos;
+                stash_rep<G>(kl.logits + (size_t)idx * G, s, 0, true);
+            }
+            kl.count += n;
+        }
+    }
 }
 
 constexpr int REP_STASH_FLOATS = 4096;   // one staging buffer: 16 KB, i.e. 1024 positions of a group of 4 (measured: the
@@ -253,15 +304,17 @@ constexpr int REP_STASH_FLOATS = 4096;   // one staging buffer: 16 KB, i.e. 1024
 // row_begin + 8*w + 32*i.  Full row steps are double-buffered in registers (tile B is in flight while
 // tile A is reduced, and vice versa); the ragged last row step is clamped for the load and masked.
 //
-// For a pivot (rep_base != nullptr) the rows are taken in chunks of REP_STASH_FLOATS / G positions: the
-// waves stash their logits in LDS, and at the end of a chunk the workgroup writes the chunk's logits to
-// rep_base as one contiguous run.  Two staging buffers alternate, so one barrier per chunk is enough;
-// the number of chunks depends only on the segment, so every wave reaches every barrier.  The register
-// pipeline of loads runs on across chunk boundaries.
-template <int G>
+// For a pivot whose logits are stored densely (rep_base != nullptr, !FILT) the rows are taken in chunks of
+// REP_STASH_FLOATS / G positions: the waves stash their logits in LDS, and at the end of a chunk the workgroup
+// writes the chunk's logits to memory as one contiguous run.  Two staging buffers alternate, so one barrier per
+// chunk is enough; the number of chunks depends only on the segment, so every wave reaches every barrier.  The
+// register pipeline of loads runs on across chunk boundaries.  With the filter (FILT) there are no chunks and no
+// barriers: the kept rows go to the wave's list `kl`.
+template <int G, bool FILT>
 __device__ __forceinline__ void process_rows(WaveState<G>& st, const uint32_t (&qreg)[G][8],
                                              const char* __restrict__ Kb, const char* __restrict__ Vb,
-                                             float* __restrict__ rep_base, float (&stash)[2][REP_STASH_FLOATS],
+                                             float* __restrict__ rep_base, FilterCtx<G>& fc, KeepList<G>& kl,
+                                             float (&stash)[2][REP_STASH_FLOATS],
                                              int row_begin, int row_end, int w, int r, int c)
 {
     constexpr int CAP = REP_STASH_FLOATS / G;      // positions per chunk
@@ -271,7 +324,8 @@ __device__ __forceinline__ void process_rows(WaveState<G>& st, const uint32_t (&
     const int wave_row0 = row_begin + 8 * w;
     const int nfull = wave_row0 + 8 <= row_end ? (row_end - 8 - wave_row0) / 32 + 1 : 0;   // unmasked row steps
     uint32_t off = (uint32_t)(wave_row0 + r) * 256u + (uint32_t)c * 16u;                   // the lane's first chunk of its row
-    const int nchunk = rep_base ? (row_end - row_begin + CAP - 1) / CAP : 1;
+    const bool dense = !FILT && rep_base != nullptr;
+    const int nchunk = dense ? (row_end - row_begin + CAP - 1) / CAP : 1;
     Tile A, B;
     int i = 0;
     if (nfull > 0) load_tile(A, Kb, Vb, off);
@@ -279,18 +333,20 @@ __device__ __forceinline__ void process_rows(WaveState<G>& st, const uint32_t (&
     for (int ch = 0; ch < nchunk; ++ch) {
         const bool last = ch == nchunk - 1;
         const int i_hi = last ? nfull : (ch + 1) * STEPS;          // a chunk before the last holds full row steps only
-        float* sp = rep_base ? &stash[ch & 1][(8 * w + r) * G] : nullptr;
+        float* sp = dense ? &stash[ch & 1][(8 * w + r) * G] : nullptr;
+        int pos = wave_row0 + 32 * i + r;
 #pragma unroll 1
         for (; i + 2 <= i_hi; i += 2, off += 2 * STEP) {
             load_tile(B, Kb, Vb, off + STEP);
-            row_step<G>(st, qreg, A, sp, c, true);
+            row_step<G, FILT>(st, qreg, A, sp, c, true, fc, kl, pos);
             if (i + 2 < nfull) load_tile(A, Kb, Vb, off + 2 * STEP);
-            row_step<G>(st, qreg, B, sp ? sp + 32 * G : nullptr, c, true);
+            row_step<G, FILT>(st, qreg, B, sp ? sp + 32 * G : nullptr, c, true, fc, kl, pos + 32);
             if (sp) sp += 64 * G;
+            pos += 64;
         }
         if (last) {
             if (i < nfull) {
-                row_step<G>(st, qreg, A, sp, c, true);
+                row_step<G, FILT>(st, qreg, A, sp, c, true, fc, kl, pos);
                 if (sp) sp += 32 * G;
                 ++i;
             }
@@ -298,10 +354,10 @@ __device__ __forceinline__ void process_rows(WaveState<G>& st, const uint32_t (&
             if (row - r < row_end) {
                 const bool valid = row < row_end;
                 load_tile(A, Kb, Vb, (uint32_t)(valid ? row : row_end - 1) * 256u + (uint32_t)c * 16u);
-                row_step<G>(st, qreg, A, sp, c, valid);
+                row_step<G, FILT>(st, qreg, A, sp, c, valid, fc, kl, row);
             }
         }
-        if (rep_base) {
+        if (dense) {
             __syncthreads();
             const int first = row_begin + ch * CAP;
             const int nf = (row_end - first < CAP ? row_end - first : CAP) * G;     // floats of this chunk
@@ -315,7 +371,67 @@ __device__ __forceinline__ void process_rows(WaveState<G>& st, const uint32_t (&
     }
 }
 
-template <int G, int WG_PER_CU>
+// The workgroup's four lists of kept rows (each ascending in position; wave w holds the rows 8 w .. 8 w + 7 of every
+// 32) merged into the segment's run: the kept rows, in position order, fill rows row_begin, row_begin + 1, ... of the
+// pivot's block of rep_logits (a segment never keeps more rows than it has), their positions the same entries of
+// `pos`, and their number is left in *count.  An entry's place is its index in its own list plus the number of
+// entries of the other lists that lie before it.  A list that ran over its capacity makes the count the segment's
+// rows + 1: "unknown", which sends the pivot to the dense passes.  Called by the whole workgroup after a barrier that
+// follows the last append.
+template <int G>
+__device__ __forceinline__ void merge_kept(const float (&lists)[2][REP_STASH_FLOATS], const int (&counts)[4], float* __restrict__ rep_base,
+                                           int32_t* __restrict__ pos_out, int32_t* __restrict__ count_out, int row_begin, int row_end)
+{
+    constexpr int CAPW = KeepCap<G>::N;
+    const float* base = &lists[0][0];
+    const int n0 = counts[0], n1 = counts[1], n2 = counts[2], n3 = counts[3];
+    if (n0 > CAPW || n1 > CAPW || n2 > CAPW || n3 > CAPW) {
+        if (threadIdx.x == 0) *count_out = row_end - row_begin + 1;
+        return;
+    }
+    const int total = n0 + n1 + n2 + n3;
+    for (int e = threadIdx.x; e < total; e += 256) {
+        const int lw = e < n0 ? 0 : e < n0 + n1 ? 1 : e < n0 + n1 + n2 ? 2 : 3;
+        const int idx = e - (lw == 0 ? 0 : lw == 1 ? n0 : lw == 2 ? n0 + n1 : n0 + n1 + n2);
+        const float* mine = base + (size_t)lw * KEEP_WAVE_FLOATS;
+        const int p = reinterpret_cast<const int32_t*>(mine + CAPW * G)[idx];
+        int rank = idx;
+#pragma unroll
+        for (int ow = 0; ow < 4; ++ow) {
+            if (ow == lw) continue;
+            const int32_t* op = reinterpret_cast<const int32_t*>(base + (size_t)ow * KEEP_WAVE_FLOATS + CAPW * G);
+            int lo = 0, hi = counts[ow];                     // entries of list ow with a position below p
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (op[mid] < p) lo = mid + 1;
+                else hi = mid;
+            }
+            rank += lo;
+        }
+        const float* e_l = mine + (size_t)idx * G;
+        float* d = rep_base + (size_t)(row_begin + rank) * G;
+        typedef float f4v __attribute__((ext_vector_type(4)));
+        if (G == 1) d[0] = e_l[0];
+        else if (G == 2) *reinterpret_cast<float2*>(d) = *reinterpret_cast<const float2*>(e_l);
+        else {
+#pragma unroll
+            for (int q4 = 0; q4 < G / 4; ++q4) reinterpret_cast<f4v*>(d)[q4] = reinterpret_cast<const f4v*>(e_l)[q4];
+        }
+        pos_out[row_begin + rank] = p;
+    }
+    if (threadIdx.x == 0) *count_out = total;
+}
+
+// What the filtered form of the split pass needs besides the arguments of the plain one.
+struct FilterArgs {
+    const RepFilter* filt;     // [n_reps] filter state, set by the monitor
+    const RepDev* reps;        // [n_reps] for the candidate range of every pivot
+    int32_t* surv_pos;         // [n_reps][max_ctx] positions of the kept rows, by segment
+    int32_t* seg_cnt;          // [segments] kept rows of every pivot segment
+    uint16_t* q_keep;          // [n_reps][G][D] copy of the pivots' queries (the monitor may have to score again)
+};
+
+template <int G, int WG_PER_CU, bool FILT>
 __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16_t* __restrict__ arena,
                                                                     const uint16_t* __restrict__ q,
                                                                     const BlkDev* __restrict__ blks,
@@ -323,12 +439,13 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
                                                                     float* __restrict__ part_acc,
                                                                     float* __restrict__ part_ml,
                                                                     float* __restrict__ rep_logits, int max_ctx,
-                                                                    unsigned long long* __restrict__ stamps)
+                                                                    unsigned long long* __restrict__ stamps, FilterArgs fa)
 {
     __shared__ float sm_m[4][G];
     __shared__ float sm_Z[16][G];
     __shared__ __attribute__((aligned(16))) float sm_red[4][G * HC_D];
     __shared__ __attribute__((aligned(16))) float sm_stash[2][REP_STASH_FLOATS];
+    __shared__ int sm_kept[4];       // filtered: rows every wave kept of the current segment
 
     const int tid = threadIdx.x;
     const int w = tid >> 6;
@@ -344,7 +461,33 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
     for (;;) {
         const char* __restrict__ Kp = reinterpret_cast<const char*>(arena + seg.k_off);
         const char* __restrict__ Vp = reinterpret_cast<const char*>(arena + seg.v_off);
-        float* rep_base = (rep_logits && seg.rep_slot >= 0) ? rep_logits + (size_t)seg.rep_slot * G * max_ctx : nullptr;
+        float* rep_base = nullptr;
+        int32_t* kept_pos = nullptr;
+        int32_t* kept_count = nullptr;
+        KeepList<G> kl{nullptr, nullptr, 0};
+        FilterCtx<G> fc;
+        fc.cutsum = 0.f;
+        fc.lo = fc.hi = 0;
+#pragma unroll
+        for (int g = 0; g < G; ++g) fc.ref[g] = fc.cg[g] = 0.f;
+        if (rep_logits && seg.rep_slot >= 0) {
+            rep_base = rep_logits + (size_t)seg.rep_slot * G * max_ctx;
+            if (FILT) {
+                kept_pos = fa.surv_pos + (size_t)seg.rep_slot * max_ctx;
+                kept_count = fa.seg_cnt + seg.slot;
+                kl.logits = &sm_stash[0][0] + (size_t)w * KEEP_WAVE_FLOATS;
+                kl.pos = reinterpret_cast<int32_t*>(kl.logits + KeepCap<G>::N * G);
+                const RepFilter f = fa.filt[seg.rep_slot];
+                fc.cutsum = f.cutsum;
+#pragma unroll
+                for (int g = 0; g < G; ++g) fc.ref[g] = f.ref[g];
+                fc.lo = fa.reps[seg.rep_slot].lo;
+                fc.hi = fa.reps[seg.rep_slot].hi;
+                if (seg.row_begin == 0 && tid < G * 16)      // the pivot's queries, kept for the monitor: G rows of 16 x 16 bytes
+                    reinterpret_cast<uint4*>(fa.q_keep + (size_t)seg.rep_slot * G * HC_D)[tid] =
+                        reinterpret_cast<const uint4*>(q + (size_t)seg.bh * G * HC_D)[tid];
+            }
+        }
 
         uint32_t qreg[G][8];
 #pragma unroll
@@ -363,7 +506,8 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
             for (int i = 0; i < 16; ++i) st.acc[g][i] = 0.f;
         }
 
-        process_rows<G>(st, qreg, Kp, Vp, rep_base, sm_stash, seg.row_begin, seg.row_end, w, r, c);
+        process_rows<G, FILT>(st, qreg, Kp, Vp, rep_base, fc, kl, sm_stash, seg.row_begin, seg.row_end, w, r, c);
+        if (FILT && lane == 0) sm_kept[w] = kl.count;
         if (stamps && threadIdx.x == 0 && next_extra >= blk.extra_end && st.Z[0] >= 0.f)      // (the condition on Z orders the stamp after the rows)
             stamps[2 * blockIdx.x + 1] = __builtin_amdgcn_s_memrealtime();
 
@@ -431,6 +575,8 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
             part_ml[((size_t)seg.slot * G + tid) * 2 + 0] = M;
             part_ml[((size_t)seg.slot * G + tid) * 2 + 1] = z;
         }
+        if (FILT && kl.logits)       // (the barrier above came after every wave's last append)
+            merge_kept<G>(sm_stash, sm_kept, rep_base, kept_pos, kept_count, seg.row_begin, seg.row_end);
         if (next_extra >= blk.extra_end) break;
         __syncthreads();
         seg = segs[next_extra++];
@@ -523,6 +669,75 @@ __global__ __launch_bounds__(COMBINE_BLK) void attn_combine_kernel(const HeadDev
 template <int G> struct Tune { static constexpr int WG = 2; };
 template <> struct Tune<8> { static constexpr int WG = 1; };
 
+// The pivots' logits over again, every row, into the dense [ctx][G] layout: what the monitor falls back on when
+// its check of a filtered step fails (need[rep] != 0; evaluated on the device, so the launch is unconditional and
+// normally finds nothing to do).  Same plan, same lanes, same dot products in the same order as the split pass,
+// so the logits are bit for bit those an unfiltered pass would have stored.  Queries come from the copy the
+// split pass kept.  Rare: plain stores, no staging.
+struct RepLogitsItem {
+    const uint16_t* arena;
+    const uint16_t* q_keep;
+    const BlkDev* blks;
+    const SegDev* segs;
+    float* rep_logits;
+    const int32_t* need;
+    int n_blocks, n_reps;
+};
+struct RepLogitsBatch {
+    RepLogitsItem it[HC_MAX_GROUP];      // blockIdx.y picks the layer
+};
+
+template <int G>
+__global__ __launch_bounds__(256) void rep_logits_kernel(RepLogitsBatch batch, int max_ctx)
+{
+    const RepLogitsItem& item = batch.it[blockIdx.y];
+    bool any = false;                                      // (a few words, read by every workgroup: the usual case is "none")
+    for (int i = 0; i < item.n_reps; ++i) any |= item.need[i] != 0;
+    if (!any) return;
+    const uint16_t* __restrict__ arena = item.arena;
+    const uint16_t* __restrict__ q_keep = item.q_keep;
+    const BlkDev* __restrict__ blks = item.blks;
+    const SegDev* __restrict__ segs = item.segs;
+    float* __restrict__ rep_logits = item.rep_logits;
+    const int32_t* __restrict__ need = item.need;
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r = lane >> 3, c = lane & 7;
+    // few workgroups (the launch is there at every step and normally has nothing to do): each takes every
+    // gridDim.x-th workgroup share of the split pass's plan
+    for (int share = blockIdx.x; share < item.n_blocks; share += gridDim.x) {
+    const BlkDev blk = blks[share];
+    SegDev seg = blk.first;
+    int next_extra = blk.extra_begin;
+    for (;;) {
+        if (seg.rep_slot >= 0 && need[seg.rep_slot] != 0) {
+            const char* __restrict__ Kp = reinterpret_cast<const char*>(arena + seg.k_off);
+            float* rep_base = rep_logits + (size_t)seg.rep_slot * G * max_ctx;
+            uint32_t qreg[G][8];
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const uint4* qp = reinterpret_cast<const uint4*>(q_keep + ((size_t)seg.rep_slot * G + g) * HC_D);
+                const uint4 a = qp[c], b = qp[8 + c];
+                qreg[g][0] = a.x; qreg[g][1] = a.y; qreg[g][2] = a.z; qreg[g][3] = a.w;
+                qreg[g][4] = b.x; qreg[g][5] = b.y; qreg[g][6] = b.z; qreg[g][7] = b.w;
+            }
+            for (int row0 = seg.row_begin + 8 * w; row0 < seg.row_end; row0 += 32) {
+                const int row = row0 + r;
+                const bool valid = row < seg.row_end;
+                const uint32_t off = (uint32_t)(valid ? row : seg.row_end - 1) * 256u + (uint32_t)c * 16u;
+                Tile t;
+                t.k0 = *reinterpret_cast<const uint4*>(Kp + off);
+                t.k1 = *reinterpret_cast<const uint4*>(Kp + off + 128);
+                t.v0 = t.v1 = make_uint4(0u, 0u, 0u, 0u);
+                float sc[G];
+                qk<G>(qreg, t, sc);
+                stash_rep<G>(rep_base + (size_t)row * G, sc, c, valid);
+            }
+        }
+        if (next_extra >= blk.extra_end) break;
+        seg = segs[next_extra++];
+    }
+    }
+}
+
 template <int G>
 hc_status launch(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* q, float* out, float* lse,
                  float* rep_logits, hipStream_t st, float* part_acc, float* part_ml)
@@ -535,15 +750,36 @@ hc_status launch(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* 
         ev_end = ctx->timing[ctx->timing_next].second;
         ++ctx->timing_next;
     }
+    const bool filtered = rep_logits != nullptr && hc_layer_filtered(ctx, L);
+    const FilterArgs fa{L->filt, L->reps, L->surv_pos, L->seg_cnt, L->q_keep};
 #define HC_LAUNCH(KERNEL)                                                                                         \
     hipExtLaunchKernelGGL(KERNEL, dim3(L->n_blocks), dim3(256), 0, st, ev_begin, ev_end, 0,                      \
                           (const uint16_t*)arena, (const uint16_t*)q, (const BlkDev*)L->blks,                    \
                           (const SegDev*)L->segs, part_acc, part_ml, rep_logits, ctx->cfg.max_ctx,                 \
-                          ctx->tune_stamps)
-    HC_LAUNCH((attn_split_kernel<G, Tune<G>::WG>));
+                          ctx->tune_stamps, fa)
+    if (filtered)
+        HC_LAUNCH((attn_split_kernel<G, Tune<G>::WG, true>));
+    else
+        HC_LAUNCH((attn_split_kernel<G, Tune<G>::WG, false>));
 #undef HC_LAUNCH
     HC_HIP(ctx, hipGetLastError());
     attn_combine_kernel<G><<<dim3(L->n_heads * G, 32 / CQ), dim3(COMBINE_BLK), 0, st>>>(L->heads, part_acc, part_ml, out, lse);
+    HC_HIP(ctx, hipGetLastError());
+    return HC_OK;
+}
+
+template <int G>
+hc_status launch_rep_logits(hc_ctx* ctx, int n, const hc_layer* const* layers, const void* const* arenas, float* const* rep_logits,
+                            hipStream_t st)
+{
+    RepLogitsBatch batch{};
+    int max_blocks = 0;
+    for (int i = 0; i < n; ++i) {
+        const hc_layer* L = layers[i];
+        batch.it[i] = RepLogitsItem{(const uint16_t*)arenas[i], L->q_keep, L->blks, L->segs, rep_logits[i], L->need, L->n_blocks, L->n_reps};
+        max_blocks = std::max(max_blocks, L->n_blocks);
+    }
+    rep_logits_kernel<G><<<dim3(std::min(max_blocks, 64), n), dim3(256), 0, st>>>(batch, ctx->cfg.max_ctx);
     HC_HIP(ctx, hipGetLastError());
     return HC_OK;
 }
@@ -595,4 +831,17 @@ hc_status hc_launch_attn_static(hc_ctx* ctx, const hc_layer* L, const void* aren
         return hc_fail(ctx, HC_ESHAPE, "hc_decode_attn_static: the layer's plan has %d partial results, the fixed scratch holds %d",
                        L->n_partials, (int)HC_STATIC_MAX_PARTIALS);
     return launch_any(ctx, L, arena, q, out, lse, rep_logits, st, ctx->static_scratch, ctx->static_scratch + STATIC_ACC_FLOATS);
+}
+
+hc_status hc_launch_rep_logits(hc_ctx* ctx, int n, const hc_layer* const* layers, const void* const* arenas, float* const* rep_logits,
+                               hipStream_t st)
+{
+    if (n < 1 || n > HC_MAX_GROUP) return hc_fail(ctx, HC_EINVAL, "batch of %d layers", n);
+    switch (ctx->G) {
+    case 1: return launch_rep_logits<1>(ctx, n, layers, arenas, rep_logits, st);
+    case 2: return launch_rep_logits<2>(ctx, n, layers, arenas, rep_logits, st);
+    case 4: return launch_rep_logits<4>(ctx, n, layers, arenas, rep_logits, st);
+    case 8: return launch_rep_logits<8>(ctx, n, layers, arenas, rep_logits, st);
+    }
+    return hc_fail(ctx, HC_ESHAPE, "unsupported group size");
 }

@@ -19,11 +19,12 @@ namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int ROWS_PER_PASS = 64;    // positions a workgroup has in flight: 8 per sub-pass, 8 sub-passes
+constexpr int ROWS_PER_PASS = 32;    // positions a workgroup has in flight: 8 per sub-pass, 4 sub-passes (96 workgroups keep 1.5 MB
+                                     // in flight, ten times what the host link's latency needs; more would cost registers, see below)
 constexpr int GATHER_WORKGROUPS = 96; // workgroups of a gather launch, whatever the batch (measured at the 224K shape, batches
                                       // of 8 layers: 48 and fewer make the refill itself the bottleneck of the step, 128 and
                                       // more slow the attention pass that runs beside it; an untriggered call costs ~2 us)
-constexpr int PLAN_THREADS = 1024;
+constexpr int PLAN_THREADS = 256;      // (a larger workgroup does not find room on a compute unit beside the attention pass)
 
 // One layer of a batched call (blockIdx.z picks the layer).
 struct GatherItem {
@@ -153,7 +154,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void gather_plan_kernel(GatherBatch B
 // 32 lanes move one position (lanes 0-15 its K row, 16-31 its V row, 16 bytes each); a workgroup has
 // ROWS_PER_PASS positions in flight.
 constexpr int MAX_GATHER_SATS = 1024;     // satellites of a batch (layers x satellites per layer)
-__global__ __launch_bounds__(256) void gather_kernel(GatherBatch B, int n_items, int max_sats, int max_k)
+__global__ __launch_bounds__(256, 8) void gather_kernel(GatherBatch B, int n_items, int max_sats, int max_k)
 {
     __shared__ int sm_start[MAX_GATHER_SATS + 1];
     __shared__ int sm_wsum[4];

@@ -198,6 +198,15 @@ extern "C" hc_status hc_set_share_weights(hc_ctx* ctx, const float* weights16)
     return HC_OK;
 }
 
+extern "C" hc_status hc_set_logit_filter(hc_ctx* ctx, float margin)
+{
+    if (!ctx_ok(ctx)) return HC_ESTATE;
+    if (!(margin == 0.f || (margin >= 1.f && margin <= 1.0e6f)))
+        return hc_fail(ctx, HC_EINVAL, "hc_set_logit_filter: margin 0 (off) or 1 .. 1e6");
+    ctx->filter_margin = margin;
+    return HC_OK;
+}
+
 extern "C" hc_status hc_set_monitor_span(hc_ctx* ctx, int32_t span)
 {
     if (!ctx_ok(ctx)) return HC_ESTATE;
@@ -256,6 +265,14 @@ static void layer_free(hc_layer* L)
     (void)hipFree(L->sel_outs);
     (void)hipFree(L->pre_src);
     (void)hipFree(L->rep_slot_dev);
+    (void)hipFree(L->filt);
+    (void)hipFree(L->surv_pos);
+    (void)hipFree(L->dense_pos);
+    (void)hipFree(L->seg_cnt);
+    (void)hipFree(L->vreps);
+    (void)hipFree(L->need);
+    (void)hipFree(L->q_keep);
+    (void)hipFree(L->mon_counts);
     if (L->ev_attn) (void)hipEventDestroy(L->ev_attn);
     if (L->ev_side) (void)hipEventDestroy(L->ev_side);
     for (int i = 0; i < 2; ++i) {
@@ -579,7 +596,10 @@ extern "C" hc_status hc_layer_create(hc_ctx* ctx, const hc_head_desc* hd, hc_lay
     L->max_r = P.max_r;
     L->max_nchunk = P.max_nchunk;
     L->max_nk = 1;
-    for (const RepDev& r : P.reps) L->max_nk = std::max(L->max_nk, r.nk);
+    for (const RepDev& r : P.reps) {
+        L->max_nk = std::max(L->max_nk, r.nk);
+        for (int t = 0; t < r.nk; ++t) L->max_k_any = std::max(L->max_k_any, r.k[t]);
+    }
     L->n_reps = (int)P.reps.size();
     L->n_outs = (int)P.outs.size();
     L->n_sats = (int)P.sats.size();
@@ -646,6 +666,29 @@ extern "C" hc_status hc_layer_create(hc_ctx* ctx, const hc_head_desc* hd, hc_lay
         if (st == HC_OK) st = upload(ctx, std::vector<PreSrc>(), &L->pre_src, (size_t)L->n_heads);
         if (st == HC_OK) st = upload(ctx, P.rep_slot_of, &L->rep_slot_dev);
     }
+    if (st == HC_OK && L->n_reps > 0) {
+        // per-pivot counters of the monitor (tests, triggers, ...), read back by hc_layer_monitor_counts
+        if (hipMalloc((void**)&L->mon_counts, (size_t)L->n_reps * 4 * sizeof(uint32_t)) != hipSuccess ||
+            hipMemset(L->mon_counts, 0, (size_t)L->n_reps * 4 * sizeof(uint32_t)) != hipSuccess)
+            st = hc_fail(ctx, HC_ENOMEM, "monitor counters");
+    }
+    if (st == HC_OK && ctx->filter_margin > 0.f && L->n_reps > 0 && L->blk_capacity < 2048) {
+        // the pivot-logit filter's buffers (a split pass of 2048 or more workgroups keeps the plain form)
+        const size_t nr = (size_t)L->n_reps, mc = (size_t)ctx->cfg.max_ctx;
+        hipError_t e = hipMalloc((void**)&L->filt, nr * sizeof(RepFilter));
+        if (e == hipSuccess) e = hipMemset(L->filt, 0, nr * sizeof(RepFilter));
+        if (e == hipSuccess) e = hipMalloc((void**)&L->surv_pos, nr * mc * sizeof(int32_t));
+        if (e == hipSuccess) e = hipMalloc((void**)&L->dense_pos, nr * mc * sizeof(int32_t));
+        if (e == hipSuccess) e = hipMalloc((void**)&L->seg_cnt, (size_t)L->seg_capacity * sizeof(int32_t));
+        if (e == hipSuccess) e = hipMemset(L->seg_cnt, 0, (size_t)L->seg_capacity * sizeof(int32_t));
+        if (e == hipSuccess) e = hipMalloc((void**)&L->vreps, nr * sizeof(RepDev));
+        if (e == hipSuccess) e = hipMemcpy(L->vreps, P.reps.data(), nr * sizeof(RepDev), hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMalloc((void**)&L->need, nr * sizeof(int32_t));
+        if (e == hipSuccess) e = hipMemset(L->need, 0, nr * sizeof(int32_t));
+        if (e == hipSuccess) e = hipMalloc((void**)&L->q_keep, nr * ctx->G * HC_D * sizeof(uint16_t));
+        if (e == hipSuccess) e = hipMemset(L->q_keep, 0, nr * ctx->G * HC_D * sizeof(uint16_t));
+        if (e != hipSuccess) st = hc_hip_fail(ctx, e, "buffers of the pivot-logit filter");
+    }
     if (st == HC_OK) {
         // staging for rebalanced plans: heads, segments, workgroup descriptors, pivots, each 16-byte aligned
         auto up16 = [](size_t x) { return (x + 15) & ~(size_t)15; };
@@ -697,6 +740,7 @@ extern "C" hc_status hc_decode_attn(hc_ctx* ctx, const hc_layer* layer, const vo
     if (!ctx_ok(ctx)) return HC_ESTATE;
     const hc_status chk = attn_check(ctx, layer, kv_arena, q, out, lse, rep_logits);
     if (chk != HC_OK) return chk;
+    if (rep_logits) const_cast<hc_layer*>(layer)->last_arena = kv_arena;
     return hc_launch_attn(ctx, layer, kv_arena, q, out, lse, rep_logits, (hipStream_t)stream);
 }
 
@@ -706,6 +750,7 @@ extern "C" hc_status hc_decode_attn_static(hc_ctx* ctx, const hc_layer* layer, c
     if (!ctx_ok(ctx)) return HC_ESTATE;
     const hc_status chk = attn_check(ctx, layer, kv_arena, q, out, lse, rep_logits);
     if (chk != HC_OK) return chk;
+    if (rep_logits) const_cast<hc_layer*>(layer)->last_arena = kv_arena;
     return hc_launch_attn_static(ctx, layer, kv_arena, q, out, lse, rep_logits, (hipStream_t)stream);
 }
 
@@ -761,6 +806,25 @@ extern "C" hc_status hc_gather_retrieve(hc_ctx* ctx, const hc_layer* layer, cons
         if (s != HC_OK) return s;
     }
     if (done_event) HC_HIP(ctx, hipEventRecord((hipEvent_t)done_event, st));
+    return HC_OK;
+}
+
+extern "C" hc_status hc_layer_monitor_counts(const hc_layer* layer, int32_t b, int32_t h, uint32_t* counts4)
+{
+    if (!layer_ok(layer)) return HC_ESTATE;
+    const hc_config& c = layer->ctx->cfg;
+    if (!counts4 || b < 0 || b >= c.B || h < 0 || h >= c.Hkv || layer->rep_slot_of[b * c.Hkv + h] < 0 || !layer->mon_counts)
+        return hc_fail(layer->ctx, HC_EINVAL, "hc_layer_monitor_counts: (b, h) is not a pivot of this layer");
+    HC_HIP(layer->ctx, hipMemcpy(counts4, layer->mon_counts + (size_t)layer->rep_slot_of[b * c.Hkv + h] * 4, 4 * sizeof(uint32_t),
+                                 hipMemcpyDeviceToHost));
+    return HC_OK;
+}
+
+extern "C" hc_status hc_layer_filter_view(const hc_layer* layer, const int32_t** kept_pos, const int32_t** fell_back)
+{
+    if (!layer_ok(layer)) return HC_ESTATE;
+    if (kept_pos) *kept_pos = layer->dense_pos;
+    if (fell_back) *fell_back = layer->need;
     return HC_OK;
 }
 
@@ -1225,7 +1289,9 @@ extern "C" hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* io, int32_t 
             hc_layer* L = x.layer;
             const bool side = L->n_reps > 0 && x.scores != nullptr;
             if (side) {
-                mon[n_mon++] = hc_monitor_call{L, x.rep_logits, x.lse, x.scores, x.topk_idx, x.base_idx, x.ring, x.inter, x.flag};
+                mon[n_mon] = hc_monitor_call{L, x.rep_logits, x.lse, x.scores, x.topk_idx, x.base_idx, x.ring, x.inter, x.flag};
+                mon[n_mon++].arena = x.kv_arena;
+                L->last_arena = x.kv_arena;
                 if (rescored) {
                     push_src[n_push] = x.q;
                     push_layer[n_push] = L;

@@ -60,6 +60,16 @@ struct OutDev {
     int32_t rep, kslot, row, is_mon;
 };
 
+// State of one pivot's logit filter: written by the monitor's decision kernel, read by the next step's split pass.
+// A row of the pivot is kept for the monitor if sum_g 2^(t_g - ref[g]) >= cutsum (t: scaled logit in log2 units).
+struct RepFilter {
+    float cutsum;          // 0: every candidate row is kept
+    float ref[8];          // the log-sum-exp of each query head of the group at the step that set the filter, log2 units
+    int32_t armed;         // 0 until a decision has set the filter
+    int32_t pad[6];
+};
+static_assert(sizeof(RepFilter) == 64, "filter state layout");
+
 // Where a head's K and V rows of the prefill stage are (element offsets in the caller's prefill buffer).
 struct PreSrc {
     int64_t k_off, v_off;
@@ -88,6 +98,7 @@ struct hc_ctx {
     int wg_per_cu;
     unsigned long long* tune_stamps = nullptr;   // non-null only inside hc_layer_tune: per-workgroup start / rows-done times
     float share_weights[16];     // by die and dispatch slot, see hc_set_share_weights
+    float filter_margin = 0.f;   // > 0: pivot logits are filtered (hc_set_logit_filter); layers created afterwards carry the buffers
     int device;
     char err[512];
     std::vector<std::pair<hipEvent_t, hipEvent_t>> timing;   // optional timing hook: one pair per split-pass launch
@@ -118,6 +129,7 @@ struct hc_layer {
     int max_r;                     // largest r among satellites
     int max_nchunk;
     int max_nk;                    // largest number of distinct set sizes of a pivot
+    int max_k_any = 1;             // largest set size of any pivot
     std::vector<int32_t> rep_slot_of;   // [B*Hkv]
     std::vector<hc_head_desc> hd_host;  // the head table as it is now (lengths grow with appended tokens)
     std::vector<int32_t> ctx0_host;     // [B*Hkv] context lengths at creation
@@ -149,6 +161,17 @@ struct hc_layer {
     RepDev* reps = nullptr;
     OutDev* outs = nullptr;
     SatDev* sats = nullptr;
+    // pivot-logit filter (only for layers created while the context's filter is on; all device memory)
+    RepFilter* filt = nullptr;     // [n_reps]
+    int32_t* surv_pos = nullptr;   // [n_reps][max_ctx] positions of the rows the split pass kept, by segment
+    int32_t* dense_pos = nullptr;  // [n_reps][max_ctx] the same positions, all of a pivot's in one ascending run
+    int32_t* seg_cnt = nullptr;    // [seg_capacity] rows kept per pivot segment
+    RepDev* vreps = nullptr;       // [n_reps] the pivots as the selection passes see them over the kept rows (lo = 0, hi = rows kept)
+    int32_t* need = nullptr;       // [n_reps] != 0: the check of this step's filter failed, the dense passes take over
+    uint16_t* q_keep = nullptr;    // [n_reps][G][D] the pivots' queries of the last attention call
+    uint32_t* mon_counts = nullptr;// [n_reps][4] tests, triggers, steps decided by the dense fallback, rows kept at the last step
+    const void* last_arena = nullptr;   // the arena of the last attention call with pivot logits (the fallback reads K from it)
+    bool filter_armed = false;     // a monitor call has set the filter: the selection passes are launched for few rows
     hipEvent_t ev_attn = nullptr;  // hc_decode_step: this layer's attention has been enqueued / its side work is done
     hipEvent_t ev_side = nullptr;
     hipEvent_t pending_ev = nullptr;   // side work of the previous hc_decode_step that this layer's attention must wait for
@@ -158,6 +181,11 @@ constexpr uint32_t HC_CTX_MAGIC = 0x48435458u;    // "HCTX"
 constexpr uint32_t HC_LAYER_MAGIC = 0x48434c59u;  // "HCLY"
 
 hc_status hc_fail(hc_ctx* ctx, hc_status st, const char* fmt, ...);
+// Does this layer's split pass filter the pivot logits (and its monitor read them that way)?
+inline bool hc_layer_filtered(const hc_ctx* ctx, const hc_layer* L)
+{
+    return ctx->filter_margin > 0.f && L->filt != nullptr && ctx->cfg.agg == HC_AGG_PROB;
+}
 hc_status hc_hip_fail(hc_ctx* ctx, hipError_t e, const char* what);
 
 #define HC_HIP(ctx, call)                                             \
@@ -181,6 +209,8 @@ struct hc_monitor_call {
     const RepDev* reps = nullptr;
     const OutDev* outs = nullptr;
     int n_reps = 0, n_outs = 0, max_nchunk = 0, max_nk = 0;
+    const void* arena = nullptr;   // the layer's K/V arena, for a layer that filters its pivot logits (nullptr: the one
+                                   // its last attention call was given)
 };
 struct hc_gather_call {
     const hc_layer* L;
@@ -195,6 +225,8 @@ hc_status hc_launch_attn(hc_ctx* ctx, const hc_layer* L, const void* arena, cons
 hc_status hc_launch_attn_static(hc_ctx* ctx, const hc_layer* L, const void* arena, const void* q, float* out,
                                 float* lse, float* rep_logits, hipStream_t st);
 hc_status hc_attn_static_scratch(hc_ctx* ctx, float** base);     // at context creation, with the context's device current
+hc_status hc_launch_rep_logits(hc_ctx* ctx, int n, const hc_layer* const* layers, const void* const* arenas,
+                               float* const* rep_logits, hipStream_t st);
 hc_status hc_launch_monitor(hc_ctx* ctx, int n, const hc_monitor_call* calls, int scores_given, hipStream_t st);
 hc_status hc_launch_gather(hc_ctx* ctx, int n, const hc_gather_call* calls, hipStream_t st);
 hc_status hc_gather_set_lds_limit();     // once per process, at context creation

@@ -89,10 +89,38 @@ struct MonItem {
     int32_t* flag;
     int n_reps, n_outs;
     int store_slot;
+    // A layer whose split pass filters the pivot logits: the selection passes run over the kept rows only
+    // (reps = the pivots as seen over those rows, pos_map = their positions), and a second, dense chain of the
+    // same passes stands by for the pivots whose check failed (need[rep] != 0).
+    int need_sense;               // -1: unconditional; 0: run where need[rep] == 0; 1: run where need[rep] != 0
+    const int32_t* need_r;        // [n_reps], read by every pass
+    int32_t* need_w;              // the same table, written by the first pass and the check
+    const RepDev* real_reps;      // the pivots by position (candidate range, table row); == reps unless filtered
+    const int32_t* pos_map;       // [n_reps][max_ctx] position of every kept row, or nullptr: a row is its position
+    int32_t* dense_pos;           // the same table, written by the first filtered pass
+    const HeadDev* heads;         // filtered first pass: where a pivot's segments are ...
+    const SegDev* segs;           // ... which rows of the pivot's block they begin at ...
+    const int32_t* seg_cnt;       // ... and how many rows each of them kept
+    const int32_t* surv_pos;      // [n_reps][max_ctx] positions of the kept rows, by segment
+    RepDev* vreps;                // written by the first filtered pass
+    RepFilter* filt;              // checked (this step's) and set (the next step's) when not nullptr
+    uint32_t* counts;             // [n_reps][4] or nullptr
+    int cap_rows;                 // filtered: more kept rows than this (or fewer than the largest list) go to the dense chain
+    float margin;                 // filter for the next step: cut = smallest list threshold / margin
 };
 struct MonBatch {
     MonItem it[HC_MAX_GROUP];
 };
+
+__device__ __forceinline__ bool mon_skip(const MonItem& it, int rep)
+{
+    return it.need_sense >= 0 && ((it.need_r[rep] != 0) != (it.need_sense != 0));
+}
+
+__device__ __forceinline__ float key_score(uint32_t key)      // inverse of score_key
+{
+    return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
+}
 
 __device__ __forceinline__ uint32_t wave_exscan(uint32_t v, uint32_t& total)
 {
@@ -201,7 +229,7 @@ __global__ __launch_bounds__(BLK) void mon_score_hist(MonBatch B, int scores_giv
     __shared__ uint32_t sh[HC_RADIX_BINS];
     const MonItem& it = B.it[blockIdx.z];
     const int rep = blockIdx.y;
-    if (rep >= it.n_reps) return;
+    if (rep >= it.n_reps || mon_skip(it, rep)) return;
     const Ws ws = it.ws;
     const RepDev* __restrict__ reps = it.reps;
     const float* __restrict__ rep_logits = it.rep_logits;
@@ -276,13 +304,13 @@ __device__ __forceinline__ int chunks_from_lo4(const RepDev& rd)
 // among keys whose upper 22 bits match.  One workgroup handles every set size of its pivot: wave ks
 // finds the digit of set size ks, then all waves histogram their candidates for each set size.
 template <int PASS>
-__global__ __launch_bounds__(BLK) void mon_hist(MonBatch B, int span)
+__global__ __launch_bounds__(BLK, 8) void mon_hist(MonBatch B, int span)
 {
     extern __shared__ uint32_t sh[];              // [nk][HC_RADIX_BINS]
     __shared__ uint32_t sm_prefix[HC_MAX_K_PER_REP];
     const MonItem& it = B.it[blockIdx.z];
     const int rep = blockIdx.y;
-    if (rep >= it.n_reps) return;
+    if (rep >= it.n_reps || mon_skip(it, rep)) return;
     const Ws ws = it.ws;
     const RepDev* __restrict__ reps = it.reps;
     const float* __restrict__ scores = it.scores;
@@ -367,12 +395,12 @@ __device__ __forceinline__ void load_keys16(const float* __restrict__ srow, int 
 
 // Finds the threshold key of every set size, then per chunk the counts of greater and of equal keys.
 // Wave v of the workgroup takes the chunks c0 + v, c0 + v + 4, ... of the workgroup's span.
-__global__ __launch_bounds__(BLK) void mon_count(MonBatch B, int span)
+__global__ __launch_bounds__(BLK) void mon_count(MonBatch B, int span, int G)
 {
     __shared__ uint32_t sm_tau[HC_MAX_K_PER_REP];
     const MonItem& it = B.it[blockIdx.z];
     const int rep = blockIdx.y;
-    if (rep >= it.n_reps) return;
+    if (rep >= it.n_reps || mon_skip(it, rep)) return;
     const Ws ws = it.ws;
     const RepDev* __restrict__ reps = it.reps;
     const float* __restrict__ scores = it.scores;
@@ -398,6 +426,22 @@ __global__ __launch_bounds__(BLK) void mon_count(MonBatch B, int span)
         }
     }
     __syncthreads();
+    if (it.need_sense == 0 && blockIdx.x == 0 && threadIdx.x == 0) {
+        // The check of this step's filter.  The split pass dropped the rows whose statistic sum_g 2^(t_g - ref_g)
+        // stayed below cutsum; with this step's own log-sum-exp such a row's score is below
+        // (cutsum / G) max_g 2^(ref_g - lse_g).  If even the smallest list threshold found among the kept rows
+        // reaches that bound (with room for the rounding of the statistic), no dropped row belongs to any list and
+        // the lists are those of all rows.  Otherwise the dense passes redo this pivot from all of its logits.
+        const RepFilter f = it.filt[rep];
+        if (f.cutsum > 0.f) {
+            uint32_t tmin = sm_tau[0];
+            for (int ks = 1; ks < rd.nk; ++ks) tmin = min(tmin, sm_tau[ks]);
+            float delta = 0.f;
+            for (int g = 0; g < G; ++g) delta = fmaxf(delta, exp2f(f.ref[g] - it.lse[(size_t)rd.bh * G + g] * 1.4426950408889634f));
+            const float bound = f.cutsum / (float)G * delta * 1.0001f;
+            if (!(key_score(tmin) >= bound)) it.need_w[rep] = 1;
+        }
+    }
     const float* srow = scores + (size_t)rep * ws.max_ctx;
     for (int ch = c0 + wv; ch < c1; ch += NWAVE) {
         uint32_t key[16], inmask;
@@ -427,18 +471,45 @@ struct DriftCfg {
     int window, metric, tau_num, tau_den, max_k, tumbling;
 };
 
-// Ordered compaction of the index lists of one pivot (blockIdx.y) into topk_idx, and |T ∩ baseline| for the
-// monitored list.  Wave v takes the chunks c0 + v, c0 + v + 4, ... of the workgroup's span and reads the
-// chunk's keys once for all set sizes; lists of equal size (satellites with the same budget) share the
-// selection and differ only in the row they are written to.  No workgroup barriers.
-__global__ __launch_bounds__(BLK) void mon_write(MonBatch B, DriftCfg cfg, int span)
+// Keys of the 8 consecutive candidates of a lane (two 16-byte loads) and the mask of those inside [lo, hi).
+__device__ __forceinline__ void load_keys8(const float* __restrict__ srow, int first8, int lo, int hi, uint32_t (&key)[8],
+                                           uint32_t& inmask)
 {
+    float4 v[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        v[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (first8 + 4 * q < hi) v[q] = *reinterpret_cast<const float4*>(srow + first8 + 4 * q);   // row stride is a multiple of 64: in bounds
+    }
+    inmask = 0;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const float f[4] = {v[q].x, v[q].y, v[q].z, v[q].w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int j = first8 + 4 * q + i;
+            if (j >= lo && j < hi) inmask |= 1u << (4 * q + i);
+            key[4 * q + i] = score_key(f[i]);
+        }
+    }
+}
+
+// Ordered compaction of the index lists of one pivot (blockIdx.y) into topk_idx, and |T ∩ baseline| for the
+// monitored list.  Wave v takes the chunks c0 + v, c0 + v + 4, ... of the workgroup's span, each as two halves of
+// 512 candidates in position order (8 per lane), and reads a half's keys once for all set sizes; what a set size
+// carries from half to half (equal keys seen, entries emitted) lives in LDS: the kernel has to fit, in registers,
+// beside the attention pass's waves on a compute unit.  Lists of equal size (satellites with the same budget)
+// share the selection and differ only in the row they are written to.  No workgroup barriers.
+__global__ __launch_bounds__(BLK, 8) void mon_write(MonBatch B, DriftCfg cfg, int span)
+{
+    __shared__ uint32_t sm_carry[NWAVE][HC_MAX_K_PER_REP][2];      // per wave and set size: equal keys before, entries emitted
     const MonItem& it = B.it[blockIdx.z];
     const int rep = blockIdx.y;
-    if (rep >= it.n_reps) return;
+    if (rep >= it.n_reps || mon_skip(it, rep)) return;
     const Ws ws = it.ws;
     const RepDev* __restrict__ reps = it.reps;
     const OutDev* __restrict__ outs = it.outs;
+    const int32_t* __restrict__ pmap = it.pos_map ? it.pos_map + (size_t)rep * ws.max_ctx : nullptr;
     const float* __restrict__ scores = it.scores;
     int32_t* __restrict__ topk_idx = it.topk_idx;
     const RepDev rd = reps[rep];
@@ -451,12 +522,8 @@ __global__ __launch_bounds__(BLK) void mon_write(MonBatch B, DriftCfg cfg, int s
     const float* srow = scores + (size_t)rep * ws.max_ctx;
 
     for (int chunk = c0 + wv; chunk < c1; chunk += NWAVE) {
-        uint32_t key[16], inmask;
-        const int first16 = lo4 + chunk * HC_SEL_CHUNK + lane * 16;
-        load_keys16(srow, first16, rd.lo, rd.hi, key, inmask);
         for (int ks = 0; ks < rd.nk; ++ks) {
-            const uint32_t tau = w.sel[ks * 4 + 0], need = w.sel[ks * 4 + 1];
-            const int k = reps[rep].k[ks];               // (indexing the register copy would spill it)
+            const uint32_t need = w.sel[ks * 4 + 1];
             const uint32_t* cnt = w.cnt + (size_t)ks * ws.max_chunks * 2;
             // Prefix over the chunks before this one: equal-keyed candidates seen, and list entries emitted.  A
             // chunk emits all its greater keys plus as many equal keys as are still needed.
@@ -472,53 +539,79 @@ __global__ __launch_bounds__(BLK) void mon_write(MonBatch B, DriftCfg cfg, int s
                 emitted += mine;
                 eq_before += etot;
             }
-            uint32_t my_eq = 0;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) my_eq += ((inmask >> i) & 1u) && key[i] == tau;
-            uint32_t tot;
-            uint32_t eq_rank = eq_before + wave_exscan(my_eq, tot);
-            uint32_t selmask = 0, my_sel = 0;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                if (!((inmask >> i) & 1u)) continue;
-                bool sel = key[i] > tau;
-                if (key[i] == tau) {
-                    sel = eq_rank < need;
-                    ++eq_rank;
-                }
-                if (sel) {
-                    selmask |= 1u << i;
-                    ++my_sel;
-                }
+            if (lane == 0) {
+                sm_carry[wv][ks][0] = eq_before;
+                sm_carry[wv][ks][1] = emitted;
             }
-            const uint32_t pos0 = emitted + wave_exscan(my_sel, tot);
-            for (int o = rd.out_begin; o < rd.out_begin + rd.out_count; ++o) {      // the rows this list goes to
-                const OutDev od = outs[o];
-                if (od.kslot != ks) continue;
-                int32_t* dst = topk_idx + (size_t)od.row * cfg.max_k;
-                uint32_t pos = pos0, hits = 0;
+        }
+        uint32_t hits = 0;
+        for (int half = 0; half < 2; ++half) {
+            uint32_t key[8], inmask;
+            const int first8 = lo4 + chunk * HC_SEL_CHUNK + half * (HC_SEL_CHUNK / 2) + lane * 8;
+            load_keys8(srow, first8, rd.lo, rd.hi, key, inmask);
+            for (int ks = 0; ks < rd.nk; ++ks) {
+                const uint32_t tau = w.sel[ks * 4 + 0], need = w.sel[ks * 4 + 1];
+                const int k = reps[rep].k[ks];               // (indexing the register copy would spill it)
+                const uint32_t eq_before = sm_carry[wv][ks][0], emitted = sm_carry[wv][ks][1];      // (written by this wave)
+                uint32_t my_eq = 0;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    if (selmask & (1u << i)) {
-                        const int j = first16 + i;
-                        if (pos < (uint32_t)k) dst[pos] = j;     // pos < k always holds; the guard keeps a corrupt state in bounds
-                        ++pos;
-                        if (od.is_mon) hits += (w.bitmap[j >> 5] >> (j & 31)) & 1u;
+                for (int i = 0; i < 8; ++i) my_eq += ((inmask >> i) & 1u) && key[i] == tau;
+                uint32_t eq_tot;
+                uint32_t eq_rank = eq_before + wave_exscan(my_eq, eq_tot);
+                uint32_t selmask = 0, my_sel = 0;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    if (!((inmask >> i) & 1u)) continue;
+                    bool sel = key[i] > tau;
+                    if (key[i] == tau) {
+                        sel = eq_rank < need;
+                        ++eq_rank;
+                    }
+                    if (sel) {
+                        selmask |= 1u << i;
+                        ++my_sel;
                     }
                 }
-                if (od.is_mon) {
-                    // per-chunk hit counts, summed by mon_decide (hundreds of atomics on one word would serialise)
-                    for (int o2 = 32; o2 > 0; o2 >>= 1) hits += __shfl_xor(hits, o2);
-                    if (lane == 0) ws.hits[(size_t)rep * (ws.max_chunks + 1) + chunk] = hits;
+                uint32_t sel_tot;
+                const uint32_t pos0 = emitted + wave_exscan(my_sel, sel_tot);
+                if (lane == 0) {
+                    sm_carry[wv][ks][0] = eq_before + eq_tot;
+                    sm_carry[wv][ks][1] = emitted + sel_tot;
+                }
+                for (int o = rd.out_begin; o < rd.out_begin + rd.out_count; ++o) {      // the rows this list goes to
+                    const OutDev od = outs[o];
+                    if (od.kslot != ks) continue;
+                    int32_t* dst = topk_idx + (size_t)od.row * cfg.max_k;
+                    uint32_t pos = pos0;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        if (selmask & (1u << i)) {
+                            const int j = pmap ? pmap[first8 + i] : first8 + i;      // the row's position
+                            if (pos < (uint32_t)k) dst[pos] = j;     // pos < k always holds; the guard keeps a corrupt state in bounds
+                            ++pos;
+                            if (od.is_mon) hits += (w.bitmap[j >> 5] >> (j & 31)) & 1u;
+                        }
+                    }
                 }
             }
         }
+        // Per-chunk hit counts of the monitored list, summed by mon_decide: hundreds of atomics on one word would serialise.
+        for (int o2 = 32; o2 > 0; o2 >>= 1) hits += __shfl_xor(hits, o2);
+        if (lane == 0) ws.hits[(size_t)rep * (ws.max_chunks + 1) + chunk] = hits;
     }
+}
+
+// Leaves a pivot's histograms and baseline bitmap clear for the next call.
+__device__ __forceinline__ void clear_rep_ws(const RepWs& w, int hi)
+{
+    uint4* h4 = reinterpret_cast<uint4*>(w.h1);
+    for (int i = threadIdx.x; i < (1 + 2 * HC_MAX_K_PER_REP) * HC_RADIX_BINS / 4; i += BLK) h4[i] = make_uint4(0u, 0u, 0u, 0u);
+    for (int i = threadIdx.x; i < (hi + 31) / 32; i += BLK) w.bitmap[i] = 0u;
 }
 
 // One workgroup per pivot, after mon_write has completed (the kernel boundary makes its lists and the
 // intersection count visible): window update, decision, baseline update.
-__global__ __launch_bounds__(BLK) void mon_decide(MonBatch B, DriftCfg cfg)
+__global__ __launch_bounds__(BLK) void mon_decide(MonBatch B, DriftCfg cfg, int G)
 {
     const MonItem& it = B.it[blockIdx.y];
     if ((int)blockIdx.x >= it.n_reps) return;
@@ -535,6 +628,15 @@ __global__ __launch_bounds__(BLK) void mon_decide(MonBatch B, DriftCfg cfg)
     __shared__ int32_t sm_med;
     __shared__ int32_t sm_trig;
     const RepDev rd = reps[blockIdx.x];
+    const int real_hi = it.real_reps[blockIdx.x].hi;     // the bitmap is indexed by position
+    if (it.need_sense >= 0) {
+        const bool need = it.need_r[blockIdx.x] != 0;
+        if (it.need_sense == 1 && !need) return;          // the filtered chain decided: nothing to redo
+        if (it.need_sense == 0 && need) {                  // the dense chain decides; it starts from a clear workspace
+            clear_rep_ws(ws.rep(blockIdx.x), real_hi);
+            return;
+        }
+    }
     const int k = rd.k[0];
     int32_t* rg = ring + (size_t)rd.bh * (cfg.window + 1);
     int n = rg[0];
@@ -556,10 +658,7 @@ __global__ __launch_bounds__(BLK) void mon_decide(MonBatch B, DriftCfg cfg)
         // the one stored when the query was current.  Only while the ring is one short of full, i.e. the
         // monitor call that follows is the one that tests.  -2: the lists were all that was wanted.
         if (threadIdx.x == 0 && it.store_slot >= 0 && n == cfg.window - 1 && it.store_slot < n) rg[1 + it.store_slot] = inter;
-        const RepWs w = ws.rep(blockIdx.x);
-        uint4* h4 = reinterpret_cast<uint4*>(w.h1);
-        for (int i = threadIdx.x; i < (1 + 2 * HC_MAX_K_PER_REP) * HC_RADIX_BINS / 4; i += BLK) h4[i] = make_uint4(0u, 0u, 0u, 0u);
-        for (int i = threadIdx.x; i < (rd.hi + 31) / 32; i += BLK) w.bitmap[i] = 0u;
+        clear_rep_ws(ws.rep(blockIdx.x), real_hi);
         return;
     }
     const int m = n - drop + 1;                      // values in the window after the push
@@ -588,6 +687,27 @@ __global__ __launch_bounds__(BLK) void mon_decide(MonBatch B, DriftCfg cfg)
         inter_out[rd.bh] = inter;
         flag_out[rd.bh] = trig;
         sm_trig = trig;
+        if (it.counts) {
+            uint32_t* cn = it.counts + (size_t)blockIdx.x * 4;
+            cn[0] += m == cfg.window;
+            cn[1] += (uint32_t)trig;
+            cn[2] += it.need_sense == 1;
+            cn[3] = it.need_sense == 0 ? (uint32_t)rd.hi : 0xffffffffu;
+        }
+        if (it.filt) {
+            // The filter of the next step's split pass: rows whose statistic, taken against this step's
+            // log-sum-exp, stays below the smallest list threshold of this step divided by the margin are dropped.
+            const RepWs w = ws.rep(blockIdx.x);
+            uint32_t tmin = w.sel[0];                  // (mon_count left every set size's threshold key in word 0)
+            for (int ks = 1; ks < rd.nk; ++ks) tmin = min(tmin, w.sel[ks * 4]);
+            const float tau = key_score(tmin);
+            RepFilter f;
+            f.cutsum = (tau > 0.f && tau < 1.0e30f && it.margin >= 1.f) ? (float)G * tau / it.margin : 0.f;
+            for (int g = 0; g < 8; ++g) f.ref[g] = g < G ? it.lse[(size_t)rd.bh * G + g] * 1.4426950408889634f : 0.f;
+            f.armed = 1;
+            for (int i = 0; i < 6; ++i) f.pad[i] = 0;
+            it.filt[blockIdx.x] = f;
+        }
     }
     __syncthreads();
     if (sm_trig) {                                   // K_base <- K_t
@@ -596,26 +716,141 @@ __global__ __launch_bounds__(BLK) void mon_decide(MonBatch B, DriftCfg cfg)
         for (int i = threadIdx.x; i < k; i += BLK) base[i] = src[i];
     }
     // every other kernel of this call is done with the histograms and the bitmap: leave them clear
-    const RepWs w = ws.rep(blockIdx.x);
-    uint4* h4 = reinterpret_cast<uint4*>(w.h1);
-    for (int i = threadIdx.x; i < (1 + 2 * HC_MAX_K_PER_REP) * HC_RADIX_BINS / 4; i += BLK) h4[i] = make_uint4(0u, 0u, 0u, 0u);
-    for (int i = threadIdx.x; i < (rd.hi + 31) / 32; i += BLK) w.bitmap[i] = 0u;
+    clear_rep_ws(ws.rep(blockIdx.x), real_hi);
+}
+
+// First pass of the selection over a pivot whose logits the split pass filtered: the rows it kept lie segment by
+// segment in the pivot's block of rep_logits (positions in surv_pos, counts in seg_cnt).  They are scored with this
+// step's log-sum-exp and laid out as one dense run in position order (scores[rep][0, n), dense_pos[rep][0, n)),
+// over which the later passes then work as over a short context; the first-digit histogram and the baseline
+// bitmap are made on the way, as in mon_score_hist.  Every workgroup makes the prefix sums of the pivot's
+// segment counts itself (a few hundred numbers).
+constexpr int MAX_FILTER_SEGS = 2048;
+template <int G>
+__global__ __launch_bounds__(BLK) void mon_sparse_score(MonBatch B, int max_k, int span)
+{
+    __shared__ uint32_t sh[HC_RADIX_BINS];
+    __shared__ int sm_pref[MAX_FILTER_SEGS + 1];
+    __shared__ int sm_row0[MAX_FILTER_SEGS];
+    __shared__ int sm_wsum[NWAVE];
+    __shared__ int sm_unknown;
+    const MonItem& it = B.it[blockIdx.z];
+    const int rep = blockIdx.y;
+    if (rep >= it.n_reps) return;
+    const Ws ws = it.ws;
+    const RepDev rd = it.real_reps[rep];
+    const HeadDev hd = it.heads[rd.bh];
+    const int nseg = min(hd.part_count, MAX_FILTER_SEGS);
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (threadIdx.x == 0) sm_unknown = 0;
+    __syncthreads();
+    int carry = 0;
+    for (int base = 0; base < nseg; base += BLK) {
+        const int sidx = base + threadIdx.x;
+        int c = 0;
+        if (sidx < nseg) {
+            const SegDev sg = it.segs[hd.part_begin + sidx];
+            c = it.seg_cnt[hd.part_begin + sidx];
+            if (c < 0 || c > sg.row_end - sg.row_begin) {      // a segment whose workgroup could not hold all the rows it kept
+                sm_unknown = 1;
+                c = 0;
+            }
+            sm_row0[sidx] = sg.row_begin;
+        }
+        int inc = c;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(inc, o);
+            if (lane >= o) inc += t;
+        }
+        if (lane == 63) sm_wsum[wv] = inc;
+        __syncthreads();
+        int before = carry;
+        for (int k = 0; k < wv; ++k) before += sm_wsum[k];
+        if (sidx < nseg) sm_pref[sidx] = before + inc - c;
+        carry += sm_wsum[0] + sm_wsum[1] + sm_wsum[2] + sm_wsum[3];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) sm_pref[nseg] = carry;
+    const int n = carry;                                    // rows kept, all of them candidates
+    int kmax = 0;
+    for (int ks = 0; ks < rd.nk; ++ks) kmax = max(kmax, it.real_reps[rep].k[ks]);       // (indexing the register copy would spill it)
+    const bool bad = n > it.cap_rows || n < kmax || hd.part_count > MAX_FILTER_SEGS || sm_unknown != 0;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        // the pivot as the later passes see it: a context of n rows, all of them candidates
+        RepDev* v = it.vreps + rep;
+        v->bh = rd.bh;
+        v->lo = 0;
+        v->hi = bad ? 0 : n;
+        v->nk = rd.nk;
+        for (int ks = 0; ks < rd.nk; ++ks) v->k[ks] = it.real_reps[rep].k[ks];
+        v->nchunk = bad ? 0 : (n + HC_SEL_CHUNK - 1) / HC_SEL_CHUNK;
+        v->out_begin = rd.out_begin;
+        v->out_count = rd.out_count;
+        it.need_w[rep] = bad ? 1 : 0;
+    }
+    if (bad) return;
+    const int nchunk = (n + HC_SEL_CHUNK - 1) / HC_SEL_CHUNK;
+    const int c0 = blockIdx.x * span, c1 = min(c0 + span, nchunk);
+    if (c0 >= nchunk) return;
+    const RepWs w = ws.rep(rep);
+    for (int i = threadIdx.x; i < HC_RADIX_BINS; i += BLK) sh[i] = 0u;
+    // baseline list -> bitmap (each active workgroup takes a slice of the list)
+    const int32_t* basel = it.base_idx + (size_t)rd.bh * max_k;
+    const int nblk = (nchunk + span - 1) / span;
+    for (int i = blockIdx.x * BLK + threadIdx.x; i < rd.k[0]; i += nblk * BLK) {
+        const int j = basel[i];
+        if (j >= rd.lo && j < rd.hi) atomicOr(&w.bitmap[j >> 5], 1u << (j & 31));
+    }
+    __syncthreads();
+    float l[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) l[g] = it.lse[(size_t)rd.bh * G + g];
+    const float* lrow = it.rep_logits + (size_t)rep * G * ws.max_ctx;
+    const int32_t* prow = it.surv_pos + (size_t)rep * ws.max_ctx;
+    float* srow = it.scores + (size_t)rep * ws.max_ctx;
+    int32_t* drow = it.dense_pos + (size_t)rep * ws.max_ctx;
+    for (int ch = c0; ch < c1; ++ch) {
+#pragma unroll
+        for (int i = 0; i < PER_THREAD; ++i) {
+            const int d = ch * HC_SEL_CHUNK + i * BLK + threadIdx.x;
+            if (d >= n) continue;
+            int lo = 0, hi = nseg;                             // the segment whose run holds kept row d
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (sm_pref[mid] <= d) lo = mid;
+                else hi = mid;
+            }
+            const int src = sm_row0[lo] + (d - sm_pref[lo]);
+            const float sc = score_of<G>(lrow, src, l, HC_AGG_PROB);
+            srow[d] = sc;
+            drow[d] = prow[src];
+            atomicAdd(&sh[score_key(sc) >> 21], 1u);
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < HC_RADIX_BINS; i += BLK)
+        if (sh[i]) atomicAdd(&w.h1[i], sh[i]);
 }
 
 }   // namespace
 
-hc_status hc_launch_monitor(hc_ctx* ctx, int n, const hc_monitor_call* calls, int scores_given, hipStream_t st)
+// The launches of one chain of selection passes over a batch of layers.  mode 0: the plain chain (every pivot, all
+// candidate positions).  mode 1: the chain over the rows a filtering split pass kept.  mode 2: the dense chain that
+// stands by behind mode 1, for the pivots whose check failed.  ws_first: which workspace copy the first layer uses.
+static hc_status run_chain(hc_ctx* ctx, int n, const hc_monitor_call* const* calls, int ws_first, int scores_given, int mode,
+                           hipStream_t st)
 {
-    if (n < 1 || n > HC_MAX_GROUP) return hc_fail(ctx, HC_EINVAL, "monitor batch of %d layers", n);
     const hc_config& c = ctx->cfg;
     MonBatch B{};
     int max_reps = 0, max_nchunk = 0, max_nk = 0;
     for (int i = 0; i < n; ++i) {
-        const hc_monitor_call& x = calls[i];
-        hc_monitor_ws& m = ctx->ws[i];
+        const hc_monitor_call& x = *calls[i];
+        hc_monitor_ws& m = ctx->ws[ws_first + i];
         MonItem& it = B.it[i];
         it.ws = Ws{m.hist, m.sel, m.misc, m.cnt, m.bitmap, m.hits, ctx->max_chunks, c.max_ctx};
         it.reps = x.reps ? x.reps : x.L->reps;
+        it.real_reps = it.reps;
         it.outs = x.reps ? x.outs : x.L->outs;
         it.rep_logits = x.rep_logits;
         it.lse = x.lse;
@@ -628,10 +863,35 @@ hc_status hc_launch_monitor(hc_ctx* ctx, int n, const hc_monitor_call* calls, in
         it.n_reps = x.reps ? x.n_reps : x.L->n_reps;
         it.n_outs = x.reps ? x.n_outs : x.L->n_outs;
         it.store_slot = x.store_slot;
+        it.need_sense = -1;
+        if (!x.reps && x.store_slot == -1) it.counts = x.L->mon_counts;
+        int nchunk = x.reps ? x.max_nchunk : x.L->max_nchunk;
+        if (mode != 0) {
+            const hc_layer* L = x.L;
+            it.need_sense = mode == 1 ? 0 : 1;
+            it.need_r = it.need_w = L->need;
+            it.filt = L->filt;
+            it.counts = L->mon_counts;
+            it.margin = ctx->filter_margin;
+            if (mode == 1) {
+                it.reps = L->vreps;
+                it.pos_map = it.dense_pos = L->dense_pos;
+                it.heads = L->heads;
+                it.segs = L->segs;
+                it.seg_cnt = L->seg_cnt;
+                it.surv_pos = L->surv_pos;
+                it.vreps = L->vreps;
+                // Once the filter is set few rows are kept (a small multiple of the longest list); a step that keeps
+                // more is handed to the dense chain, so the launches need not be sized for it.
+                const int armed_cap = std::min(c.max_ctx, 4 * L->max_k_any + 4096);
+                it.cap_rows = L->filter_armed ? armed_cap : c.max_ctx;
+                nchunk = std::min(nchunk, (it.cap_rows + HC_SEL_CHUNK - 1) / HC_SEL_CHUNK);
+            }
+        }
         max_reps = std::max(max_reps, it.n_reps);
-        max_nchunk = std::max(max_nchunk, x.reps ? x.max_nchunk : x.L->max_nchunk);
+        max_nchunk = std::max(max_nchunk, nchunk);
         max_nk = std::max(max_nk, x.reps ? x.max_nk : x.L->max_nk);
-        if (m.dirty) {     // a previous call that used this workspace copy did not run to its last kernel
+        if (m.dirty && mode != 2) {     // a previous call that used this workspace copy did not run to its last kernel
             mon_prep<<<dim3(16, ctx->max_reps), dim3(256), 0, st>>>(it.ws, c.max_ctx);
             HC_HIP(ctx, hipGetLastError());
         }
@@ -639,13 +899,24 @@ hc_status hc_launch_monitor(hc_ctx* ctx, int n, const hc_monitor_call* calls, in
     }
     if (max_reps == 0) return HC_OK;
     // chunks per workgroup: aim at about 512 workgroups per launch, at most 8 chunks each
-    const int span = ctx->monitor_span > 0 ? ctx->monitor_span : std::max(1, std::min(8, (n * max_reps * (max_nchunk + 1)) / 512));
+    // (the stand-by chain is there at every step and normally has nothing to do: few, long workgroups)
+    const int span = mode == 2 ? 32
+                               : ctx->monitor_span > 0 ? ctx->monitor_span : std::max(1, std::min(8, (n * max_reps * (max_nchunk + 1)) / 512));
     const dim3 g1((max_nchunk + span - 1) / span, max_reps, n);
-    switch (ctx->G) {
-    case 1: mon_score_hist<1><<<g1, dim3(BLK), 0, st>>>(B, scores_given, c.agg, c.max_k, span); break;
-    case 2: mon_score_hist<2><<<g1, dim3(BLK), 0, st>>>(B, scores_given, c.agg, c.max_k, span); break;
-    case 4: mon_score_hist<4><<<g1, dim3(BLK), 0, st>>>(B, scores_given, c.agg, c.max_k, span); break;
-    default: mon_score_hist<8><<<g1, dim3(BLK), 0, st>>>(B, scores_given, c.agg, c.max_k, span); break;
+    if (mode == 1) {
+        switch (ctx->G) {
+        case 1: mon_sparse_score<1><<<g1, dim3(BLK), 0, st>>>(B, c.max_k, span); break;
+        case 2: mon_sparse_score<2><<<g1, dim3(BLK), 0, st>>>(B, c.max_k, span); break;
+        case 4: mon_sparse_score<4><<<g1, dim3(BLK), 0, st>>>(B, c.max_k, span); break;
+        default: mon_sparse_score<8><<<g1, dim3(BLK), 0, st>>>(B, c.max_k, span); break;
+        }
+    } else {
+        switch (ctx->G) {
+        case 1: mon_score_hist<1><<<g1, dim3(BLK), 0, st>>>(B, scores_given, c.agg, c.max_k, span); break;
+        case 2: mon_score_hist<2><<<g1, dim3(BLK), 0, st>>>(B, scores_given, c.agg, c.max_k, span); break;
+        case 4: mon_score_hist<4><<<g1, dim3(BLK), 0, st>>>(B, scores_given, c.agg, c.max_k, span); break;
+        default: mon_score_hist<8><<<g1, dim3(BLK), 0, st>>>(B, scores_given, c.agg, c.max_k, span); break;
+        }
     }
     HC_HIP(ctx, hipGetLastError());
     // the later passes start at a multiple of 4 positions, which can add one chunk
@@ -655,15 +926,56 @@ hc_status hc_launch_monitor(hc_ctx* ctx, int n, const hc_monitor_call* calls, in
     HC_HIP(ctx, hipGetLastError());
     mon_hist<3><<<gk, dim3(BLK), hist_lds, st>>>(B, span);
     HC_HIP(ctx, hipGetLastError());
-    mon_count<<<gk, dim3(BLK), 0, st>>>(B, span);
+    mon_count<<<gk, dim3(BLK), 0, st>>>(B, span, ctx->G);
     HC_HIP(ctx, hipGetLastError());
     DriftCfg dc{c.window, c.metric, c.tau_num, c.tau_den, c.max_k, c.window_mode != HC_WINDOW_SLIDING};
     // the write pass has no per-workgroup set-up to amortise: one chunk per wave
-    const int span_w = NWAVE;
+    const int span_w = mode == 2 ? 4 * NWAVE : NWAVE;
     mon_write<<<dim3((max_nchunk + 1 + span_w - 1) / span_w, max_reps, n), dim3(BLK), 0, st>>>(B, dc, span_w);
     HC_HIP(ctx, hipGetLastError());
-    mon_decide<<<dim3(max_reps, n), dim3(BLK), 0, st>>>(B, dc);
+    mon_decide<<<dim3(max_reps, n), dim3(BLK), 0, st>>>(B, dc, ctx->G);
     HC_HIP(ctx, hipGetLastError());
+    return HC_OK;
+}
+
+hc_status hc_launch_monitor(hc_ctx* ctx, int n, const hc_monitor_call* calls, int scores_given, hipStream_t st)
+{
+    if (n < 1 || n > HC_MAX_GROUP) return hc_fail(ctx, HC_EINVAL, "monitor batch of %d layers", n);
+    // Layers whose split pass filtered the pivot logits are handled over the kept rows, with the dense chain behind
+    // them; all others (and every call that brings its own scores or logits: given scores, the window's re-scored
+    // queries, the prefill-time selection) by the plain chain.
+    const hc_monitor_call* plain[HC_MAX_GROUP];
+    const hc_monitor_call* filt[HC_MAX_GROUP];
+    int n_plain = 0, n_filt = 0;
+    for (int i = 0; i < n; ++i) {
+        const hc_monitor_call& x = calls[i];
+        const bool f = !scores_given && x.store_slot == -1 && x.reps == nullptr && hc_layer_filtered(ctx, x.L);
+        if (f && !(x.arena ? x.arena : x.L->last_arena))
+            return hc_fail(ctx, HC_ESTATE, "monitor of a filtering layer before any attention call with pivot logits");
+        (f ? filt[n_filt++] : plain[n_plain++]) = &x;
+    }
+    hc_status s = HC_OK;
+    if (n_plain > 0) s = run_chain(ctx, n_plain, plain, 0, scores_given, 0, st);
+    if (s == HC_OK && n_filt > 0) {
+        s = run_chain(ctx, n_filt, filt, n_plain, 0, 1, st);
+        // behind it, for the pivots whose check failed (decided on the device; normally none): all logits over
+        // again, then the plain passes over them
+        if (s == HC_OK) {
+            const hc_layer* layers[HC_MAX_GROUP];
+            const void* arenas[HC_MAX_GROUP];
+            float* logits[HC_MAX_GROUP];
+            for (int i = 0; i < n_filt; ++i) {
+                layers[i] = filt[i]->L;
+                arenas[i] = filt[i]->arena ? filt[i]->arena : filt[i]->L->last_arena;
+                logits[i] = const_cast<float*>(filt[i]->rep_logits);
+            }
+            s = hc_launch_rep_logits(ctx, n_filt, layers, arenas, logits, st);
+        }
+        if (s == HC_OK) s = run_chain(ctx, n_filt, filt, n_plain, 0, 2, st);
+        if (s == HC_OK)
+            for (int i = 0; i < n_filt; ++i) const_cast<hc_layer*>(filt[i]->L)->filter_armed = true;
+    }
+    if (s != HC_OK) return s;
     // everything enqueued: the workspace copies will be clear again when this call completes.  (Not so under
     // stream capture, where nothing has run yet and the graph may never be launched: they stay marked.)
     hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;

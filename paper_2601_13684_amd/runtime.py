@@ -61,13 +61,16 @@ def make_descs(spec: LayerSpec, growth: int = 0) -> Tuple[List[hc.hc_head_desc],
 class Context:
     """Owns an hc_ctx and the scratch that consecutive layers can share."""
 
-    def __init__(self, cfg: hc.hc_config, device: str = "cuda:0", workgroups_per_cu: Optional[int] = None):
+    def __init__(self, cfg: hc.hc_config, device: str = "cuda:0", workgroups_per_cu: Optional[int] = None,
+                 filter_margin: float = 0.0):
         self.cfg = cfg
         self.device = torch.device(device)
         with torch.cuda.device(self.device):
             self.handle = hc.hc_create(cfg)
         if workgroups_per_cu:
             hc.hc_set_split(self.handle, workgroups_per_cu)
+        if filter_margin:
+            hc.hc_set_logit_filter(self.handle, filter_margin)
         self.G = cfg.Hq // cfg.Hkv
         self._scratch: Dict[int, Tuple[torch.Tensor, torch.Tensor]] = {}
 
@@ -169,6 +172,24 @@ class LayerRuntime:
 
     def rep_slot(self, b: int, h: int) -> int:
         return hc.hc_layer_rep_slot(self.handle, b, h)
+
+    def monitor_counts(self, b: int, h: int) -> dict:
+        return hc.hc_layer_monitor_counts(self.handle, b, h)
+
+    def kept_rows(self, b: int, h: int):
+        """With the pivot-logit filter: (positions, scores) of the rows kept for pivot (b, h) at the last monitored
+        step (device tensors, ascending positions), or None if that step fell back to the dense passes (then
+        ``scores`` holds every candidate's score by position, as without the filter)."""
+        pos_addr, need_addr = hc.hc_layer_filter_view(self.handle)
+        if not pos_addr:
+            return None
+        slot, mc = self.rep_slot(b, h), self.ctx.cfg.max_ctx
+        n = self.monitor_counts(b, h)["kept"]
+        need = _view_i32(need_addr, self.n_reps, self.ctx.device)
+        if n is None or int(need[slot]) != 0:
+            return None
+        pos = _view_i32(pos_addr + 4 * slot * mc, n, self.ctx.device)
+        return pos, self.scores[slot, :n]
 
     # -- the three calls ------------------------------------------------------------------------
     def attn(self, q: torch.Tensor, monitor: bool = True, stream=None) -> None:
@@ -281,6 +302,20 @@ class LayerRuntime:
         if self.handle:
             hc.hc_layer_destroy(self.handle)
             self.handle = None
+
+
+class _DeviceInts:
+    """n int32 at a raw device address, in the form torch.as_tensor understands."""
+
+    def __init__(self, addr: int, n: int):
+        self.__cuda_array_interface__ = {"shape": (n,), "typestr": "<i4", "data": (addr, False), "version": 2}
+
+
+def _view_i32(addr: int, n: int, device) -> torch.Tensor:
+    """A copy of n int32 of library-owned device memory."""
+    if n <= 0:
+        return torch.empty((0,), dtype=torch.int32, device=device)
+    return torch.as_tensor(_DeviceInts(addr, n), device=device).clone()
 
 
 def make_step_io(layers: List[LayerRuntime], q_per_layer: torch.Tensor, monitor: bool = True):

@@ -37,6 +37,20 @@ def check_scores(s_gpu: np.ndarray, s_ref: np.ndarray, lo: int, hi: int, where: 
     return float(d.max()), float((d / np.maximum(np.abs(s_ref[lo:hi]), 1e-300)).max())
 
 
+def check_gpu_scores(gpu, b: int, pv: int, s_ref: np.ndarray, lo: int, hi: int, where: str = ""):
+    """The scores pivot (b, pv)'s last monitor call decided on, against the fp64 scores.  Without the pivot-logit
+    filter (or after a fallback) that is every candidate's score by position; with it, the scores of the rows the
+    split pass kept, whose positions must be ascending candidates.  Returns (max abs difference, max relative)."""
+    kept = gpu.kept_rows(b, pv)
+    if kept is None:
+        return check_scores(gpu.scores[gpu.rep_slot(b, pv)].cpu().numpy(), s_ref, lo, hi, where)
+    pos, sc = kept[0].cpu().numpy(), kept[1].cpu().numpy().astype(np.float64)
+    assert pos.size and (np.diff(pos) > 0).all() and pos[0] >= lo and pos[-1] < hi, (where, "kept positions")
+    d = np.abs(sc - s_ref[pos])
+    assert (d <= 1e-5 + 1e-4 * np.abs(s_ref[pos])).all(), (where, "kept scores", d.max())
+    return float(d.max()), float((d / np.maximum(np.abs(s_ref[pos]), 1e-300)).max())
+
+
 def band_of(dabs: float) -> float:
     """Width of the near-tie band around the k-th fp64 score inside which the GPU's set may differ from the
     oracle's: 4 times the largest difference between the GPU's fp32 scores and the fp64 scores of this very
@@ -71,18 +85,20 @@ def check_set_valid(T_gpu: np.ndarray, T_ref: np.ndarray, s_ref: np.ndarray, ban
 class Pair:
     """One layer on the GPU and its oracle twin, fed the same inputs."""
 
-    def __init__(self, spec, data, device="cuda:0", ctx=None, host_tier=True, wg_per_cu=None, delta_gather=True, growth=0):
+    def __init__(self, spec, data, device="cuda:0", ctx=None, host_tier=True, wg_per_cu=None, delta_gather=True, growth=0,
+                 filter_margin=0.0):
         self.spec, self.data = spec, data
         self.ctx0 = list(spec.ctx)
         retrieved, base = I.initial_lists(spec)
         self.own_ctx = ctx is None
-        self.ctx = ctx or R.Context(R.make_config(spec, growth=growth), device, workgroups_per_cu=wg_per_cu)
+        self.ctx = ctx or R.Context(R.make_config(spec, growth=growth), device, workgroups_per_cu=wg_per_cu,
+                                    filter_margin=filter_margin)
         self.gpu = R.LayerRuntime(self.ctx, spec, data, retrieved, base, host_tier=host_tier, delta_gather=delta_gather, growth=growth)
         cpu = I.LayerData({k: v.cpu() for k, v in data.K.items()}, {k: v.cpu() for k, v in data.V.items()}, {})
         self.ref = ref.RefLayer(spec, cpu, retrieved, base)
 
     @classmethod
-    def from_prefill(cls, spec, data, q_last, pool, device="cuda:0", growth=0, where="prefill"):
+    def from_prefill(cls, spec, data, q_last, pool, device="cuda:0", growth=0, where="prefill", filter_margin=0.0):
         """The GPU side builds its initial state with hc_prefill_init, the oracle twin with oracle/prefill.py.  Scores
         and lists are compared here (a list may differ from the oracle's inside the near-tie band: the twin
         then starts from the GPU's list, so that everything downstream compares like with like).
@@ -91,7 +107,7 @@ class Pair:
         self.spec, self.data = spec, data
         self.ctx0 = list(spec.ctx)
         self.own_ctx = True
-        self.ctx = R.Context(R.make_config(spec, growth=growth), device)
+        self.ctx = R.Context(R.make_config(spec, growth=growth), device, filter_margin=filter_margin)
         self.gpu = R.LayerRuntime(self.ctx, spec, data, None, None, growth=growth, prefill=(q_last, pool))
         torch.cuda.synchronize()
         cpu = I.LayerData({k: v.cpu() for k, v in data.K.items()}, {k: v.cpu() for k, v in data.V.items()}, {})

@@ -54,7 +54,7 @@ def run_stack(ws, steps, group, tag, max_k=None):
             worst_s = 0.0
             for (b, pv), s_ref in rec["scores"].items():
                 lo, hi = p.ref.cand_range(b, pv)
-                dabs, drel = U.check_scores(p.gpu.scores[p.gpu.rep_slot(b, pv)].cpu().numpy(), s_ref, lo, hi, f"{tag} L{l} step {t}")
+                dabs, drel = U.check_gpu_scores(p.gpu, b, pv, s_ref, lo, hi, f"{tag} L{l} step {t}")
                 worst_s = max(worst_s, drel)
                 for h in [pv] + sp.satellites(b, pv):
                     Tl = rec["topk"][(b, h)]

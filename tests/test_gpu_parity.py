@@ -560,7 +560,7 @@ def run_steps(p, sched, steps, side=None, tag="", stepper=None, append_seed=None
         same = True
         for (b, pv), s_ref in rec["scores"].items():
             lo, hi = p.ref.cand_range(b, pv)
-            dabs, _ = U.check_scores(p.gpu.scores[p.gpu.rep_slot(b, pv)].cpu().numpy(), s_ref, lo, hi, f"{tag} step {t}")
+            dabs, _ = U.check_gpu_scores(p.gpu, b, pv, s_ref, lo, hi, f"{tag} step {t}")
             for h in [pv] + sp.satellites(b, pv):
                 T = rec["topk"][(b, h)]
                 if U.check_set_valid(topk[b * sp.Hkv + h, :T.size], T, s_ref, U.band_of(dabs), f"{tag} step {t} head {h}"):
@@ -825,7 +825,7 @@ def test_config4_full_size_single_layer():
         nd = 0
         for (b, pv), s_ref in rec["scores"].items():
             lo, hi = w.spec.cand_range(b, pv)
-            dabs, _ = U.check_scores(p.gpu.scores[p.gpu.rep_slot(b, pv)].cpu().numpy(), s_ref, lo, hi, "cfg4")
+            dabs, _ = U.check_gpu_scores(p.gpu, b, pv, s_ref, lo, hi, "cfg4")
             for h in [pv] + w.spec.satellites(b, pv):
                 T = rec["topk"][(b, h)]
                 nd += U.check_set_valid(topk[b * 8 + h, :T.size], T, s_ref, U.band_of(dabs), f"cfg4 head {h}")
@@ -856,7 +856,7 @@ def test_config4_full_size_after_measuring_the_share_weights():
     worst, lerr = U.check_attention(p.gpu.out, p.gpu.lse, rec, "cfg4 tuned")
     for (b, pv), s_ref in rec["scores"].items():
         lo, hi = w.spec.cand_range(b, pv)
-        U.check_scores(p.gpu.scores[p.gpu.rep_slot(b, pv)].cpu().numpy(), s_ref, lo, hi, "cfg4 tuned")
+        U.check_gpu_scores(p.gpu, b, pv, s_ref, lo, hi, "cfg4 tuned")
     say(f"  err/rms {worst:.2e} lse {lerr:.1e}")
     p.close()
 
@@ -900,7 +900,7 @@ def test_config4_full_size_in_the_benchmark_launch_configuration():
             nd = 0
             for (b, pv), s_ref in rec["scores"].items():
                 lo, hi = w.spec.cand_range(b, pv)
-                dabs, _ = U.check_scores(p.gpu.scores[p.gpu.rep_slot(b, pv)].cpu().numpy(), s_ref, lo, hi, "cfg4")
+                dabs, _ = U.check_gpu_scores(p.gpu, b, pv, s_ref, lo, hi, "cfg4")
                 for h in [pv] + w.spec.satellites(b, pv):
                     T = rec["topk"][(b, h)]
                     nd += U.check_set_valid(topk[b * 8 + h, :T.size], T, s_ref, U.band_of(dabs), f"cfg4 head {h}")
@@ -1196,7 +1196,7 @@ def test_rescored_window_in_the_decode_step(W):
             topk = pr.gpu.topk_idx.cpu().numpy()
             for (b, pv), s_ref in rec["scores"].items():
                 lo, hi = pr.ref.cand_range(b, pv)
-                dabs, _ = U.check_scores(pr.gpu.scores[pr.gpu.rep_slot(b, pv)].cpu().numpy(), s_ref, lo, hi, f"L{l} t{t}")
+                dabs, _ = U.check_gpu_scores(pr.gpu, b, pv, s_ref, lo, hi, f"L{l} t{t}")
                 for h in [pv] + specs[l].satellites(b, pv):
                     T = rec["topk"][(b, h)]
                     if U.check_set_valid(topk[b * Hkv + h, :T.size], T, s_ref, U.band_of(dabs), f"L{l} t{t} head {h}"):

@@ -165,7 +165,7 @@ def test_random_stack_through_the_decode_step(seed):
             topk = pr.gpu.topk_idx.cpu().numpy()
             for (b, pv), s_ref in rec["scores"].items():
                 lo, hi = pr.ref.cand_range(b, pv)
-                dabs, _ = U.check_scores(pr.gpu.scores[pr.gpu.rep_slot(b, pv)].cpu().numpy(), s_ref, lo, hi, f"stack {seed} L{l} t{t}")
+                dabs, _ = U.check_gpu_scores(pr.gpu, b, pv, s_ref, lo, hi, f"stack {seed} L{l} t{t}")
                 for h in [pv] + sp.satellites(b, pv):
                     Tl = rec["topk"][(b, h)]
                     if U.check_set_valid(topk[b * Hkv + h, :Tl.size], Tl, s_ref, U.band_of(dabs), f"stack {seed} L{l} t{t} head {h}"):
