@@ -59,22 +59,23 @@ def test_random_layer(seed):
     use_prefill = rng.random() < 0.5
     side = torch.cuda.Stream() if rng.random() < 0.5 else None
     step_api = rng.random() < 0.4           # the layer's steps go through hc_decode_step instead of the three calls
+    margin = random.Random(77 + seed).choice([0.0, 1.25, 1.02, 4.0])      # the pivot-logit filter: off, usual, tight, loose
     T.say(f"random layer {seed}: B {spec.B} G {spec.G} Hkv {spec.Hkv} ctx {spec.ctx} W {spec.window} mode {spec.window_mode} "
-          f"agg {spec.agg} grow {grow} prefill {use_prefill} side {side is not None} decode_step {step_api}")
+          f"agg {spec.agg} grow {grow} prefill {use_prefill} side {side is not None} decode_step {step_api} filter {margin}")
     q0 = I.draw_q(spec, 5000 + seed)
     data = I.draw_layer(spec, q0, 6000 + seed, heavy_count=12)
     growth = steps + 1 if grow else 0
     if use_prefill:
-        p, _ = U.Pair.from_prefill(spec, data, q0.to(torch.bfloat16), rng.choice([1, 3, 7]), DEV, growth=growth)
+        p, _ = U.Pair.from_prefill(spec, data, q0.to(torch.bfloat16), rng.choice([1, 3, 7]), DEV, growth=growth, filter_margin=margin)
         assert p.slots_equal_oracle() and p.tier_equals_masters()
     else:
         # a third of these run on "8 or 16 compute units": few, long shares per workgroup, i.e. the weighted and
         # cost-charged split of the long passes, and rebalanced plans, at sizes the oracle still likes
         ctx = None
         if rng.random() < 0.35:
-            ctx = R.Context(R.make_config(spec, growth=growth), DEV)
+            ctx = R.Context(R.make_config(spec, growth=growth), DEV, filter_margin=margin)
             hc.hc_set_split(ctx.handle, 2, rng.choice([8, 16]))
-        p = U.Pair(spec, data, DEV, ctx=ctx, growth=growth)
+        p = U.Pair(spec, data, DEV, ctx=ctx, growth=growth, filter_margin=margin)
         p.own_ctx = True
     sched = I.QuerySchedule(q0, 7000 + seed, step_deg=rng.choice([3.0, 10.0, 30.0]))
     stepper = None
@@ -127,7 +128,7 @@ def test_random_stack_through_the_decode_step(seed):
     T.say(f"random stack {seed}: {n_layers} layers, B {first.B} G {first.G} Hkv {first.Hkv} ctx {first.ctx} W {first.window} "
           f"mode {first.window_mode} grow {grow} group {group} side {side is not None}")
     cfg = R.make_config(first, growth=growth, max_k=max(R.make_config(sp, growth=growth).max_k for sp in specs))
-    ctx = R.Context(cfg, DEV)
+    ctx = R.Context(cfg, DEV, filter_margin=random.Random(99 + seed).choice([0.0, 1.25, 1.02]))
     pairs, scheds = [], []
     for l, sp in enumerate(specs):
         q0 = I.draw_q(sp, 3100 + 10 * seed + l)
