@@ -59,7 +59,11 @@ def main():
     ap.add_argument("--share-weights", default="", help="16 comma-separated share weights [die*2+slot] (tuning)")
     ap.add_argument("--filter-margin", type=float, default=1.25, help="pivot-logit filter (hc_set_logit_filter): 0 = off, every "
                     "logit of a pivot is stored and scored; >= 1: only the rows that can reach a list, checked on the device")
-    ap.add_argument("--group", type=int, default=8, help="layers per cross-stream sync group in step mode")
+    ap.add_argument("--filter-min-candidates", type=int, default=65536, help="layers whose pivots all have fewer candidate positions "
+                    "than this do not filter (the filtered monitor costs more launches, which a short context does not earn back)")
+    ap.add_argument("--gather-shape", default="", help="workgroups,threads of the gather kernel (tuning; default 96,256)")
+    ap.add_argument("--group", type=int, default=0, help="layers per cross-stream sync group in step mode (0: a quarter of the "
+                    "stack, at most 8, so that the side work of all but the last group overlaps later groups' attention)")
     ap.add_argument("--serial", action="store_true", help="monitor and gather on the main stream (no overlap)")
     ap.add_argument("--attn-only", action="store_true", help="time hc_decode_attn alone (no monitor, no gather)")
     ap.add_argument("--oracle-seconds", type=float, default=12.0)
@@ -91,6 +95,8 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     L = args.layers or I.CONFIG_LAYERS[args.config]
+    if args.group == 0:
+        args.group = max(1, min(8, L // 4))
     K, W = args.steps, args.warmup
     T_total = W + 2 * K + 9           # warm-up, timed pass, kernel-timing pass, comparison pass
     t_setup = time.time()
@@ -115,11 +121,14 @@ def main():
             cfg = R.make_config(spec, growth=T_total if args.append else 0)
             if args.config == 5:
                 cfg.max_k = 4096 - 64 - 256          # the largest list any layer of this config can draw
-            ctx = R.Context(cfg, dev, workgroups_per_cu=args.wg_per_cu or None, filter_margin=args.filter_margin)
+            ctx = R.Context(cfg, dev, workgroups_per_cu=args.wg_per_cu or None, filter_margin=args.filter_margin,
+                            filter_min_candidates=args.filter_min_candidates)
             if args.share_weights:
                 hc.hc_set_share_weights(ctx.handle, [float(x) for x in args.share_weights.split(",")])
             if args.monitor_span:
                 hc.hc_set_monitor_span(ctx.handle, args.monitor_span)
+            if args.gather_shape:
+                hc.hc_set_gather_shape(ctx.handle, *[int(x) for x in args.gather_shape.split(",")])
         retrieved, base = I.initial_lists(spec)
         pre = None
         if args.prefill_init:

@@ -175,8 +175,11 @@ hc_status hc_set_monitor_span(hc_ctx* ctx, int32_t span);
  *   fell back, whose rows of both are dense as without the filter; the layer remembers the kv_arena of its last
  *   attention call (the fallback reads K from it) and keeps its own copy of the pivots' queries.  Only with
  *   HC_AGG_PROB; with HC_AGG_LOGIT, given scores, the window's re-scored queries and the prefill-time selection
- *   the plain passes run. */
-hc_status hc_set_logit_filter(hc_ctx* ctx, float margin);
+ *   the plain passes run.
+ *   min_candidates: only layers in which some pivot has at least this many candidate positions filter.  The filtered
+ *   monitor costs more launches per call (the stand-by passes are enqueued whether or not they find work), which a
+ *   short context does not earn back: measured on MI355X, filtering pays from about 64K candidates per pivot. */
+hc_status hc_set_logit_filter(hc_ctx* ctx, float margin, int32_t min_candidates);
 /* Per-pivot counters of the monitor since the layer was created, copied to host memory (synchronous):
  * counts4[0] decisions taken (windows tested), [1] retrievals triggered, [2] steps decided by the dense fallback of
  * the filter, [3] rows the filter kept at the last step (0xffffffff: the last step was not filtered). */
@@ -185,6 +188,12 @@ hc_status hc_layer_monitor_counts(const hc_layer* layer, int32_t b, int32_t h, u
  * kept_pos [num_reps][max_ctx] int32, the positions of the rows kept at the last step, ascending, the scores of
  * which are scores[p][0, n); fell_back [num_reps] int32, != 0 where the last step's check failed. */
 hc_status hc_layer_filter_view(const hc_layer* layer, const int32_t** kept_pos, const int32_t** fell_back);
+
+/* Tuning knob: launch shape of the gather kernel: at most `workgroups` workgroups (1..4096) of `threads` threads (64,
+ * 128 or 256); a workgroup has threads / 8 positions in flight.  Default 96 x 256.  What matters is how the host
+ * reads, which take microseconds each, are spread over the compute units: the attention pass's loads on a unit queue
+ * behind them. */
+hc_status hc_set_gather_shape(hc_ctx* ctx, int32_t workgroups, int32_t threads);
 
 /* Measurement hook: hands the library n pairs of hipEvent_t (host arrays of handles, copied).  The
  * next n launches of the split-pass kernel, from hc_decode_attn or hc_decode_step, attach pair i to

@@ -19,8 +19,7 @@ namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int ROWS_PER_PASS = 32;    // positions a workgroup has in flight: 8 per sub-pass, 4 sub-passes (96 workgroups keep 1.5 MB
-                                     // in flight, ten times what the host link's latency needs; more would cost registers, see below)
+constexpr int GATHER_PASSES = 4;     // host reads a lane has in flight; a workgroup of T threads has T / 32 * 4 positions in flight
 constexpr int GATHER_WORKGROUPS = 96; // workgroups of a gather launch, whatever the batch (measured at the 224K shape, batches
                                       // of 8 layers: 48 and fewer make the refill itself the bottleneck of the step, 128 and
                                       // more slow the attention pass that runs beside it; an untriggered call costs ~2 us)
@@ -159,9 +158,12 @@ __global__ __launch_bounds__(256, 8) void gather_kernel(GatherBatch B, int n_ite
     __shared__ int sm_start[MAX_GATHER_SATS + 1];
     __shared__ int sm_wsum[4];
     const int n_ent = n_items * max_sats;
+    const int nthr = blockDim.x;            // 64, 128 or 256
+    if (threadIdx.x < 4) sm_wsum[threadIdx.x] = 0;
+    __syncthreads();
     // counts -> exclusive prefix sums (entry e = item e / max_sats, satellite e % max_sats)
     int carry = 0;
-    for (int base = 0; base < n_ent; base += 256) {
+    for (int base = 0; base < n_ent; base += nthr) {
         const int e = base + threadIdx.x;
         int c = 0;
         if (e < n_ent) {
@@ -193,16 +195,17 @@ __global__ __launch_bounds__(256, 8) void gather_kernel(GatherBatch B, int n_ite
     if (total == 0) return;
     const int per = ((total + (int)gridDim.x - 1) / (int)gridDim.x + 7) & ~7;
     const int g_begin = blockIdx.x * per, g_end = min(total, g_begin + per);
-    const int sub = threadIdx.x >> 5;          // which of the 8 positions of a sub-pass
+    const int nsub = nthr >> 5;                // positions of a sub-pass
+    const int sub = threadIdx.x >> 5;          // which of them this half-wave moves
     const int l32 = threadIdx.x & 31;
     const int is_v = l32 >> 4;                 // lanes 16..31 move the V row
     const int chunk = l32 & 15;                // 16-byte chunk of the 256-byte row
-    for (int row_first = g_begin; row_first < g_end; row_first += ROWS_PER_PASS) {
-        u32x4 buf[ROWS_PER_PASS / 8];
-        u32x4* dst[ROWS_PER_PASS / 8];
+    for (int row_first = g_begin; row_first < g_end; row_first += nsub * GATHER_PASSES) {
+        u32x4 buf[GATHER_PASSES];
+        u32x4* dst[GATHER_PASSES];
 #pragma unroll
-        for (int p = 0; p < ROWS_PER_PASS / 8; ++p) {      // issue every host read first: they are latency-bound
-            const int g = row_first + p * 8 + sub;
+        for (int p = 0; p < GATHER_PASSES; ++p) {          // issue every host read first: they are latency-bound
+            const int g = row_first + p * nsub + sub;
             dst[p] = nullptr;
             if (g < g_end) {
                 int lo = 0, hi = n_ent;                    // the entry whose run holds row g
@@ -226,7 +229,7 @@ __global__ __launch_bounds__(256, 8) void gather_kernel(GatherBatch B, int n_ite
             }
         }
 #pragma unroll
-        for (int p = 0; p < ROWS_PER_PASS / 8; ++p)
+        for (int p = 0; p < GATHER_PASSES; ++p)
             if (dst[p]) *dst[p] = buf[p];
     }
 }
@@ -267,8 +270,9 @@ hc_status hc_launch_gather(hc_ctx* ctx, int n, const hc_gather_call* calls, hipS
     if (n * max_sats > MAX_GATHER_SATS) return hc_fail(ctx, HC_ESHAPE, "hc_gather: more than %d satellites in a batch", MAX_GATHER_SATS);
     long long rows_max = 0;
     for (int i = 0; i < n; ++i) rows_max += (long long)calls[i].L->n_sats * calls[i].L->max_r;
-    const int nwg = (int)std::max<long long>(1, std::min<long long>(GATHER_WORKGROUPS, (rows_max + ROWS_PER_PASS - 1) / ROWS_PER_PASS));
-    gather_kernel<<<dim3(nwg), dim3(256), 0, st>>>(B, n, max_sats, max_k);
+    const int thr = ctx->gather_threads, in_flight = thr / 32 * GATHER_PASSES;
+    const int nwg = (int)std::max<long long>(1, std::min<long long>(ctx->gather_workgroups, (rows_max + in_flight - 1) / in_flight));
+    gather_kernel<<<dim3(nwg), dim3(thr), 0, st>>>(B, n, max_sats, max_k);
     HC_HIP(ctx, hipGetLastError());
     return HC_OK;
 }

@@ -198,12 +198,23 @@ extern "C" hc_status hc_set_share_weights(hc_ctx* ctx, const float* weights16)
     return HC_OK;
 }
 
-extern "C" hc_status hc_set_logit_filter(hc_ctx* ctx, float margin)
+extern "C" hc_status hc_set_logit_filter(hc_ctx* ctx, float margin, int32_t min_candidates)
 {
     if (!ctx_ok(ctx)) return HC_ESTATE;
-    if (!(margin == 0.f || (margin >= 1.f && margin <= 1.0e6f)))
-        return hc_fail(ctx, HC_EINVAL, "hc_set_logit_filter: margin 0 (off) or 1 .. 1e6");
+    if (!(margin == 0.f || (margin >= 1.f && margin <= 1.0e6f)) || min_candidates < 0)
+        return hc_fail(ctx, HC_EINVAL, "hc_set_logit_filter: margin 0 (off) or 1 .. 1e6, min_candidates >= 0");
     ctx->filter_margin = margin;
+    ctx->filter_min_candidates = min_candidates;
+    return HC_OK;
+}
+
+extern "C" hc_status hc_set_gather_shape(hc_ctx* ctx, int32_t workgroups, int32_t threads)
+{
+    if (!ctx_ok(ctx)) return HC_ESTATE;
+    if (workgroups < 1 || workgroups > 4096 || (threads != 64 && threads != 128 && threads != 256))
+        return hc_fail(ctx, HC_EINVAL, "hc_set_gather_shape: 1..4096 workgroups of 64, 128 or 256 threads");
+    ctx->gather_workgroups = workgroups;
+    ctx->gather_threads = threads;
     return HC_OK;
 }
 
@@ -672,7 +683,9 @@ extern "C" hc_status hc_layer_create(hc_ctx* ctx, const hc_head_desc* hd, hc_lay
             hipMemset(L->mon_counts, 0, (size_t)L->n_reps * 4 * sizeof(uint32_t)) != hipSuccess)
             st = hc_fail(ctx, HC_ENOMEM, "monitor counters");
     }
-    if (st == HC_OK && ctx->filter_margin > 0.f && L->n_reps > 0 && L->blk_capacity < 2048) {
+    int widest = 0;                                  // the longest candidate range of any pivot of the layer
+    for (const RepDev& r : P.reps) widest = std::max(widest, r.hi - r.lo);
+    if (st == HC_OK && ctx->filter_margin > 0.f && L->n_reps > 0 && L->blk_capacity < 2048 && widest >= ctx->filter_min_candidates) {
         // the pivot-logit filter's buffers (a split pass of 2048 or more workgroups keeps the plain form)
         const size_t nr = (size_t)L->n_reps, mc = (size_t)ctx->cfg.max_ctx;
         hipError_t e = hipMalloc((void**)&L->filt, nr * sizeof(RepFilter));

@@ -98,7 +98,9 @@ struct hc_ctx {
     int wg_per_cu;
     unsigned long long* tune_stamps = nullptr;   // non-null only inside hc_layer_tune: per-workgroup start / rows-done times
     float share_weights[16];     // by die and dispatch slot, see hc_set_share_weights
+    int gather_workgroups = 96, gather_threads = 256;   // launch shape of the gather (hc_set_gather_shape)
     float filter_margin = 0.f;   // > 0: pivot logits are filtered (hc_set_logit_filter); layers created afterwards carry the buffers
+    int filter_min_candidates = 0;   // ... if one of their pivots has at least this many candidate positions
     int device;
     char err[512];
     std::vector<std::pair<hipEvent_t, hipEvent_t>> timing;   // optional timing hook: one pair per split-pass launch

@@ -439,7 +439,7 @@ __global__ __launch_bounds__(BLK) void mon_count(MonBatch B, int span, int G)
             float delta = 0.f;
             for (int g = 0; g < G; ++g) delta = fmaxf(delta, exp2f(f.ref[g] - it.lse[(size_t)rd.bh * G + g] * 1.4426950408889634f));
             const float bound = f.cutsum / (float)G * delta * 1.0001f;
-            if (!(key_score(tmin) >= bound)) it.need_w[rep] = 1;
+            if (!(key_score(tmin) >= bound)) it.need_w[rep] = 5;
         }
     }
     const float* srow = scores + (size_t)rep * ws.max_ctx;
@@ -549,6 +549,18 @@ __global__ __launch_bounds__(BLK, 8) void mon_write(MonBatch B, DriftCfg cfg, in
             uint32_t key[8], inmask;
             const int first8 = lo4 + chunk * HC_SEL_CHUNK + half * (HC_SEL_CHUNK / 2) + lane * 8;
             load_keys8(srow, first8, rd.lo, rd.hi, key, inmask);
+            // the positions of the lane's 8 rows: themselves, or (rows a filtering split pass kept) what the map says
+            int32_t jj[8];
+            if (pmap) {
+                int4 pa = make_int4(0, 0, 0, 0), pb = pa;
+                if (first8 < rd.hi) pa = *reinterpret_cast<const int4*>(pmap + first8);          // (row stride a multiple of 64: in bounds)
+                if (first8 + 4 < rd.hi) pb = *reinterpret_cast<const int4*>(pmap + first8 + 4);
+                jj[0] = pa.x; jj[1] = pa.y; jj[2] = pa.z; jj[3] = pa.w;
+                jj[4] = pb.x; jj[5] = pb.y; jj[6] = pb.z; jj[7] = pb.w;
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) jj[i] = first8 + i;
+            }
             for (int ks = 0; ks < rd.nk; ++ks) {
                 const uint32_t tau = w.sel[ks * 4 + 0], need = w.sel[ks * 4 + 1];
                 const int k = reps[rep].k[ks];               // (indexing the register copy would spill it)
@@ -578,6 +590,15 @@ __global__ __launch_bounds__(BLK, 8) void mon_write(MonBatch B, DriftCfg cfg, in
                     sm_carry[wv][ks][0] = eq_before + eq_tot;
                     sm_carry[wv][ks][1] = emitted + sel_tot;
                 }
+                if (ks == 0) {
+                    // |T ∩ baseline| of the monitored list (set size 0): the bitmap words of the selected rows, all
+                    // loads issued together (a row that is not selected reads word 0 and does not count)
+                    uint32_t wd[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) wd[i] = w.bitmap[((selmask >> i) & 1u) ? (jj[i] >> 5) : 0];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) hits += ((selmask >> i) & 1u) & (wd[i] >> (jj[i] & 31));
+                }
                 for (int o = rd.out_begin; o < rd.out_begin + rd.out_count; ++o) {      // the rows this list goes to
                     const OutDev od = outs[o];
                     if (od.kslot != ks) continue;
@@ -586,10 +607,8 @@ __global__ __launch_bounds__(BLK, 8) void mon_write(MonBatch B, DriftCfg cfg, in
 #pragma unroll
                     for (int i = 0; i < 8; ++i) {
                         if (selmask & (1u << i)) {
-                            const int j = pmap ? pmap[first8 + i] : first8 + i;      // the row's position
-                            if (pos < (uint32_t)k) dst[pos] = j;     // pos < k always holds; the guard keeps a corrupt state in bounds
+                            if (pos < (uint32_t)k) dst[pos] = jj[i];     // pos < k always holds; the guard keeps a corrupt state in bounds
                             ++pos;
-                            if (od.is_mon) hits += (w.bitmap[j >> 5] >> (j & 31)) & 1u;
                         }
                     }
                 }
@@ -775,7 +794,10 @@ __global__ __launch_bounds__(BLK) void mon_sparse_score(MonBatch B, int max_k, i
     const int n = carry;                                    // rows kept, all of them candidates
     int kmax = 0;
     for (int ks = 0; ks < rd.nk; ++ks) kmax = max(kmax, it.real_reps[rep].k[ks]);       // (indexing the register copy would spill it)
-    const bool bad = n > it.cap_rows || n < kmax || hd.part_count > MAX_FILTER_SEGS || sm_unknown != 0;
+    // why a pivot goes to the dense passes: 1 more rows kept than the launch was sized for, 2 fewer than the longest
+    // list needs, 3 a workgroup could not hold the rows it kept, 4 too many segments, (5: the check failed, below)
+    const int why = sm_unknown != 0 ? 3 : hd.part_count > MAX_FILTER_SEGS ? 4 : n > it.cap_rows ? 1 : n < kmax ? 2 : 0;
+    const bool bad = why != 0;
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         // the pivot as the later passes see it: a context of n rows, all of them candidates
         RepDev* v = it.vreps + rep;
@@ -787,7 +809,7 @@ __global__ __launch_bounds__(BLK) void mon_sparse_score(MonBatch B, int max_k, i
         v->nchunk = bad ? 0 : (n + HC_SEL_CHUNK - 1) / HC_SEL_CHUNK;
         v->out_begin = rd.out_begin;
         v->out_count = rd.out_count;
-        it.need_w[rep] = bad ? 1 : 0;
+        it.need_w[rep] = why;
     }
     if (bad) return;
     const int nchunk = (n + HC_SEL_CHUNK - 1) / HC_SEL_CHUNK;

@@ -62,7 +62,7 @@ class Context:
     """Owns an hc_ctx and the scratch that consecutive layers can share."""
 
     def __init__(self, cfg: hc.hc_config, device: str = "cuda:0", workgroups_per_cu: Optional[int] = None,
-                 filter_margin: float = 0.0):
+                 filter_margin: float = 0.0, filter_min_candidates: int = 0):
         self.cfg = cfg
         self.device = torch.device(device)
         with torch.cuda.device(self.device):
@@ -70,7 +70,7 @@ class Context:
         if workgroups_per_cu:
             hc.hc_set_split(self.handle, workgroups_per_cu)
         if filter_margin:
-            hc.hc_set_logit_filter(self.handle, filter_margin)
+            hc.hc_set_logit_filter(self.handle, filter_margin, filter_min_candidates)
         self.G = cfg.Hq // cfg.Hkv
         self._scratch: Dict[int, Tuple[torch.Tensor, torch.Tensor]] = {}
 
