@@ -57,12 +57,13 @@ def main():
     ap.add_argument("--monitor-span", type=int, default=0, help="1024-candidate chunks per workgroup of the selection passes (0: chosen per launch)")
     ap.add_argument("--tune-rounds", type=int, default=0, help="rounds of on-device measurement of the share weights on the first layer (0: built-in weights, as the parity tests use)")
     ap.add_argument("--share-weights", default="", help="16 comma-separated share weights [die*2+slot] (tuning)")
-    ap.add_argument("--filter-margin", type=float, default=1.25, help="pivot-logit filter (hc_set_logit_filter): 0 = off, every "
-                    "logit of a pivot is stored and scored; >= 1: only the rows that can reach a list, checked on the device")
+    ap.add_argument("--filter-margin", type=float, default=-1.0, help="pivot-logit filter (hc_set_logit_filter): 0 = off, every "
+                    "logit of a pivot is stored and scored; >= 1: only the rows that can reach a list, checked on the device; "
+                    "-1 (default): 1.25 for a single sequence, off for a batch (measured: see DESIGN.md)")
     ap.add_argument("--filter-min-candidates", type=int, default=65536, help="layers whose pivots all have fewer candidate positions "
                     "than this do not filter (the filtered monitor costs more launches, which a short context does not earn back)")
     ap.add_argument("--gather-shape", default="", help="workgroups,threads of the gather kernel (tuning; default 96,256)")
-    ap.add_argument("--group", type=int, default=0, help="layers per cross-stream sync group in step mode (0: a quarter of the "
+    ap.add_argument("--group", type=int, default=0, help="layers per cross-stream sync group in step mode (0: half of the "
                     "stack, at most 8, so that the side work of all but the last group overlaps later groups' attention)")
     ap.add_argument("--serial", action="store_true", help="monitor and gather on the main stream (no overlap)")
     ap.add_argument("--attn-only", action="store_true", help="time hc_decode_attn alone (no monitor, no gather)")
@@ -96,7 +97,7 @@ def main():
         del src, dst
     L = args.layers or I.CONFIG_LAYERS[args.config]
     if args.group == 0:
-        args.group = max(1, min(8, L // 4))
+        args.group = max(1, min(8, L // 2))
     K, W = args.steps, args.warmup
     T_total = W + 2 * K + 9           # warm-up, timed pass, kernel-timing pass, comparison pass
     t_setup = time.time()
@@ -118,6 +119,8 @@ def main():
         if args.window_mode >= 0:
             spec.window_mode = args.window_mode
         if ctx is None:
+            if args.filter_margin < 0:
+                args.filter_margin = 1.25 if spec.B == 1 else 0.0
             cfg = R.make_config(spec, growth=T_total if args.append else 0)
             if args.config == 5:
                 cfg.max_k = 4096 - 64 - 256          # the largest list any layer of this config can draw

@@ -417,7 +417,8 @@ hc_status hc_layer_set_window_slot(hc_layer* layer, int32_t slot);
 
 /* One decode step over a stack of layers (Algorithm 1, the body of the loop over t, for every layer):
  * for each layer in order, hc_decode_attn on main_stream, then hc_rep_topk_drift and hc_gather_retrieve
- * on side_stream (NULL = on main_stream, no overlap).  Layers are handled in groups of layers_per_group
+ * on side_stream (NULL = on main_stream, no overlap; a stack of at most layers_per_group layers is handled that way
+ * too, since a single group's side work has nothing to overlap).  Layers are handled in groups of layers_per_group
  * (1..HC_MAX_GROUP; 8 measured best at 32 layers of 224K): the group's appended tokens (k_new / v_new) in
  * one launch, the group's attentions, then one cross-stream event, then ONE batched monitor and ONE
  * batched gather for the whole group, which overlap the attention of the following groups; with

@@ -873,13 +873,15 @@ def test_config4_full_size_after_measuring_the_share_weights():
     p.close()
 
 
-def test_config4_full_size_in_the_benchmark_launch_configuration():
-    """Two full-size layers through hc_decode_step as bench.py launches it (groups of 8, monitor and gather
-    batched on a side stream, 7 chunks per monitor workgroup as a batch of 8 layers gets at this size),
-    2 steps, every output of both layers against the oracle."""
-    say("config 4 full size, decode step, 2 layers, 2 steps")
+@pytest.mark.parametrize("margin", [1.25, 0.0])
+def test_config4_full_size_in_the_benchmark_launch_configuration(margin):
+    """Two full-size layers through hc_decode_step as bench.py launches it (monitor and gather batched on a side
+    stream, 7 chunks per monitor workgroup as a batch of 8 layers gets at this size; with the pivot-logit filter
+    at the margin bench.py uses, and without it), 3 steps, every output of both layers against the oracle.
+    (Groups of 1 here: a two-layer stack that is one group would not use the side stream at all.)"""
+    say("config 4 full size, decode step, 2 layers, 3 steps, filter margin", margin)
     ws = [I.make_workload(4, layer=l, device=DEV) for l in range(2)]
-    ctx = R.Context(R.make_config(ws[0].spec), DEV)
+    ctx = R.Context(R.make_config(ws[0].spec), DEV, filter_margin=margin, filter_min_candidates=65536)
     hc.hc_set_monitor_span(ctx.handle, 7)
     pairs = [U.Pair(w.spec, w.data, DEV, ctx=ctx) for w in ws]
     for p in pairs:
@@ -888,10 +890,10 @@ def test_config4_full_size_in_the_benchmark_launch_configuration():
     q_cur = torch.zeros((2, 1, 32, 128), dtype=torch.bfloat16, device=DEV)
     io = R.make_step_io([p.gpu for p in pairs], q_cur)
     side = torch.cuda.Stream()
-    for t in range(2):
+    for t in range(3):
         qs = [w.schedule.next() for w in ws]
         q_cur.copy_(torch.stack([q.to(DEV) for q in qs]))
-        hc.hc_decode_step(ctx.handle, io, 2, None, side, 8)
+        hc.hc_decode_step(ctx.handle, io, 2, None, side, 1)
         torch.cuda.synchronize()
         for l, (p, w) in enumerate(zip(pairs, ws)):
             rec = p.ref.step(qs[l].cpu())
@@ -905,10 +907,14 @@ def test_config4_full_size_in_the_benchmark_launch_configuration():
                     T = rec["topk"][(b, h)]
                     nd += U.check_set_valid(topk[b * 8 + h, :T.size], T, s_ref, U.band_of(dabs), f"cfg4 head {h}")
                 assert int(p.gpu.flag[pv]) == rec["flag"][(b, pv)] or nd
-            say(f"  layer {l} step {t}: err/rms {worst:.2e} lse {lerr:.1e} set differences {nd} flags {rec['flag']}")
+            say(f"  layer {l} step {t}: err/rms {worst:.2e} lse {lerr:.1e} set differences {nd} flags {rec['flag']} "
+                f"counters {[p.gpu.monitor_counts(0, pv) for pv in (0, 1)]}")
             if nd:
                 resync(p, rec)
             assert p.slots_equal_oracle()
+    if margin:
+        kept = [p.gpu.monitor_counts(0, pv) for p in pairs for pv in (0, 1)]
+        assert all(c["fallbacks"] == 0 and c["kept"] is not None and c["kept"] < 40000 for c in kept), kept
     for p in pairs:
         p.close()
     ctx.close()
@@ -1186,7 +1192,7 @@ def test_rescored_window_in_the_decode_step(W):
             k_cur[l].copy_(toks[l][0])
             v_cur[l].copy_(toks[l][1])
             pairs[l].ref.append(*toks[l])
-        hc.hc_decode_step(ctx.handle, io, 2, None, side, 2)
+        hc.hc_decode_step(ctx.handle, io, 2, None, side, 1)
         q_cur.zero_()                       # the caller may reuse q at once: the window buffer has its own copy
         torch.cuda.synchronize()
         for l, pr in enumerate(pairs):
