@@ -1271,17 +1271,45 @@ extern "C" hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* io, int32_t 
         }
         if (st != HC_OK) return st;
     }
-    hipEvent_t last_waited = nullptr;
-    for (int g0 = 0; g0 < n_layers; g0 += layers_per_group) {
-        const int g1 = std::min(n_layers, g0 + layers_per_group);
+    // The side work of a group is handed to the GPU only after the attention of the NEXT group has been: the
+    // main stream then never waits for the host to get through a side chain's launches (which matters when the
+    // host is slow, e.g. under a tracer), and the side chain loses nothing, since it overlaps that attention.
+    struct SideWork {
         hc_monitor_call mon[HC_MAX_GROUP];
         hc_gather_call gat[HC_MAX_GROUP];
-        int n_mon = 0, n_gat = 0;
+        RescoreJob test_job[HC_MAX_GROUP];
+        int n_mon = 0, n_gat = 0, n_test = 0;
+        hc_layer* Lg = nullptr;                 // the group's events live in its last layer
+    };
+    SideWork work[2];
+    auto launch_side = [&](SideWork& w) -> hc_status {
+        if (w.n_mon == 0) return HC_OK;
+        hipStream_t run = ss ? ss : ms;
+        if (ss) HC_HIP(ctx, hipStreamWaitEvent(ss, w.Lg->ev_attn, 0));
+        hc_status st = HC_OK;
+        if (w.n_test > 0) st = rescore_passes(ctx, w.n_test, w.test_job, run);       // test step of a re-scored window: the earlier queries first
+        if (st == HC_OK) st = hc_launch_monitor(ctx, w.n_mon, w.mon, 0, run);
+        if (st == HC_OK && w.n_gat > 0) st = hc_launch_gather(ctx, w.n_gat, w.gat, run);
+        if (ss) {
+            // recorded even after a failed launch, so that no later call waits on a stale event
+            const hipError_t e = hipEventRecord(w.Lg->ev_side, ss);
+            for (int i = 0; i < w.n_mon; ++i) const_cast<hc_layer*>(w.mon[i].L)->pending_ev = w.Lg->ev_side;
+            if (st == HC_OK) HC_HIP(ctx, e);
+        }
+        w.n_mon = 0;
+        return st;
+    };
+    hipEvent_t last_waited = nullptr;
+    int cur = 0;
+    hc_status result = HC_OK;
+    for (int g0 = 0; g0 < n_layers && result == HC_OK; g0 += layers_per_group) {
+        const int g1 = std::min(n_layers, g0 + layers_per_group);
+        SideWork& w = work[cur];
+        w.n_mon = w.n_gat = w.n_test = 0;
         const void* push_src[HC_MAX_GROUP];
         void* push_dst[HC_MAX_GROUP];
         hc_layer* push_layer[HC_MAX_GROUP];
-        RescoreJob test_job[HC_MAX_GROUP];
-        int n_push = 0, n_test = 0;
+        int n_push = 0;
         // the tokens of the group's layers enter their caches with one launch, ahead of the group's attention
         hc_append_call app[HC_MAX_GROUP];
         int n_app = 0;
@@ -1289,65 +1317,61 @@ extern "C" hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* io, int32_t 
             const hc_layer_io& x = io[l];
             hc_layer* L = x.layer;
             if (L->pending_ev) {
-                if (L->pending_ev != last_waited) HC_HIP(ctx, hipStreamWaitEvent(ms, L->pending_ev, 0));
+                if (L->pending_ev != last_waited) {
+                    const hipError_t e = hipStreamWaitEvent(ms, L->pending_ev, 0);
+                    if (e != hipSuccess) result = hc_fail(ctx, HC_EHIP, "hc_decode_step: hipStreamWaitEvent: %s", hipGetErrorString(e));
+                }
                 last_waited = L->pending_ev;
                 L->pending_ev = nullptr;
             }
             if (x.k_new || x.v_new)
                 app[n_app++] = hc_append_call{L, x.k_new, x.v_new, const_cast<void*>(x.kv_arena), const_cast<void*>(x.host_tier)};
         }
-        if (n_app > 0) {
-            hc_status sa = hc_launch_append(ctx, n_app, app, ms);
-            for (int i = 0; i < n_app && sa == HC_OK; ++i) sa = append_done(ctx, const_cast<hc_layer*>(app[i].L), ms);
-            if (sa != HC_OK) return sa;
+        if (result == HC_OK && n_app > 0) {
+            result = hc_launch_append(ctx, n_app, app, ms);
+            for (int i = 0; i < n_app && result == HC_OK; ++i) result = append_done(ctx, const_cast<hc_layer*>(app[i].L), ms);
         }
-        for (int l = g0; l < g1; ++l) {
+        for (int l = g0; l < g1 && result == HC_OK; ++l) {
             const hc_layer_io& x = io[l];
             hc_layer* L = x.layer;
             const bool side = L->n_reps > 0 && x.scores != nullptr;
             if (side) {
-                mon[n_mon] = hc_monitor_call{L, x.rep_logits, x.lse, x.scores, x.topk_idx, x.base_idx, x.ring, x.inter, x.flag};
-                mon[n_mon++].arena = x.kv_arena;
+                w.mon[w.n_mon] = hc_monitor_call{L, x.rep_logits, x.lse, x.scores, x.topk_idx, x.base_idx, x.ring, x.inter, x.flag};
+                w.mon[w.n_mon++].arena = x.kv_arena;
                 L->last_arena = x.kv_arena;
                 if (rescored) {
                     push_src[n_push] = x.q;
                     push_layer[n_push] = L;
                     push_dst[n_push++] = (char*)x.q_window + (size_t)L->window_slot * ctx->cfg.B * ctx->cfg.Hq * HC_D * 2;
                     if (L->window_slot == ctx->cfg.window - 1)
-                        test_job[n_test++] = RescoreJob{L, x.kv_arena, x.q_window, x.base_idx, x.ring, x.rescore_work};
+                        w.test_job[w.n_test++] = RescoreJob{L, x.kv_arena, x.q_window, x.base_idx, x.ring, x.rescore_work};
                 }
                 if (x.host_tier && L->n_sats > 0)
-                    gat[n_gat++] = hc_gather_call{L, x.host_tier, x.topk_idx, x.flag, const_cast<void*>(x.kv_arena), x.slot_pos};
+                    w.gat[w.n_gat++] = hc_gather_call{L, x.host_tier, x.topk_idx, x.flag, const_cast<void*>(x.kv_arena), x.slot_pos};
             }
-            const hc_status st = hc_launch_attn(ctx, L, x.kv_arena, x.q, x.out, x.lse, side ? x.rep_logits : nullptr, ms);
-            if (st != HC_OK) return st;
+            result = hc_launch_attn(ctx, L, x.kv_arena, x.q, x.out, x.lse, side ? x.rep_logits : nullptr, ms);
         }
-        if (n_mon == 0) continue;
         // The queries go into the window buffers on the main stream: the caller may overwrite q as soon
         // as this call returns, in main-stream order, while the side stream may still be behind.  A layer's
         // count of steps inside its window moves on once its query is in the buffer.
-        if (n_push > 0) {
-            const hc_status sp = hc_launch_rescore_push(ctx, n_push, push_src, push_dst, ms);
-            if (sp != HC_OK) return sp;
-            for (int i = 0; i < n_push; ++i) push_layer[i]->window_slot = (push_layer[i]->window_slot + 1) % ctx->cfg.window;
+        if (result == HC_OK && n_push > 0) {
+            result = hc_launch_rescore_push(ctx, n_push, push_src, push_dst, ms);
+            if (result == HC_OK)
+                for (int i = 0; i < n_push; ++i) push_layer[i]->window_slot = (push_layer[i]->window_slot + 1) % ctx->cfg.window;
         }
-        hc_layer* Lg = io[g1 - 1].layer;          // the group's events live in its last layer
-        hipStream_t run = ss ? ss : ms;
-        if (ss) {
-            HC_HIP(ctx, hipEventRecord(Lg->ev_attn, ms));
-            HC_HIP(ctx, hipStreamWaitEvent(ss, Lg->ev_attn, 0));
+        if (result != HC_OK) w.n_mon = 0;              // this group's side work is dropped; the previous group's still goes out
+        if (w.n_mon > 0) {
+            w.Lg = io[g1 - 1].layer;
+            if (ss) {
+                const hipError_t e = hipEventRecord(w.Lg->ev_attn, ms);
+                if (e != hipSuccess) { result = hc_fail(ctx, HC_EHIP, "hc_decode_step: hipEventRecord: %s", hipGetErrorString(e)); w.n_mon = 0; }
+            }
         }
-        hc_status st = HC_OK;
-        if (n_test > 0) st = rescore_passes(ctx, n_test, test_job, run);       // test step of a re-scored window: the earlier queries first
-        if (st == HC_OK) st = hc_launch_monitor(ctx, n_mon, mon, 0, run);
-        if (st == HC_OK && n_gat > 0) st = hc_launch_gather(ctx, n_gat, gat, run);
-        if (ss) {
-            // recorded even after a failed launch, so that no later call waits on a stale event
-            const hipError_t e = hipEventRecord(Lg->ev_side, ss);
-            for (int i = 0; i < n_mon; ++i) const_cast<hc_layer*>(mon[i].L)->pending_ev = Lg->ev_side;
-            if (st == HC_OK) HC_HIP(ctx, e);
-        }
-        if (st != HC_OK) return st;
+        const hc_status sp = launch_side(work[cur ^ 1]);
+        if (result == HC_OK) result = sp;
+        cur ^= 1;
     }
-    return HC_OK;
+    const hc_status sl = launch_side(work[cur ^ 1]);
+    if (result == HC_OK) result = sl;
+    return result;
 }
