@@ -28,8 +28,8 @@ METRIC = "µs per decode step per layer + achieved HBM GB/s at 224K context, 1 G
 HBM_PEAK_GBPS = 8000.0
 # HBM traffic of one launch of the split kernel (bytes), from the hardware counters FETCH_SIZE and
 # WRITE_SIZE of profiler runs of this script, scaled by what the same counters read for the streaming
-# kernel of --calibrate-copy; keyed by (config, dense).  The runs and factors are in profiles/.
-MEASURED_TRAFFIC = {(4, False): 254641233}
+# kernel of --calibrate-copy; keyed by (config, dense, pivot-logit filter on).  The runs and factors are in profiles/.
+MEASURED_TRAFFIC = {(4, False, True): 249558272, (4, False, False): 254641233}
 
 
 def main():
@@ -528,7 +528,7 @@ def main():
         "step_GBps": kv_bytes * L / (ms_per_step * 1e-3) / 1e9,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": MEASURED_TRAFFIC.get((args.config, args.dense)) if not args.ctx else None,
+                     "traffic": MEASURED_TRAFFIC.get((args.config, args.dense, args.filter_margin > 0)) if not args.ctx else None,
                      "kernel": "attn_split_kernel", "kernel_us_mean": kern_us,
                      "kernel_us_median": float(np.median(kern_ms) * 1e3), "kernel_us_p95": float(np.percentile(kern_ms, 95) * 1e3),
                      "launches_timed": n_pairs,
