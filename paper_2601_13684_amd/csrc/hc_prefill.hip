@@ -16,6 +16,8 @@
 
 namespace {
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 constexpr int PF_BLK = 256;
 constexpr int PF_CHUNK = 1024;       // positions per workgroup of the score kernel
 
@@ -85,8 +87,11 @@ __global__ __launch_bounds__(PF_BLK) void prefill_score_kernel(const RepDev* __r
 }
 
 // Slot i of a compressed head holds: i < sink: position i; then the last `recent` positions in order; then
-// the selected positions in ascending order.  A full head holds all of its positions.  One 16-byte piece
-// per thread; a row (K then V) is 32 consecutive pieces.
+// the selected positions in ascending order.  A full head holds all of its positions.  A workgroup takes
+// tiles of 32 slots (1024 16-byte pieces; a row, K then V, is 32 consecutive pieces), tile x, x + gridDim.x,
+// ... of its head; a thread moves four pieces of a tile, all four loads issued before the first store, so
+// that a long head's copy has 16 KB per workgroup in flight.  Source rows are read once and destination
+// rows are not read again by this call: streaming loads and stores.
 __global__ __launch_bounds__(PF_BLK) void prefill_place_kernel(const HeadDev* __restrict__ heads, const PreSrc* __restrict__ src,
                                                                const RepDev* __restrict__ reps, const int32_t* __restrict__ rep_slot_of,
                                                                const uint4* __restrict__ kv_prefill, uint4* __restrict__ arena,
@@ -100,19 +105,28 @@ __global__ __launch_bounds__(PF_BLK) void prefill_place_kernel(const HeadDev* __
     const int32_t* list = topk_idx + (size_t)bh * max_k;
     const int fixed = hd.sink + hd.recent;
     const bool full = hd.role == HC_ROLE_FULL;
-    const long long pieces = (long long)hd.len * 32;
-    for (long long idx = (long long)blockIdx.x * PF_BLK + threadIdx.x; idx < pieces; idx += (long long)gridDim.x * PF_BLK) {
-        const int slot = (int)(idx >> 5), piece = (int)(idx & 31);
-        int pos = slot;
-        if (!full) {
-            if (slot >= fixed) pos = list[slot - fixed];
-            else if (slot >= hd.sink) pos = hd.ctx - hd.recent + (slot - hd.sink);
-            pos = min(max(pos, 0), hd.ctx - 1);               // a corrupt list cannot lead outside the head's rows
+    const int tiles = (hd.len + 31) / 32;
+    const int piece = threadIdx.x & 31, row_in = threadIdx.x >> 5;        // 8 rows per quarter of a tile
+    const bool isv = piece >= 16;
+    const size_t from0 = (size_t)(isv ? s.v_off : s.k_off) / 8 + (piece & 15);
+    const size_t to0 = (size_t)(isv ? hd.v_off : hd.k_off) / 8 + (piece & 15);
+    for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+        u32x4 v[4];
+        int slot[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            slot[u] = tile * 32 + u * 8 + row_in;
+            int pos = slot[u];
+            if (!full && slot[u] < hd.len) {
+                if (slot[u] >= fixed) pos = list[slot[u] - fixed];
+                else if (slot[u] >= hd.sink) pos = hd.ctx - hd.recent + (slot[u] - hd.sink);
+                pos = min(max(pos, 0), hd.ctx - 1);               // a corrupt list cannot lead outside the head's rows
+            }
+            if (slot[u] < hd.len) v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kv_prefill) + from0 + (size_t)pos * 16);
         }
-        const bool isv = piece >= 16;
-        const size_t from = (size_t)(isv ? s.v_off : s.k_off) / 8 + (size_t)pos * 16 + (piece & 15);
-        const size_t to = (size_t)(isv ? hd.v_off : hd.k_off) / 8 + (size_t)slot * 16 + (piece & 15);
-        arena[to] = kv_prefill[from];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (slot[u] < hd.len) __builtin_nontemporal_store(v[u], reinterpret_cast<u32x4*>(arena) + to0 + (size_t)slot[u] * 16);
     }
     if (blockIdx.x != 0) return;
     // tables: the ring starts empty; a satellite's slot map names what its retrieved slots hold; a pivot's
@@ -194,8 +208,11 @@ hc_status hc_launch_prefill_place(hc_ctx* ctx, const hc_layer* L, const void* kv
         max_len = std::max(max_len, (int)h.len);
         max_ctx = std::max(max_ctx, (int)h.ctx);
     }
-    // enough workgroups per head to fill the chip over all heads, each with at least 8 rows
-    const int per_head = std::max(1, std::min((max_len * 32 + PF_BLK * 8 - 1) / (PF_BLK * 8), std::max(1, 8 * ctx->n_cu / L->n_heads)));
+    // Workgroups per head: the longest head's tiles of 32 rows, four to a workgroup (at most 2048); the
+    // workgroups of a shorter head beyond its tiles exit at once.  Heads differ in length by up to the ratio of
+    // context to budget, so a share per head by count would leave the chip to the few long heads' workgroups.
+    const int max_tiles = (max_len + 31) / 32;
+    const int per_head = std::max(1, std::min((max_tiles + 3) / 4, 2048));
     prefill_place_kernel<<<dim3(per_head, L->n_heads), dim3(PF_BLK), 0, st>>>(L->heads, L->pre_src, L->reps, L->rep_slot_dev,
                                                                                (const uint4*)kv_prefill, (uint4*)arena, topk_idx, base_idx,
                                                                                slot_pos, ring, c.max_k, c.window);
