@@ -59,7 +59,7 @@ def main():
     ap.add_argument("--share-weights", default="", help="16 comma-separated share weights [die*2+slot] (tuning)")
     ap.add_argument("--filter-margin", type=float, default=-1.0, help="pivot-logit filter (hc_set_logit_filter): 0 = off, every "
                     "logit of a pivot is stored and scored; >= 1: only the rows that can reach a list, checked on the device; "
-                    "-1 (default): 1.25 for a single sequence, off for a batch, where it measured slower")
+                    "-1 (default): 1.25")
     ap.add_argument("--filter-min-candidates", type=int, default=65536, help="layers whose pivots all have fewer candidate positions "
                     "than this do not filter (the filtered monitor costs more launches, which a short context does not earn back)")
     ap.add_argument("--gather-shape", default="", help="workgroups,threads of the gather kernel (tuning; default 96,256)")
@@ -120,7 +120,7 @@ def main():
             spec.window_mode = args.window_mode
         if ctx is None:
             if args.filter_margin < 0:
-                args.filter_margin = 1.25 if spec.B == 1 else 0.0
+                args.filter_margin = 1.25
             cfg = R.make_config(spec, growth=T_total if args.append else 0)
             if args.config == 5:
                 cfg.max_k = 4096 - 64 - 256          # the largest list any layer of this config can draw

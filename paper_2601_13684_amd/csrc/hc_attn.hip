@@ -143,17 +143,21 @@ __device__ __forceinline__ void qk(const uint32_t (&qreg)[G][8], const Tile& t, 
 // the reduction.  They go to a staging buffer in LDS first (stash points at the row's G floats there) and
 // reach memory in long contiguous runs: 128-byte stores scattered through a pass that streams reads at
 // full rate cost several times their share of the traffic.
+constexpr uint32_t DROPPED = 0xffffffffu;   // first logit of a staged row that the filter dropped (see row_step)
+
 template <int G>
-__device__ __forceinline__ void stash_rep(float* stash, const float (&s)[G], int c, bool valid)
+__device__ __forceinline__ void stash_rep(float* stash, const float (&s)[G], int c, bool valid, bool dropped = false)
 {
     if (c != 0 || !valid) return;
+    const float first = dropped ? __uint_as_float(DROPPED) : s[0] * INV_SQRT_D;
     if (G == 1) {
-        stash[0] = s[0] * INV_SQRT_D;
+        stash[0] = first;
     } else if (G == 2) {
-        *reinterpret_cast<float2*>(stash) = make_float2(s[0] * INV_SQRT_D, s[1] * INV_SQRT_D);
+        *reinterpret_cast<float2*>(stash) = make_float2(first, s[1] * INV_SQRT_D);
     } else {
+        reinterpret_cast<float4*>(stash)[0] = make_float4(first, s[1] * INV_SQRT_D, s[2] * INV_SQRT_D, s[3] * INV_SQRT_D);
 #pragma unroll
-        for (int q = 0; q < G / 4; ++q)
+        for (int q = 1; q < G / 4; ++q)
             reinterpret_cast<float4*>(stash)[q] = make_float4(s[4 * q] * INV_SQRT_D, s[4 * q + 1] * INV_SQRT_D,
                                                               s[4 * q + 2] * INV_SQRT_D, s[4 * q + 3] * INV_SQRT_D);
     }
@@ -251,23 +255,16 @@ __device__ __forceinline__ float pv(WaveState<G>& st, const float (&x)[G], const
     return est;
 }
 
-// Filtered pivot logits: a wave appends the rows it keeps, in the order it meets them (ascending positions), to
-// a list of its own in LDS; the workgroup merges its four lists once, at the end of the segment.
-template <int G>
-struct KeepList {
-    float* logits;      // [CAPW][G] in LDS, or nullptr: this segment keeps nothing (not a pivot, or no logits wanted)
-    int32_t* pos;       // [CAPW]
-    int count;          // rows kept so far (wave-uniform); beyond the capacity the rows are only counted
-};
-constexpr int KEEP_WAVE_FLOATS = 2048;                                       // LDS floats of one wave's list
-template <int G> struct KeepCap { static constexpr int N = (KEEP_WAVE_FLOATS / (G + 1)) & ~3; };
+// Filtered pivot logits: every row of a pivot is staged in LDS like the dense logits are, but a row the filter
+// drops gets the bit pattern DROPPED as its first logit (no sum of products of bf16 inputs has it: a NaN that
+// comes out of arithmetic on them keeps the zero low half of their payload or is the canonical one), and at the
+// end of a chunk the workgroup writes only the rows it kept.
 
-// One row step: logits, (pivot) logit stash, reference check, accumulate.  With the filter on (FILT) the rows that are
-// candidate positions and whose statistic reaches the filter's cut are appended to `kl` instead (`pos`: the position of
-// the lane's row).
+// One row step: logits, (pivot) logit stash, reference check, accumulate.  With the filter on (FILT) a staged row
+// whose statistic misses the filter's cut is marked as dropped.
 template <int G, bool FILT>
 __device__ __forceinline__ void row_step(WaveState<G>& st, const uint32_t (&qreg)[G][8], const Tile& t, float* stash,
-                                         int c, bool valid, FilterCtx<G>& fc, KeepList<G>& kl, int pos)
+                                         int c, bool valid, FilterCtx<G>& fc)
 {
     float s[G], x[G], alpha[G];
     qk<G>(qreg, t, s);
@@ -279,21 +276,10 @@ __device__ __forceinline__ void row_step(WaveState<G>& st, const uint32_t (&qreg
 #pragma unroll
     for (int g = 0; g < G; ++g) scale_if(over, alpha[g], st.Z[g], st.acc[g]);
     const float est = pv<G, FILT>(st, x, t, fc);
-    if (FILT && kl.logits) {
+    if (FILT && stash) {
         // (not "est >= cutsum": a statistic that is not a number, 0 * inf after an extreme move of the reference,
         // keeps its row)
-        uint64_t m = __builtin_amdgcn_ballot_w64(valid && c == 0 && !(est < fc.cutsum));     // bits 0, 8, ..., 56: the wave's 8 rows, ascending
-        if (m) {                                                           // most row steps keep nothing
-            const bool keep = valid && c == 0 && !(est < fc.cutsum) && pos >= fc.lo && pos < fc.hi;       // candidate positions only
-            m = __builtin_amdgcn_ballot_w64(keep);
-            const int n = __builtin_popcountll(m);
-            if (keep && kl.count + n <= KeepCap<G>::N) {
-                const int idx = kl.count + __builtin_popcountll(m & ((1ull << (threadIdx.x & 63)) - 1ull));
-                kl.pos[idx] = pos;
-                stash_rep<G>(kl.logits + (size_t)idx * G, s, 0, true);
-            }
-            kl.count += n;
-        }
+        stash_rep<G>(stash, s, c, valid, est < fc.cutsum);
     }
 }
 
@@ -308,14 +294,16 @@ constexpr int REP_STASH_FLOATS = 4096;   // one staging buffer: 16 KB, i.e. 1024
 // REP_STASH_FLOATS / G positions: the waves stash their logits in LDS, and at the end of a chunk the workgroup
 // writes the chunk's logits to memory as one contiguous run.  Two staging buffers alternate, so one barrier per
 // chunk is enough; the number of chunks depends only on the segment, so every wave reaches every barrier.  The
-// register pipeline of loads runs on across chunk boundaries.  With the filter (FILT) there are no chunks and no
-// barriers: the kept rows go to the wave's list `kl`.
+// register pipeline of loads runs on across chunk boundaries.  With the filter (FILT) the chunk's kept rows, in
+// position order, are appended to rows row_begin, row_begin + 1, ... of the pivot's block of rep_logits (a segment
+// never keeps more rows than it has) and their positions to the same entries of kept_pos; the number of rows the
+// segment kept is returned (the same in every thread).
 template <int G, bool FILT>
-__device__ __forceinline__ void process_rows(WaveState<G>& st, const uint32_t (&qreg)[G][8],
-                                             const char* __restrict__ Kb, const char* __restrict__ Vb,
-                                             float* __restrict__ rep_base, FilterCtx<G>& fc, KeepList<G>& kl,
-                                             float (&stash)[2][REP_STASH_FLOATS],
-                                             int row_begin, int row_end, int w, int r, int c)
+__device__ __forceinline__ int process_rows(WaveState<G>& st, const uint32_t (&qreg)[G][8],
+                                            const char* __restrict__ Kb, const char* __restrict__ Vb,
+                                            float* __restrict__ rep_base, FilterCtx<G>& fc, int32_t* __restrict__ kept_pos,
+                                            float (&stash)[2][REP_STASH_FLOATS], int (&sm_cnt)[4],
+                                            int row_begin, int row_end, int w, int r, int c)
 {
     constexpr int CAP = REP_STASH_FLOATS / G;      // positions per chunk
     constexpr int STEPS = CAP / 32;                // row steps of one wave per chunk
@@ -324,7 +312,8 @@ __device__ __forceinline__ void process_rows(WaveState<G>& st, const uint32_t (&
     const int wave_row0 = row_begin + 8 * w;
     const int nfull = wave_row0 + 8 <= row_end ? (row_end - 8 - wave_row0) / 32 + 1 : 0;   // unmasked row steps
     uint32_t off = (uint32_t)(wave_row0 + r) * 256u + (uint32_t)c * 16u;                   // the lane's first chunk of its row
-    const bool dense = !FILT && rep_base != nullptr;
+    const bool dense = rep_base != nullptr;
+    int seg_kept = 0;
     const int nchunk = dense ? (row_end - row_begin + CAP - 1) / CAP : 1;
     Tile A, B;
     int i = 0;
@@ -334,19 +323,17 @@ __device__ __forceinline__ void process_rows(WaveState<G>& st, const uint32_t (&
         const bool last = ch == nchunk - 1;
         const int i_hi = last ? nfull : (ch + 1) * STEPS;          // a chunk before the last holds full row steps only
         float* sp = dense ? &stash[ch & 1][(8 * w + r) * G] : nullptr;
-        int pos = wave_row0 + 32 * i + r;
 #pragma unroll 1
         for (; i + 2 <= i_hi; i += 2, off += 2 * STEP) {
             load_tile(B, Kb, Vb, off + STEP);
-            row_step<G, FILT>(st, qreg, A, sp, c, true, fc, kl, pos);
+            row_step<G, FILT>(st, qreg, A, sp, c, true, fc);
             if (i + 2 < nfull) load_tile(A, Kb, Vb, off + 2 * STEP);
-            row_step<G, FILT>(st, qreg, B, sp ? sp + 32 * G : nullptr, c, true, fc, kl, pos + 32);
+            row_step<G, FILT>(st, qreg, B, sp ? sp + 32 * G : nullptr, c, true, fc);
             if (sp) sp += 64 * G;
-            pos += 64;
         }
         if (last) {
             if (i < nfull) {
-                row_step<G, FILT>(st, qreg, A, sp, c, true, fc, kl, pos);
+                row_step<G, FILT>(st, qreg, A, sp, c, true, fc);
                 if (sp) sp += 32 * G;
                 ++i;
             }
@@ -354,10 +341,57 @@ __device__ __forceinline__ void process_rows(WaveState<G>& st, const uint32_t (&
             if (row - r < row_end) {
                 const bool valid = row < row_end;
                 load_tile(A, Kb, Vb, (uint32_t)(valid ? row : row_end - 1) * 256u + (uint32_t)c * 16u);
-                row_step<G, FILT>(st, qreg, A, sp, c, valid, fc, kl, row);
+                row_step<G, FILT>(st, qreg, A, sp, c, valid, fc);
             }
         }
-        if (dense) {
+        if (dense && FILT) {
+            // Every wave takes a quarter of the chunk's positions, 64 at a time in position order: first it counts the
+            // rows it will keep (candidate positions that are not marked), then, knowing the other waves' counts, it
+            // writes them.
+            __syncthreads();
+            const int first = row_begin + ch * CAP;
+            const int n = row_end - first < CAP ? row_end - first : CAP;
+            const float* src = stash[ch & 1];
+            const int lane = 8 * r + c;
+            constexpr int Q = CAP / 4, ROUNDS = Q / 64;
+            static_assert(Q % 64 == 0, "a wave's quarter of a chunk is whole rounds of 64 positions");
+            int mine = 0;
+#pragma unroll 1
+            for (int rd = 0; rd < ROUNDS; ++rd) {
+                const int j = w * Q + rd * 64 + lane;
+                if (j - lane >= n) break;
+                const bool keep = j < n && first + j >= fc.lo && first + j < fc.hi && __float_as_uint(src[(size_t)j * G]) != DROPPED;
+                mine += __builtin_popcountll(__builtin_amdgcn_ballot_w64(keep));
+            }
+            if (lane == 0) sm_cnt[w] = mine;
+            __syncthreads();
+            const int c0 = sm_cnt[0], c1 = sm_cnt[1], c2 = sm_cnt[2], c3 = sm_cnt[3];
+            int at = row_begin + seg_kept + (w > 0 ? c0 : 0) + (w > 1 ? c1 : 0) + (w > 2 ? c2 : 0);
+            seg_kept += c0 + c1 + c2 + c3;
+            if (mine > 0) {
+#pragma unroll 1
+                for (int rd = 0; rd < ROUNDS; ++rd) {
+                    const int j = w * Q + rd * 64 + lane;
+                    if (j - lane >= n) break;
+                    const bool keep = j < n && first + j >= fc.lo && first + j < fc.hi && __float_as_uint(src[(size_t)j * G]) != DROPPED;
+                    const uint64_t m = __builtin_amdgcn_ballot_w64(keep);
+                    if (keep) {
+                        const int idx = at + __builtin_popcountll(m & ((1ull << lane) - 1ull));
+                        const float* e_l = src + (size_t)j * G;
+                        float* d = rep_base + (size_t)idx * G;
+                        typedef float f4v __attribute__((ext_vector_type(4)));
+                        if (G == 1) d[0] = e_l[0];
+                        else if (G == 2) *reinterpret_cast<float2*>(d) = *reinterpret_cast<const float2*>(e_l);
+                        else {
+#pragma unroll
+                            for (int q4 = 0; q4 < G / 4; ++q4) reinterpret_cast<f4v*>(d)[q4] = reinterpret_cast<const f4v*>(e_l)[q4];
+                        }
+                        kept_pos[idx] = first + j;
+                    }
+                    at += __builtin_popcountll(m);
+                }
+            }
+        } else if (dense) {
             __syncthreads();
             const int first = row_begin + ch * CAP;
             const int nf = (row_end - first < CAP ? row_end - first : CAP) * G;     // floats of this chunk
@@ -369,57 +403,7 @@ __device__ __forceinline__ void process_rows(WaveState<G>& st, const uint32_t (&
             for (int f = (nf & ~3) + (int)threadIdx.x; f < nf; f += 256) dst[f] = src[f];
         }
     }
-}
-
-// The workgroup's four lists of kept rows (each ascending in position; wave w holds the rows 8 w .. 8 w + 7 of every
-// 32) merged into the segment's run: the kept rows, in position order, fill rows row_begin, row_begin + 1, ... of the
-// pivot's block of rep_logits (a segment never keeps more rows than it has), their positions the same entries of
-// `pos`, and their number is left in *count.  An entry's place is its index in its own list plus the number of
-// entries of the other lists that lie before it.  A list that ran over its capacity makes the count the segment's
-// rows + 1: "unknown", which sends the pivot to the dense passes.  Called by the whole workgroup after a barrier that
-// follows the last append.
-template <int G>
-__device__ __forceinline__ void merge_kept(const float (&lists)[2][REP_STASH_FLOATS], const int (&counts)[4], float* __restrict__ rep_base,
-                                           int32_t* __restrict__ pos_out, int32_t* __restrict__ count_out, int row_begin, int row_end)
-{
-    constexpr int CAPW = KeepCap<G>::N;
-    const float* base = &lists[0][0];
-    const int n0 = counts[0], n1 = counts[1], n2 = counts[2], n3 = counts[3];
-    if (n0 > CAPW || n1 > CAPW || n2 > CAPW || n3 > CAPW) {
-        if (threadIdx.x == 0) *count_out = row_end - row_begin + 1;
-        return;
-    }
-    const int total = n0 + n1 + n2 + n3;
-    for (int e = threadIdx.x; e < total; e += 256) {
-        const int lw = e < n0 ? 0 : e < n0 + n1 ? 1 : e < n0 + n1 + n2 ? 2 : 3;
-        const int idx = e - (lw == 0 ? 0 : lw == 1 ? n0 : lw == 2 ? n0 + n1 : n0 + n1 + n2);
-        const float* mine = base + (size_t)lw * KEEP_WAVE_FLOATS;
-        const int p = reinterpret_cast<const int32_t*>(mine + CAPW * G)[idx];
-        int rank = idx;
-#pragma unroll
-        for (int ow = 0; ow < 4; ++ow) {
-            if (ow == lw) continue;
-            const int32_t* op = reinterpret_cast<const int32_t*>(base + (size_t)ow * KEEP_WAVE_FLOATS + CAPW * G);
-            int lo = 0, hi = counts[ow];                     // entries of list ow with a position below p
-            while (lo < hi) {
-                const int mid = (lo + hi) >> 1;
-                if (op[mid] < p) lo = mid + 1;
-                else hi = mid;
-            }
-            rank += lo;
-        }
-        const float* e_l = mine + (size_t)idx * G;
-        float* d = rep_base + (size_t)(row_begin + rank) * G;
-        typedef float f4v __attribute__((ext_vector_type(4)));
-        if (G == 1) d[0] = e_l[0];
-        else if (G == 2) *reinterpret_cast<float2*>(d) = *reinterpret_cast<const float2*>(e_l);
-        else {
-#pragma unroll
-            for (int q4 = 0; q4 < G / 4; ++q4) reinterpret_cast<f4v*>(d)[q4] = reinterpret_cast<const f4v*>(e_l)[q4];
-        }
-        pos_out[row_begin + rank] = p;
-    }
-    if (threadIdx.x == 0) *count_out = total;
+    return seg_kept;
 }
 
 // What the filtered form of the split pass needs besides the arguments of the plain one.
@@ -445,7 +429,7 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
     __shared__ float sm_Z[16][G];
     __shared__ __attribute__((aligned(16))) float sm_red[4][G * HC_D];
     __shared__ __attribute__((aligned(16))) float sm_stash[2][REP_STASH_FLOATS];
-    __shared__ int sm_kept[4];       // filtered: rows every wave kept of the current segment
+    __shared__ int sm_kept[4];       // filtered: rows every wave keeps of the current chunk
 
     const int tid = threadIdx.x;
     const int w = tid >> 6;
@@ -464,7 +448,6 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
         float* rep_base = nullptr;
         int32_t* kept_pos = nullptr;
         int32_t* kept_count = nullptr;
-        KeepList<G> kl{nullptr, nullptr, 0};
         FilterCtx<G> fc;
         fc.cutsum = 0.f;
         fc.lo = fc.hi = 0;
@@ -475,8 +458,6 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
             if (FILT) {
                 kept_pos = fa.surv_pos + (size_t)seg.rep_slot * max_ctx;
                 kept_count = fa.seg_cnt + seg.slot;
-                kl.logits = &sm_stash[0][0] + (size_t)w * KEEP_WAVE_FLOATS;
-                kl.pos = reinterpret_cast<int32_t*>(kl.logits + KeepCap<G>::N * G);
                 const RepFilter f = fa.filt[seg.rep_slot];
                 fc.cutsum = f.cutsum;
 #pragma unroll
@@ -506,8 +487,8 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
             for (int i = 0; i < 16; ++i) st.acc[g][i] = 0.f;
         }
 
-        process_rows<G, FILT>(st, qreg, Kp, Vp, rep_base, fc, kl, sm_stash, seg.row_begin, seg.row_end, w, r, c);
-        if (FILT && lane == 0) sm_kept[w] = kl.count;
+        const int seg_kept = process_rows<G, FILT>(st, qreg, Kp, Vp, rep_base, fc, kept_pos, sm_stash, sm_kept, seg.row_begin, seg.row_end, w, r, c);
+        if (FILT && rep_base && tid == 0) *kept_count = seg_kept;
         if (stamps && threadIdx.x == 0 && next_extra >= blk.extra_end && st.Z[0] >= 0.f)      // (the condition on Z orders the stamp after the rows)
             stamps[2 * blockIdx.x + 1] = __builtin_amdgcn_s_memrealtime();
 
@@ -575,8 +556,6 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
             part_ml[((size_t)seg.slot * G + tid) * 2 + 0] = M;
             part_ml[((size_t)seg.slot * G + tid) * 2 + 1] = z;
         }
-        if (FILT && kl.logits)       // (the barrier above came after every wave's last append)
-            merge_kept<G>(sm_stash, sm_kept, rep_base, kept_pos, kept_count, seg.row_begin, seg.row_end);
         if (next_extra >= blk.extra_end) break;
         __syncthreads();
         seg = segs[next_extra++];

@@ -770,7 +770,7 @@ __global__ __launch_bounds__(BLK) void mon_sparse_score(MonBatch B, int max_k, i
         if (sidx < nseg) {
             const SegDev sg = it.segs[hd.part_begin + sidx];
             c = it.seg_cnt[hd.part_begin + sidx];
-            if (c < 0 || c > sg.row_end - sg.row_begin) {      // a segment whose workgroup could not hold all the rows it kept
+            if (c < 0 || c > sg.row_end - sg.row_begin) {      // not a count the split pass can have written
                 sm_unknown = 1;
                 c = 0;
             }
@@ -795,7 +795,7 @@ __global__ __launch_bounds__(BLK) void mon_sparse_score(MonBatch B, int max_k, i
     int kmax = 0;
     for (int ks = 0; ks < rd.nk; ++ks) kmax = max(kmax, it.real_reps[rep].k[ks]);       // (indexing the register copy would spill it)
     // why a pivot goes to the dense passes: 1 more rows kept than the launch was sized for, 2 fewer than the longest
-    // list needs, 3 a workgroup could not hold the rows it kept, 4 too many segments, (5: the check failed, below)
+    // list needs, 3 a segment's count is out of range, 4 too many segments, (5: the check failed, below)
     const int why = sm_unknown != 0 ? 3 : hd.part_count > MAX_FILTER_SEGS ? 4 : n > it.cap_rows ? 1 : n < kmax ? 2 : 0;
     const bool bad = why != 0;
     if (blockIdx.x == 0 && threadIdx.x == 0) {

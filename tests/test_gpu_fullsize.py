@@ -107,18 +107,20 @@ def test_config3_full_size_two_layers_five_steps(margin):
     assert resyncs <= 1, (resyncs, ties)
 
 
-def test_config5_full_size_batch_of_16():
+@pytest.mark.parametrize("margin", [0.0, 1.25])
+def test_config5_full_size_batch_of_16(margin):
     """16 sequences of 8192 ... 131072 tokens, two of eight KV heads full per sequence, budgets from
     {512, ..., 4096}, every sequence with its own jump events: 128 ragged head rows in one split pass (the long-pass
-    plan: weighted shares, boundary costs), 32 pivots in one monitor call, refills of single sequences."""
-    say("config 5 full size: B = 16, 2 layers, 4 steps")
+    plan: weighted shares, boundary costs), 32 pivots in one monitor call, refills of single sequences; without and with
+    the pivot-logit filter (lists of up to a third of a short sequence's positions)."""
+    say("config 5 full size: B = 16, 2 layers, 4 steps, filter margin", margin)
     w = I.make_workload(5, device=DEV)
     sp = w.spec
     say("  contexts", sp.ctx)
     assert sp.B == 16 and min(sp.ctx) >= 8192 and max(sp.ctx) <= 131072
     w1 = I.make_workload(5, layer=1, device=DEV, ctx=sp.ctx)        # the same batch, the roles drawn again for the second layer
     assert w1.spec.ctx == sp.ctx and w1.spec.heads != sp.heads
-    trig, resyncs, ties = run_stack([w, w1], 4, 1, "cfg5", max_k=4096 - 64 - 256)
+    trig, resyncs, ties = run_stack([w, w1], 4, 1, "cfg5", max_k=4096 - 64 - 256, filter_margin=margin)
     n_piv = sum(len(x.spec.reps(b)) for x in (w, w1) for b in range(sp.B))
     say("  pivots", n_piv, "triggers per step", trig, "re-synchronisations", resyncs)
     assert trig[0] == n_piv                              # initial fill replaced
