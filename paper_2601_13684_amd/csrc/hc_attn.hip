@@ -92,8 +92,7 @@ struct WaveState {
 template <int G>
 struct FilterCtx {
     float cutsum;
-    float ref[G];
-    float cg[G];        // 2^(m_g - ref_g): turns the weights 2^(t - m) the softmax computes anyway into 2^(t - ref)
+    float ref[G];       // log2 units
     int lo, hi;         // the pivot's candidate positions
 };
 
@@ -143,13 +142,11 @@ __device__ __forceinline__ void qk(const uint32_t (&qreg)[G][8], const Tile& t, 
 // the reduction.  They go to a staging buffer in LDS first (stash points at the row's G floats there) and
 // reach memory in long contiguous runs: 128-byte stores scattered through a pass that streams reads at
 // full rate cost several times their share of the traffic.
-constexpr uint32_t DROPPED = 0xffffffffu;   // first logit of a staged row that the filter dropped (see row_step)
-
 template <int G>
-__device__ __forceinline__ void stash_rep(float* stash, const float (&s)[G], int c, bool valid, bool dropped = false)
+__device__ __forceinline__ void stash_rep(float* stash, const float (&s)[G], int c, bool valid)
 {
     if (c != 0 || !valid) return;
-    const float first = dropped ? __uint_as_float(DROPPED) : s[0] * INV_SQRT_D;
+    const float first = s[0] * INV_SQRT_D;
     if (G == 1) {
         stash[0] = first;
     } else if (G == 2) {
@@ -181,9 +178,8 @@ __device__ __forceinline__ uint64_t exponents(const WaveState<G>& st, const floa
 // Rare: raise the reference to the largest logit of this row step and recompute the exponents.
 // Returns, per head, the factor 2^(old reference - new reference) by which everything accumulated so
 // far has to be multiplied.
-template <int G, bool FILT>
-__device__ __forceinline__ void move_reference(WaveState<G>& st, const float (&s)[G], float (&x)[G], float (&alpha)[G],
-                                               bool valid, FilterCtx<G>& fc)
+template <int G>
+__device__ __forceinline__ void move_reference(WaveState<G>& st, const float (&s)[G], float (&x)[G], float (&alpha)[G], bool valid)
 {
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -196,7 +192,6 @@ __device__ __forceinline__ void move_reference(WaveState<G>& st, const float (&s
         alpha[g] = __builtin_amdgcn_exp2f(st.m[g] - mn);
         st.m[g] = mn;
         x[g] = t - mn;
-        if (FILT) fc.cg[g] = __builtin_amdgcn_exp2f(mn - fc.ref[g]);
     }
 }
 
@@ -233,58 +228,118 @@ __device__ __forceinline__ void scale_if(uint64_t mask, float alpha, float& z, f
         : "scc");
 }
 
-// p.V: weights 2^x[g], accumulated into the lane's 16 columns.  Returns sum_g 2^x[g] cg[g] (the filter's
-// statistic of the lane's row) when FILT, else 0.
-template <int G, bool FILT>
-__device__ __forceinline__ float pv(WaveState<G>& st, const float (&x)[G], const Tile& t, const FilterCtx<G>& fc)
+// p.V: weights 2^x[g], accumulated into the lane's 16 columns.
+template <int G>
+__device__ __forceinline__ void pv(WaveState<G>& st, const float (&x)[G], const Tile& t)
 {
     float vf[16];
     vf[0] = bf_lo(t.v0.x); vf[1] = bf_hi(t.v0.x); vf[2] = bf_lo(t.v0.y); vf[3] = bf_hi(t.v0.y);
     vf[4] = bf_lo(t.v0.z); vf[5] = bf_hi(t.v0.z); vf[6] = bf_lo(t.v0.w); vf[7] = bf_hi(t.v0.w);
     vf[8] = bf_lo(t.v1.x); vf[9] = bf_hi(t.v1.x); vf[10] = bf_lo(t.v1.y); vf[11] = bf_hi(t.v1.y);
     vf[12] = bf_lo(t.v1.z); vf[13] = bf_hi(t.v1.z); vf[14] = bf_lo(t.v1.w); vf[15] = bf_hi(t.v1.w);
-    float est = 0.f;
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         const float p = __builtin_amdgcn_exp2f(x[g]);
         st.Z[g] += p;
-        if (FILT) est = fmaf(p, fc.cg[g], est);
 #pragma unroll
         for (int i = 0; i < 16; ++i) st.acc[g][i] = fmaf(p, vf[i], st.acc[g][i]);
     }
-    return est;
 }
 
-// Filtered pivot logits: every row of a pivot is staged in LDS like the dense logits are, but a row the filter
-// drops gets the bit pattern DROPPED as its first logit (no sum of products of bf16 inputs has it: a NaN that
-// comes out of arithmetic on them keeps the zero low half of their payload or is the canonical one), and at the
-// end of a chunk the workgroup writes only the rows it kept.
-
-// One row step: logits, (pivot) logit stash, reference check, accumulate.  With the filter on (FILT) a staged row
-// whose statistic misses the filter's cut is marked as dropped.
-template <int G, bool FILT>
-__device__ __forceinline__ void row_step(WaveState<G>& st, const uint32_t (&qreg)[G][8], const Tile& t, float* stash,
-                                         int c, bool valid, FilterCtx<G>& fc)
+// One row step: logits, (pivot) logit stash, reference check, accumulate.  The row loop is the same with and
+// without the pivot-logit filter: which of the staged rows are kept is decided when a chunk is written out.
+template <int G>
+__device__ __forceinline__ void row_step(WaveState<G>& st, const uint32_t (&qreg)[G][8], const Tile& t, float* stash, int c, bool valid)
 {
     float s[G], x[G], alpha[G];
     qk<G>(qreg, t, s);
-    if (!FILT && stash) stash_rep<G>(stash, s, c, valid);
+    if (stash) stash_rep<G>(stash, s, c, valid);
     const uint64_t over = exponents<G>(st, s, x, valid);
 #pragma unroll
     for (int g = 0; g < G; ++g) alpha[g] = 1.0f;
-    if (over) move_reference<G, FILT>(st, s, x, alpha, valid, fc);
+    if (over) move_reference<G>(st, s, x, alpha, valid);
 #pragma unroll
     for (int g = 0; g < G; ++g) scale_if(over, alpha[g], st.Z[g], st.acc[g]);
-    const float est = pv<G, FILT>(st, x, t, fc);
-    if (FILT && stash) {
-        // (not "est >= cutsum": a statistic that is not a number, 0 * inf after an extreme move of the reference,
-        // keeps its row)
-        stash_rep<G>(stash, s, c, valid, est < fc.cutsum);
+    pv<G>(st, x, t);
+}
+
+// The filter's statistic of a staged row, sum_g 2^(t_g - ref_g) with t the scaled logit in log2 units, against the
+// cut (not "sum >= cut": a statistic that is not a number keeps its row).
+template <int G>
+__device__ __forceinline__ bool keeps(const float* row, const FilterCtx<G>& fc)
+{
+    float l[G];
+    if (G == 1) l[0] = row[0];
+    else if (G == 2) { const float2 t = *reinterpret_cast<const float2*>(row); l[0] = t.x; l[1] = t.y; }
+    else {
+#pragma unroll
+        for (int q = 0; q < G / 4; ++q) {
+            const float4 t = reinterpret_cast<const float4*>(row)[q];
+            l[4 * q] = t.x; l[4 * q + 1] = t.y; l[4 * q + 2] = t.z; l[4 * q + 3] = t.w;
+        }
     }
+    float est = 0.f;
+#pragma unroll
+    for (int g = 0; g < G; ++g) est += __builtin_amdgcn_exp2f(fmaf(l[g], LOG2E, -fc.ref[g]));
+    return !(est < fc.cutsum);
 }
 
 constexpr int REP_STASH_FLOATS = 4096;   // one staging buffer: 16 KB, i.e. 1024 positions of a group of 4 (measured: the
                                          // longer the runs, the cheaper the stores; two workgroups' buffers still fit a CU's LDS)
+
+// Writes the kept rows of one staged chunk (n positions from `first`, logits in src) to rows at, at + 1, ... of the
+// pivot's block of rep_logits and their positions to the same entries of kept_pos; returns how many (the same in
+// every thread).  Called by the whole workgroup after a barrier that follows the chunk's last staged row; holds one
+// barrier itself.  Every wave takes a quarter of the chunk's positions, 64 at a time in position order: first it
+// counts the rows it will keep (candidate positions whose statistic reaches the cut), then, knowing the other
+// waves' counts, it writes them.
+template <int G>
+__device__ __forceinline__ int write_kept(const float* src, int first, int n, float* __restrict__ rep_base, int32_t* __restrict__ kept_pos,
+                                          int at, const FilterCtx<G>& fc, int (&sm_cnt)[4], int w, int lane)
+{
+    constexpr int CAP = REP_STASH_FLOATS / G, Q = CAP / 4, ROUNDS = Q / 64;
+    static_assert(Q % 64 == 0, "a wave's quarter of a chunk is whole rounds of 64 positions");
+    static_assert(ROUNDS <= 32, "a lane remembers its decisions of a chunk in one word");
+    constexpr int UNR = ROUNDS < 4 ? ROUNDS : 4;
+    int mine = 0;
+    uint32_t kept_bits = 0;              // bit rd: this lane's row of round rd is kept
+    // (unrolled: the rounds' LDS reads and exponentials overlap; rows past the chunk's end read staged data of an
+    // earlier chunk or nothing that matters, and are masked)
+#pragma unroll UNR
+    for (int rd = 0; rd < ROUNDS; ++rd) {
+        const int j = w * Q + rd * 64 + lane;
+        const bool keep = keeps<G>(src + (size_t)j * G, fc) && j < n && first + j >= fc.lo && first + j < fc.hi;
+        kept_bits |= keep ? 1u << rd : 0u;
+        mine += __builtin_popcountll(__builtin_amdgcn_ballot_w64(keep));
+    }
+    if (lane == 0) sm_cnt[w] = mine;
+    __syncthreads();
+    const int c0 = sm_cnt[0], c1 = sm_cnt[1], c2 = sm_cnt[2], c3 = sm_cnt[3];
+    at += (w > 0 ? c0 : 0) + (w > 1 ? c1 : 0) + (w > 2 ? c2 : 0);
+    if (mine > 0) {
+#pragma unroll UNR
+        for (int rd = 0; rd < ROUNDS; ++rd) {
+            const int j = w * Q + rd * 64 + lane;
+            const bool keep = (kept_bits >> rd) & 1u;
+            const uint64_t m = __builtin_amdgcn_ballot_w64(keep);
+            if (keep) {
+                const int idx = at + __builtin_popcountll(m & ((1ull << lane) - 1ull));
+                const float* e_l = src + (size_t)j * G;
+                float* d = rep_base + (size_t)idx * G;
+                typedef float f4v __attribute__((ext_vector_type(4)));
+                if (G == 1) d[0] = e_l[0];
+                else if (G == 2) *reinterpret_cast<float2*>(d) = *reinterpret_cast<const float2*>(e_l);
+                else {
+#pragma unroll
+                    for (int q4 = 0; q4 < G / 4; ++q4) reinterpret_cast<f4v*>(d)[q4] = reinterpret_cast<const f4v*>(e_l)[q4];
+                }
+                kept_pos[idx] = first + j;
+            }
+            at += __builtin_popcountll(m);
+        }
+    }
+    return c0 + c1 + c2 + c3;
+}
 
 // Streams rows [row_begin, row_end) of one head through the wave state.  The wave takes the row steps
 // row_begin + 8*w + 32*i.  Full row steps are double-buffered in registers (tile B is in flight while
@@ -294,10 +349,11 @@ constexpr int REP_STASH_FLOATS = 4096;   // one staging buffer: 16 KB, i.e. 1024
 // REP_STASH_FLOATS / G positions: the waves stash their logits in LDS, and at the end of a chunk the workgroup
 // writes the chunk's logits to memory as one contiguous run.  Two staging buffers alternate, so one barrier per
 // chunk is enough; the number of chunks depends only on the segment, so every wave reaches every barrier.  The
-// register pipeline of loads runs on across chunk boundaries.  With the filter (FILT) the chunk's kept rows, in
+// register pipeline of loads runs on across chunk boundaries.  With the filter (FILT) a chunk's kept rows, in
 // position order, are appended to rows row_begin, row_begin + 1, ... of the pivot's block of rep_logits (a segment
-// never keeps more rows than it has) and their positions to the same entries of kept_pos; the number of rows the
-// segment kept is returned (the same in every thread).
+// never keeps more rows than it has) and their positions to the same entries of kept_pos (write_kept); the
+// segment's last chunk is left staged for the caller, which writes it out behind the barrier of its merge; the
+// number of rows kept of the chunks before it is returned (the same in every thread).
 template <int G, bool FILT>
 __device__ __forceinline__ int process_rows(WaveState<G>& st, const uint32_t (&qreg)[G][8],
                                             const char* __restrict__ Kb, const char* __restrict__ Vb,
@@ -326,14 +382,14 @@ __device__ __forceinline__ int process_rows(WaveState<G>& st, const uint32_t (&q
 #pragma unroll 1
         for (; i + 2 <= i_hi; i += 2, off += 2 * STEP) {
             load_tile(B, Kb, Vb, off + STEP);
-            row_step<G, FILT>(st, qreg, A, sp, c, true, fc);
+            row_step<G>(st, qreg, A, sp, c, true);
             if (i + 2 < nfull) load_tile(A, Kb, Vb, off + 2 * STEP);
-            row_step<G, FILT>(st, qreg, B, sp ? sp + 32 * G : nullptr, c, true, fc);
+            row_step<G>(st, qreg, B, sp ? sp + 32 * G : nullptr, c, true);
             if (sp) sp += 64 * G;
         }
         if (last) {
             if (i < nfull) {
-                row_step<G, FILT>(st, qreg, A, sp, c, true, fc);
+                row_step<G>(st, qreg, A, sp, c, true);
                 if (sp) sp += 32 * G;
                 ++i;
             }
@@ -341,56 +397,14 @@ __device__ __forceinline__ int process_rows(WaveState<G>& st, const uint32_t (&q
             if (row - r < row_end) {
                 const bool valid = row < row_end;
                 load_tile(A, Kb, Vb, (uint32_t)(valid ? row : row_end - 1) * 256u + (uint32_t)c * 16u);
-                row_step<G, FILT>(st, qreg, A, sp, c, valid, fc);
+                row_step<G>(st, qreg, A, sp, c, valid);
             }
         }
         if (dense && FILT) {
-            // Every wave takes a quarter of the chunk's positions, 64 at a time in position order: first it counts the
-            // rows it will keep (candidate positions that are not marked), then, knowing the other waves' counts, it
-            // writes them.
+            if (last) break;                 // the segment's last chunk is written out by the caller, behind the barrier it has anyway
             __syncthreads();
-            const int first = row_begin + ch * CAP;
-            const int n = row_end - first < CAP ? row_end - first : CAP;
-            const float* src = stash[ch & 1];
-            const int lane = 8 * r + c;
-            constexpr int Q = CAP / 4, ROUNDS = Q / 64;
-            static_assert(Q % 64 == 0, "a wave's quarter of a chunk is whole rounds of 64 positions");
-            int mine = 0;
-#pragma unroll 1
-            for (int rd = 0; rd < ROUNDS; ++rd) {
-                const int j = w * Q + rd * 64 + lane;
-                if (j - lane >= n) break;
-                const bool keep = j < n && first + j >= fc.lo && first + j < fc.hi && __float_as_uint(src[(size_t)j * G]) != DROPPED;
-                mine += __builtin_popcountll(__builtin_amdgcn_ballot_w64(keep));
-            }
-            if (lane == 0) sm_cnt[w] = mine;
-            __syncthreads();
-            const int c0 = sm_cnt[0], c1 = sm_cnt[1], c2 = sm_cnt[2], c3 = sm_cnt[3];
-            int at = row_begin + seg_kept + (w > 0 ? c0 : 0) + (w > 1 ? c1 : 0) + (w > 2 ? c2 : 0);
-            seg_kept += c0 + c1 + c2 + c3;
-            if (mine > 0) {
-#pragma unroll 1
-                for (int rd = 0; rd < ROUNDS; ++rd) {
-                    const int j = w * Q + rd * 64 + lane;
-                    if (j - lane >= n) break;
-                    const bool keep = j < n && first + j >= fc.lo && first + j < fc.hi && __float_as_uint(src[(size_t)j * G]) != DROPPED;
-                    const uint64_t m = __builtin_amdgcn_ballot_w64(keep);
-                    if (keep) {
-                        const int idx = at + __builtin_popcountll(m & ((1ull << lane) - 1ull));
-                        const float* e_l = src + (size_t)j * G;
-                        float* d = rep_base + (size_t)idx * G;
-                        typedef float f4v __attribute__((ext_vector_type(4)));
-                        if (G == 1) d[0] = e_l[0];
-                        else if (G == 2) *reinterpret_cast<float2*>(d) = *reinterpret_cast<const float2*>(e_l);
-                        else {
-#pragma unroll
-                            for (int q4 = 0; q4 < G / 4; ++q4) reinterpret_cast<f4v*>(d)[q4] = reinterpret_cast<const f4v*>(e_l)[q4];
-                        }
-                        kept_pos[idx] = first + j;
-                    }
-                    at += __builtin_popcountll(m);
-                }
-            }
+            seg_kept += write_kept<G>(stash[ch & 1], row_begin + ch * CAP, CAP, rep_base, kept_pos, row_begin + seg_kept, fc, sm_cnt,
+                                      w, 8 * r + c);
         } else if (dense) {
             __syncthreads();
             const int first = row_begin + ch * CAP;
@@ -452,7 +466,7 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
         fc.cutsum = 0.f;
         fc.lo = fc.hi = 0;
 #pragma unroll
-        for (int g = 0; g < G; ++g) fc.ref[g] = fc.cg[g] = 0.f;
+        for (int g = 0; g < G; ++g) fc.ref[g] = 0.f;
         if (rep_logits && seg.rep_slot >= 0) {
             rep_base = rep_logits + (size_t)seg.rep_slot * G * max_ctx;
             if (FILT) {
@@ -487,8 +501,7 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
             for (int i = 0; i < 16; ++i) st.acc[g][i] = 0.f;
         }
 
-        const int seg_kept = process_rows<G, FILT>(st, qreg, Kp, Vp, rep_base, fc, kept_pos, sm_stash, sm_kept, seg.row_begin, seg.row_end, w, r, c);
-        if (FILT && rep_base && tid == 0) *kept_count = seg_kept;
+        int seg_kept = process_rows<G, FILT>(st, qreg, Kp, Vp, rep_base, fc, kept_pos, sm_stash, sm_kept, seg.row_begin, seg.row_end, w, r, c);
         if (stamps && threadIdx.x == 0 && next_extra >= blk.extra_end && st.Z[0] >= 0.f)      // (the condition on Z orders the stamp after the rows)
             stamps[2 * blockIdx.x + 1] = __builtin_amdgcn_s_memrealtime();
 
@@ -555,6 +568,14 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
             for (int p = 0; p < 16; ++p) z += sm_Z[p][tid] * __builtin_amdgcn_exp2f(sm_m[p / 4][tid] - M);
             part_ml[((size_t)seg.slot * G + tid) * 2 + 0] = M;
             part_ml[((size_t)seg.slot * G + tid) * 2 + 1] = z;
+        }
+        if (FILT && rep_base) {          // the last chunk's kept rows (the barrier above followed its last staged row)
+            constexpr int CAP = REP_STASH_FLOATS / G;
+            const int lastc = (seg.row_end - seg.row_begin - 1) / CAP;
+            const int first = seg.row_begin + lastc * CAP;
+            seg_kept += write_kept<G>(sm_stash[lastc & 1], first, seg.row_end - first, rep_base, kept_pos, seg.row_begin + seg_kept, fc,
+                                      sm_kept, w, lane);
+            if (tid == 0) *kept_count = seg_kept;
         }
         if (next_extra >= blk.extra_end) break;
         __syncthreads();
