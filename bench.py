@@ -276,14 +276,19 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     step_ev[0].record()
+    host_t = [t0]
     for i in range(K):
         run()
         step_ev[i + 1].record()
-    t_host = time.perf_counter()
+        host_t.append(time.perf_counter())
+    t_host = host_t[-1]
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     step_ms = np.array([step_ev[i].elapsed_time(step_ev[i + 1]) for i in range(K)])
     host_enqueue_ms = (t_host - t0) * 1e3 / K
+    # the first steps after the synchronisation are enqueued into empty queues: what a step costs the host when
+    # nothing holds it back (later steps may wait for room in the queues, which then reads as host time)
+    host_first_ms = float(np.median(np.diff(host_t[:min(K, 4) + 1])) * 1e3)
     ms_per_step = (t1 - t0) * 1e3 / K
     us_per_layer = ms_per_step * 1e3 / L
 
@@ -523,6 +528,7 @@ def main():
                    "split_workgroups": hc.hc_layer_num_workgroups(layers[0].handle),
                    "split_partials": hc.hc_layer_num_partials(layers[0].handle)},
         "host_enqueue_ms_per_step": host_enqueue_ms,
+        "host_enqueue_ms_first_steps": host_first_ms,
         "prefill_init_ms_per_layer": float(np.mean(prefill_ms)) if prefill_ms else None,
         "tokens_per_s": spec0.B / (ms_per_step * 1e-3),
         "step_GBps": kv_bytes * L / (ms_per_step * 1e-3) / 1e9,
