@@ -74,6 +74,9 @@ def run_stack(ws, steps, group, tag, max_k=None, filter_margin=0.0):
         trig_per_step.append(trig)
     ties = U.NEAR_TIES[ties_before:]
     assert resyncs <= len(ties), (tag, f"{resyncs} re-synchronisations but {len(ties)} near-ties logged")
+    # the monitor's own counters (tests, triggers, filter fall-backs) summed over the stack, for the caller
+    run_stack.counts = {k: sum(p.gpu.monitor_counts(b, pv)[k] for p in pairs for b in range(p.spec.B) for pv in p.spec.reps(b))
+                        for k in ("tests", "triggers", "fallbacks")}
     for p in pairs:
         p.close()
     ctx.close()
@@ -104,6 +107,22 @@ def test_config3_full_size_two_layers_five_steps(margin):
     trig, resyncs, ties = run_stack(ws, 5, 1, "cfg3", filter_margin=margin)              # two groups: the side stream is in use
     say("  triggers per step", trig, "re-synchronisations", resyncs)
     assert trig[0] == 4 and sum(trig[1:]) >= 2, trig
+    assert resyncs <= 1, (resyncs, ties)
+
+
+def test_config4_full_size_across_a_query_jump():
+    """229376 tokens, two layers, 18 steps with the pivot-logit filter as bench.py runs it: the initial refill, fifteen
+    quiet steps, and the step at which every query jumps by 15 degrees (every pivot fires, a quarter of every list
+    is replaced, the filter's cut of the step before no longer fits the scores), then the step that attends over
+    the refilled slots."""
+    say("config 4 full size: 224K context, 2 layers, 18 steps across the jump at step 16")
+    ws = [I.make_workload(4, layer=l, device=DEV) for l in range(2)]
+    assert ws[0].spec.ctx == [229376]
+    trig, resyncs, ties = run_stack(ws, 18, 1, "cfg4", filter_margin=1.25)
+    say("  triggers per step", trig, "re-synchronisations", resyncs, "counters", run_stack.counts)
+    assert trig[0] == 4 and trig[16] == 4 and sum(trig) == 8, trig
+    assert run_stack.counts["tests"] == 4 * 18 and run_stack.counts["triggers"] == 8
+    assert run_stack.counts["fallbacks"] <= 4, run_stack.counts          # at most the jump step itself goes the long way
     assert resyncs <= 1, (resyncs, ties)
 
 
