@@ -62,6 +62,8 @@ def main():
                     "-1 (default): 1.25")
     ap.add_argument("--filter-min-candidates", type=int, default=65536, help="layers whose pivots all have fewer candidate positions "
                     "than this do not filter (the filtered monitor costs more launches, which a short context does not earn back)")
+    ap.add_argument("--side-lds", type=int, default=-1, help="KB of LDS every side-stream workgroup reserves (hc_set_side_lds; tuning; "
+                    "-1: 81 for configs 4 and 5, whose side stream has slack, else 0 = none)")
     ap.add_argument("--gather-shape", default="", help="workgroups,threads of the gather kernel (tuning; default 96,256)")
     ap.add_argument("--group", type=int, default=0, help="layers per cross-stream sync group in step mode (0: half of the "
                     "stack, at most 8, so that the side work of all but the last group overlaps later groups' attention)")
@@ -132,6 +134,9 @@ def main():
                 hc.hc_set_monitor_span(ctx.handle, args.monitor_span)
             if args.gather_shape:
                 hc.hc_set_gather_shape(ctx.handle, *[int(x) for x in args.gather_shape.split(",")])
+            if args.side_lds < 0:
+                args.side_lds = 81 if args.config in (4, 5) and not args.ctx else 0
+            hc.hc_set_side_lds(ctx.handle, args.side_lds * 1024)
         retrieved, base = I.initial_lists(spec)
         pre = None
         if args.prefill_init:
@@ -523,7 +528,7 @@ def main():
         "config": {"workload": f"config{args.config}{' dense' if args.dense else ''}: "
                                f"{spec0.ctx[0] if spec0.B == 1 else '%d..%d (sum %d)' % (min(spec0.ctx), max(spec0.ctx), sum(spec0.ctx))} ctx, {L} layers, "
                                f"B={spec0.B}, {spec0.Hq}q/{spec0.Hkv}kv heads, D=128",
-                   "layers": L, "context": spec0.ctx[0], "mode": args.mode, "host_tier": not args.no_tier, "gather": "none" if args.no_tier else ("whole lists" if args.full_gather else "difference only"), "overlap_monitor": not args.serial, "logit_filter_margin": args.filter_margin, "layers_per_group": args.group, "growing_context": args.append,
+                   "layers": L, "context": spec0.ctx[0], "mode": args.mode, "host_tier": not args.no_tier, "gather": "none" if args.no_tier else ("whole lists" if args.full_gather else "difference only"), "overlap_monitor": not args.serial, "logit_filter_margin": args.filter_margin, "side_lds_kb": args.side_lds, "layers_per_group": args.group, "growing_context": args.append,
                    "kv_bytes_per_layer_step": kv_bytes,
                    "split_workgroups": hc.hc_layer_num_workgroups(layers[0].handle),
                    "split_partials": hc.hc_layer_num_partials(layers[0].handle)},

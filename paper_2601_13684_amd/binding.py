@@ -21,7 +21,7 @@ HC_STATIC_MAX_PARTIALS = 1024
 
 EXPORTS = ["hc_create", "hc_destroy", "hc_strerror", "hc_last_error", "hc_layer_create", "hc_layer_destroy",
            "hc_layer_num_reps", "hc_layer_rep_slot", "hc_layer_num_workgroups", "hc_layer_num_partials",
-           "hc_set_split", "hc_set_gather_shape", "hc_set_logit_filter", "hc_layer_monitor_counts", "hc_layer_filter_view", "hc_set_share_weights", "hc_get_share_weights", "hc_layer_tune", "hc_set_monitor_span",
+           "hc_set_split", "hc_set_gather_shape", "hc_set_side_lds", "hc_set_logit_filter", "hc_layer_monitor_counts", "hc_layer_filter_view", "hc_set_share_weights", "hc_get_share_weights", "hc_layer_tune", "hc_set_monitor_span",
            "hc_set_timing_events", "hc_plan_describe", "hc_decode_attn", "hc_decode_attn_static", "hc_rep_topk_drift", "hc_gather_retrieve",
            "hc_append_kv", "hc_rescore_work_bytes", "hc_rescore_work_layout", "hc_rescore_window", "hc_prefill_work_bytes", "hc_prefill_work_layout", "hc_prefill_init",
            "hc_layer_window_slot",
@@ -89,6 +89,7 @@ def lib():
         L.hc_set_split.argtypes = [vp, i32, i32]
         L.hc_set_logit_filter.argtypes = [vp, C.c_float, i32]
         L.hc_set_gather_shape.argtypes = [vp, i32, i32]
+        L.hc_set_side_lds.argtypes = [vp, i32]
         L.hc_layer_monitor_counts.argtypes = [vp, i32, i32, C.POINTER(C.c_uint32)]
         L.hc_layer_filter_view.argtypes = [vp, C.POINTER(vp), C.POINTER(vp)]
         L.hc_set_share_weights.argtypes = [vp, C.POINTER(C.c_float)]
@@ -195,6 +196,10 @@ def hc_set_logit_filter(ctx: int, margin: float, min_candidates: int = 0) -> Non
 
 def hc_set_gather_shape(ctx: int, workgroups: int = 96, threads: int = 256) -> None:
     _check(lib().hc_set_gather_shape(ctx, workgroups, threads), "hc_set_gather_shape", ctx)
+
+
+def hc_set_side_lds(ctx: int, nbytes: int) -> None:
+    _check(lib().hc_set_side_lds(ctx, int(nbytes)), "hc_set_side_lds", ctx)
 
 
 def hc_layer_monitor_counts(layer: int, b: int, h: int) -> dict:

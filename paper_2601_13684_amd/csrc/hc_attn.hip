@@ -358,7 +358,7 @@ template <int G, bool FILT>
 __device__ __forceinline__ int process_rows(WaveState<G>& st, const uint32_t (&qreg)[G][8],
                                             const char* __restrict__ Kb, const char* __restrict__ Vb,
                                             float* __restrict__ rep_base, FilterCtx<G>& fc, int32_t* __restrict__ kept_pos,
-                                            float (&stash)[2][REP_STASH_FLOATS], int (&sm_cnt)[4],
+                                            float (&stash)[FILT ? 1 : 2][REP_STASH_FLOATS], int (&sm_cnt)[4],
                                             int row_begin, int row_end, int w, int r, int c)
 {
     constexpr int CAP = REP_STASH_FLOATS / G;      // positions per chunk
@@ -378,7 +378,7 @@ __device__ __forceinline__ int process_rows(WaveState<G>& st, const uint32_t (&q
     for (int ch = 0; ch < nchunk; ++ch) {
         const bool last = ch == nchunk - 1;
         const int i_hi = last ? nfull : (ch + 1) * STEPS;          // a chunk before the last holds full row steps only
-        float* sp = dense ? &stash[ch & 1][(8 * w + r) * G] : nullptr;
+        float* sp = dense ? &stash[FILT ? 0 : ch & 1][(8 * w + r) * G] : nullptr;
 #pragma unroll 1
         for (; i + 2 <= i_hi; i += 2, off += 2 * STEP) {
             load_tile(B, Kb, Vb, off + STEP);
@@ -403,8 +403,9 @@ __device__ __forceinline__ int process_rows(WaveState<G>& st, const uint32_t (&q
         if (dense && FILT) {
             if (last) break;                 // the segment's last chunk is written out by the caller, behind the barrier it has anyway
             __syncthreads();
-            seg_kept += write_kept<G>(stash[ch & 1], row_begin + ch * CAP, CAP, rep_base, kept_pos, row_begin + seg_kept, fc, sm_cnt,
+            seg_kept += write_kept<G>(stash[0], row_begin + ch * CAP, CAP, rep_base, kept_pos, row_begin + seg_kept, fc, sm_cnt,
                                       w, 8 * r + c);
+            __syncthreads();                 // one staging buffer: the next chunk's rows wait until every wave has written this one's
         } else if (dense) {
             __syncthreads();
             const int first = row_begin + ch * CAP;
@@ -442,7 +443,7 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
     __shared__ float sm_m[4][G];
     __shared__ float sm_Z[16][G];
     __shared__ __attribute__((aligned(16))) float sm_red[4][G * HC_D];
-    __shared__ __attribute__((aligned(16))) float sm_stash[2][REP_STASH_FLOATS];
+    __shared__ __attribute__((aligned(16))) float sm_stash[FILT ? 1 : 2][REP_STASH_FLOATS];
     __shared__ int sm_kept[4];       // filtered: rows every wave keeps of the current chunk
 
     const int tid = threadIdx.x;
@@ -573,7 +574,7 @@ __global__ __launch_bounds__(256, WG_PER_CU) void attn_split_kernel(const uint16
             constexpr int CAP = REP_STASH_FLOATS / G;
             const int lastc = (seg.row_end - seg.row_begin - 1) / CAP;
             const int first = seg.row_begin + lastc * CAP;
-            seg_kept += write_kept<G>(sm_stash[lastc & 1], first, seg.row_end - first, rep_base, kept_pos, seg.row_begin + seg_kept, fc,
+            seg_kept += write_kept<G>(sm_stash[0], first, seg.row_end - first, rep_base, kept_pos, seg.row_begin + seg_kept, fc,
                                       sm_kept, w, lane);
             if (tid == 0) *kept_count = seg_kept;
         }
@@ -779,7 +780,7 @@ hc_status launch_rep_logits(hc_ctx* ctx, int n, const hc_layer* const* layers, c
         batch.it[i] = RepLogitsItem{(const uint16_t*)arenas[i], L->q_keep, L->blks, L->segs, rep_logits[i], L->need, L->n_blocks, L->n_reps};
         max_blocks = std::max(max_blocks, L->n_blocks);
     }
-    rep_logits_kernel<G><<<dim3(std::min(max_blocks, 64), n), dim3(256), 0, st>>>(batch, ctx->cfg.max_ctx);
+    rep_logits_kernel<G><<<dim3(std::min(max_blocks, 64), n), dim3(256), hc_side_lds(ctx, (const void*)rep_logits_kernel<G>, 0), st>>>(batch, ctx->cfg.max_ctx);
     HC_HIP(ctx, hipGetLastError());
     return HC_OK;
 }
@@ -844,4 +845,13 @@ hc_status hc_launch_rep_logits(hc_ctx* ctx, int n, const hc_layer* const* layers
     case 8: return launch_rep_logits<8>(ctx, n, layers, arenas, rep_logits, st);
     }
     return hc_fail(ctx, HC_ESHAPE, "unsupported group size");
+}
+
+hc_status hc_attn_set_lds_limit()
+{
+    const void* fns[] = {(const void*)rep_logits_kernel<1>, (const void*)rep_logits_kernel<2>, (const void*)rep_logits_kernel<4>,
+                         (const void*)rep_logits_kernel<8>};
+    for (const void* fn : fns)
+        if (hc_allow_lds(fn) != hipSuccess) return HC_EHIP;
+    return HC_OK;
 }

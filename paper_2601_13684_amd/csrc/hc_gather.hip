@@ -260,7 +260,7 @@ hc_status hc_launch_gather(hc_ctx* ctx, int n, const hc_gather_call* calls, hipS
             if (!calls[i].slot_pos) return hc_fail(ctx, HC_EINVAL, "hc_gather: in one batch either every layer has a slot map or none");
         const size_t lds = (size_t)max_k * (sizeof(int32_t) + 2);
         if (lds > 144 * 1024) return hc_fail(ctx, HC_ESHAPE, "hc_gather: max_k %d is too large for the slot-map path", max_k);
-        gather_plan_kernel<<<dim3(1, max_sats, n), dim3(PLAN_THREADS), lds, st>>>(B, max_k);
+        gather_plan_kernel<<<dim3(1, max_sats, n), dim3(PLAN_THREADS), hc_side_lds(ctx, (const void*)gather_plan_kernel, (unsigned)lds), st>>>(B, max_k);
         HC_HIP(ctx, hipGetLastError());
     }
     // A few dozen workgroups keep the host link busy.  More do not make the refill faster, and every compute unit
@@ -272,15 +272,15 @@ hc_status hc_launch_gather(hc_ctx* ctx, int n, const hc_gather_call* calls, hipS
     for (int i = 0; i < n; ++i) rows_max += (long long)calls[i].L->n_sats * calls[i].L->max_r;
     const int thr = ctx->gather_threads, in_flight = thr / 32 * GATHER_PASSES;
     const int nwg = (int)std::max<long long>(1, std::min<long long>(ctx->gather_workgroups, (rows_max + in_flight - 1) / in_flight));
-    gather_kernel<<<dim3(nwg), dim3(thr), 0, st>>>(B, n, max_sats, max_k);
+    gather_kernel<<<dim3(nwg), dim3(thr), hc_side_lds(ctx, (const void*)gather_kernel, 0), st>>>(B, n, max_sats, max_k);
     HC_HIP(ctx, hipGetLastError());
     return HC_OK;
 }
 
+// the plan kernel may need more dynamic LDS than the default 64 KB limit, and beside the attention pass both kernels
+// reserve more than half of a compute unit's LDS (hc_side_lds)
 hc_status hc_gather_set_lds_limit()
 {
-    // the plan kernel may need more dynamic LDS than the default 64 KB limit
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gather_plan_kernel),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
-    return e == hipSuccess ? HC_OK : HC_EHIP;
+    if (hc_allow_lds((const void*)gather_plan_kernel) != hipSuccess || hc_allow_lds((const void*)gather_kernel) != hipSuccess) return HC_EHIP;
+    return HC_OK;
 }

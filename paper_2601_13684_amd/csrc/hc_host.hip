@@ -140,6 +140,7 @@ extern "C" hc_status hc_create(const hc_config* cfg, hc_ctx** out)
         c->npairs = g + 2 * pair_w;
         (void)hc_gather_set_lds_limit();
         (void)hc_monitor_set_lds_limit();
+        (void)hc_attn_set_lds_limit();
         // the fixed scratch of hc_decode_attn_static: its address on this device (left null if the lookup fails;
         // that entry point then refuses to run, the others do not need it)
         if (hc_attn_static_scratch(c, &c->static_scratch) != HC_OK) c->static_scratch = nullptr;
@@ -205,6 +206,15 @@ extern "C" hc_status hc_set_logit_filter(hc_ctx* ctx, float margin, int32_t min_
         return hc_fail(ctx, HC_EINVAL, "hc_set_logit_filter: margin 0 (off) or 1 .. 1e6, min_candidates >= 0");
     ctx->filter_margin = margin;
     ctx->filter_min_candidates = min_candidates;
+    return HC_OK;
+}
+
+extern "C" hc_status hc_set_side_lds(hc_ctx* ctx, int32_t bytes)
+{
+    if (!ctx_ok(ctx)) return HC_ESTATE;
+    if (bytes != 0 && (bytes <= HC_LDS_PER_CU / 2 || bytes > 100 * 1024))
+        return hc_fail(ctx, HC_EINVAL, "hc_set_side_lds: 0, or more than half of a compute unit's LDS (%d bytes) up to 100 KB", HC_LDS_PER_CU / 2);
+    ctx->side_lds_total = bytes;
     return HC_OK;
 }
 
@@ -1279,6 +1289,7 @@ extern "C" hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* io, int32_t 
         hc_gather_call gat[HC_MAX_GROUP];
         RescoreJob test_job[HC_MAX_GROUP];
         int n_mon = 0, n_gat = 0, n_test = 0;
+        bool all_filtered = true;               // every monitored layer's split pass filters its pivot logits
         hc_layer* Lg = nullptr;                 // the group's events live in its last layer
     };
     SideWork work[2];
@@ -1288,8 +1299,10 @@ extern "C" hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* io, int32_t 
         if (ss) HC_HIP(ctx, hipStreamWaitEvent(ss, w.Lg->ev_attn, 0));
         hc_status st = HC_OK;
         if (w.n_test > 0) st = rescore_passes(ctx, w.n_test, w.test_job, run);       // test step of a re-scored window: the earlier queries first
+        ctx->side_pad_now = ss != nullptr && w.all_filtered;
         if (st == HC_OK) st = hc_launch_monitor(ctx, w.n_mon, w.mon, 0, run);
         if (st == HC_OK && w.n_gat > 0) st = hc_launch_gather(ctx, w.n_gat, w.gat, run);
+        ctx->side_pad_now = false;
         if (ss) {
             // recorded even after a failed launch, so that no later call waits on a stale event
             const hipError_t e = hipEventRecord(w.Lg->ev_side, ss);
@@ -1306,6 +1319,7 @@ extern "C" hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* io, int32_t 
         const int g1 = std::min(n_layers, g0 + layers_per_group);
         SideWork& w = work[cur];
         w.n_mon = w.n_gat = w.n_test = 0;
+        w.all_filtered = true;
         const void* push_src[HC_MAX_GROUP];
         void* push_dst[HC_MAX_GROUP];
         hc_layer* push_layer[HC_MAX_GROUP];
@@ -1339,6 +1353,7 @@ extern "C" hc_status hc_decode_step(hc_ctx* ctx, const hc_layer_io* io, int32_t 
                 w.mon[w.n_mon] = hc_monitor_call{L, x.rep_logits, x.lse, x.scores, x.topk_idx, x.base_idx, x.ring, x.inter, x.flag};
                 w.mon[w.n_mon++].arena = x.kv_arena;
                 L->last_arena = x.kv_arena;
+                w.all_filtered = w.all_filtered && hc_layer_filtered(ctx, L);
                 if (rescored) {
                     push_src[n_push] = x.q;
                     push_layer[n_push] = L;

@@ -4,6 +4,8 @@
 #include <stdint.h>
 
 #include <utility>
+#include <mutex>
+#include <unordered_map>
 #include <vector>
 
 #include "../../include/hc.h"
@@ -101,6 +103,8 @@ struct hc_ctx {
     int gather_workgroups = 96, gather_threads = 256;   // launch shape of the gather (hc_set_gather_shape)
     float filter_margin = 0.f;   // > 0: pivot logits are filtered (hc_set_logit_filter); layers created afterwards carry the buffers
     int filter_min_candidates = 0;   // ... if one of their pivots has at least this many candidate positions
+    int side_lds_total = 0;      // > 0: LDS bytes every side-stream workgroup of hc_decode_step reserves (hc_set_side_lds)
+    bool side_pad_now = false;   // set while hc_decode_step enqueues a group's side work on a stream of its own
     int device;
     char err[512];
     std::vector<std::pair<hipEvent_t, hipEvent_t>> timing;   // optional timing hook: one pair per split-pass launch
@@ -232,7 +236,36 @@ hc_status hc_launch_rep_logits(hc_ctx* ctx, int n, const hc_layer* const* layers
 hc_status hc_launch_monitor(hc_ctx* ctx, int n, const hc_monitor_call* calls, int scores_given, hipStream_t st);
 hc_status hc_launch_gather(hc_ctx* ctx, int n, const hc_gather_call* calls, hipStream_t st);
 hc_status hc_gather_set_lds_limit();     // once per process, at context creation
-hc_status hc_monitor_set_lds_limit();    // likewise
+hc_status hc_monitor_set_lds_limit();
+hc_status hc_attn_set_lds_limit();
+// Dynamic LDS for a launch of side-stream kernel fn that itself needs dyn_needed bytes.  Beside the attention pass
+// (side_pad_now) the workgroup's LDS is brought up to side_lds_total bytes, more than half of a compute unit's: a
+// compute unit then never holds more than one workgroup of the side stream, whatever got there first, and always has
+// room (LDS, registers, wave slots) for its two workgroups of the attention pass.
+inline unsigned hc_side_lds(const hc_ctx* ctx, const void* fn, unsigned dyn_needed)
+{
+    if (!ctx->side_pad_now || ctx->side_lds_total <= 0) return dyn_needed;
+    static std::unordered_map<const void*, unsigned> static_lds;      // of the kernels seen so far (a property of the code)
+    static std::mutex guard;
+    std::lock_guard<std::mutex> lock(guard);
+    auto it = static_lds.find(fn);
+    if (it == static_lds.end()) {
+        hipFuncAttributes a{};
+        if (hipFuncGetAttributes(&a, fn) != hipSuccess) return dyn_needed;
+        it = static_lds.emplace(fn, (unsigned)a.sharedSizeBytes).first;
+    }
+    const unsigned st = it->second;
+    const unsigned want = (unsigned)ctx->side_lds_total > st ? (unsigned)ctx->side_lds_total - st : 0u;
+    return want > dyn_needed ? want : dyn_needed;
+}
+constexpr int HC_LDS_PER_CU = 160 * 1024;
+inline hipError_t hc_allow_lds(const void* fn)       // lets fn be launched with any dynamic LDS a compute unit can give
+{
+    hipFuncAttributes a{};
+    hipError_t e = hipFuncGetAttributes(&a, fn);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, HC_LDS_PER_CU - (int)a.sharedSizeBytes);
+}    // likewise
 // Work buffer of the window re-scoring pass (offsets in bytes, item sizes in elements).
 constexpr int HC_RESCORE_MAX_BLOCKS = 512;
 struct hc_rescore_layout {

@@ -927,35 +927,35 @@ static hc_status run_chain(hc_ctx* ctx, int n, const hc_monitor_call* const* cal
     const dim3 g1((max_nchunk + span - 1) / span, max_reps, n);
     if (mode == 1) {
         switch (ctx->G) {
-        case 1: mon_sparse_score<1><<<g1, dim3(BLK), 0, st>>>(B, c.max_k, span); break;
-        case 2: mon_sparse_score<2><<<g1, dim3(BLK), 0, st>>>(B, c.max_k, span); break;
-        case 4: mon_sparse_score<4><<<g1, dim3(BLK), 0, st>>>(B, c.max_k, span); break;
-        default: mon_sparse_score<8><<<g1, dim3(BLK), 0, st>>>(B, c.max_k, span); break;
+        case 1: mon_sparse_score<1><<<g1, dim3(BLK), hc_side_lds(ctx, (const void*)mon_sparse_score<1>, 0), st>>>(B, c.max_k, span); break;
+        case 2: mon_sparse_score<2><<<g1, dim3(BLK), hc_side_lds(ctx, (const void*)mon_sparse_score<2>, 0), st>>>(B, c.max_k, span); break;
+        case 4: mon_sparse_score<4><<<g1, dim3(BLK), hc_side_lds(ctx, (const void*)mon_sparse_score<4>, 0), st>>>(B, c.max_k, span); break;
+        default: mon_sparse_score<8><<<g1, dim3(BLK), hc_side_lds(ctx, (const void*)mon_sparse_score<8>, 0), st>>>(B, c.max_k, span); break;
         }
     } else {
         switch (ctx->G) {
-        case 1: mon_score_hist<1><<<g1, dim3(BLK), 0, st>>>(B, scores_given, c.agg, c.max_k, span); break;
-        case 2: mon_score_hist<2><<<g1, dim3(BLK), 0, st>>>(B, scores_given, c.agg, c.max_k, span); break;
-        case 4: mon_score_hist<4><<<g1, dim3(BLK), 0, st>>>(B, scores_given, c.agg, c.max_k, span); break;
-        default: mon_score_hist<8><<<g1, dim3(BLK), 0, st>>>(B, scores_given, c.agg, c.max_k, span); break;
+        case 1: mon_score_hist<1><<<g1, dim3(BLK), hc_side_lds(ctx, (const void*)mon_score_hist<1>, 0), st>>>(B, scores_given, c.agg, c.max_k, span); break;
+        case 2: mon_score_hist<2><<<g1, dim3(BLK), hc_side_lds(ctx, (const void*)mon_score_hist<2>, 0), st>>>(B, scores_given, c.agg, c.max_k, span); break;
+        case 4: mon_score_hist<4><<<g1, dim3(BLK), hc_side_lds(ctx, (const void*)mon_score_hist<4>, 0), st>>>(B, scores_given, c.agg, c.max_k, span); break;
+        default: mon_score_hist<8><<<g1, dim3(BLK), hc_side_lds(ctx, (const void*)mon_score_hist<8>, 0), st>>>(B, scores_given, c.agg, c.max_k, span); break;
         }
     }
     HC_HIP(ctx, hipGetLastError());
     // the later passes start at a multiple of 4 positions, which can add one chunk
     const dim3 gk((max_nchunk + 1 + span - 1) / span, max_reps, n);
     const size_t hist_lds = (size_t)max_nk * HC_RADIX_BINS * sizeof(uint32_t);
-    mon_hist<2><<<gk, dim3(BLK), hist_lds, st>>>(B, span);
+    mon_hist<2><<<gk, dim3(BLK), hc_side_lds(ctx, (const void*)mon_hist<2>, (unsigned)hist_lds), st>>>(B, span);
     HC_HIP(ctx, hipGetLastError());
-    mon_hist<3><<<gk, dim3(BLK), hist_lds, st>>>(B, span);
+    mon_hist<3><<<gk, dim3(BLK), hc_side_lds(ctx, (const void*)mon_hist<3>, (unsigned)hist_lds), st>>>(B, span);
     HC_HIP(ctx, hipGetLastError());
-    mon_count<<<gk, dim3(BLK), 0, st>>>(B, span, ctx->G);
+    mon_count<<<gk, dim3(BLK), hc_side_lds(ctx, (const void*)mon_count, 0), st>>>(B, span, ctx->G);
     HC_HIP(ctx, hipGetLastError());
     DriftCfg dc{c.window, c.metric, c.tau_num, c.tau_den, c.max_k, c.window_mode != HC_WINDOW_SLIDING};
     // the write pass has no per-workgroup set-up to amortise: one chunk per wave
     const int span_w = mode == 2 ? 4 * NWAVE : NWAVE;
-    mon_write<<<dim3((max_nchunk + 1 + span_w - 1) / span_w, max_reps, n), dim3(BLK), 0, st>>>(B, dc, span_w);
+    mon_write<<<dim3((max_nchunk + 1 + span_w - 1) / span_w, max_reps, n), dim3(BLK), hc_side_lds(ctx, (const void*)mon_write, 0), st>>>(B, dc, span_w);
     HC_HIP(ctx, hipGetLastError());
-    mon_decide<<<dim3(max_reps, n), dim3(BLK), 0, st>>>(B, dc, ctx->G);
+    mon_decide<<<dim3(max_reps, n), dim3(BLK), hc_side_lds(ctx, (const void*)mon_decide, 0), st>>>(B, dc, ctx->G);
     HC_HIP(ctx, hipGetLastError());
     return HC_OK;
 }
@@ -1010,10 +1010,13 @@ hc_status hc_launch_monitor(hc_ctx* ctx, int n, const hc_monitor_call* calls, in
 hc_status hc_monitor_set_lds_limit()
 {
     // a pivot with HC_MAX_K_PER_REP distinct set sizes needs 64 KB of dynamic LDS for its histograms, on top of
-    // the kernels' static LDS: above the default limit of 64 KB per workgroup
-    const int bytes = HC_MAX_K_PER_REP * HC_RADIX_BINS * (int)sizeof(uint32_t);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(mon_hist<2>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    if (e == hipSuccess)
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(mon_hist<3>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    return e == hipSuccess ? HC_OK : HC_EHIP;
+    // the kernels' static LDS: above the default limit of 64 KB per workgroup; and beside the attention pass every
+    // kernel here reserves more than half of a compute unit's LDS (hc_side_lds)
+    const void* fns[] = {(const void*)mon_hist<2>, (const void*)mon_hist<3>, (const void*)mon_count, (const void*)mon_write,
+                         (const void*)mon_decide, (const void*)mon_sparse_score<1>, (const void*)mon_sparse_score<2>,
+                         (const void*)mon_sparse_score<4>, (const void*)mon_sparse_score<8>, (const void*)mon_score_hist<1>,
+                         (const void*)mon_score_hist<2>, (const void*)mon_score_hist<4>, (const void*)mon_score_hist<8>};
+    for (const void* fn : fns)
+        if (hc_allow_lds(fn) != hipSuccess) return HC_EHIP;
+    return HC_OK;
 }

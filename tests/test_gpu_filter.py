@@ -140,13 +140,15 @@ def test_filter_with_a_growing_context():
     p.close()
 
 
-@pytest.mark.parametrize("n_layers,group", [(5, 2), (10, 8)])
-def test_filter_through_the_decode_step(n_layers, group):
+@pytest.mark.parametrize("n_layers,group,side_lds", [(5, 2, 0), (10, 8, 0), (5, 2, 81 * 1024), (10, 4, 100 * 1024)])
+def test_filter_through_the_decode_step(n_layers, group, side_lds):
     """A stack of layers through hc_decode_step with the filter on: the filtered and the stand-by dense chains are
-    batched over the layers of a group."""
-    say(f"filter, hc_decode_step, {n_layers} layers, groups of {group}")
+    batched over the layers of a group.  Also with the side stream's workgroups reserving most of a compute unit's LDS
+    (hc_set_side_lds), which changes where and when they run, never what they compute."""
+    say(f"filter, hc_decode_step, {n_layers} layers, groups of {group}, side LDS {side_lds}")
     ws = [I.make_workload(2, layer=l, N=8192, scale=0.25) for l in range(n_layers)]
     ctx = R.Context(R.make_config(ws[0].spec), DEV, filter_margin=1.25)
+    hc.hc_set_side_lds(ctx.handle, side_lds)
     pairs = [U.Pair(w.spec, w.data, DEV, ctx=ctx) for w in ws]
     for p in pairs:
         p.gpu.rep_logits = torch.zeros_like(p.gpu.rep_logits)
@@ -180,4 +182,14 @@ def test_filter_through_the_decode_step(n_layers, group):
     assert fb[1] >= 2 and sum(fb) == fb[1]
     for p in pairs:
         p.close()
+    ctx.close()
+
+
+def test_side_lds_argument_range():
+    ctx = R.Context(R.make_config(I.make_workload(1).spec), DEV)
+    for ok in (0, 80 * 1024 + 1, 81 * 1024, 100 * 1024):
+        hc.hc_set_side_lds(ctx.handle, ok)
+    for bad in (-1, 1024, 80 * 1024, 100 * 1024 + 1):
+        with pytest.raises(hc.HcError):
+            hc.hc_set_side_lds(ctx.handle, bad)
     ctx.close()
