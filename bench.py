@@ -63,7 +63,7 @@ def main():
     ap.add_argument("--filter-min-candidates", type=int, default=65536, help="layers whose pivots all have fewer candidate positions "
                     "than this do not filter (the filtered monitor costs more launches, which a short context does not earn back)")
     ap.add_argument("--side-lds", type=int, default=-1, help="KB of LDS every side-stream workgroup reserves (hc_set_side_lds; tuning; "
-                    "-1: 81 for configs 4 and 5, whose side stream has slack, else 0 = none)")
+                    "-1: the library's default of 81, 0: none)")
     ap.add_argument("--gather-shape", default="", help="workgroups,threads of the gather kernel (tuning; default 96,256)")
     ap.add_argument("--group", type=int, default=0, help="layers per cross-stream sync group in step mode (0: half of the "
                     "stack, at most 8, so that the side work of all but the last group overlaps later groups' attention)")
@@ -135,7 +135,7 @@ def main():
             if args.gather_shape:
                 hc.hc_set_gather_shape(ctx.handle, *[int(x) for x in args.gather_shape.split(",")])
             if args.side_lds < 0:
-                args.side_lds = 81 if args.config in (4, 5) and not args.ctx else 0
+                args.side_lds = 81
             hc.hc_set_side_lds(ctx.handle, args.side_lds * 1024)
         retrieved, base = I.initial_lists(spec)
         pre = None

@@ -195,17 +195,16 @@ hc_status hc_layer_filter_view(const hc_layer* layer, const int32_t** kept_pos, 
  * behind them. */
 hc_status hc_set_gather_shape(hc_ctx* ctx, int32_t workgroups, int32_t threads);
 
-/* Tuning knob: how much LDS every workgroup that hc_decode_step launches on its side stream reserves (bytes: 0, the
- * default: only what the kernels need; or 80 KB + 1 .. 100 KB).  More than half of a compute unit's LDS means that a
+/* Tuning knob: how much LDS every workgroup that hc_decode_step launches on its side stream reserves (bytes: 80 KB + 1
+ * .. 100 KB, default 81 KB; or 0: only what the kernels need).  More than half of a compute unit's LDS means that a
  * compute unit never holds two workgroups of the side stream at once, so that, whichever stream's kernel gets to an
  * idle compute unit first, the two workgroups of the attention pass still find their registers, wave slots and LDS
  * there: an attention workgroup that has to wait for a place delays its whole launch.  The price: a side-stream
- * kernel with more workgroups than compute units runs in several rounds, so a group's monitor and gather take longer.
- * It pays where the side stream has slack (refills now and then: measured -1.1 % of the step at the 224K workload)
- * and costs where the side stream is what the next step waits for (refills at most steps: +4 % at the 128K workload
- * with queries that rotate at every step).  Applies to groups of layers whose attention passes all filter the pivot
- * logits (hc_set_logit_filter): only that form of the split pass is small enough (25 KB of LDS per workgroup) to fit
- * twice beside such a reservation. */
+ * kernel with more workgroups than compute units runs in several rounds (the filtered monitor's launches are sized
+ * for about twice the longest list, not for the context, to stay below that).  Measured: -1.1 % of the step at the
+ * 224K workload, -1.5 % with 16 ragged sequences, no change at 128K with refills at most steps.  Applies to groups of
+ * layers whose attention passes all filter the pivot logits (hc_set_logit_filter): only that form of the split pass
+ * is small enough (25 KB of LDS per workgroup) to fit twice beside such a reservation. */
 hc_status hc_set_side_lds(hc_ctx* ctx, int32_t bytes);
 
 /* Measurement hook: hands the library n pairs of hipEvent_t (host arrays of handles, copied).  The

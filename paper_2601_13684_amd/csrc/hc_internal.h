@@ -103,7 +103,7 @@ struct hc_ctx {
     int gather_workgroups = 96, gather_threads = 256;   // launch shape of the gather (hc_set_gather_shape)
     float filter_margin = 0.f;   // > 0: pivot logits are filtered (hc_set_logit_filter); layers created afterwards carry the buffers
     int filter_min_candidates = 0;   // ... if one of their pivots has at least this many candidate positions
-    int side_lds_total = 0;      // > 0: LDS bytes every side-stream workgroup of hc_decode_step reserves (hc_set_side_lds)
+    int side_lds_total = 81 * 1024;   // > 0: LDS bytes every side-stream workgroup of hc_decode_step reserves (hc_set_side_lds)
     bool side_pad_now = false;   // set while hc_decode_step enqueues a group's side work on a stream of its own
     int device;
     char err[512];

@@ -903,9 +903,10 @@ static hc_status run_chain(hc_ctx* ctx, int n, const hc_monitor_call* const* cal
                 it.seg_cnt = L->seg_cnt;
                 it.surv_pos = L->surv_pos;
                 it.vreps = L->vreps;
-                // Once the filter is set few rows are kept (a small multiple of the longest list); a step that keeps
-                // more is handed to the dense chain, so the launches need not be sized for it.
-                const int armed_cap = std::min(c.max_ctx, 4 * L->max_k_any + 4096);
+                // Once the filter is set few rows are kept (about 1.6 times the longest list at the usual margin of
+                // 1.25); a step that keeps more is handed to the dense chain, so the launches need not be sized for
+                // it, and every workgroup a launch does not have is one that does not queue for a compute unit.
+                const int armed_cap = std::min(c.max_ctx, (ctx->filter_margin <= 1.5f ? 2 : 4) * L->max_k_any + 4096);
                 it.cap_rows = L->filter_armed ? armed_cap : c.max_ctx;
                 nchunk = std::min(nchunk, (it.cap_rows + HC_SEL_CHUNK - 1) / HC_SEL_CHUNK);
             }
